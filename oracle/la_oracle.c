@@ -1,0 +1,246 @@
+/*
+ * CPU oracle for the lookahead-step attention and the greedy verification
+ * reduction of Lookahead Decoding (arXiv 2402.02057).
+ *
+ * THIS FILE IS TEST INFRASTRUCTURE.  It is a plain, slow, fp64 statement of
+ * what the hot path computes, written from the paper, and it shares no code,
+ * header, table or helper with the HIP library.  Only the tests, the smoke
+ * check and the benchmark's cpu_baseline leg may call it; the product path
+ * never does.
+ *
+ * What is pinned (see tests/test_oracle_*.py): the mask against a
+ * parent-pointer (ancestor) formulation, the position-chain invariant, the
+ * closed-form count of visible pairs and the worked example of Sec. 3.3;
+ * the attention arithmetic against textbook causal attention run on each
+ * row's own token chain, against a library softmax-attention for the
+ * one-token decode special case, and against isolation / permutation
+ * invariants; the verification reduction against exhaustive enumeration on
+ * tiny vocabularies, a library argmax, and the paper's Algorithm 3.
+ *
+ * Row / key order of one step (same for q, step_k, step_v, out):
+ *   r = 0                               the current input token, relative position 0
+ *   r = 1 + l*W + j                     lookahead level l (0 = oldest of the N-1
+ *                                       kept Jacobi iterates), column j; relative
+ *                                       position 1 + l + j           (Sec. 3.1)
+ *   r = 1 + W*(N-1) + g*(N-1) + k       candidate n-gram g, its k-th token after
+ *                                       the shared first token; position 1 + k
+ *                                                                    (Sec. 3.2)
+ * T = 1 + (W + G)*(N - 1).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { TOK_CURRENT = 0, TOK_LOOKAHEAD = 1, TOK_CANDIDATE = 2 };
+
+typedef struct {
+    int branch; /* TOK_* */
+    int level;  /* lookahead: level l; candidate: index g of the n-gram */
+    int offset; /* lookahead: column j; candidate: token index k */
+    int pos;    /* position relative to the current token */
+} token_t;
+
+int la_oracle_num_rows(int W, int N, int G) { return 1 + (W + G) * (N - 1); }
+
+static token_t token_of(int r, int W, int N, int G)
+{
+    token_t t;
+    (void)G;
+    if (r == 0) {
+        t.branch = TOK_CURRENT; t.level = 0; t.offset = 0; t.pos = 0;
+    } else if (r < 1 + W * (N - 1)) {
+        int x = r - 1;
+        t.branch = TOK_LOOKAHEAD; t.level = x / W; t.offset = x % W;
+        t.pos = 1 + t.level + t.offset;
+    } else {
+        int x = r - 1 - W * (N - 1);
+        t.branch = TOK_CANDIDATE; t.level = x / (N - 1); t.offset = x % (N - 1);
+        t.pos = 1 + t.offset;
+    }
+    return t;
+}
+
+/* Relative position of step row r (the digit printed on each token in Fig. 2(b)). */
+int la_oracle_position(int r, int W, int N, int G) { return token_of(r, W, N, G).pos; }
+
+/*
+ * May step row r attend to step key c?  (Sec. 3.3, Fig. 2(b); the conditioning
+ * sets of Algorithm 2.)
+ *  - every row sees the current token;
+ *  - a lookahead row (l, j) is conditioned on its own column at the levels up
+ *    to its own, and on the oldest level up to its own column: that is its
+ *    Jacobi trajectory followed back to the current token;
+ *  - a candidate row (g, k) sees the earlier tokens of the same candidate;
+ *  - the two branches do not see each other, nor do different candidates.
+ */
+int la_oracle_visible(int r, int c, int W, int N, int G)
+{
+    token_t tr = token_of(r, W, N, G), tc = token_of(c, W, N, G);
+    if (tc.branch == TOK_CURRENT) return 1;
+    if (tc.branch == TOK_LOOKAHEAD) {
+        if (tr.branch != TOK_LOOKAHEAD) return 0;
+        if (tc.level == 0 && tc.offset <= tr.offset) return 1;
+        if (tc.offset == tr.offset && tc.level <= tr.level) return 1;
+        return 0;
+    }
+    /* tc is a candidate token */
+    if (tr.branch != TOK_CANDIDATE) return 0;
+    return tc.level == tr.level && tc.offset <= tr.offset;
+}
+
+/* mask[r*T + c] = 1 iff step row r may attend to step key c. */
+void la_oracle_step_mask(int W, int N, int G, uint8_t *mask)
+{
+    int T = la_oracle_num_rows(W, N, G);
+    for (int r = 0; r < T; ++r)
+        for (int c = 0; c < T; ++c)
+            mask[(size_t)r * T + c] = (uint8_t)la_oracle_visible(r, c, W, N, G);
+}
+
+static double bf16_bits_to_double(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+int la_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/*
+ * out = softmax(mask(q k^T / sqrt(head_dim))) v, per head (Sec. 2, "Causal
+ * Attention in Decoder Models", with the mask of Sec. 3.3).  Keys of a row are
+ * the P prefix keys of its KV head (all visible) followed by the T step keys
+ * (visible per la_oracle_visible).  Query head h reads KV head h / (heads /
+ * kv_heads).  All inputs are bf16 bit patterns, arithmetic is fp64.
+ *
+ *   q       [T][heads][head_dim]
+ *   k_cache [kv_heads][P][head_dim]   v_cache likewise
+ *   step_k  [T][kv_heads][head_dim]   step_v likewise
+ *   out     [T][heads][head_dim]      fp64
+ * Returns 0, or -1 for an impossible shape.
+ */
+int la_oracle_step_attention(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache,
+                             const uint16_t *step_k, const uint16_t *step_v, int P, int W, int N,
+                             int G, int heads, int kv_heads, int head_dim, double *out)
+{
+    if (P < 0 || W < 0 || G < 0 || N < 2 || heads < 1 || kv_heads < 1 || head_dim < 1) return -1;
+    if (heads % kv_heads != 0) return -1;
+    const int T = la_oracle_num_rows(W, N, G);
+    const int group = heads / kv_heads;
+    const int d = head_dim;
+    const size_t L = (size_t)P + (size_t)T; /* keys per row */
+    const double scale = 1.0 / sqrt((double)d);
+
+    /* the explicit boolean mask over [T][P + T] */
+    uint8_t *mask = (uint8_t *)malloc((size_t)T * L);
+    if (!mask) return -1;
+    for (int r = 0; r < T; ++r) {
+        for (int p = 0; p < P; ++p) mask[(size_t)r * L + p] = 1;
+        for (int c = 0; c < T; ++c)
+            mask[(size_t)r * L + P + c] = (uint8_t)la_oracle_visible(r, c, W, N, G);
+    }
+
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int h = 0; h < heads; ++h) {
+        const int kvh = h / group;
+        double *K = (double *)malloc(L * d * sizeof(double));
+        double *V = (double *)malloc(L * d * sizeof(double));
+        double *S = (double *)malloc((size_t)T * L * sizeof(double));
+        double *qr = (double *)malloc((size_t)d * sizeof(double));
+        if (!K || !V || !S || !qr) {
+            failed = 1;
+            free(K); free(V); free(S); free(qr);
+            continue;
+        }
+        /* keys and values of this head, prefix then step tokens, as fp64 */
+        for (int p = 0; p < P; ++p)
+            for (int e = 0; e < d; ++e) {
+                size_t src = ((size_t)kvh * P + p) * d + e;
+                K[(size_t)p * d + e] = bf16_bits_to_double(k_cache[src]);
+                V[(size_t)p * d + e] = bf16_bits_to_double(v_cache[src]);
+            }
+        for (int c = 0; c < T; ++c)
+            for (int e = 0; e < d; ++e) {
+                size_t src = ((size_t)c * kv_heads + kvh) * d + e;
+                K[((size_t)P + c) * d + e] = bf16_bits_to_double(step_k[src]);
+                V[((size_t)P + c) * d + e] = bf16_bits_to_double(step_v[src]);
+            }
+        /* dense scores */
+        for (int r = 0; r < T; ++r) {
+            for (int e = 0; e < d; ++e)
+                qr[e] = bf16_bits_to_double(q[((size_t)r * heads + h) * d + e]);
+            for (size_t c = 0; c < L; ++c) {
+                double s = 0.0;
+                for (int e = 0; e < d; ++e) s += qr[e] * K[c * d + e];
+                S[(size_t)r * L + c] = s * scale;
+            }
+        }
+        /* masked softmax and the weighted sum of values */
+        for (int r = 0; r < T; ++r) {
+            const uint8_t *mr = mask + (size_t)r * L;
+            double *sr = S + (size_t)r * L;
+            double m = -INFINITY;
+            for (size_t c = 0; c < L; ++c)
+                if (mr[c] && sr[c] > m) m = sr[c];
+            double denom = 0.0;
+            for (size_t c = 0; c < L; ++c) {
+                sr[c] = mr[c] ? exp(sr[c] - m) : 0.0;
+                denom += sr[c];
+            }
+            double *o = out + ((size_t)r * heads + h) * d;
+            for (int e = 0; e < d; ++e) o[e] = 0.0;
+            for (size_t c = 0; c < L; ++c) {
+                if (!mr[c]) continue;
+                double w = sr[c] / denom;
+                for (int e = 0; e < d; ++e) o[e] += w * V[c * d + e];
+            }
+        }
+        free(K); free(V); free(S); free(qr);
+    }
+    free(mask);
+    return failed ? -1 : 0;
+}
+
+/*
+ * Greedy verification reduction (Sec. 2 "Guess-And-Verify": accept while the
+ * model's greedy choice equals the draft token, stop at the first mismatch;
+ * Algorithm 3 applies it to G candidates at once).
+ *
+ *   logits      [G][N-1][V] fp32; row (g,k) is the model output that judges
+ *               cand_tokens[g][k]
+ *   cand_tokens [G][N-1]
+ *   accepted    [G][N-1]  out: argmax of every row, lowest index on ties
+ *   accept_len  [G]       out: number of leading k with accepted == cand_tokens
+ */
+int la_oracle_verify(const float *logits, const int32_t *cand_tokens, int G, int N, int V,
+                     int32_t *accept_len, int32_t *accepted)
+{
+    if (G < 0 || N < 2 || V < 1) return -1;
+    const int n1 = N - 1;
+    for (int g = 0; g < G; ++g) {
+        for (int k = 0; k < n1; ++k) {
+            const float *row = logits + ((size_t)g * n1 + k) * V;
+            int best = 0;
+            for (int v = 1; v < V; ++v)
+                if (row[v] > row[best]) best = v;
+            accepted[g * n1 + k] = best;
+        }
+        int len = 0;
+        while (len < n1 && accepted[g * n1 + len] == cand_tokens[g * n1 + len]) ++len;
+        accept_len[g] = len;
+    }
+    return 0;
+}

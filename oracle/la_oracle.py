@@ -1,0 +1,128 @@
+"""ctypes front end of the plain-C fp64 oracle, plus the paper's Algorithm 3 in Python.
+
+Test infrastructure only (tests, the smoke check, the benchmark's cpu_baseline leg).
+bf16 tensors travel as numpy uint16 bit patterns; nothing here touches the GPU library.
+"""
+import ctypes
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(_build.build())
+        i, p = ctypes.c_int, ctypes.c_void_p
+        lib.la_oracle_num_rows.argtypes = [i, i, i]
+        lib.la_oracle_num_rows.restype = i
+        lib.la_oracle_position.argtypes = [i, i, i, i]
+        lib.la_oracle_position.restype = i
+        lib.la_oracle_visible.argtypes = [i, i, i, i, i]
+        lib.la_oracle_visible.restype = i
+        lib.la_oracle_step_mask.argtypes = [i, i, i, p]
+        lib.la_oracle_step_mask.restype = None
+        lib.la_oracle_threads.argtypes = []
+        lib.la_oracle_threads.restype = i
+        lib.la_oracle_step_attention.argtypes = [p, p, p, p, p, i, i, i, i, i, i, i, p]
+        lib.la_oracle_step_attention.restype = i
+        lib.la_oracle_verify.argtypes = [p, p, i, i, i, p, p]
+        lib.la_oracle_verify.restype = i
+        _lib = lib
+    return _lib
+
+
+def num_rows(W, N, G):
+    return _load().la_oracle_num_rows(W, N, G)
+
+
+def position(r, W, N, G):
+    return _load().la_oracle_position(r, W, N, G)
+
+
+def threads():
+    return _load().la_oracle_threads()
+
+
+def step_mask(W, N, G):
+    """bool [T, T]: may step row r attend to step key c (Sec. 3.3)."""
+    T = num_rows(W, N, G)
+    m = np.zeros((T, T), dtype=np.uint8)
+    _load().la_oracle_step_mask(W, N, G, m.ctypes.data)
+    return m.astype(bool)
+
+
+def _u16(a, shape):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint16, a.dtype
+    assert tuple(a.shape) == tuple(shape), (a.shape, shape)
+    return a
+
+
+def step_attention(q, k_cache, v_cache, step_k, step_v, P, W, N, G, heads, kv_heads, head_dim):
+    """fp64 [T, heads, head_dim] from bf16 bit patterns (uint16 arrays)."""
+    T = num_rows(W, N, G)
+    q = _u16(q, (T, heads, head_dim))
+    k_cache = _u16(k_cache, (kv_heads, P, head_dim))
+    v_cache = _u16(v_cache, (kv_heads, P, head_dim))
+    step_k = _u16(step_k, (T, kv_heads, head_dim))
+    step_v = _u16(step_v, (T, kv_heads, head_dim))
+    out = np.empty((T, heads, head_dim), dtype=np.float64)
+    rc = _load().la_oracle_step_attention(q.ctypes.data, k_cache.ctypes.data, v_cache.ctypes.data,
+                                          step_k.ctypes.data, step_v.ctypes.data, P, W, N, G,
+                                          heads, kv_heads, head_dim, out.ctypes.data)
+    if rc != 0:
+        raise ValueError("la_oracle_step_attention: bad shape (rc=%d)" % rc)
+    return out
+
+
+def verify(logits, cand_tokens, G, N, V):
+    """(accept_len int32 [G], accepted int32 [G, N-1]) from fp32 logits [G, N-1, V]."""
+    logits = np.ascontiguousarray(logits)
+    cand = np.ascontiguousarray(cand_tokens)
+    assert logits.dtype == np.float32 and logits.shape == (G, N - 1, V)
+    assert cand.dtype == np.int32 and cand.shape == (G, N - 1)
+    accept_len = np.zeros((G,), dtype=np.int32)
+    accepted = np.zeros((G, N - 1), dtype=np.int32)
+    rc = _load().la_oracle_verify(logits.ctypes.data, cand.ctypes.data, G, N, V,
+                                  accept_len.ctypes.data, accepted.ctypes.data)
+    if rc != 0:
+        raise ValueError("la_oracle_verify: bad shape (rc=%d)" % rc)
+    return accept_len, accepted
+
+
+def greedy_verification(candidates, dist_argmax):
+    """The whole of Algorithm 3 (greedy verification of G disjoint n-gram tails), small inputs.
+
+    candidates:  list of G tuples, the N-1 tokens of each n-gram after its first token.
+    dist_argmax: dist_argmax[g][i] = greedy token of the i-th of the N distributions the model
+                 returned for candidate g (i = 0: output at the last accepted token; i >= 1:
+                 output at candidate token i-1).
+    Returns the accepted tokens, between 1 and N of them.
+
+    Position by position the surviving candidates are scanned in order; the first whose token
+    equals the model's greedy token is accepted and only candidates sharing that token survive;
+    if none matches, the model's own token is emitted and the walk stops; when every position
+    was accepted the N-th distribution of the first survivor gives a bonus token.
+    """
+    alive = list(range(len(candidates)))
+    assert alive, "Algorithm 3 needs at least one candidate"
+    n1 = len(candidates[0])
+    out = []
+    for i in range(n1):
+        target = dist_argmax[alive[0]][i]
+        hit = None
+        for pos, g in enumerate(alive):
+            if candidates[g][i] == target:
+                hit = pos
+                break
+        if hit is None:
+            out.append(target)
+            return out
+        out.append(target)
+        alive = [g for g in alive[hit:] if candidates[g][i] == target]
+    out.append(dist_argmax[alive[0]][n1])
+    return out

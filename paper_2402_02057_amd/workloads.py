@@ -1,0 +1,127 @@
+"""Seeded synthetic inputs shaped like the paper's workloads.
+
+This module holds shapes, seeds and random draws only: none of the method's arithmetic
+(no mask, no attention, no argmax) lives here, so both the HIP path and the CPU oracle can
+take their inputs from it without sharing anything else.
+
+The shapes follow the (W, N, G) settings the paper reports as good for each model size
+(Table 4: N = 5 and G = W, with W = 15 / 10 / 7) on LLaMA-2-shaped attention layers; the
+tensors are N(0,1) draws rounded to bf16, standing in for real activations and KV caches.
+"""
+from dataclasses import dataclass
+
+import numpy as np
+
+BASE_SEED = 20240205
+# tensor ids within a config
+_Q, _KC, _VC, _SK, _SV, _LOGITS, _CAND, _PLAN, _PLIST = range(9)
+
+
+@dataclass(frozen=True)
+class StepShape:
+    """One lookahead step of one sequence on one attention layer."""
+    name: str
+    config: int      # index used for seeding
+    heads: int
+    kv_heads: int
+    head_dim: int
+    P: int           # prefix (KV cache) length
+    W: int           # lookahead window width
+    N: int           # n-gram size
+    G: int           # number of candidate n-grams verified this step
+    V: int           # vocabulary size of the verification logits
+    planted: bool    # whether verify logits carry planted accept lengths
+
+    @property
+    def T(self):
+        return 1 + (self.W + self.G) * (self.N - 1)
+
+
+TINY = StepShape("tiny", 0, 4, 4, 64, 64, 4, 3, 2, 512, False)
+LLAMA2_7B = StepShape("llama2-7b", 1, 32, 32, 128, 1024, 15, 5, 15, 32000, True)
+LLAMA2_13B = StepShape("llama2-13b", 2, 40, 40, 128, 2048, 10, 5, 10, 32000, True)
+LLAMA2_70B = StepShape("llama2-70b-gqa", 3, 64, 8, 128, 4096, 7, 5, 7, 32000, True)
+SHAPES = {s.name: s for s in (TINY, LLAMA2_7B, LLAMA2_13B, LLAMA2_70B)}
+
+RAGGED_W = (5, 10, 15, 20, 30)
+RAGGED_SEQS = 8
+
+
+def seed_for(config, tensor_id, extra=0):
+    return BASE_SEED + 100 * config + tensor_id + 1000003 * extra
+
+
+def ragged_prefix_lengths():
+    """The 8 prefix lengths of the ragged long-context sweep, uniform in [512, 16384]."""
+    rng = np.random.default_rng(seed_for(4, _PLIST))
+    return [int(x) for x in rng.integers(512, 16384, endpoint=True, size=RAGGED_SEQS)]
+
+
+def ragged_shape(seq, W):
+    """Sequence `seq` (0..7) of the ragged sweep at window width W (N = 5, G = W, GQA 32/8)."""
+    P = ragged_prefix_lengths()[seq]
+    return StepShape("ragged-s%d-w%d" % (seq, W), 4, 32, 8, 128, P, W, 5, W, 32016, True)
+
+
+def f32_to_bf16_bits(x):
+    """Round-to-nearest-even fp32 -> bf16, returned as uint16 bit patterns (finite inputs)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = u + 0x7FFF + ((u >> 16) & 1)
+    return (u >> 16).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b):
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+def _normal_bf16(seed, shape):
+    rng = np.random.default_rng(seed)
+    return f32_to_bf16_bits(rng.standard_normal(size=shape, dtype=np.float32))
+
+
+def attention_inputs(s: StepShape, extra=0):
+    """dict of bf16 bit-pattern (uint16) arrays: q, k_cache, v_cache, step_k, step_v.
+
+    `extra` selects an independent draw of the same shape (distinct layers of one model).
+    """
+    T, H, KV, d, P = s.T, s.heads, s.kv_heads, s.head_dim, s.P
+    return {
+        "q": _normal_bf16(seed_for(s.config, _Q, extra), (T, H, d)),
+        "k_cache": _normal_bf16(seed_for(s.config, _KC, extra), (KV, P, d)),
+        "v_cache": _normal_bf16(seed_for(s.config, _VC, extra), (KV, P, d)),
+        "step_k": _normal_bf16(seed_for(s.config, _SK, extra), (T, KV, d)),
+        "step_v": _normal_bf16(seed_for(s.config, _SV, extra), (T, KV, d)),
+    }
+
+
+PLANT_VALUE = np.float32(12.0)   # far above the largest of 32000 N(0,1) draws (about 4.2)
+
+
+def verify_inputs(s: StepShape, extra=0):
+    """(logits fp32 [G, N-1, V], cand_tokens int32 [G, N-1], planted accept lengths or None).
+
+    With `planted`, candidate g is given the accept length (g + shift) mod N: its first rows
+    peak at the candidate token, the next row peaks elsewhere, and on odd g the later rows
+    peak at the candidate token again, so that counting matches instead of the leading run
+    gives a different answer.
+    """
+    G, n1, V = s.G, s.N - 1, s.V
+    rng = np.random.default_rng(seed_for(s.config, _LOGITS, extra))
+    logits = rng.standard_normal(size=(G, n1, V), dtype=np.float32)
+    rng = np.random.default_rng(seed_for(s.config, _CAND, extra))
+    cand = rng.integers(0, V, size=(G, n1)).astype(np.int32)
+    if not s.planted:
+        return logits, cand, None
+    rng = np.random.default_rng(seed_for(s.config, _PLAN, extra))
+    shift = int(rng.integers(0, s.N))
+    lens = np.zeros((G,), dtype=np.int32)
+    for g in range(G):
+        L = (g + shift) % s.N
+        lens[g] = L
+        for k in range(n1):
+            if k < L or (k > L and g % 2 == 1):
+                logits[g, k, cand[g, k]] = PLANT_VALUE
+            elif k == L:
+                other = (int(cand[g, k]) + 1 + int(rng.integers(0, V - 1))) % V
+                logits[g, k, other] = PLANT_VALUE
+    return logits, cand, lens
