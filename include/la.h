@@ -1,0 +1,111 @@
+/*
+ * la.h - C ABI of the MI355X (gfx950) lookahead-decoding hot path.
+ *
+ * Lookahead Decoding (arXiv 2402.02057) evaluates, in ONE model forward per
+ * decoding step, the current input token, a W x (N-1) window of Jacobi
+ * lookahead tokens and G candidate n-grams against the prefix KV cache
+ * (Sec. 3, Sec. 3.3 "Decode, Predict, and Verify in The Same Step"), then
+ * verifies the candidates greedily (Sec. 3.2, Algorithm 3).  This library is
+ * the attention of that forward and the verification reduction.  The n-gram
+ * pool, the window update, projections, RoPE and the LM head are the
+ * caller's.
+ *
+ * Row order of one step (shared by q, step_k, step_v and out):
+ *   row 0                              current input token        position 0
+ *   row 1 + l*W + j                    lookahead level l in [0,N-2] (0 = oldest
+ *                                      kept Jacobi iterate), column j in [0,W-1]
+ *                                                                 position 1+l+j
+ *   row 1 + W*(N-1) + g*(N-1) + k      candidate g in [0,G-1], its k-th token
+ *                                      after the shared first one position 1+k
+ *   T = 1 + (W + G) * (N - 1) rows.
+ * "Position" is relative to the current token (the digits of Fig. 2(b)); the
+ * library does not use it, the caller's RoPE does.
+ *
+ * Visibility (Fig. 2(b), Sec. 3.3; conditioning sets of Algorithm 2):
+ *   - every row attends to all P prefix keys and to the current token;
+ *   - lookahead row (l, j) also attends to level-0 columns <= j and to its
+ *     own column at levels <= l (its Jacobi trajectory, itself included);
+ *   - candidate row (g, k) also attends to tokens <= k of candidate g;
+ *   - nothing else: the branches and distinct candidates are mutually
+ *     invisible.
+ * Compared with the figure, whose oldest level starts with the current token,
+ * the window here is a full W x (N-1) rectangle behind a separate current-token
+ * row (every position shifted by one); the trajectories are the same.
+ *
+ * All pointers are DEVICE pointers unless said otherwise.  The caller owns
+ * every buffer; nothing is retained after the call's work has run.  Calls are
+ * asynchronous on `stream` (a hipStream_t passed as void*, NULL = the default
+ * stream) and never synchronise the device.  The library keeps a small device
+ * workspace per device (split partials, tickets), grown on demand with
+ * hipMalloc - so the first call at a new size may allocate - and shared by
+ * all calls on that device: calls issued to one stream are ordered; calls on
+ * different streams of the same device must not overlap in time.
+ *
+ * Errors are returned, never thrown; on error nothing has been launched.
+ */
+#ifndef LA_H
+#define LA_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int la_status;
+#define LA_OK 0
+#define LA_EINVAL (-1)       /* null pointer, negative size, N < 2, misaligned buffer */
+#define LA_EUNSUPPORTED (-2) /* head_dim not 64 or 128, heads % kv_heads != 0, group too large */
+#define LA_ENOMEM (-3)       /* workspace allocation failed */
+#define LA_EHIP (-4)         /* a HIP call or the launch failed (see la_last_error) */
+
+/*
+ * Lookahead-step attention (Sec. 2 causal-attention definition with the mask
+ * of Sec. 3.3):  out[r][h] = sum_c softmax_c(q[r][h].k[c] / sqrt(head_dim)) v[c]
+ * over the P prefix keys of KV head h / (heads / kv_heads) and the step keys
+ * row r may see.  bf16 in, fp32 accumulation and softmax, bf16 out (round to
+ * nearest even).
+ *
+ *   q        bf16 [T][heads][head_dim]           16-byte aligned
+ *   k_cache  bf16 [kv_heads][P][head_dim]        16-byte aligned; may be NULL iff P == 0
+ *   v_cache  same shape as k_cache
+ *   step_k   bf16 [T][kv_heads][head_dim]        this step's keys, row order as q
+ *   step_v   same shape as step_k
+ *   out      bf16 [T][heads][head_dim]
+ *   P >= 0, W >= 0, G >= 0, N >= 2; head_dim in {64, 128}; heads % kv_heads == 0.
+ */
+la_status la_step_attention(const void* q, const void* k_cache, const void* v_cache,
+                            const void* step_k, const void* step_v, int P, int W, int N, int G,
+                            int heads, int kv_heads, int head_dim, void* out, void* stream);
+
+/*
+ * Greedy verification reduction (Sec. 2 "Guess-And-Verify": accept a draft
+ * token while it equals the model's greedy token, stop at the first mismatch;
+ * Algorithm 3 runs it over G candidates).
+ *
+ *   logits       fp32 [G][N-1][V]; row (g,k) is the model output that judges
+ *                cand_tokens[g][k]: k = 0 the output at the current token,
+ *                k >= 1 the output at candidate token k-1.  Values must not be NaN.
+ *   cand_tokens  int32 [G][N-1]
+ *   accept_len   int32 [G]       out: number of leading k with argmax == cand_tokens
+ *   accepted     int32 [G][N-1]  out: argmax of every row, lowest index on ties
+ *   G >= 0 (G == 0 is a no-op), N >= 2, V >= 1.
+ */
+la_status la_verify(const float* logits, const int* cand_tokens, int G, int N, int V,
+                    int* accept_len, int* accepted, void* stream);
+
+/* Bytes of device workspace la_step_attention needs for this shape (0 if none). */
+long long la_step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int kv_heads,
+                                            int head_dim);
+
+/* Free the per-device workspaces.  No call may be in flight.  Optional at exit. */
+void la_shutdown(void);
+
+/* Host string describing the most recent error on this thread ("" if none). */
+const char* la_last_error(void);
+
+/* Library version, major * 1000 + minor. */
+int la_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LA_H */

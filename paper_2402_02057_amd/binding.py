@@ -1,0 +1,136 @@
+"""Thin ctypes binding of the C-ABI HIP library (include/la.h): argument marshalling only.
+
+Every step of the hot path runs in the library's kernels.  There is no fallback: if the
+library has not been built (python -m paper_2402_02057_amd.buildlib, or
+__graft_entry__.build()) loading fails loudly.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libla_hip.so")
+
+LA_OK = 0
+_lib = None
+
+
+class LaError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__("la error %d: %s" % (code, message))
+        self.code = code
+
+
+def load():
+    """Open libla_hip.so (once).  Raises if it is missing: the HIP path is the only path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("HIP library %s is not built; run __graft_entry__.build()" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    i, p = ctypes.c_int, ctypes.c_void_p
+    lib.la_step_attention.argtypes = [p, p, p, p, p, i, i, i, i, i, i, i, p, p]
+    lib.la_step_attention.restype = i
+    lib.la_verify.argtypes = [p, p, i, i, i, p, p, p]
+    lib.la_verify.restype = i
+    lib.la_step_attention_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
+    lib.la_step_attention_workspace_bytes.restype = ctypes.c_longlong
+    lib.la_shutdown.argtypes = []
+    lib.la_shutdown.restype = None
+    lib.la_last_error.argtypes = []
+    lib.la_last_error.restype = ctypes.c_char_p
+    lib.la_version.argtypes = []
+    lib.la_version.restype = i
+    _lib = lib
+    return lib
+
+
+EXPORTS = ("la_step_attention", "la_verify", "la_step_attention_workspace_bytes", "la_shutdown",
+           "la_last_error", "la_version")
+
+
+def _check(rc):
+    if rc != LA_OK:
+        raise LaError(rc, load().la_last_error().decode())
+
+
+def _ptr(x, dtype, shape, name, allow_empty_null=False):
+    """Device pointer of a contiguous CUDA tensor of the expected dtype and shape."""
+    if x is None:
+        if allow_empty_null:
+            return None
+        raise ValueError("%s is None" % name)
+    if not isinstance(x, torch.Tensor):
+        raise TypeError("%s must be a torch.Tensor" % name)
+    if not x.is_cuda:
+        raise ValueError("%s must live on the GPU" % name)
+    if x.dtype != dtype:
+        raise ValueError("%s must be %s, got %s" % (name, dtype, x.dtype))
+    if tuple(x.shape) != tuple(shape):
+        raise ValueError("%s must have shape %s, got %s" % (name, tuple(shape), tuple(x.shape)))
+    if not x.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    return x.data_ptr() if x.numel() else None
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream
+    return int(stream)
+
+
+def la_step_attention(q, k_cache, v_cache, step_k, step_v, P, W, N, G, heads, kv_heads, head_dim,
+                      out, stream=None):
+    """out[T, heads, head_dim] (bf16) <- lookahead-step attention; asynchronous on `stream`."""
+    T = 1 + (W + G) * (N - 1)
+    bf = torch.bfloat16
+    rc = load().la_step_attention(
+        _ptr(q, bf, (T, heads, head_dim), "q"),
+        _ptr(k_cache, bf, (kv_heads, P, head_dim), "k_cache", allow_empty_null=True),
+        _ptr(v_cache, bf, (kv_heads, P, head_dim), "v_cache", allow_empty_null=True),
+        _ptr(step_k, bf, (T, kv_heads, head_dim), "step_k"),
+        _ptr(step_v, bf, (T, kv_heads, head_dim), "step_v"),
+        P, W, N, G, heads, kv_heads, head_dim,
+        _ptr(out, bf, (T, heads, head_dim), "out"), _stream(stream))
+    _check(rc)
+    return out
+
+
+def la_verify(logits, cand_tokens, G, N, V, accept_len, accepted, stream=None):
+    """accept_len[G], accepted[G, N-1] (int32) <- greedy verification; asynchronous."""
+    rc = load().la_verify(
+        _ptr(logits, torch.float32, (G, N - 1, V), "logits"),
+        _ptr(cand_tokens, torch.int32, (G, N - 1), "cand_tokens"), G, N, V,
+        _ptr(accept_len, torch.int32, (G,), "accept_len"),
+        _ptr(accepted, torch.int32, (G, N - 1), "accepted"), _stream(stream))
+    _check(rc)
+    return accept_len, accepted
+
+
+def la_step_attention_workspace_bytes(P, W, N, G, heads, kv_heads, head_dim):
+    return int(load().la_step_attention_workspace_bytes(P, W, N, G, heads, kv_heads, head_dim))
+
+
+def la_shutdown():
+    load().la_shutdown()
+
+
+def la_version():
+    return int(load().la_version())
+
+
+def bf16_tensor(bits, device="cuda"):
+    """numpy uint16 bit patterns -> bf16 tensor on the device (no value conversion)."""
+    import numpy as np
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16).copy())
+    return t.view(torch.bfloat16).to(device)
+
+
+def bf16_bits(t):
+    """bf16 tensor -> numpy uint16 bit patterns on the host."""
+    import numpy as np
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)

@@ -1,0 +1,173 @@
+// C-ABI entry points of the lookahead-decoding hot path (declared in include/la.h):
+// argument validation, error reporting and the per-device workspaces.  The kernels
+// live in la_attention.hip and la_verify.hip.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include <mutex>
+
+#include "la_internal.h"
+
+namespace la {
+
+static thread_local char g_error[512] = "";
+
+la_status fail(la_status code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof g_error, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+namespace {
+constexpr int kMaxDevices = 16;
+struct Pool {
+    void* zeroed = nullptr;
+    size_t zeroed_bytes = 0;
+    void* scratch = nullptr;
+    size_t scratch_bytes = 0;
+};
+Pool g_pools[kMaxDevices];
+std::mutex g_mutex;
+
+Pool* current_pool()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        fail(LA_EHIP, "hipGetDevice failed or device index out of range");
+        return nullptr;
+    }
+    return &g_pools[dev];
+}
+}  // namespace
+
+void* zeroed_workspace(size_t bytes, hipStream_t stream)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    Pool* p = current_pool();
+    if (!p) return nullptr;
+    if (bytes <= p->zeroed_bytes) return p->zeroed;
+    // Growing: earlier work that still uses the old block has been issued to a stream; wait
+    // for the device to drain before freeing it.  This happens only when a larger shape
+    // than any before is seen.
+    size_t want = bytes < (1u << 16) ? (1u << 16) : bytes;
+    void* fresh = nullptr;
+    if (hipMalloc(&fresh, want) != hipSuccess) {
+        fail(LA_ENOMEM, "hipMalloc of %zu bytes of ticket workspace failed", want);
+        return nullptr;
+    }
+    if (hipMemsetAsync(fresh, 0, want, stream) != hipSuccess) {
+        (void)hipFree(fresh);
+        fail(LA_EHIP, "hipMemsetAsync on the ticket workspace failed");
+        return nullptr;
+    }
+    if (p->zeroed) {
+        (void)hipDeviceSynchronize();
+        (void)hipFree(p->zeroed);
+    }
+    p->zeroed = fresh;
+    p->zeroed_bytes = want;
+    return fresh;
+}
+
+void* scratch_workspace(size_t bytes)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    Pool* p = current_pool();
+    if (!p) return nullptr;
+    if (bytes <= p->scratch_bytes) return p->scratch;
+    size_t want = bytes < (size_t(8) << 20) ? (size_t(8) << 20) : bytes + bytes / 4;
+    void* fresh = nullptr;
+    if (hipMalloc(&fresh, want) != hipSuccess) {
+        fail(LA_ENOMEM, "hipMalloc of %zu bytes of partial-result workspace failed", want);
+        return nullptr;
+    }
+    if (p->scratch) {
+        (void)hipDeviceSynchronize();
+        (void)hipFree(p->scratch);
+    }
+    p->scratch = fresh;
+    p->scratch_bytes = want;
+    return fresh;
+}
+
+void free_workspaces()
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    int saved = 0;
+    (void)hipGetDevice(&saved);
+    for (int d = 0; d < kMaxDevices; ++d) {
+        Pool& p = g_pools[d];
+        if (!p.zeroed && !p.scratch) continue;
+        if (hipSetDevice(d) != hipSuccess) continue;
+        (void)hipDeviceSynchronize();
+        if (p.zeroed) (void)hipFree(p.zeroed);
+        if (p.scratch) (void)hipFree(p.scratch);
+        p = Pool();
+    }
+    (void)hipSetDevice(saved);
+}
+
+}  // namespace la
+
+extern "C" {
+
+la_status la_step_attention(const void* q, const void* k_cache, const void* v_cache,
+                            const void* step_k, const void* step_v, int P, int W, int N, int G,
+                            int heads, int kv_heads, int head_dim, void* out, void* stream)
+{
+    if (P < 0 || W < 0 || G < 0 || N < 2 || heads < 1 || kv_heads < 1)
+        return la::fail(LA_EINVAL, "la_step_attention: need P,W,G >= 0, N >= 2, heads,kv_heads >= 1 "
+                                   "(got P=%d W=%d N=%d G=%d heads=%d kv_heads=%d)",
+                        P, W, N, G, heads, kv_heads);
+    if (head_dim != 64 && head_dim != 128)
+        return la::fail(LA_EUNSUPPORTED, "la_step_attention: head_dim %d is not 64 or 128", head_dim);
+    if (heads % kv_heads != 0)
+        return la::fail(LA_EUNSUPPORTED, "la_step_attention: heads %d not a multiple of kv_heads %d",
+                        heads, kv_heads);
+    const long long T = 1 + (long long)(W + G) * (N - 1);
+    if (T > (1 << 20) || (long long)P > (1ll << 30))
+        return la::fail(LA_EINVAL, "la_step_attention: step of %lld rows / prefix %d too large", T, P);
+    if (!q || !step_k || !step_v || !out || (P > 0 && (!k_cache || !v_cache)))
+        return la::fail(LA_EINVAL, "la_step_attention: null pointer");
+    const uintptr_t bits = (uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache |
+                           (uintptr_t)step_k | (uintptr_t)step_v | (uintptr_t)out;
+    if (bits & 15) return la::fail(LA_EINVAL, "la_step_attention: buffers must be 16-byte aligned");
+    return la::launch_step_attention(q, k_cache, v_cache, step_k, step_v, P, W, N, G, heads,
+                                     kv_heads, head_dim, out, (hipStream_t)stream);
+}
+
+la_status la_verify(const float* logits, const int* cand_tokens, int G, int N, int V,
+                    int* accept_len, int* accepted, void* stream)
+{
+    if (G < 0 || N < 2 || V < 1)
+        return la::fail(LA_EINVAL, "la_verify: need G >= 0, N >= 2, V >= 1 (got G=%d N=%d V=%d)", G,
+                        N, V);
+    if (G == 0) return LA_OK;
+    if ((long long)G * (N - 1) > (1 << 20))
+        return la::fail(LA_EINVAL, "la_verify: %lld rows is too many", (long long)G * (N - 1));
+    if (!logits || !cand_tokens || !accept_len || !accepted)
+        return la::fail(LA_EINVAL, "la_verify: null pointer");
+    if (((uintptr_t)logits | (uintptr_t)cand_tokens | (uintptr_t)accept_len | (uintptr_t)accepted) & 3)
+        return la::fail(LA_EINVAL, "la_verify: buffers must be 4-byte aligned");
+    return la::launch_verify(logits, cand_tokens, G, N, V, accept_len, accepted, (hipStream_t)stream);
+}
+
+long long la_step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int kv_heads,
+                                            int head_dim)
+{
+    if (P < 0 || W < 0 || G < 0 || N < 2 || heads < 1 || kv_heads < 1 || heads % kv_heads != 0 ||
+        (head_dim != 64 && head_dim != 128))
+        return 0;
+    return (long long)la::step_attention_workspace_bytes(P, W, N, G, heads, kv_heads, head_dim);
+}
+
+void la_shutdown(void) { la::free_workspaces(); }
+
+const char* la_last_error(void) { return la::g_error; }
+
+int la_version(void) { return 1000; }
+
+}  // extern "C"

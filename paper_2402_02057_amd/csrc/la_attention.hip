@@ -1,0 +1,668 @@
+// Lookahead-step attention for gfx950 (Sec. 2 causal attention under the mask of Sec. 3.3,
+// Fig. 2(b)): the current token, the W x (N-1) lookahead window and G candidate n-grams
+// attend to the prefix KV cache and to each other in one pass.
+//
+// Shape of the problem.  The T = 1 + (W+G)(N-1) step rows of the g = heads/kv_heads query
+// heads that share one KV head form R = T*g query rows over the same P + T keys, so QK^T and
+// PV are dense [R x d] x [d x keys] contractions: they run on the matrix cores
+// (v_mfma_f32_32x32x16_bf16, fp32 accumulate) while K and V stream from HBM exactly once per
+// row block.
+//
+// Decomposition.  A workgroup owns (KV head, block of RT*RW 32-row tiles, one of XS ranges of
+// 64-key chunks).  Chunks are copied HBM -> LDS by direct-to-LDS loads into a ring of stages;
+// the 16-byte pieces of a row are stored XOR-swizzled so that both the K operand reads
+// (ds_read_b128, one key per lane) and the transposing V reads (ds_read_b64_tr_b16) are free
+// of bank conflicts.  Within a workgroup, KS waves share a row tile and take alternate 32-key
+// blocks of each chunk; they are merged through LDS at the end.
+//
+// Per 32-key block a wave computes S^T = K Q^T (keys x rows), so that every lane holds 16
+// scores of ONE query row: the row maximum and sum are in-register reductions plus one
+// cross-lane step, and the exponentiated scores, converted to bf16, already have the layout
+// of the B operand of O^T += V^T P^T - no LDS round trip for P.
+//
+// Mask.  Prefix keys are visible to every row.  For step keys the visible set of row t is
+//   {0} u [0, 1+j] u {t - k*W : k = 0..l}      lookahead (l, j)
+//   {0} u [t - k, t]                            candidate token k
+// (Algorithm 2's conditioning sets read as index ranges), turned into one 32-bit word per
+// (row, key block) from integer ranges in registers; no mask tensor exists anywhere.
+//
+// Split combine.  With XS > 1 each workgroup stores its unnormalised fp32 accumulator and
+// (max, sum) per row, takes a ticket, and the workgroup that arrives last merges all XS
+// partials in index order (so results do not depend on arrival order), normalises and
+// writes bf16.  Tickets return to zero, so no memset is needed between calls.
+#include <stdlib.h>
+
+#include "la_internal.h"
+
+namespace la {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float kNegInf = -__builtin_huge_valf();
+
+struct AttnParams {
+    const __bf16* q;
+    const __bf16* k_cache;
+    const __bf16* v_cache;
+    const __bf16* step_k;
+    const __bf16* step_v;
+    __bf16* out;
+    float* partials;    // XS > 1: per workgroup, fragment-layout accumulators and (m, l)
+    unsigned* tickets;  // XS > 1: one counter per (KV head, row block), zero between calls
+    int P, W, N, G, T;
+    int heads, kv_heads, group;
+    int R;                // T * group query rows per KV head
+    int n_prefix_chunks;  // ceil(P / KC)
+    int n_chunks;         // prefix chunks + step chunks
+    int n_row_blocks;
+    int XS;
+    int total_wg;         // kv_heads * n_row_blocks * XS
+    int wg_per_xcd;       // ceil(total_wg / 8)
+    float scale_log2;     // log2(e) / sqrt(head_dim)
+};
+
+// Which step keys a step row may see, as index ranges (see the header comment).
+struct RowVis {
+    int t;      // step index of the row
+    int e0;     // keys 0..e0 are visible
+    int s1;     // keys t, t-s1, t-2*s1, ... (cnt of them) are visible
+    int cnt;
+};
+
+__device__ __forceinline__ RowVis row_visibility(int t, int W, int N)
+{
+    RowVis v;
+    v.t = t;
+    const int n_look = W * (N - 1);
+    if (t == 0) {
+        v.e0 = 0; v.s1 = 1; v.cnt = 1;
+    } else if (t <= n_look) {
+        const int x = t - 1;
+        const int l = x / W, j = x - l * W;
+        v.e0 = 1 + j; v.s1 = W; v.cnt = l + 1;
+    } else {
+        const int x = t - 1 - n_look;
+        const int k = x % (N - 1);
+        v.e0 = 0; v.s1 = 1; v.cnt = k + 1;
+    }
+    return v;
+}
+
+// Bit b set iff step key (key0 + b) is visible to the row.
+__device__ __forceinline__ unsigned step_block_word(const RowVis& v, int key0)
+{
+    unsigned w = 0;
+    const int n0 = v.e0 - key0 + 1;  // keys key0 .. e0
+    if (n0 > 0) w = n0 >= 32 ? 0xFFFFFFFFu : ((1u << n0) - 1u);
+    int c = v.t;
+    for (int k = 0; k < v.cnt; ++k, c -= v.s1) {
+        const unsigned d = (unsigned)(c - key0);
+        if (d < 32u) w |= 1u << d;
+    }
+    return w;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// 16-byte piece `lc` of row `row` lives at piece position lc ^ swizzle(row) of that row.
+template <int D>
+__device__ __forceinline__ int swizzle(int row)
+{
+    if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+    return (row >> 1) & 7;
+}
+
+template <int D, int RW, int RT, int KS, int KC, int NSTAGE>
+struct Cfg {
+    static constexpr int NW = RT * KS;
+    static constexpr int NT = NW * 64;
+    static constexpr int RBYTES = D * 2;
+    static constexpr int NCH = D / 8;                     // 16-byte pieces per row
+    static constexpr int KB = KC / 32;                    // 32-key blocks per chunk
+    static constexpr int KBW = KB / KS;                   // blocks per wave per chunk
+    static constexpr int KV_BYTES = KC * RBYTES;          // one of K or V of a chunk
+    static constexpr int STAGE_BYTES = 2 * KV_BYTES;
+    static constexpr int WLOADS = STAGE_BYTES / 1024;     // 64-lane x 16-byte loads per chunk
+    static constexpr int LPW = WLOADS / NW;               // loads per wave per chunk
+    static constexpr int TILES = RT * RW;                 // 32-row tiles per workgroup
+    static constexpr int ROWS = TILES * 32;
+    static constexpr int DB = D / 32;                     // 32-wide blocks of head_dim
+    static constexpr int FRAG_FLOATS = DB * 16 * 64;      // one tile's accumulators
+    static constexpr int TILE_FLOATS = FRAG_FLOATS + 128; // + m and l per lane
+    static constexpr int OUT_PITCH = RBYTES + 16;         // LDS pitch of the output transpose
+    static constexpr int LDS_MAIN = NSTAGE * STAGE_BYTES;
+    static constexpr int LDS_MERGE = (KS - 1) * RT * RW * TILE_FLOATS * 4;
+    static constexpr int LDS_OUT = ROWS * OUT_PITCH;
+    static constexpr int LDS_BYTES =
+        LDS_MAIN > LDS_MERGE ? (LDS_MAIN > LDS_OUT ? LDS_MAIN : LDS_OUT)
+                             : (LDS_MERGE > LDS_OUT ? LDS_MERGE : LDS_OUT);
+    static_assert(KB % KS == 0, "key blocks of a chunk must divide among the key-split waves");
+    static_assert(WLOADS % NW == 0, "chunk loads must divide among the waves");
+    static_assert(LPW * (NSTAGE - 1) < 64, "vmcnt is a 6-bit counter");
+};
+
+template <int D, int RW, int RT, int KS, int KC, int NSTAGE>
+__global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnParams p)
+{
+    using C = Cfg<D, RW, RT, KS, KC, NSTAGE>;
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+
+    // Consecutive workgroup ids go round-robin over the 8 XCDs (each with its own L2); put
+    // the workgroups that stream the same KV head on one XCD.
+    const int logical = (int)(blockIdx.x & 7) * p.wg_per_xcd + (int)(blockIdx.x >> 3);
+    if (logical >= p.total_wg) return;
+    const int xs = logical % p.XS;
+    const int rb = (logical / p.XS) % p.n_row_blocks;
+    const int kvh = logical / (p.XS * p.n_row_blocks);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rt = wave / KS;   // row tile group of this wave
+    const int ks = wave % KS;   // which key blocks of a chunk it takes
+    const int hi = lane >> 5;   // upper half-wave
+    const int l32 = lane & 31;
+
+    const int row_base = rb * C::ROWS + rt * (RW * 32);  // first row of this wave (in R space)
+    const bool wave_active = row_base < p.R;            // else: only helps loading
+
+    // ---- Q as the B operand of S^T = K Q^T: lane holds row l32, d = ks16*16 + hi*8 .. +8
+    bf16x8 qreg[RW][D / 16];
+    RowVis vis[RW];
+#pragma unroll
+    for (int rw = 0; rw < RW; ++rw) {
+        const int rr = row_base + rw * 32 + l32;
+        const bool ok = rr < p.R;
+        const int t = ok ? rr / p.group : 0;
+        const int hh = ok ? rr - t * p.group : 0;
+        vis[rw] = row_visibility(t, p.W, p.N);
+        const __bf16* src = p.q + ((size_t)t * p.heads + (size_t)kvh * p.group + hh) * D + hi * 8;
+#pragma unroll
+        for (int k16 = 0; k16 < D / 16; ++k16) {
+            bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (ok) v = *reinterpret_cast<const bf16x8*>(src + k16 * 16);
+            qreg[rw][k16] = v;
+        }
+    }
+
+    f32x16 o[RW][C::DB];
+    float m_run[RW], l_run[RW];
+#pragma unroll
+    for (int rw = 0; rw < RW; ++rw) {
+        m_run[rw] = kNegInf;
+        l_run[rw] = 0.0f;
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o[rw][db][i] = 0.0f;
+    }
+
+    // ---- chunk range of this split
+    const int c_begin = (int)(((long long)xs * p.n_chunks) / p.XS);
+    const int c_end = (int)(((long long)(xs + 1) * p.n_chunks) / p.XS);
+    const int n_my = c_end - c_begin;
+
+    // Issue the direct-to-LDS loads of chunk `c` into stage `st`.
+    auto issue_chunk = [&](int c, int st) {
+        const bool is_step = c >= p.n_prefix_chunks;
+        const int key0 = (is_step ? c - p.n_prefix_chunks : c) * KC;
+        const int limit = is_step ? p.T : p.P;
+        const int last_row = min(KC, limit - key0) - 1;  // >= 0
+        const size_t stride = is_step ? (size_t)p.kv_heads * D : (size_t)D;
+        const __bf16* kbase = is_step ? p.step_k + ((size_t)key0 * p.kv_heads + kvh) * D
+                                      : p.k_cache + ((size_t)kvh * p.P + key0) * D;
+        const __bf16* vbase = is_step ? p.step_v + ((size_t)key0 * p.kv_heads + kvh) * D
+                                      : p.v_cache + ((size_t)kvh * p.P + key0) * D;
+        unsigned char* stage = lds + st * C::STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < C::LPW; ++i) {
+            const int wl = wave + i * C::NW;                  // wave-load index in the chunk
+            const bool is_v = wl >= C::WLOADS / 2;
+            const int piece = (is_v ? wl - C::WLOADS / 2 : wl) * 64 + lane;
+            const int row = piece / C::NCH;
+            const int pc = piece % C::NCH;
+            const int lc = pc ^ swizzle<D>(row);
+            const int srow = min(row, last_row);              // rows past the end repeat the last
+            const __bf16* src = (is_v ? vbase : kbase) + (size_t)srow * stride + lc * 8;
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)src,
+                (__attribute__((address_space(3))) void*)(stage + wl * 1024), 16, 0, 0);
+        }
+    };
+
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; ++s)
+        if (s < n_my) issue_chunk(c_begin + s, s);
+
+    for (int it = 0; it < n_my; ++it) {
+        // wait for this wave's loads of chunk `it`; later chunks may stay in flight
+        const int later = min(n_my - 1 - it, NSTAGE - 2);
+        if (NSTAGE >= 3 && later >= 1) {
+            if (NSTAGE >= 4 && later >= 2) wait_vmcnt<2 * C::LPW>();
+            else wait_vmcnt<C::LPW>();
+        } else {
+            wait_vmcnt<0>();
+        }
+        __syncthreads();  // chunk `it` complete in LDS; everyone is done with chunk it-1
+        if (it + NSTAGE - 1 < n_my) issue_chunk(c_begin + it + NSTAGE - 1, (it + NSTAGE - 1) % NSTAGE);
+        if (!wave_active) continue;
+
+        const int c = c_begin + it;
+        const bool is_step = c >= p.n_prefix_chunks;
+        const int chunk_key0 = (is_step ? c - p.n_prefix_chunks : c) * KC;
+        const int limit = is_step ? p.T : p.P;
+        const unsigned char* kst = lds + (it % NSTAGE) * C::STAGE_BYTES;
+        const unsigned char* vst = kst + C::KV_BYTES;
+
+#pragma unroll
+        for (int kbw = 0; kbw < C::KBW; ++kbw) {
+            const int kb = ks + kbw * KS;
+            const int key0 = chunk_key0 + kb * 32;
+            if (key0 >= limit) continue;  // block entirely past the end (wave-uniform)
+
+            // ---- S^T block: 32 keys x 32 rows per tile
+            f32x16 s[RW];
+#pragma unroll
+            for (int rw = 0; rw < RW; ++rw)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s[rw][i] = 0.0f;
+            {
+                const int krow = kb * 32 + l32;
+                const unsigned char* kr = kst + krow * C::RBYTES;
+                const int sw = swizzle<D>(krow);
+#pragma unroll
+                for (int k16 = 0; k16 < D / 16; ++k16) {
+                    const bf16x8 kf =
+                        *reinterpret_cast<const bf16x8*>(kr + (((k16 * 2 + hi) ^ sw) << 4));
+#pragma unroll
+                    for (int rw = 0; rw < RW; ++rw)
+                        s[rw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qreg[rw][k16], s[rw], 0, 0, 0);
+                }
+            }
+
+            // ---- mask, running max, exponentials
+            const bool full = !is_step && (key0 + 32 <= limit);  // wave-uniform
+            bf16x8 pf[RW][2];
+#pragma unroll
+            for (int rw = 0; rw < RW; ++rw) {
+                if (!full) {
+                    unsigned word;
+                    if (is_step) {
+                        word = step_block_word(vis[rw], key0);
+                    } else {
+                        const int n = limit - key0;  // 1..31
+                        word = (1u << n) - 1u;
+                    }
+                    word >>= hi * 4;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int bit = (i >> 2) * 8 + (i & 3);  // + hi*4 already shifted out
+                        if (!((word >> bit) & 1u)) s[rw][i] = kNegInf;
+                    }
+                }
+                float mx = s[rw][0];
+#pragma unroll
+                for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[rw][i]);
+                mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                const float m_new = fmaxf(m_run[rw], mx);
+                // scores are kept unscaled; exp(x/sqrt(d)) = exp2(x * scale_log2)
+                const float m_use = (m_new == kNegInf) ? 0.0f : m_new;
+                const float alpha = fast_exp2((m_run[rw] - m_use) * p.scale_log2);
+                const float neg_mc = -m_use * p.scale_log2;
+                float psum = 0.0f;
+                float pv[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    pv[i] = fast_exp2(__builtin_fmaf(s[rw][i], p.scale_log2, neg_mc));
+                    psum += pv[i];
+                }
+                l_run[rw] = l_run[rw] * alpha + psum;
+                m_run[rw] = m_new;
+                if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0ull) {
+#pragma unroll
+                    for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) o[rw][db][i] *= alpha;
+                }
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) pf[rw][kk][e] = (__bf16)pv[kk * 8 + e];
+            }
+
+            // ---- O^T += V^T P^T.  k-slot e of half `hi` of 16-key step kk is key
+            //      kb*32 + kk*16 + (e/4)*8 + hi*4 + e%4 (the layout S^T left P in).
+            {
+                const int b16 = lane >> 4;      // 16-lane block: reads 4 keys x 16 columns
+                const int i16 = lane & 15;
+                const int jj = i16 >> 2;        // key within the group of 4
+                const int q4 = i16 & 3;         // 4-column segment
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk) {
+                    const int vrow0 = kb * 32 + kk * 16 + hi * 4 + jj;  // e = 0..3
+                    const int vrow1 = vrow0 + 8;                        // e = 4..7
+                    const int sw0 = swizzle<D>(vrow0), sw1 = swizzle<D>(vrow1);
+#pragma unroll
+                    for (int db = 0; db < C::DB; ++db) {
+                        const int col = db * 32 + (b16 & 1) * 16 + q4 * 4;
+                        const int lc = col >> 3, within = (col & 7) * 2;
+                        const unsigned char* a0 = vst + vrow0 * C::RBYTES + ((lc ^ sw0) << 4) + within;
+                        const unsigned char* a1 = vst + vrow1 * C::RBYTES + ((lc ^ sw1) << 4) + within;
+                        const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (short4v __attribute__((address_space(3)))*)a0);
+                        const short4v hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (short4v __attribute__((address_space(3)))*)a1);
+                        union { struct { short4v a, b; } s; bf16x8 v; } u;
+                        u.s.a = lo; u.s.b = hi4;
+#pragma unroll
+                        for (int rw = 0; rw < RW; ++rw)
+                            o[rw][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf[rw][kk], o[rw][db], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+
+    // the two half-waves of a row hold the sums over their own keys
+#pragma unroll
+    for (int rw = 0; rw < RW; ++rw) l_run[rw] += __shfl_xor(l_run[rw], 32, 64);
+
+    __syncthreads();  // all stages consumed: LDS is reused below
+
+    // ---- merge the KS waves of a row tile through LDS (fragment layout: [reg][lane])
+    if (KS > 1) {
+        float* mg = reinterpret_cast<float*>(lds);
+        if (ks > 0 && wave_active) {
+#pragma unroll
+            for (int rw = 0; rw < RW; ++rw) {
+                float* dst = mg + (((ks - 1) * RT + rt) * RW + rw) * C::TILE_FLOATS;
+#pragma unroll
+                for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) dst[(db * 16 + i) * 64 + lane] = o[rw][db][i];
+                dst[C::FRAG_FLOATS + lane] = m_run[rw];
+                dst[C::FRAG_FLOATS + 64 + lane] = l_run[rw];
+            }
+        }
+        __syncthreads();
+        if (ks == 0 && wave_active) {
+            for (int k2 = 1; k2 < KS; ++k2) {
+#pragma unroll
+                for (int rw = 0; rw < RW; ++rw) {
+                    const float* src = mg + (((k2 - 1) * RT + rt) * RW + rw) * C::TILE_FLOATS;
+                    const float m2 = src[C::FRAG_FLOATS + lane];
+                    const float l2 = src[C::FRAG_FLOATS + 64 + lane];
+                    const float m_new = fmaxf(m_run[rw], m2);
+                    const float m_use = (m_new == kNegInf) ? 0.0f : m_new;
+                    const float a1 = fast_exp2((m_run[rw] - m_use) * p.scale_log2);
+                    const float a2 = fast_exp2((m2 - m_use) * p.scale_log2);
+                    l_run[rw] = l_run[rw] * a1 + l2 * a2;
+                    m_run[rw] = m_new;
+#pragma unroll
+                    for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i)
+                            o[rw][db][i] = o[rw][db][i] * a1 + src[(db * 16 + i) * 64 + lane] * a2;
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- cross-workgroup combine (XS > 1): store partial, ticket, last arriver merges all
+    bool writer = (ks == 0) && wave_active;
+    if (p.XS > 1) {
+        const size_t wg_floats = (size_t)C::TILES * C::TILE_FLOATS;
+        float* group_base = p.partials + (size_t)((kvh * p.n_row_blocks + rb) * p.XS) * wg_floats;
+        if (writer) {
+#pragma unroll
+            for (int rw = 0; rw < RW; ++rw) {
+                float* dst = group_base + (size_t)xs * wg_floats + (size_t)(rt * RW + rw) * C::TILE_FLOATS;
+#pragma unroll
+                for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                    for (int i4 = 0; i4 < 4; ++i4) {
+                        f32x4 v = {o[rw][db][i4 * 4], o[rw][db][i4 * 4 + 1], o[rw][db][i4 * 4 + 2],
+                                   o[rw][db][i4 * 4 + 3]};
+                        *reinterpret_cast<f32x4*>(dst + ((db * 4 + i4) * 64 + lane) * 4) = v;
+                    }
+                dst[C::FRAG_FLOATS + lane] = m_run[rw];
+                dst[C::FRAG_FLOATS + 64 + lane] = l_run[rw];
+            }
+        }
+        __threadfence();
+        __syncthreads();
+        __shared__ unsigned is_last;
+        if (tid == 0) {
+            unsigned* ticket = p.tickets + (kvh * p.n_row_blocks + rb);
+            const unsigned t = atomicAdd(ticket, 1u);
+            is_last = (t == (unsigned)p.XS - 1u) ? 1u : 0u;
+            if (is_last) *ticket = 0u;  // everyone has arrived; clean for the next call
+        }
+        __syncthreads();
+        if (!is_last) return;
+        __threadfence();
+        if (writer) {
+#pragma unroll
+            for (int rw = 0; rw < RW; ++rw) {
+                m_run[rw] = kNegInf;
+                l_run[rw] = 0.0f;
+#pragma unroll
+                for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) o[rw][db][i] = 0.0f;
+            }
+            for (int s2 = 0; s2 < p.XS; ++s2) {
+#pragma unroll
+                for (int rw = 0; rw < RW; ++rw) {
+                    const float* src = group_base + (size_t)s2 * wg_floats + (size_t)(rt * RW + rw) * C::TILE_FLOATS;
+                    const float m2 = __builtin_nontemporal_load(src + C::FRAG_FLOATS + lane);
+                    const float l2 = __builtin_nontemporal_load(src + C::FRAG_FLOATS + 64 + lane);
+                    const float m_new = fmaxf(m_run[rw], m2);
+                    const float m_use = (m_new == kNegInf) ? 0.0f : m_new;
+                    const float a1 = fast_exp2((m_run[rw] - m_use) * p.scale_log2);
+                    const float a2 = fast_exp2((m2 - m_use) * p.scale_log2);
+                    l_run[rw] = l_run[rw] * a1 + l2 * a2;
+                    m_run[rw] = m_new;
+#pragma unroll
+                    for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                        for (int i4 = 0; i4 < 4; ++i4) {
+                            const f32x4 v = __builtin_nontemporal_load(
+                                reinterpret_cast<const f32x4*>(src + ((db * 4 + i4) * 64 + lane) * 4));
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                o[rw][db][i4 * 4 + e] = o[rw][db][i4 * 4 + e] * a1 + v[e] * a2;
+                        }
+                }
+            }
+        }
+    }
+
+    // ---- normalise, transpose through LDS, write bf16 rows with 16-byte stores
+    if (writer) {
+#pragma unroll
+        for (int rw = 0; rw < RW; ++rw) {
+            const float inv = 1.0f / l_run[rw];  // >= 1 visible key per row, so l > 0
+            unsigned char* row_ptr = lds + ((rt * RW + rw) * 32 + l32) * C::OUT_PITCH;
+#pragma unroll
+            for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    bf16x4 v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = (__bf16)(o[rw][db][i4 * 4 + e] * inv);
+                    const int dcol = db * 32 + i4 * 8 + hi * 4;
+                    *reinterpret_cast<bf16x4*>(row_ptr + dcol * 2) = v;
+                }
+        }
+    }
+    __syncthreads();
+    {
+        const int rows_here = min(C::ROWS, p.R - rb * C::ROWS);
+        for (int piece = tid; piece < rows_here * C::NCH; piece += C::NT) {
+            const int r = piece / C::NCH, ch = piece % C::NCH;
+            const int rr = rb * C::ROWS + r;
+            const int t = rr / p.group, hh = rr - t * p.group;
+            const f32x4 v = *reinterpret_cast<const f32x4*>(lds + r * C::OUT_PITCH + ch * 16);
+            *reinterpret_cast<f32x4*>(p.out + ((size_t)t * p.heads + (size_t)kvh * p.group + hh) * D + ch * 8) = v;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// host side
+
+struct Plan {
+    int RW, RT, KS, XS;
+    int n_row_blocks;
+    int n_prefix_chunks, n_chunks;
+    size_t partial_floats_per_wg;
+};
+
+constexpr int kKC = 64;
+
+bool plan_supported(int D, int RW, int RT, int KS)
+{
+    if (D == 128)
+        return (RW == 1 && ((RT == 1 && KS == 2) || (RT == 2 && KS == 2) || (RT == 4 && KS == 1) ||
+                            (RT == 2 && KS == 1))) ||
+               (RW == 2 && ((RT == 2 && KS == 2) || (RT == 4 && KS == 1)));
+    return RW == 1 && ((RT == 1 && KS == 2) || (RT == 2 && KS == 2) || (RT == 4 && KS == 1));
+}
+
+Plan make_plan(int P, int T, int group, int kv_heads, int D)
+{
+    Plan pl;
+    const int R = T * group;
+    const int tiles = (R + 31) / 32;
+    pl.n_prefix_chunks = (P + kKC - 1) / kKC;
+    pl.n_chunks = pl.n_prefix_chunks + (T + kKC - 1) / kKC;
+    if (tiles <= 1) { pl.RW = 1; pl.RT = 1; pl.KS = 2; }
+    else if (tiles <= 4 || D != 128) { pl.RW = 1; pl.RT = 2; pl.KS = 2; }
+    else if (tiles <= 8) { pl.RW = 1; pl.RT = 4; pl.KS = 1; }
+    else { pl.RW = 2; pl.RT = 4; pl.KS = 1; }
+    pl.XS = 0;
+    // developer override: LA_ATTN_PLAN="RW,RT,KS,XS" (XS = 0 keeps the heuristic)
+    if (const char* env = getenv("LA_ATTN_PLAN")) {
+        int a = 0, b = 0, c = 0, d = 0;
+        if (sscanf(env, "%d,%d,%d,%d", &a, &b, &c, &d) == 4 && plan_supported(D, a, b, c)) {
+            pl.RW = a; pl.RT = b; pl.KS = c; pl.XS = d;
+        }
+    }
+    const int rows_wg = pl.RT * pl.RW * 32;
+    pl.n_row_blocks = (R + rows_wg - 1) / rows_wg;
+    if (pl.XS <= 0) {
+        // about one workgroup per compute unit, at least two chunks per workgroup
+        const int units = kv_heads * pl.n_row_blocks;
+        int xs = (256 + units - 1) / units;
+        if (xs > pl.n_chunks / 2) xs = pl.n_chunks / 2;
+        pl.XS = xs < 1 ? 1 : xs;
+    }
+    if (pl.XS > pl.n_chunks) pl.XS = pl.n_chunks;
+    if (pl.XS > 64) pl.XS = 64;
+    pl.partial_floats_per_wg = (size_t)pl.RT * pl.RW * ((size_t)(D / 32) * 16 * 64 + 128);
+    return pl;
+}
+
+template <int D, int RW, int RT, int KS>
+la_status launch_cfg(const AttnParams& prm, hipStream_t stream)
+{
+    constexpr int NSTAGE = 2;
+    using C = Cfg<D, RW, RT, KS, kKC, NSTAGE>;
+    auto kern = step_attention_kernel<D, RW, RT, KS, kKC, NSTAGE>;
+    static bool attr_set[16] = {false};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return fail(LA_EHIP, "hipGetDevice failed");
+    if (!attr_set[dev]) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+        if (e != hipSuccess) return fail(LA_EHIP, "hipFuncSetAttribute(%d bytes LDS): %s", C::LDS_BYTES, hipGetErrorString(e));
+        attr_set[dev] = true;
+    }
+    const unsigned grid = (unsigned)prm.wg_per_xcd * 8u;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), C::LDS_BYTES, stream, prm);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(LA_EHIP, "la_step_attention launch: %s", hipGetErrorString(e));
+    return LA_OK;
+}
+
+}  // namespace
+
+size_t step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int kv_heads, int head_dim)
+{
+    const int T = 1 + (W + G) * (N - 1);
+    const Plan pl = make_plan(P, T, heads / kv_heads, kv_heads, head_dim);
+    if (pl.XS <= 1) return 0;
+    return (size_t)kv_heads * pl.n_row_blocks * pl.XS * pl.partial_floats_per_wg * sizeof(float);
+}
+
+la_status launch_step_attention(const void* q, const void* k_cache, const void* v_cache,
+                                const void* step_k, const void* step_v, int P, int W, int N, int G,
+                                int heads, int kv_heads, int head_dim, void* out, hipStream_t stream)
+{
+    const int T = 1 + (W + G) * (N - 1);
+    const int group = heads / kv_heads;
+    if ((long long)T * group > (1 << 24)) return fail(LA_EUNSUPPORTED, "la_step_attention: too many rows per KV head");
+    const Plan pl = make_plan(P, T, group, kv_heads, head_dim);
+
+    AttnParams prm;
+    prm.q = (const __bf16*)q;
+    prm.k_cache = (const __bf16*)k_cache;
+    prm.v_cache = (const __bf16*)v_cache;
+    prm.step_k = (const __bf16*)step_k;
+    prm.step_v = (const __bf16*)step_v;
+    prm.out = (__bf16*)out;
+    prm.partials = nullptr;
+    prm.tickets = nullptr;
+    prm.P = P; prm.W = W; prm.N = N; prm.G = G; prm.T = T;
+    prm.heads = heads; prm.kv_heads = kv_heads; prm.group = group;
+    prm.R = T * group;
+    prm.n_prefix_chunks = pl.n_prefix_chunks;
+    prm.n_chunks = pl.n_chunks;
+    prm.n_row_blocks = pl.n_row_blocks;
+    prm.XS = pl.XS;
+    const long long total = (long long)kv_heads * pl.n_row_blocks * pl.XS;
+    if (total > (1 << 28)) return fail(LA_EUNSUPPORTED, "la_step_attention: too many workgroups");
+    prm.total_wg = (int)total;
+    prm.wg_per_xcd = (int)((total + 7) / 8);
+    prm.scale_log2 = 1.4426950408889634f / sqrtf((float)head_dim);
+
+    if (pl.XS > 1) {
+        const size_t ticket_bytes = (size_t)kv_heads * pl.n_row_blocks * sizeof(unsigned);
+        prm.tickets = (unsigned*)zeroed_workspace(ticket_bytes, stream);
+        if (!prm.tickets) return LA_ENOMEM;
+        const size_t bytes = (size_t)total * pl.partial_floats_per_wg * sizeof(float);
+        prm.partials = (float*)scratch_workspace(bytes);
+        if (!prm.partials) return LA_ENOMEM;
+    }
+
+#define LA_DISPATCH(D_, RW_, RT_, KS_)                                              \
+    if (head_dim == D_ && pl.RW == RW_ && pl.RT == RT_ && pl.KS == KS_)             \
+        return launch_cfg<D_, RW_, RT_, KS_>(prm, stream);
+    LA_DISPATCH(128, 1, 1, 2)
+    LA_DISPATCH(128, 1, 2, 2)
+    LA_DISPATCH(128, 1, 2, 1)
+    LA_DISPATCH(128, 1, 4, 1)
+    LA_DISPATCH(128, 2, 2, 2)
+    LA_DISPATCH(128, 2, 4, 1)
+    LA_DISPATCH(64, 1, 1, 2)
+    LA_DISPATCH(64, 1, 2, 2)
+    LA_DISPATCH(64, 1, 4, 1)
+#undef LA_DISPATCH
+    return fail(LA_EUNSUPPORTED, "la_step_attention: no kernel for head_dim=%d plan (%d,%d,%d)",
+                head_dim, pl.RW, pl.RT, pl.KS);
+}
+
+}  // namespace la

@@ -1,0 +1,32 @@
+// Internal declarations shared by the translation units of the HIP library.
+// Nothing here is part of the C ABI (include/la.h is).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "la.h"
+
+namespace la {
+
+// Record a message for la_last_error() and hand back `code`.
+la_status fail(la_status code, const char* fmt, ...);
+
+// Per-device scratch memory.  `bytes` of zero-initialised device memory that every kernel
+// leaves zeroed again (tickets, packed argmax keys), and `bytes` of uninitialised memory
+// (split partials).  Grown on demand; returns nullptr (and records the error) on failure.
+void* zeroed_workspace(size_t bytes, hipStream_t stream);
+void* scratch_workspace(size_t bytes);
+void free_workspaces();
+
+// Launchers (defined next to their kernels).
+la_status launch_verify(const float* logits, const int* cand_tokens, int G, int N, int V,
+                        int* accept_len, int* accepted, hipStream_t stream);
+la_status launch_step_attention(const void* q, const void* k_cache, const void* v_cache,
+                                const void* step_k, const void* step_v, int P, int W, int N, int G,
+                                int heads, int kv_heads, int head_dim, void* out,
+                                hipStream_t stream);
+size_t step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int kv_heads,
+                                      int head_dim);
+
+}  // namespace la

@@ -1,0 +1,159 @@
+// Greedy verification reduction for gfx950: per-row argmax over the vocabulary and the
+// longest accepted prefix of every candidate n-gram (Sec. 2 "Guess-And-Verify"; the
+// accept/stop rule Algorithm 3 applies to each candidate), in one launch.
+//
+// The G*(N-1) logits rows are far fewer than the 256 compute units, so every row is cut
+// into segments and each workgroup scans one segment with 16-byte loads.  A segment's
+// winner is folded into one 64-bit key per row with atomicMax,
+//     key = (order-preserving image of the fp32 value) << 32 | (0xFFFFFFFF - index),
+// so the largest value wins and, among equal values, the lowest index: the result does
+// not depend on the order in which workgroups finish.  The workgroup that finishes last
+// (a ticket counter) turns the keys into `accepted` and `accept_len` and zeroes keys and
+// ticket again, so the workspace is clean for the next call without a memset.
+#include "la_internal.h"
+
+namespace la {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+
+__device__ __forceinline__ unsigned long long pack_key(float v, int idx)
+{
+    if (v == 0.0f) v = 0.0f;  // -0.0 and +0.0 compare equal: give them one image
+    unsigned b = __float_as_uint(v);
+    unsigned ord = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+    return ((unsigned long long)ord << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)idx);
+}
+
+__device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long x, int mask)
+{
+    unsigned lo = __shfl_xor((unsigned)x, mask, 64);
+    unsigned hi = __shfl_xor((unsigned)(x >> 32), mask, 64);
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+// rows = G * n1 logits rows of V floats; row r is cut into nseg segments of seg_len
+// (a multiple of 4) elements; blockIdx.x = r * nseg + segment.
+template <bool kVec>
+__global__ __launch_bounds__(kThreads) void verify_kernel(
+    const float* __restrict__ logits, const int* __restrict__ cand_tokens, int G, int n1, int V,
+    int seg_len, int nseg, unsigned long long* keys, unsigned* ticket,
+    int* __restrict__ accept_len, int* __restrict__ accepted)
+{
+    const int row = blockIdx.x / nseg;
+    const int seg = blockIdx.x - row * nseg;
+    const int v0 = seg * seg_len;
+    const int v1 = min(V, v0 + seg_len);
+    const float* p = logits + (size_t)row * V;
+    const int tid = threadIdx.x;
+
+    // Per thread: indices are visited in increasing order and only a strictly larger value
+    // replaces the best, so the earliest of equal values is kept.
+    float best = 0.0f;
+    int best_idx = -1;
+    if (kVec) {
+        const float4* p4 = reinterpret_cast<const float4*>(p);
+        const int q1 = v1 >> 2;  // V % 4 == 0 on this path
+        for (int i = (v0 >> 2) + tid; i < q1; i += kThreads) {
+            const float4 x = p4[i];
+            const int base = i << 2;
+            if (best_idx < 0) { best = x.x; best_idx = base; }
+            if (x.x > best) { best = x.x; best_idx = base; }
+            if (x.y > best) { best = x.y; best_idx = base + 1; }
+            if (x.z > best) { best = x.z; best_idx = base + 2; }
+            if (x.w > best) { best = x.w; best_idx = base + 3; }
+        }
+    } else {
+        for (int i = v0 + tid; i < v1; i += kThreads) {
+            const float x = p[i];
+            if (best_idx < 0 || x > best) { best = x; best_idx = i; }
+        }
+    }
+    unsigned long long key = best_idx < 0 ? 0ull : pack_key(best, best_idx);
+
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+        const unsigned long long o = shfl_xor_u64(key, m);
+        key = o > key ? o : key;
+    }
+    __shared__ unsigned long long wave_key[kWaves];
+    __shared__ unsigned last_flag;
+    if ((tid & 63) == 0) wave_key[tid >> 6] = key;
+    __syncthreads();
+    if (tid == 0) {
+        unsigned long long k = wave_key[0];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) k = wave_key[w] > k ? wave_key[w] : k;
+        atomicMax(&keys[row], k);
+        __threadfence();
+        const unsigned t = atomicAdd(ticket, 1u);
+        last_flag = (t == gridDim.x - 1) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!last_flag) return;
+
+    // Last workgroup: every key is final.
+    __threadfence();
+    const int rows = G * n1;
+    for (int r = tid; r < rows; r += kThreads) {
+        const unsigned long long k =
+            __hip_atomic_load(&keys[r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        accepted[r] = (int)(0xFFFFFFFFu - (unsigned)k);
+    }
+    for (int g = tid; g < G; g += kThreads) {
+        int len = 0;
+        while (len < n1) {
+            const unsigned long long k =
+                __hip_atomic_load(&keys[g * n1 + len], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((int)(0xFFFFFFFFu - (unsigned)k) != cand_tokens[g * n1 + len]) break;
+            ++len;
+        }
+        accept_len[g] = len;
+    }
+    __syncthreads();
+    for (int r = tid; r < rows; r += kThreads) keys[r] = 0ull;
+    if (tid == 0) *ticket = 0u;
+}
+
+}  // namespace
+
+la_status launch_verify(const float* logits, const int* cand_tokens, int G, int N, int V,
+                        int* accept_len, int* accepted, hipStream_t stream)
+{
+    const int n1 = N - 1;
+    const int rows = G * n1;
+    // Segment length: at least 4096 elements (16 elements per thread), and enough segments
+    // to put about four workgroups on each of the 256 compute units.
+    int nseg = (V + 4095) / 4096;
+    const int want = (1024 + rows - 1) / rows;
+    if (nseg > want) nseg = want;
+    if (nseg < 1) nseg = 1;
+    int seg_len = (V + nseg - 1) / nseg;
+    seg_len = (seg_len + 3) & ~3;
+    nseg = (V + seg_len - 1) / seg_len;
+    const long long blocks = (long long)rows * nseg;
+    if (blocks > 0x7fffffffll) return fail(LA_EINVAL, "la_verify: too many workgroups");
+
+    // workspace: one 64-bit key per row, then the ticket
+    const size_t bytes = (size_t)rows * 8 + 8;
+    char* ws = (char*)zeroed_workspace(bytes, stream);
+    if (!ws) return LA_ENOMEM;
+    unsigned long long* keys = (unsigned long long*)ws;
+    unsigned* ticket = (unsigned*)(ws + (size_t)rows * 8);
+
+    const bool vec = (V % 4 == 0) && (((uintptr_t)logits & 15) == 0);
+    if (vec)
+        hipLaunchKernelGGL(verify_kernel<true>, dim3((unsigned)blocks), dim3(kThreads), 0, stream,
+                           logits, cand_tokens, G, n1, V, seg_len, nseg, keys, ticket, accept_len,
+                           accepted);
+    else
+        hipLaunchKernelGGL(verify_kernel<false>, dim3((unsigned)blocks), dim3(kThreads), 0, stream,
+                           logits, cand_tokens, G, n1, V, seg_len, nseg, keys, ticket, accept_len,
+                           accepted);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(LA_EHIP, "la_verify launch: %s", hipGetErrorString(e));
+    return LA_OK;
+}
+
+}  // namespace la

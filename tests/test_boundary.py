@@ -1,0 +1,64 @@
+"""The C-ABI library builds, loads without a GPU and exports what include/la.h declares."""
+import os
+import re
+
+import pytest
+
+from paper_2402_02057_amd import binding, buildlib
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if buildlib.is_stale():
+        buildlib.build()
+    return binding.load()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "la.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(la_[a-z_]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_error_string(lib):
+    assert binding.la_version() >= 1000
+    assert isinstance(lib.la_last_error(), bytes)
+
+
+def test_argument_errors_are_reported_without_a_gpu(lib):
+    # validation happens before any HIP call
+    rc = lib.la_step_attention(None, None, None, None, None, 0, 1, 1, 1, 1, 1, 128, None, None)
+    assert rc == -1 and b"N >= 2" in lib.la_last_error()
+    rc = lib.la_step_attention(None, None, None, None, None, 0, 1, 3, 1, 4, 4, 96, None, None)
+    assert rc == -2 and b"head_dim" in lib.la_last_error()
+    rc = lib.la_step_attention(None, None, None, None, None, 0, 1, 3, 1, 6, 4, 128, None, None)
+    assert rc == -2
+    rc = lib.la_step_attention(None, None, None, None, None, 0, 1, 3, 1, 4, 4, 128, None, None)
+    assert rc == -1 and b"null" in lib.la_last_error()
+    rc = lib.la_step_attention(16, None, None, 16, 24, 0, 1, 3, 1, 4, 4, 128, 16, None)
+    assert rc == -1 and b"aligned" in lib.la_last_error()
+    assert lib.la_verify(None, None, 0, 3, 10, None, None, None) == 0      # G = 0: no-op
+    assert lib.la_verify(None, None, 2, 3, 10, None, None, None) == -1
+    assert lib.la_verify(None, None, 2, 1, 10, None, None, None) == -1
+
+
+def test_workspace_query(lib):
+    assert binding.la_step_attention_workspace_bytes(1024, 15, 5, 15, 32, 32, 128) > 0
+    assert binding.la_step_attention_workspace_bytes(0, 0, 2, 0, 1, 1, 128) == 0
+    assert binding.la_step_attention_workspace_bytes(0, 0, 2, 0, 3, 2, 128) == 0
+
+
+def test_binding_rejects_host_tensors():
+    import torch
+    z = torch.zeros((1, 1, 64), dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        binding.la_step_attention(z, None, None, z, z, 0, 0, 2, 0, 1, 1, 64, z)

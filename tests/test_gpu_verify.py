@@ -1,0 +1,115 @@
+"""GPU parity: la_verify (HIP, through the C ABI) against the CPU oracle, bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import la_oracle as orc
+from paper_2402_02057_amd import binding, workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def run_hip(logits, cand, G, N, V):
+    alen = torch.full((G,), -7, dtype=torch.int32, device="cuda")
+    acc = torch.full((G, N - 1), -7, dtype=torch.int32, device="cuda")
+    binding.la_verify(torch.from_numpy(logits).cuda(), torch.from_numpy(cand).cuda(), G, N, V, alen, acc)
+    torch.cuda.synchronize()
+    return alen.cpu().numpy(), acc.cpu().numpy()
+
+
+def check(logits, cand, G, N, V, tag=""):
+    print("case", tag, dict(G=G, N=N, V=V), flush=True)
+    alen, acc = run_hip(logits, cand, G, N, V)
+    want_len, want_acc = orc.verify(logits, cand, G, N, V)
+    np.testing.assert_array_equal(acc, want_acc)
+    np.testing.assert_array_equal(alen, want_len)
+    return alen
+
+
+def test_tiny_config():
+    s = wl.TINY
+    logits, cand, _ = wl.verify_inputs(s)
+    check(logits, cand, s.G, s.N, s.V, "tiny")
+
+
+@pytest.mark.parametrize("shape", [wl.LLAMA2_7B, wl.LLAMA2_13B, wl.LLAMA2_70B, wl.ragged_shape(0, 30),
+                                   wl.ragged_shape(3, 5)], ids=lambda s: s.name)
+def test_planted_paper_configs(shape):
+    s = shape
+    logits, cand, lens = wl.verify_inputs(s)
+    alen = check(logits, cand, s.G, s.N, s.V, s.name)
+    np.testing.assert_array_equal(alen, lens)
+
+
+@pytest.mark.parametrize("V", [1, 2, 3, 5, 63, 64, 65, 255, 1000, 1023, 4096, 4097, 32001, 50257])
+def test_odd_vocabulary_sizes_and_ties(V):
+    rng = np.random.default_rng(V)
+    G, N = 3, 4
+    logits = rng.standard_normal(size=(G, N - 1, V)).astype(np.float32)
+    logits[1] = np.round(logits[1])          # many exact ties: lowest index must win
+    logits[2, 0] = 0.0
+    logits[2, 1, ::2] = -0.0                 # signed zeros compare equal
+    logits[2, 1, 1::2] = 0.0
+    cand = np.argmax(logits, axis=-1).astype(np.int32)
+    cand[0, 1] = (cand[0, 1] + 1) % V if V > 1 else cand[0, 1]
+    check(logits, cand, G, N, V)
+
+
+def test_ties_across_segments():
+    """Equal maxima far apart (different workgroups of one row): the lowest index wins."""
+    G, N, V = 2, 3, 32000
+    logits = np.full((G, N - 1, V), -1.0, dtype=np.float32)
+    logits[0, 0, [31999, 17000, 4001]] = 5.0
+    logits[0, 1, [31999]] = 5.0
+    logits[1, 0, :] = -np.inf                # a fully masked row: index 0
+    logits[1, 1, [8000, 8001]] = -0.5
+    cand = np.array([[4001, 31999], [0, 8000]], dtype=np.int32)
+    alen = check(logits, cand, G, N, V)
+    assert alen.tolist() == [2, 2]
+
+
+def test_extreme_values():
+    G, N, V = 1, 3, 4099
+    logits = np.full((G, N - 1, V), -3.0e38, dtype=np.float32)
+    logits[0, 0, 4098] = -2.9e38
+    logits[0, 1, 7] = 3.4e38
+    logits[0, 1, 9] = np.inf
+    cand = np.array([[4098, 9]], dtype=np.int32)
+    alen = check(logits, cand, G, N, V)
+    assert alen.tolist() == [2]
+
+
+def test_exhaustive_tiny_vocabulary():
+    rng = np.random.default_rng(0)
+    for V in (2, 3):
+        for N in (2, 3, 4):
+            for G in (1, 2, 3):
+                for _ in range(6):
+                    logits = rng.integers(-2, 3, size=(G, N - 1, V)).astype(np.float32)
+                    cand = rng.integers(0, V, size=(G, N - 1)).astype(np.int32)
+                    check(logits, cand, G, N, V)
+
+
+def test_repeated_calls_leave_the_workspace_clean():
+    s = wl.LLAMA2_7B
+    logits, cand, lens = wl.verify_inputs(s)
+    for _ in range(3):
+        alen, _ = run_hip(logits, cand, s.G, s.N, s.V)
+        np.testing.assert_array_equal(alen, lens)
+    # a smaller problem right after a larger one
+    t = wl.TINY
+    logits, cand, _ = wl.verify_inputs(t)
+    check(logits, cand, t.G, t.N, t.V)
+
+
+def test_many_rows():
+    G, N, V = 64, 9, 777
+    rng = np.random.default_rng(5)
+    logits = rng.standard_normal(size=(G, N - 1, V)).astype(np.float32)
+    cand = np.argmax(logits, axis=-1).astype(np.int32)
+    cut = rng.integers(0, N, size=G)
+    for g in range(G):
+        if cut[g] < N - 1:
+            cand[g, cut[g]] = (cand[g, cut[g]] + 1) % V
+    alen = check(logits, cand, G, N, V)
+    np.testing.assert_array_equal(alen, np.minimum(cut, N - 1))
