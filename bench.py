@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the lookahead-decoding hot path on one MI355X.
+
+One "step" is one lookahead decoding step of a LLaMA-2-shaped model as the hot path sees
+it: L back-to-back la_step_attention calls, one per layer and each on its own KV cache (so
+the 256 MB Infinity Cache cannot hold what is streamed), followed by one la_verify call on
+the step's verification logits.  Inputs are seeded synthetic tensors resident in HBM before
+the timed region.  The reported value is microseconds per layer-step (step time / L).
+
+Prints ONE JSON line; see the design doc for the roofline and cpu_baseline fields.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+LAYERS = {"llama2-7b": 32, "llama2-13b": 40, "llama2-70b-gqa": 80}
+
+
+def visible_pairs(W, N, G):
+    n1 = N - 1
+    return 1 + sum(2 + j for j in range(W)) + sum(2 + j + l for l in range(1, n1) for j in range(W)) \
+        + G * sum(2 + k for k in range(n1))
+
+
+def algorithmic_bytes(s):
+    """HBM bytes one layer-step must move: K/V cache once, step K/V, q in, out (all bf16)."""
+    T, H, KV, d, P = s.T, s.heads, s.kv_heads, s.head_dim, s.P
+    return 2 * P * KV * d * 2 + 2 * T * KV * d * 2 + 2 * T * H * d * 2
+
+
+def algorithmic_flops(s):
+    return 4 * s.head_dim * s.heads * (s.T * s.P + visible_pairs(s.W, s.N, s.G))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="llama2-7b", choices=sorted(LAYERS))
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true", help="replay each step as one HIP graph")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus %d is not supported "
+              "(see DESIGN.md, 'More than one GPU')" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2402_02057_amd import binding, buildlib, workloads as wl
+
+    if not os.path.exists(buildlib.LIB):
+        buildlib.build()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    s = wl.SHAPES[args.workload]
+    L = args.layers or LAYERS[args.workload]
+    T, H, KV, d, P = s.T, s.heads, s.kv_heads, s.head_dim, s.P
+
+    # ---- inputs, resident in HBM: one independent draw per layer
+    layers = []
+    host0 = None
+    for layer in range(L):
+        x = wl.attention_inputs(s, extra=layer)
+        if layer == 0:
+            host0 = x
+        layers.append({k: binding.bf16_tensor(v) for k, v in x.items()})
+    outs = [torch.empty((T, H, d), dtype=torch.bfloat16, device="cuda") for _ in range(L)]
+    logits_h, cand_h, lens_h = wl.verify_inputs(s)
+    logits = torch.from_numpy(logits_h).cuda()
+    cand = torch.from_numpy(cand_h).cuda()
+    alen = torch.empty((s.G,), dtype=torch.int32, device="cuda")
+    acc = torch.empty((s.G, s.N - 1), dtype=torch.int32, device="cuda")
+
+    def attention_layers():
+        for x, o in zip(layers, outs):
+            binding.la_step_attention(x["q"], x["k_cache"], x["v_cache"], x["step_k"], x["step_v"],
+                                      P, s.W, s.N, s.G, H, KV, d, o)
+
+    def step():
+        attention_layers()
+        binding.la_verify(logits, cand, s.G, s.N, s.V, alen, acc)
+
+    step()
+    torch.cuda.synchronize()
+    run_step = step
+    if args.graph:
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g):
+            step()
+        run_step = g.replay
+
+    for _ in range(args.warmup):
+        run_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run_step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    us_per_layer = ms_per_step * 1e3 / L
+
+    # ---- dominant kernel (attention) and the verify kernel, by HIP events on the launch stream
+    reps = max(10, min(args.steps, 100))
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    attn_ms, ver_ms = [], []
+    for _ in range(reps):
+        e[0].record()
+        attention_layers()
+        e[1].record()
+        binding.la_verify(logits, cand, s.G, s.N, s.V, alen, acc)
+        e[2].record()
+        torch.cuda.synchronize()
+        attn_ms.append(e[0].elapsed_time(e[1]))
+        ver_ms.append(e[1].elapsed_time(e[2]))
+    attn_us = float(np.median(attn_ms)) * 1e3 / L       # per launch, launch gaps included
+    verify_us = float(np.median(ver_ms)) * 1e3
+    abytes = algorithmic_bytes(s)
+    aflops = algorithmic_flops(s)
+    t_hbm = abytes / (HBM_PEAK_GBS * 1e9)
+    t_mfma = aflops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    if t_hbm >= t_mfma:
+        roof = {"bound": "hbm", "achieved": abytes / (attn_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": aflops / (attn_us * 1e-6) / 1e12,
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = "step_attention_kernel"
+    roof["us_per_launch"] = attn_us
+    roof["algorithmic_bytes"] = abytes
+    roof["algorithmic_flops"] = aflops
+
+    # ---- validity: layer 0 and the verification against the CPU oracle
+    from oracle import la_oracle as orc
+    want = orc.step_attention(host0["q"], host0["k_cache"], host0["v_cache"], host0["step_k"],
+                              host0["step_v"], P, s.W, s.N, s.G, H, KV, d)
+    err = float(np.abs(outs[0].float().cpu().numpy().astype(np.float64) - want).max())
+    want_len, want_acc = orc.verify(logits_h, cand_h, s.G, s.N, s.V)
+    exact = bool(np.array_equal(alen.cpu().numpy(), want_len) and np.array_equal(acc.cpu().numpy(), want_acc))
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        # the oracle as it stands, on the host cores: repeated layer-steps of layer 0's inputs
+        # plus one verification, until about 10 s of wall time have passed
+        n_done, t_start = 0, time.perf_counter()
+        while True:
+            orc.step_attention(host0["q"], host0["k_cache"], host0["v_cache"], host0["step_k"],
+                               host0["step_v"], P, s.W, s.N, s.G, H, KV, d)
+            n_done += 1
+            if time.perf_counter() - t_start > 10.0 or n_done >= 4 * L:
+                break
+        t_attn = time.perf_counter() - t_start
+        t_start = time.perf_counter()
+        orc.verify(logits_h, cand_h, s.G, s.N, s.V)
+        t_ver = time.perf_counter() - t_start
+        cpu = {"value": (t_attn / n_done + t_ver / L) * 1e6, "unit": "us/layer-step",
+               "cores": orc.threads(), "kind": "oracle",
+               "sample": "%d attention layer-steps of the %s shape (fp64, OpenMP over heads) + one "
+                         "verification amortised over %d layers" % (n_done, s.name, L)}
+
+    line = {
+        "metric": "lookahead-step attention + verification, us per layer-step",
+        "value": us_per_layer, "unit": "us/layer-step", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: H%d/KV%d/d%d P=%d W=%d N=%d G=%d (T=%d), %d layers + verify "
+                               "[%d,%d,%d] fp32" % (s.name, H, KV, d, P, s.W, s.N, s.G, T, L, s.G,
+                                                     s.N - 1, s.V),
+                   "layers": L, "graph": bool(args.graph)},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "verify_us": verify_us,
+        "attention_tflops": aflops / (attn_us * 1e-6) / 1e12,
+        "attention_gbs": abytes / (attn_us * 1e-6) / 1e9,
+        "parity": {"attention_max_abs_err_layer0": err, "verify_bit_exact": exact},
+    }
+    print(json.dumps(line))
+    if err > 2e-2 or not exact:
+        print("bench.py: PARITY FAILURE", file=sys.stderr)
+        sys.exit(1)
+
+
+if __name__ == "__main__":
+    main()

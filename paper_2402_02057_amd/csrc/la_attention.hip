@@ -26,10 +26,18 @@
 // (Algorithm 2's conditioning sets read as index ranges), turned into one 32-bit word per
 // (row, key block) from integer ranges in registers; no mask tensor exists anywhere.
 //
-// Split combine.  With XS > 1 each workgroup stores its unnormalised fp32 accumulator and
-// (max, sum) per row, takes a ticket, and the workgroup that arrives last merges all XS
-// partials in index order (so results do not depend on arrival order), normalises and
-// writes bf16.  Tickets return to zero, so no memset is needed between calls.
+// Split combine, in the same launch.  With XS > 1 each workgroup stores its unnormalised fp32
+// accumulator and (max, sum) per row, waits for the stores to reach the L2, and takes a
+// ticket; the workgroup that arrives last merges all XS partials in index order (so results
+// do not depend on arrival order), normalises and writes bf16.  The L2 of one XCD is
+// coherent for all its compute units, but the eight L2s are not coherent with each other
+// inside a kernel, and an agent-scope fence (L2 write-back + invalidate) costs tens of
+// microseconds here.  So the workgroups of a split group are laid out on one XCD (workgroup
+// ids go round-robin over XCDs) and the ticket also carries the XCD id each member read
+// from the hardware register: if all ids agree the partials are read straight from the shared
+// L2; if not, the last workgroup ignores the partials and recomputes its rows over all
+// chunks from the read-only inputs.  Either way the result is exact; tickets return to zero,
+// so no memset is needed between calls.
 #include <stdlib.h>
 
 #include "la_internal.h"
@@ -64,6 +72,11 @@ struct AttnParams {
     int total_wg;         // kv_heads * n_row_blocks * XS
     int wg_per_xcd;       // ceil(total_wg / 8)
     float scale_log2;     // log2(e) / sqrt(head_dim)
+    int force_recompute;  // testing: treat every group as spread over several XCDs
+#ifdef LA_DEV_KNOBS
+    int dev_mode;         // timing experiments only (results are wrong): see LA_DEV_MODE
+    long long* dev_trace; // 8 wall-clock stamps per workgroup
+#endif
 };
 
 // Which step keys a step row may see, as index ranges (see the header comment).
@@ -115,6 +128,24 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// One direct-to-LDS load: every lane fetches 16 bytes from its own global address, the wave's
+// 1 KB lands at LDS byte address `lds_base` + lane * 16 (M0 carries the base).  Written as
+// assembly so that the compiler's wait-count bookkeeping does not know of these loads: it would
+// otherwise make every later LDS read wait for ALL of them, including the chunks being
+// prefetched.  Completion is tracked by hand: s_waitcnt vmcnt(n) + workgroup barrier.
+__device__ __forceinline__ void dma16(const void* src, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(src), "s"(lds_base)
+                 : "memory");
+}
+
+__device__ __forceinline__ unsigned lds_address(const void* p)
+{
+    return (unsigned)(size_t)(const __attribute__((address_space(3))) void*)p;
+}
+
 // 16-byte piece `lc` of row `row` lives at piece position lc ^ swizzle(row) of that row.
 template <int D>
 __device__ __forceinline__ int swizzle(int row)
@@ -141,7 +172,10 @@ struct Cfg {
     static constexpr int FRAG_FLOATS = DB * 16 * 64;      // one tile's accumulators
     static constexpr int TILE_FLOATS = FRAG_FLOATS + 128; // + m and l per lane
     static constexpr int OUT_PITCH = RBYTES + 16;         // LDS pitch of the output transpose
-    static constexpr int LDS_MAIN = NSTAGE * STAGE_BYTES;
+    static constexpr int Q_BYTES = ROWS * RBYTES;         // the workgroup's query rows
+    static constexpr int Q_OFFSET = NSTAGE * STAGE_BYTES; // they sit behind the stage ring
+    static constexpr int QLPW = Q_BYTES / 1024 / NW;      // Q loads per wave
+    static constexpr int LDS_MAIN = NSTAGE * STAGE_BYTES + Q_BYTES;
     static constexpr int LDS_MERGE = (KS - 1) * RT * RW * TILE_FLOATS * 4;
     static constexpr int LDS_OUT = ROWS * OUT_PITCH;
     static constexpr int LDS_BYTES =
@@ -149,8 +183,39 @@ struct Cfg {
                              : (LDS_MERGE > LDS_OUT ? LDS_MERGE : LDS_OUT);
     static_assert(KB % KS == 0, "key blocks of a chunk must divide among the key-split waves");
     static_assert(WLOADS % NW == 0, "chunk loads must divide among the waves");
-    static_assert(LPW * (NSTAGE - 1) < 64, "vmcnt is a 6-bit counter");
+    static_assert((Q_BYTES / 1024) % NW == 0, "Q loads must divide among the waves");
+    static_assert(LPW * (NSTAGE - 1) + QLPW < 64, "vmcnt is a 6-bit counter");
+    static_assert(LDS_BYTES <= 160 * 1024 - 64, "LDS of a compute unit");
 };
+
+#ifdef LA_DEV_KNOBS
+#define LA_STAMP(k) do { if (p.dev_trace && threadIdx.x == 0) p.dev_trace[(size_t)blockIdx.x * 8 + (k)] = wall_clock64(); } while (0)
+#else
+#define LA_STAMP(k) do { } while (0)
+#endif
+
+// Id of the XCD (accelerator die, with its own L2) this wave runs on.
+__device__ __forceinline__ unsigned xcc_id()
+{
+    unsigned v;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(v));
+    return v & 0xfu;
+}
+
+// Copy the workgroup's finished rows (bf16, pitch C::OUT_PITCH in LDS) to `out`, 16 bytes a lane.
+template <class C, int D = C::RBYTES / 2>
+__device__ __forceinline__ void write_rows_from_lds(const AttnParams& p, const unsigned char* lds,
+                                                    int rb, int kvh, int tid)
+{
+    const int rows_here = min(C::ROWS, p.R - rb * C::ROWS);
+    for (int piece = tid; piece < rows_here * C::NCH; piece += C::NT) {
+        const int r = piece / C::NCH, ch = piece % C::NCH;
+        const int rr = rb * C::ROWS + r;
+        const int t = rr / p.group, hh = rr - t * p.group;
+        const f32x4 v = *reinterpret_cast<const f32x4*>(lds + r * C::OUT_PITCH + ch * 16);
+        *reinterpret_cast<f32x4*>(p.out + ((size_t)t * p.heads + (size_t)kvh * p.group + hh) * D + ch * 8) = v;
+    }
+}
 
 template <int D, int RW, int RT, int KS, int KC, int NSTAGE>
 __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnParams p)
@@ -160,6 +225,7 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
 
     // Consecutive workgroup ids go round-robin over the 8 XCDs (each with its own L2); put
     // the workgroups that stream the same KV head on one XCD.
+    LA_STAMP(0);
     const int logical = (int)(blockIdx.x & 7) * p.wg_per_xcd + (int)(blockIdx.x >> 3);
     if (logical >= p.total_wg) return;
     const int xs = logical % p.XS;
@@ -174,44 +240,14 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
     const int hi = lane >> 5;   // upper half-wave
     const int l32 = lane & 31;
 
+    const unsigned lds_base = lds_address(lds);
     const int row_base = rb * C::ROWS + rt * (RW * 32);  // first row of this wave (in R space)
     const bool wave_active = row_base < p.R;            // else: only helps loading
 
-    // ---- Q as the B operand of S^T = K Q^T: lane holds row l32, d = ks16*16 + hi*8 .. +8
-    bf16x8 qreg[RW][D / 16];
-    RowVis vis[RW];
-#pragma unroll
-    for (int rw = 0; rw < RW; ++rw) {
-        const int rr = row_base + rw * 32 + l32;
-        const bool ok = rr < p.R;
-        const int t = ok ? rr / p.group : 0;
-        const int hh = ok ? rr - t * p.group : 0;
-        vis[rw] = row_visibility(t, p.W, p.N);
-        const __bf16* src = p.q + ((size_t)t * p.heads + (size_t)kvh * p.group + hh) * D + hi * 8;
-#pragma unroll
-        for (int k16 = 0; k16 < D / 16; ++k16) {
-            bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (ok) v = *reinterpret_cast<const bf16x8*>(src + k16 * 16);
-            qreg[rw][k16] = v;
-        }
-    }
-
-    f32x16 o[RW][C::DB];
-    float m_run[RW], l_run[RW];
-#pragma unroll
-    for (int rw = 0; rw < RW; ++rw) {
-        m_run[rw] = kNegInf;
-        l_run[rw] = 0.0f;
-#pragma unroll
-        for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[rw][db][i] = 0.0f;
-    }
-
     // ---- chunk range of this split
-    const int c_begin = (int)(((long long)xs * p.n_chunks) / p.XS);
-    const int c_end = (int)(((long long)(xs + 1) * p.n_chunks) / p.XS);
-    const int n_my = c_end - c_begin;
+    int c_begin = (int)(((long long)xs * p.n_chunks) / p.XS);
+    int c_end = (int)(((long long)(xs + 1) * p.n_chunks) / p.XS);
+    bool direct = p.XS == 1;  // this pass covers every key of the rows: write `out` directly
 
     // Issue the direct-to-LDS loads of chunk `c` into stage `st`.
     auto issue_chunk = [&](int c, int st) {
@@ -224,7 +260,6 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                                       : p.k_cache + ((size_t)kvh * p.P + key0) * D;
         const __bf16* vbase = is_step ? p.step_v + ((size_t)key0 * p.kv_heads + kvh) * D
                                       : p.v_cache + ((size_t)kvh * p.P + key0) * D;
-        unsigned char* stage = lds + st * C::STAGE_BYTES;
 #pragma unroll
         for (int i = 0; i < C::LPW; ++i) {
             const int wl = wave + i * C::NW;                  // wave-load index in the chunk
@@ -235,121 +270,117 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
             const int lc = pc ^ swizzle<D>(row);
             const int srow = min(row, last_row);              // rows past the end repeat the last
             const __bf16* src = (is_v ? vbase : kbase) + (size_t)srow * stride + lc * 8;
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)src,
-                (__attribute__((address_space(3))) void*)(stage + wl * 1024), 16, 0, 0);
+            dma16(src, __builtin_amdgcn_readfirstlane(lds_base + st * C::STAGE_BYTES + wl * 1024));
         }
     };
 
+    // Request Q and the first chunks before anything else: the stream from HBM is the critical
+    // path.  The workgroup's query rows go to LDS (same swizzle as K) and are the oldest loads
+    // in flight, so the first chunk's wait covers them.  Rows past the end repeat the last row.
+    {
+#pragma unroll
+        for (int i = 0; i < C::QLPW; ++i) {
+            const int wl = wave + i * C::NW;
+            const int piece = wl * 64 + lane;
+            const int row = piece / C::NCH, pc = piece % C::NCH;
+            const int lc = pc ^ swizzle<D>(row);
+            const int rr = min(rb * C::ROWS + row, p.R - 1);
+            const int t = rr / p.group, hh = rr - t * p.group;
+            const __bf16* src = p.q + ((size_t)t * p.heads + (size_t)kvh * p.group + hh) * D + lc * 8;
+            dma16(src, __builtin_amdgcn_readfirstlane(lds_base + C::Q_OFFSET + wl * 1024));
+        }
+    }
 #pragma unroll
     for (int s = 0; s < NSTAGE - 1; ++s)
-        if (s < n_my) issue_chunk(c_begin + s, s);
+        if (s < c_end - c_begin) issue_chunk(c_begin + s, s);
+    LA_STAMP(1);
 
-    for (int it = 0; it < n_my; ++it) {
-        // wait for this wave's loads of chunk `it`; later chunks may stay in flight
-        const int later = min(n_my - 1 - it, NSTAGE - 2);
-        if (NSTAGE >= 3 && later >= 1) {
-            if (NSTAGE >= 4 && later >= 2) wait_vmcnt<2 * C::LPW>();
-            else wait_vmcnt<C::LPW>();
-        } else {
-            wait_vmcnt<0>();
+    // which step keys each of this lane's rows may see
+    RowVis vis[RW];
+#pragma unroll
+    for (int rw = 0; rw < RW; ++rw) {
+        const int rr = min(row_base + rw * 32 + l32, p.R - 1);
+        vis[rw] = row_visibility(rr / p.group, p.W, p.N);
+    }
+    bf16x8 qreg[RW][D / 16];  // B operand of S^T = K Q^T: row l32, d = k16*16 + hi*8 .. +8
+
+    f32x16 o[RW][C::DB];
+    float m_run[RW], l_run[RW];
+    __shared__ unsigned s_role;  // after the ticket: 0 not last, 1 last and co-located, 2 recompute
+
+    for (int pass = 0;; ++pass) {
+#pragma unroll
+        for (int rw = 0; rw < RW; ++rw) {
+            m_run[rw] = kNegInf;
+            l_run[rw] = 0.0f;
+#pragma unroll
+            for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[rw][db][i] = 0.0f;
         }
-        __syncthreads();  // chunk `it` complete in LDS; everyone is done with chunk it-1
-        if (it + NSTAGE - 1 < n_my) issue_chunk(c_begin + it + NSTAGE - 1, (it + NSTAGE - 1) % NSTAGE);
-        if (!wave_active) continue;
+        const int n_my = c_end - c_begin;
+        if (pass > 0) {
+#pragma unroll
+            for (int s = 0; s < NSTAGE - 1; ++s)
+                if (s < n_my) issue_chunk(c_begin + s, s);
+        }
 
-        const int c = c_begin + it;
-        const bool is_step = c >= p.n_prefix_chunks;
-        const int chunk_key0 = (is_step ? c - p.n_prefix_chunks : c) * KC;
-        const int limit = is_step ? p.T : p.P;
-        const unsigned char* kst = lds + (it % NSTAGE) * C::STAGE_BYTES;
-        const unsigned char* vst = kst + C::KV_BYTES;
+        for (int it = 0; it < n_my; ++it) {
+            // wait for this wave's loads of chunk `it`; later chunks may stay in flight
+            const int later = min(n_my - 1 - it, NSTAGE - 2);
+            if (NSTAGE >= 4 && later >= 2) wait_vmcnt<(NSTAGE >= 4 ? 2 : 0) * C::LPW>();
+            else if (NSTAGE >= 3 && later >= 1) wait_vmcnt<(NSTAGE >= 3 ? 1 : 0) * C::LPW>();
+            else wait_vmcnt<0>();
+            __syncthreads();  // chunk `it` complete in LDS; everyone is done with chunk it-1
+            if (it == 0) LA_STAMP(2);
+            if (it == 0 && pass == 0) {
+                // Q has landed with the first chunk: move this wave's rows to registers
+#pragma unroll
+                for (int rw = 0; rw < RW; ++rw) {
+                    const int qrow = (rt * RW + rw) * 32 + l32;
+                    const unsigned char* qr = lds + C::Q_OFFSET + qrow * C::RBYTES;
+                    const int qsw = swizzle<D>(qrow);
+#pragma unroll
+                    for (int k16 = 0; k16 < D / 16; ++k16)
+                        qreg[rw][k16] = *reinterpret_cast<const bf16x8*>(qr + (((k16 * 2 + hi) ^ qsw) << 4));
+                }
+            }
+            if (it + NSTAGE - 1 < n_my)
+                issue_chunk(c_begin + it + NSTAGE - 1, (it + NSTAGE - 1) % NSTAGE);
+            if (!wave_active) continue;
+#ifdef LA_DEV_KNOBS
+            if (p.dev_mode == 2) continue;  // loads only
+#endif
+
+            const int c = c_begin + it;
+            const bool is_step = c >= p.n_prefix_chunks;
+            const int chunk_key0 = (is_step ? c - p.n_prefix_chunks : c) * KC;
+            const int limit = is_step ? p.T : p.P;
+            const unsigned char* kst = lds + (it % NSTAGE) * C::STAGE_BYTES;
+            const unsigned char* vst = kst + C::KV_BYTES;
 
 #pragma unroll
-        for (int kbw = 0; kbw < C::KBW; ++kbw) {
-            const int kb = ks + kbw * KS;
-            const int key0 = chunk_key0 + kb * 32;
-            if (key0 >= limit) continue;  // block entirely past the end (wave-uniform)
+            for (int kbw = 0; kbw < C::KBW; ++kbw) {
+                const int kb = ks + kbw * KS;
+                const int key0 = chunk_key0 + kb * 32;
+                if (key0 >= limit) continue;  // block entirely past the end (wave-uniform)
 
-            // ---- S^T block: 32 keys x 32 rows per tile
-            f32x16 s[RW];
-#pragma unroll
-            for (int rw = 0; rw < RW; ++rw)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) s[rw][i] = 0.0f;
-            {
+                // ---- operands: all K pieces of the block, and the V pieces of its first 16 keys,
+                //      are requested from LDS before the first MFMA (LDS answers in order)
                 const int krow = kb * 32 + l32;
                 const unsigned char* kr = kst + krow * C::RBYTES;
-                const int sw = swizzle<D>(krow);
+                const int ksw = swizzle<D>(krow);
+                bf16x8 kf[D / 16];
 #pragma unroll
-                for (int k16 = 0; k16 < D / 16; ++k16) {
-                    const bf16x8 kf =
-                        *reinterpret_cast<const bf16x8*>(kr + (((k16 * 2 + hi) ^ sw) << 4));
-#pragma unroll
-                    for (int rw = 0; rw < RW; ++rw)
-                        s[rw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qreg[rw][k16], s[rw], 0, 0, 0);
-                }
-            }
-
-            // ---- mask, running max, exponentials
-            const bool full = !is_step && (key0 + 32 <= limit);  // wave-uniform
-            bf16x8 pf[RW][2];
-#pragma unroll
-            for (int rw = 0; rw < RW; ++rw) {
-                if (!full) {
-                    unsigned word;
-                    if (is_step) {
-                        word = step_block_word(vis[rw], key0);
-                    } else {
-                        const int n = limit - key0;  // 1..31
-                        word = (1u << n) - 1u;
-                    }
-                    word >>= hi * 4;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int bit = (i >> 2) * 8 + (i & 3);  // + hi*4 already shifted out
-                        if (!((word >> bit) & 1u)) s[rw][i] = kNegInf;
-                    }
-                }
-                float mx = s[rw][0];
-#pragma unroll
-                for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[rw][i]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-                const float m_new = fmaxf(m_run[rw], mx);
-                // scores are kept unscaled; exp(x/sqrt(d)) = exp2(x * scale_log2)
-                const float m_use = (m_new == kNegInf) ? 0.0f : m_new;
-                const float alpha = fast_exp2((m_run[rw] - m_use) * p.scale_log2);
-                const float neg_mc = -m_use * p.scale_log2;
-                float psum = 0.0f;
-                float pv[16];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    pv[i] = fast_exp2(__builtin_fmaf(s[rw][i], p.scale_log2, neg_mc));
-                    psum += pv[i];
-                }
-                l_run[rw] = l_run[rw] * alpha + psum;
-                m_run[rw] = m_new;
-                if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0ull) {
-#pragma unroll
-                    for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) o[rw][db][i] *= alpha;
-                }
-#pragma unroll
-                for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) pf[rw][kk][e] = (__bf16)pv[kk * 8 + e];
-            }
-
-            // ---- O^T += V^T P^T.  k-slot e of half `hi` of 16-key step kk is key
-            //      kb*32 + kk*16 + (e/4)*8 + hi*4 + e%4 (the layout S^T left P in).
-            {
-                const int b16 = lane >> 4;      // 16-lane block: reads 4 keys x 16 columns
-                const int i16 = lane & 15;
-                const int jj = i16 >> 2;        // key within the group of 4
-                const int q4 = i16 & 3;         // 4-column segment
-#pragma unroll
-                for (int kk = 0; kk < 2; ++kk) {
+                for (int k16 = 0; k16 < D / 16; ++k16)
+                    kf[k16] = *reinterpret_cast<const bf16x8*>(kr + (((k16 * 2 + hi) ^ ksw) << 4));
+                // V^T operand: k-slot e of half `hi` of 16-key step kk is key
+                // kb*32 + kk*16 + (e/4)*8 + hi*4 + e%4 (the layout S^T leaves P in).  A 16-lane
+                // block reads 4 keys x 16 columns; the transposing read hands lane n column n.
+                const int b16 = lane >> 4, i16 = lane & 15;
+                const int jj = i16 >> 2, q4 = i16 & 3;
+                bf16x8 vf[2][C::DB];
+                auto read_v = [&](int kk) {
                     const int vrow0 = kb * 32 + kk * 16 + hi * 4 + jj;  // e = 0..3
                     const int vrow1 = vrow0 + 8;                        // e = 4..7
                     const int sw0 = swizzle<D>(vrow0), sw1 = swizzle<D>(vrow1);
@@ -359,73 +390,167 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                         const int lc = col >> 3, within = (col & 7) * 2;
                         const unsigned char* a0 = vst + vrow0 * C::RBYTES + ((lc ^ sw0) << 4) + within;
                         const unsigned char* a1 = vst + vrow1 * C::RBYTES + ((lc ^ sw1) << 4) + within;
-                        const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (short4v __attribute__((address_space(3)))*)a0);
-                        const short4v hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (short4v __attribute__((address_space(3)))*)a1);
                         union { struct { short4v a, b; } s; bf16x8 v; } u;
-                        u.s.a = lo; u.s.b = hi4;
-#pragma unroll
-                        for (int rw = 0; rw < RW; ++rw)
-                            o[rw][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf[rw][kk], o[rw][db], 0, 0, 0);
+                        u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (short4v __attribute__((address_space(3)))*)a0);
+                        u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (short4v __attribute__((address_space(3)))*)a1);
+                        vf[kk][db] = u.v;
                     }
-                }
-            }
-        }
-    }
+                };
+                read_v(0);
+                __builtin_amdgcn_sched_barrier(0);
 
-    // the two half-waves of a row hold the sums over their own keys
+                // ---- S^T block: 32 keys x 32 rows per tile
+                f32x16 s[RW];
 #pragma unroll
-    for (int rw = 0; rw < RW; ++rw) l_run[rw] += __shfl_xor(l_run[rw], 32, 64);
+                for (int rw = 0; rw < RW; ++rw)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) s[rw][i] = 0.0f;
+#pragma unroll
+                for (int k16 = 0; k16 < D / 16; ++k16)
+#pragma unroll
+                    for (int rw = 0; rw < RW; ++rw)
+                        s[rw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[k16], qreg[rw][k16], s[rw], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                read_v(1);  // in flight during the softmax arithmetic
 
-    __syncthreads();  // all stages consumed: LDS is reused below
-
-    // ---- merge the KS waves of a row tile through LDS (fragment layout: [reg][lane])
-    if (KS > 1) {
-        float* mg = reinterpret_cast<float*>(lds);
-        if (ks > 0 && wave_active) {
-#pragma unroll
-            for (int rw = 0; rw < RW; ++rw) {
-                float* dst = mg + (((ks - 1) * RT + rt) * RW + rw) * C::TILE_FLOATS;
-#pragma unroll
-                for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) dst[(db * 16 + i) * 64 + lane] = o[rw][db][i];
-                dst[C::FRAG_FLOATS + lane] = m_run[rw];
-                dst[C::FRAG_FLOATS + 64 + lane] = l_run[rw];
-            }
-        }
-        __syncthreads();
-        if (ks == 0 && wave_active) {
-            for (int k2 = 1; k2 < KS; ++k2) {
+                // ---- mask, running max, exponentials
+                const bool full = !is_step && (key0 + 32 <= limit);  // wave-uniform
+                bf16x8 pf[RW][2];
 #pragma unroll
                 for (int rw = 0; rw < RW; ++rw) {
-                    const float* src = mg + (((k2 - 1) * RT + rt) * RW + rw) * C::TILE_FLOATS;
-                    const float m2 = src[C::FRAG_FLOATS + lane];
-                    const float l2 = src[C::FRAG_FLOATS + 64 + lane];
-                    const float m_new = fmaxf(m_run[rw], m2);
+                    if (!full) {
+                        unsigned word;
+                        if (is_step) {
+                            word = step_block_word(vis[rw], key0);
+                        } else {
+                            const int n = limit - key0;  // 1..31
+                            word = (1u << n) - 1u;
+                        }
+                        word >>= hi * 4;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const int bit = (i >> 2) * 8 + (i & 3);  // hi*4 already shifted out
+                            if (!((word >> bit) & 1u)) s[rw][i] = kNegInf;
+                        }
+                    }
+                    float mx = fmaxf(s[rw][0], s[rw][1]);
+#pragma unroll
+                    for (int i = 2; i < 16; i += 2) mx = fmaxf(mx, fmaxf(s[rw][i], s[rw][i + 1]));
+                    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                    // Scores stay unscaled; exp(x/sqrt(d)) = exp2(x * scale_log2).  The reference
+                    // m_run only moves when the block maximum exceeds it by more than 2^8 in the
+                    // exponent (or no key was seen yet): softmax is invariant to the reference, and
+                    // skipping small moves saves rescaling the accumulators nearly every time.
+                    const bool move = (mx - m_run[rw]) * p.scale_log2 > 8.0f || m_run[rw] == kNegInf;
+                    const float m_new = move ? mx : m_run[rw];
                     const float m_use = (m_new == kNegInf) ? 0.0f : m_new;
-                    const float a1 = fast_exp2((m_run[rw] - m_use) * p.scale_log2);
-                    const float a2 = fast_exp2((m2 - m_use) * p.scale_log2);
-                    l_run[rw] = l_run[rw] * a1 + l2 * a2;
+                    const float neg_mc = -m_use * p.scale_log2;
+                    if (__builtin_amdgcn_ballot_w64(move) != 0ull) {
+                        const float alpha = fast_exp2(__builtin_fmaf(m_run[rw], p.scale_log2, neg_mc));
+                        l_run[rw] *= alpha;
+#pragma unroll
+                        for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) o[rw][db][i] *= alpha;
+                    }
                     m_run[rw] = m_new;
+                    float psum0 = 0.0f, psum1 = 0.0f;
+                    float pv[16];
+#pragma unroll
+                    for (int i = 0; i < 16; i += 2) {
+                        pv[i] = fast_exp2(__builtin_fmaf(s[rw][i], p.scale_log2, neg_mc));
+                        pv[i + 1] = fast_exp2(__builtin_fmaf(s[rw][i + 1], p.scale_log2, neg_mc));
+                        psum0 += pv[i];
+                        psum1 += pv[i + 1];
+                    }
+                    l_run[rw] += psum0 + psum1;
+#pragma unroll
+                    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) pf[rw][kk][e] = (__bf16)pv[kk * 8 + e];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+
+                // ---- O^T += V^T P^T
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
                     for (int db = 0; db < C::DB; ++db)
 #pragma unroll
-                        for (int i = 0; i < 16; ++i)
-                            o[rw][db][i] = o[rw][db][i] * a1 + src[(db * 16 + i) * 64 + lane] * a2;
-                }
+                        for (int rw = 0; rw < RW; ++rw)
+                            o[rw][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kk][db], pf[rw][kk], o[rw][db], 0, 0, 0);
             }
         }
-        __syncthreads();
-    }
 
-    // ---- cross-workgroup combine (XS > 1): store partial, ticket, last arriver merges all
-    bool writer = (ks == 0) && wave_active;
-    if (p.XS > 1) {
+        LA_STAMP(3);
+#ifdef LA_DEV_KNOBS
+        if (p.dev_mode == 1 || p.dev_mode == 2) {  // stop after the main loop
+            if (l_run[0] == 123.456f) p.out[tid] = (__bf16)o[0][0][0];
+            return;
+        }
+#endif
+        // the two half-waves of a row hold the sums over their own keys
+#pragma unroll
+        for (int rw = 0; rw < RW; ++rw) l_run[rw] += __shfl_xor(l_run[rw], 32, 64);
+
+        __syncthreads();  // all stages consumed: LDS is reused below
+
+        // ---- merge the KS waves of a row tile through LDS (fragment layout: [4 regs][lane])
+        if (KS > 1) {
+            float* mg = reinterpret_cast<float*>(lds);
+            if (ks > 0 && wave_active) {
+#pragma unroll
+                for (int rw = 0; rw < RW; ++rw) {
+                    float* dst = mg + (((ks - 1) * RT + rt) * RW + rw) * C::TILE_FLOATS;
+#pragma unroll
+                    for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                        for (int i4 = 0; i4 < 4; ++i4) {
+                            f32x4 v = {o[rw][db][i4 * 4], o[rw][db][i4 * 4 + 1], o[rw][db][i4 * 4 + 2],
+                                       o[rw][db][i4 * 4 + 3]};
+                            *reinterpret_cast<f32x4*>(dst + ((db * 4 + i4) * 64 + lane) * 4) = v;
+                        }
+                    dst[C::FRAG_FLOATS + lane] = m_run[rw];
+                    dst[C::FRAG_FLOATS + 64 + lane] = l_run[rw];
+                }
+            }
+            __syncthreads();
+            if (ks == 0 && wave_active) {
+                for (int k2 = 1; k2 < KS; ++k2) {
+#pragma unroll
+                    for (int rw = 0; rw < RW; ++rw) {
+                        const float* src = mg + (((k2 - 1) * RT + rt) * RW + rw) * C::TILE_FLOATS;
+                        const float m2 = src[C::FRAG_FLOATS + lane];
+                        const float l2 = src[C::FRAG_FLOATS + 64 + lane];
+                        const float m_new = fmaxf(m_run[rw], m2);
+                        const float m_use = (m_new == kNegInf) ? 0.0f : m_new;
+                        const float a1 = fast_exp2((m_run[rw] - m_use) * p.scale_log2);
+                        const float a2 = fast_exp2((m2 - m_use) * p.scale_log2);
+                        l_run[rw] = l_run[rw] * a1 + l2 * a2;
+                        m_run[rw] = m_new;
+#pragma unroll
+                        for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                            for (int i4 = 0; i4 < 4; ++i4) {
+                                const f32x4 v = *reinterpret_cast<const f32x4*>(src + ((db * 4 + i4) * 64 + lane) * 4);
+#pragma unroll
+                                for (int e = 0; e < 4; ++e)
+                                    o[rw][db][i4 * 4 + e] = o[rw][db][i4 * 4 + e] * a1 + v[e] * a2;
+                            }
+                    }
+                }
+            }
+            __syncthreads();
+        }
+        LA_STAMP(4);
+        if (direct) break;
+
+        // ---- split combine: store this split's partial, then take a ticket
         const size_t wg_floats = (size_t)C::TILES * C::TILE_FLOATS;
         float* group_base = p.partials + (size_t)((kvh * p.n_row_blocks + rb) * p.XS) * wg_floats;
-        if (writer) {
+        if (ks == 0 && wave_active) {
 #pragma unroll
             for (int rw = 0; rw < RW; ++rw) {
                 float* dst = group_base + (size_t)xs * wg_floats + (size_t)(rt * RW + rw) * C::TILE_FLOATS;
@@ -441,57 +566,119 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                 dst[C::FRAG_FLOATS + 64 + lane] = l_run[rw];
             }
         }
-        __threadfence();
+        // Stores are acknowledged by the L2 of this XCD: wait for them, then publish.
+        __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        __shared__ unsigned is_last;
+        LA_STAMP(5);
         if (tid == 0) {
+            // One atomic carries the arrival count and, to tell whether every member of the group
+            // ran on the same XCD (and so shares one L2), the sum and the sum of squares of the
+            // members' XCD ids: XS * sum(x^2) == (sum x)^2 holds iff all ids are equal.
+            const unsigned x = xcc_id();
+            const unsigned mine = 1u | (x << 8) | ((x * x) << 18);
             unsigned* ticket = p.tickets + (kvh * p.n_row_blocks + rb);
-            const unsigned t = atomicAdd(ticket, 1u);
-            is_last = (t == (unsigned)p.XS - 1u) ? 1u : 0u;
-            if (is_last) *ticket = 0u;  // everyone has arrived; clean for the next call
+            const unsigned total = atomicAdd(ticket, mine) + mine;
+            const unsigned cnt = total & 0xffu, sum = (total >> 8) & 0x3ffu, sq = total >> 18;
+            unsigned role = 0;
+            if (cnt == (unsigned)p.XS) {
+                *ticket = 0u;  // everyone has arrived; clean for the next call
+                role = (sq * (unsigned)p.XS == sum * sum && !p.force_recompute) ? 1u : 2u;
+            }
+            s_role = role;
         }
         __syncthreads();
-        if (!is_last) return;
-        __threadfence();
-        if (writer) {
+        const unsigned role = s_role;
+        LA_STAMP(6);
+        if (role == 0) return;
+#ifdef LA_DEV_KNOBS
+        if (p.dev_mode == 4) return;  // everything but the final merge
+#endif
+        if (role == 1) {
+            // ---- last to arrive, all partials sit in the L2 this XCD shares: merge them in
+            //      index order.  Work unit: one (tile, 32-column block); a wave takes two units
+            //      at a time and requests all their partials before merging any, so that the
+            //      usual case (at most 4 splits) costs one trip to the L2.
+            constexpr int NSUB = C::TILES * C::DB;
+            constexpr int NU = RW == 1 ? 2 : 1;  // units in flight per wave
+            constexpr int MB = RW == 1 ? 4 : 2;  // splits requested at a time
+            for (int st0 = wave; st0 < NSUB; st0 += NU * C::NW) {
+                float m_acc[NU], l_acc[NU];
+                float acc[NU][16];
 #pragma unroll
-            for (int rw = 0; rw < RW; ++rw) {
-                m_run[rw] = kNegInf;
-                l_run[rw] = 0.0f;
+                for (int u = 0; u < NU; ++u) {
+                    m_acc[u] = kNegInf;
+                    l_acc[u] = 0.0f;
 #pragma unroll
-                for (int db = 0; db < C::DB; ++db)
+                    for (int i = 0; i < 16; ++i) acc[u][i] = 0.0f;
+                }
+                for (int s0 = 0; s0 < p.XS; s0 += MB) {
+                    float m2[NU][MB], l2[NU][MB];
+                    f32x4 v[NU][MB][4];
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) o[rw][db][i] = 0.0f;
-            }
-            for (int s2 = 0; s2 < p.XS; ++s2) {
+                    for (int u = 0; u < NU; ++u) {
+                        const int st = min(st0 + u * C::NW, NSUB - 1);
+                        const int tile = st / C::DB, db = st - tile * C::DB;
+                        const float* src0 = group_base + (size_t)tile * C::TILE_FLOATS;
 #pragma unroll
-                for (int rw = 0; rw < RW; ++rw) {
-                    const float* src = group_base + (size_t)s2 * wg_floats + (size_t)(rt * RW + rw) * C::TILE_FLOATS;
-                    const float m2 = __builtin_nontemporal_load(src + C::FRAG_FLOATS + lane);
-                    const float l2 = __builtin_nontemporal_load(src + C::FRAG_FLOATS + 64 + lane);
-                    const float m_new = fmaxf(m_run[rw], m2);
-                    const float m_use = (m_new == kNegInf) ? 0.0f : m_new;
-                    const float a1 = fast_exp2((m_run[rw] - m_use) * p.scale_log2);
-                    const float a2 = fast_exp2((m2 - m_use) * p.scale_log2);
-                    l_run[rw] = l_run[rw] * a1 + l2 * a2;
-                    m_run[rw] = m_new;
+                        for (int w = 0; w < MB; ++w) {
+                            const int s2 = min(s0 + w, p.XS - 1);
+                            const float* src = src0 + (size_t)s2 * wg_floats;
+                            m2[u][w] = src[C::FRAG_FLOATS + lane];
+                            l2[u][w] = src[C::FRAG_FLOATS + 64 + lane];
 #pragma unroll
-                    for (int db = 0; db < C::DB; ++db)
+                            for (int i4 = 0; i4 < 4; ++i4)
+                                v[u][w][i4] = *reinterpret_cast<const f32x4*>(src + ((db * 4 + i4) * 64 + lane) * 4);
+                        }
+                    }
 #pragma unroll
-                        for (int i4 = 0; i4 < 4; ++i4) {
-                            const f32x4 v = __builtin_nontemporal_load(
-                                reinterpret_cast<const f32x4*>(src + ((db * 4 + i4) * 64 + lane) * 4));
+                    for (int u = 0; u < NU; ++u)
 #pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                o[rw][db][i4 * 4 + e] = o[rw][db][i4 * 4 + e] * a1 + v[e] * a2;
+                        for (int w = 0; w < MB; ++w) {
+                            if (s0 + w >= p.XS) break;
+                            const float m_new = fmaxf(m_acc[u], m2[u][w]);
+                            const float m_use = (m_new == kNegInf) ? 0.0f : m_new;
+                            const float a1 = fast_exp2((m_acc[u] - m_use) * p.scale_log2);
+                            const float a2 = fast_exp2((m2[u][w] - m_use) * p.scale_log2);
+                            l_acc[u] = l_acc[u] * a1 + l2[u][w] * a2;
+                            m_acc[u] = m_new;
+#pragma unroll
+                            for (int i4 = 0; i4 < 4; ++i4)
+#pragma unroll
+                                for (int e = 0; e < 4; ++e)
+                                    acc[u][i4 * 4 + e] = acc[u][i4 * 4 + e] * a1 + v[u][w][i4][e] * a2;
                         }
                 }
+#pragma unroll
+                for (int u = 0; u < NU; ++u) {
+                    const int st = st0 + u * C::NW;
+                    if (st >= NSUB) break;
+                    const int tile = st / C::DB, db = st - tile * C::DB;
+                    const float inv = 1.0f / l_acc[u];
+                    unsigned char* row_ptr = lds + (tile * 32 + l32) * C::OUT_PITCH;
+#pragma unroll
+                    for (int i4 = 0; i4 < 4; ++i4) {
+                        bf16x4 ov;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(acc[u][i4 * 4 + e] * inv);
+                        *reinterpret_cast<bf16x4*>(row_ptr + (db * 32 + i4 * 8 + hi * 4) * 2) = ov;
+                    }
+                }
             }
+            __syncthreads();
+            write_rows_from_lds<C>(p, lds, rb, kvh, tid);
+            LA_STAMP(7);
+            return;
         }
+        // ---- role 2: the group was spread over several XCDs, whose L2s are not coherent with
+        //      each other inside a kernel.  Inputs are read-only and always coherent, so the last
+        //      workgroup simply recomputes its rows over every chunk and writes them directly.
+        c_begin = 0;
+        c_end = p.n_chunks;
+        direct = true;
     }
 
     // ---- normalise, transpose through LDS, write bf16 rows with 16-byte stores
-    if (writer) {
+    if (ks == 0 && wave_active) {
 #pragma unroll
         for (int rw = 0; rw < RW; ++rw) {
             const float inv = 1.0f / l_run[rw];  // >= 1 visible key per row, so l > 0
@@ -509,23 +696,14 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
         }
     }
     __syncthreads();
-    {
-        const int rows_here = min(C::ROWS, p.R - rb * C::ROWS);
-        for (int piece = tid; piece < rows_here * C::NCH; piece += C::NT) {
-            const int r = piece / C::NCH, ch = piece % C::NCH;
-            const int rr = rb * C::ROWS + r;
-            const int t = rr / p.group, hh = rr - t * p.group;
-            const f32x4 v = *reinterpret_cast<const f32x4*>(lds + r * C::OUT_PITCH + ch * 16);
-            *reinterpret_cast<f32x4*>(p.out + ((size_t)t * p.heads + (size_t)kvh * p.group + hh) * D + ch * 8) = v;
-        }
-    }
+    write_rows_from_lds<C>(p, lds, rb, kvh, tid);
 }
 
 // ---------------------------------------------------------------------------------------
 // host side
 
 struct Plan {
-    int RW, RT, KS, XS;
+    int RW, RT, KS, XS, NS;   // NS = LDS stages (chunks in flight + 1)
     int n_row_blocks;
     int n_prefix_chunks, n_chunks;
     size_t partial_floats_per_wg;
@@ -533,8 +711,17 @@ struct Plan {
 
 constexpr int kKC = 64;
 
-bool plan_supported(int D, int RW, int RT, int KS)
+// Most LDS stages (chunks in flight + 1) that fit beside the workgroup's Q rows.
+int max_stages(int D, int RW, int RT)
 {
+    const int tiles = RW * RT;
+    if (D != 128) return 4;
+    return tiles <= 2 ? 4 : (tiles <= 4 ? 3 : 2);
+}
+
+bool plan_supported(int D, int RW, int RT, int KS, int NS)
+{
+    if (NS != 2 && NS != max_stages(D, RW, RT)) return false;
     if (D == 128)
         return (RW == 1 && ((RT == 1 && KS == 2) || (RT == 2 && KS == 2) || (RT == 4 && KS == 1) ||
                             (RT == 2 && KS == 1))) ||
@@ -554,13 +741,15 @@ Plan make_plan(int P, int T, int group, int kv_heads, int D)
     else if (tiles <= 8) { pl.RW = 1; pl.RT = 4; pl.KS = 1; }
     else { pl.RW = 2; pl.RT = 4; pl.KS = 1; }
     pl.XS = 0;
-    // developer override: LA_ATTN_PLAN="RW,RT,KS,XS" (XS = 0 keeps the heuristic)
+    pl.NS = 0;
+    // developer override: LA_ATTN_PLAN="RW,RT,KS,XS,NS" (XS = 0 keeps the heuristic)
     if (const char* env = getenv("LA_ATTN_PLAN")) {
-        int a = 0, b = 0, c = 0, d = 0;
-        if (sscanf(env, "%d,%d,%d,%d", &a, &b, &c, &d) == 4 && plan_supported(D, a, b, c)) {
-            pl.RW = a; pl.RT = b; pl.KS = c; pl.XS = d;
+        int a = 0, b = 0, c = 0, d = 0, e = 0;
+        if (sscanf(env, "%d,%d,%d,%d,%d", &a, &b, &c, &d, &e) == 5 && plan_supported(D, a, b, c, e)) {
+            pl.RW = a; pl.RT = b; pl.KS = c; pl.XS = d; pl.NS = e;
         }
     }
+    if (pl.NS == 0) pl.NS = max_stages(D, pl.RW, pl.RT);
     const int rows_wg = pl.RT * pl.RW * 32;
     pl.n_row_blocks = (R + rows_wg - 1) / rows_wg;
     if (pl.XS <= 0) {
@@ -576,10 +765,9 @@ Plan make_plan(int P, int T, int group, int kv_heads, int D)
     return pl;
 }
 
-template <int D, int RW, int RT, int KS>
+template <int D, int RW, int RT, int KS, int NSTAGE>
 la_status launch_cfg(const AttnParams& prm, hipStream_t stream)
 {
-    constexpr int NSTAGE = 2;
     using C = Cfg<D, RW, RT, KS, kKC, NSTAGE>;
     auto kern = step_attention_kernel<D, RW, RT, KS, kKC, NSTAGE>;
     static bool attr_set[16] = {false};
@@ -638,6 +826,15 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
     prm.total_wg = (int)total;
     prm.wg_per_xcd = (int)((total + 7) / 8);
     prm.scale_log2 = 1.4426950408889634f / sqrtf((float)head_dim);
+    // testing hook: exercise the path taken when a split group is not on one XCD
+    const char* fr = getenv("LA_FORCE_RECOMPUTE");
+    prm.force_recompute = (fr && fr[0] == '1') ? 1 : 0;
+#ifdef LA_DEV_KNOBS
+    const char* dm = getenv("LA_DEV_MODE");
+    prm.dev_mode = dm ? atoi(dm) : 0;
+    const char* tp = getenv("LA_DEV_TRACE_PTR");
+    prm.dev_trace = tp ? (long long*)strtoull(tp, nullptr, 16) : nullptr;
+#endif
 
     if (pl.XS > 1) {
         const size_t ticket_bytes = (size_t)kv_heads * pl.n_row_blocks * sizeof(unsigned);
@@ -648,18 +845,20 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
         if (!prm.partials) return LA_ENOMEM;
     }
 
-#define LA_DISPATCH(D_, RW_, RT_, KS_)                                              \
-    if (head_dim == D_ && pl.RW == RW_ && pl.RT == RT_ && pl.KS == KS_)             \
-        return launch_cfg<D_, RW_, RT_, KS_>(prm, stream);
-    LA_DISPATCH(128, 1, 1, 2)
-    LA_DISPATCH(128, 1, 2, 2)
-    LA_DISPATCH(128, 1, 2, 1)
-    LA_DISPATCH(128, 1, 4, 1)
-    LA_DISPATCH(128, 2, 2, 2)
-    LA_DISPATCH(128, 2, 4, 1)
-    LA_DISPATCH(64, 1, 1, 2)
-    LA_DISPATCH(64, 1, 2, 2)
-    LA_DISPATCH(64, 1, 4, 1)
+#define LA_DISPATCH(D_, RW_, RT_, KS_, NSMAX_)                                       \
+    if (head_dim == D_ && pl.RW == RW_ && pl.RT == RT_ && pl.KS == KS_) {           \
+        if (pl.NS == 2) return launch_cfg<D_, RW_, RT_, KS_, 2>(prm, stream);       \
+        return launch_cfg<D_, RW_, RT_, KS_, NSMAX_>(prm, stream);                  \
+    }
+    LA_DISPATCH(128, 1, 1, 2, 4)
+    LA_DISPATCH(128, 1, 2, 2, 4)
+    LA_DISPATCH(128, 1, 2, 1, 4)
+    LA_DISPATCH(128, 1, 4, 1, 3)
+    LA_DISPATCH(128, 2, 2, 2, 3)
+    LA_DISPATCH(128, 2, 4, 1, 2)
+    LA_DISPATCH(64, 1, 1, 2, 4)
+    LA_DISPATCH(64, 1, 2, 2, 4)
+    LA_DISPATCH(64, 1, 4, 1, 4)
 #undef LA_DISPATCH
     return fail(LA_EUNSUPPORTED, "la_step_attention: no kernel for head_dim=%d plan (%d,%d,%d)",
                 head_dim, pl.RW, pl.RT, pl.KS);

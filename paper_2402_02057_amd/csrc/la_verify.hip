@@ -7,9 +7,13 @@
 // winner is folded into one 64-bit key per row with atomicMax,
 //     key = (order-preserving image of the fp32 value) << 32 | (0xFFFFFFFF - index),
 // so the largest value wins and, among equal values, the lowest index: the result does
-// not depend on the order in which workgroups finish.  The workgroup that finishes last
-// (a ticket counter) turns the keys into `accepted` and `accept_len` and zeroes keys and
-// ticket again, so the workspace is clean for the next call without a memset.
+// not depend on the order in which workgroups finish.  Each candidate has a ticket counter;
+// the workgroup that finishes last among a candidate's (N-1) x segments workgroups turns that
+// candidate's keys into `accepted` and `accept_len` and zeroes keys and ticket again, so the
+// workspace is clean for the next call without a memset.  Keys and tickets are touched only
+// by device-scope atomics that return their old value (the ticket is taken after the key
+// update has come back), so no cache write-back or invalidate is needed: those cost tens of
+// microseconds on this part, more than the whole scan.
 #include "la_internal.h"
 
 namespace la {
@@ -38,7 +42,7 @@ __device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long x,
 template <bool kVec>
 __global__ __launch_bounds__(kThreads) void verify_kernel(
     const float* __restrict__ logits, const int* __restrict__ cand_tokens, int G, int n1, int V,
-    int seg_len, int nseg, unsigned long long* keys, unsigned* ticket,
+    int seg_len, int nseg, unsigned long long* keys, unsigned* tickets,
     int* __restrict__ accept_len, int* __restrict__ accepted)
 {
     const int row = blockIdx.x / nseg;
@@ -85,35 +89,32 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(
         unsigned long long k = wave_key[0];
 #pragma unroll
         for (int w = 1; w < kWaves; ++w) k = wave_key[w] > k ? wave_key[w] : k;
-        atomicMax(&keys[row], k);
-        __threadfence();
-        const unsigned t = atomicAdd(ticket, 1u);
-        last_flag = (t == gridDim.x - 1) ? 1u : 0u;
+        // returning atomics: the ticket is requested only after the key update has come back
+        const unsigned long long before = atomicMax(&keys[row], k);
+        asm volatile("" ::"v"((unsigned)before) : "memory");  // consume the returned value first
+        const int g = row / n1;
+        const unsigned t = atomicAdd(&tickets[g], 1u);
+        last_flag = (t == (unsigned)(n1 * nseg) - 1u) ? 1u : 0u;
     }
     __syncthreads();
     if (!last_flag) return;
 
-    // Last workgroup: every key is final.
-    __threadfence();
-    const int rows = G * n1;
-    for (int r = tid; r < rows; r += kThreads) {
-        const unsigned long long k =
-            __hip_atomic_load(&keys[r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        accepted[r] = (int)(0xFFFFFFFFu - (unsigned)k);
-    }
-    for (int g = tid; g < G; g += kThreads) {
+    // Last workgroup of candidate g: its N-1 keys are final.  Read them with atomics too.
+    if (tid == 0) {
+        const int g = row / n1;
         int len = 0;
-        while (len < n1) {
-            const unsigned long long k =
-                __hip_atomic_load(&keys[g * n1 + len], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if ((int)(0xFFFFFFFFu - (unsigned)k) != cand_tokens[g * n1 + len]) break;
-            ++len;
+        bool run = true;
+        for (int k = 0; k < n1; ++k) {
+            const unsigned long long key = atomicMax(&keys[g * n1 + k], 0ull);
+            const int tok = (int)(0xFFFFFFFFu - (unsigned)key);
+            accepted[g * n1 + k] = tok;
+            run = run && (tok == cand_tokens[g * n1 + k]);
+            len += run ? 1 : 0;
         }
         accept_len[g] = len;
+        for (int k = 0; k < n1; ++k) atomicExch(&keys[g * n1 + k], 0ull);
+        atomicExch(&tickets[g], 0u);
     }
-    __syncthreads();
-    for (int r = tid; r < rows; r += kThreads) keys[r] = 0ull;
-    if (tid == 0) *ticket = 0u;
 }
 
 }  // namespace
@@ -135,8 +136,8 @@ la_status launch_verify(const float* logits, const int* cand_tokens, int G, int 
     const long long blocks = (long long)rows * nseg;
     if (blocks > 0x7fffffffll) return fail(LA_EINVAL, "la_verify: too many workgroups");
 
-    // workspace: one 64-bit key per row, then the ticket
-    const size_t bytes = (size_t)rows * 8 + 8;
+    // workspace: one 64-bit key per row, then one ticket per candidate
+    const size_t bytes = (size_t)rows * 8 + (size_t)G * 4;
     char* ws = (char*)zeroed_workspace(bytes, stream);
     if (!ws) return LA_ENOMEM;
     unsigned long long* keys = (unsigned long long*)ws;

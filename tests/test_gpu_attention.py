@@ -167,6 +167,28 @@ def test_ragged_long_context(seq, W):
           s.name)
 
 
+def test_recompute_path_for_groups_not_on_one_xcd(monkeypatch):
+    """Force the path the last workgroup takes when its split group is spread over several
+    XCDs (it recomputes from the inputs instead of reading the other workgroups' partials)."""
+    monkeypatch.setenv("LA_FORCE_RECOMPUTE", "1")
+    for s in (wl.LLAMA2_7B, wl.LLAMA2_70B, wl.TINY):
+        check(wl.attention_inputs(s), s.P, s.W, s.N, s.G, s.heads, s.kv_heads, s.head_dim,
+              s.name + "-recompute")
+    x = rand_inputs(77, 333, 15, 5, 15, 4, 4, 128)
+    check(x, 333, 15, 5, 15, 4, 4, 128, "recompute-small")
+
+
+@pytest.mark.parametrize("plan", ["1,1,2,3,2", "1,2,2,5,4", "1,2,1,7,4", "1,4,1,2,2", "2,2,2,3,4",
+                                  "2,4,1,4,2", "1,4,1,1,4", "1,2,2,1,2"])
+def test_every_kernel_variant(monkeypatch, plan):
+    """Each compiled decomposition (rows per wave, row tiles, key-split waves, splits, stages)."""
+    monkeypatch.setenv("LA_ATTN_PLAN", plan)
+    x = rand_inputs(123, 777, 9, 5, 9, 8, 2, 128)      # R = 292 rows per KV head
+    check(x, 777, 9, 5, 9, 8, 2, 128, "plan " + plan)
+    x = rand_inputs(124, 130, 2, 3, 1, 2, 2, 128)      # R = 7
+    check(x, 130, 2, 3, 1, 2, 2, 128, "plan " + plan)
+
+
 def test_errors_surface_as_exceptions():
     z = torch.zeros((1, 4, 96), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(binding.LaError) as e:
