@@ -49,7 +49,10 @@ def main():
     ap.add_argument("--workload", default="llama2-7b", choices=sorted(LAYERS))
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--graph", action="store_true", help="replay each step as one HIP graph")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="launch every call from Python instead of replaying the step as one HIP graph")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 64 MiB device copy a few times (reference for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus %d is not supported "
@@ -95,7 +98,8 @@ def main():
     step()
     torch.cuda.synchronize()
     run_step = step
-    if args.graph:
+    use_graph = not args.no_graph
+    if use_graph:
         g = torch.cuda.CUDAGraph()
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
@@ -122,15 +126,28 @@ def main():
     reps = max(10, min(args.steps, 100))
     e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
     attn_ms, ver_ms = [], []
+    if use_graph:
+        # the L attention launches alone, and the verify launch alone, as graphs
+        ga, gv = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+        with torch.cuda.graph(ga):
+            attention_layers()
+        with torch.cuda.graph(gv):
+            for _ in range(8):
+                binding.la_verify(logits, cand, s.G, s.N, s.V, alen, acc)
+        run_attn, run_ver, ver_calls = ga.replay, gv.replay, 8
+    else:
+        run_attn = attention_layers
+        run_ver = lambda: binding.la_verify(logits, cand, s.G, s.N, s.V, alen, acc)
+        ver_calls = 1
     for _ in range(reps):
         e[0].record()
-        attention_layers()
+        run_attn()
         e[1].record()
-        binding.la_verify(logits, cand, s.G, s.N, s.V, alen, acc)
+        run_ver()
         e[2].record()
         torch.cuda.synchronize()
         attn_ms.append(e[0].elapsed_time(e[1]))
-        ver_ms.append(e[1].elapsed_time(e[2]))
+        ver_ms.append(e[1].elapsed_time(e[2]) / ver_calls)
     attn_us = float(np.median(attn_ms)) * 1e3 / L       # per launch, launch gaps included
     verify_us = float(np.median(ver_ms)) * 1e3
     abytes = algorithmic_bytes(s)
@@ -149,6 +166,14 @@ def main():
     roof["us_per_launch"] = attn_us
     roof["algorithmic_bytes"] = abytes
     roof["algorithmic_flops"] = aflops
+
+    if args.copy_calibration:
+        # a copy kernel of known size: 64 MiB read + 64 MiB written per launch
+        src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda").random_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     # ---- validity: layer 0 and the verification against the CPU oracle
     from oracle import la_oracle as orc
@@ -186,7 +211,7 @@ def main():
         "config": {"workload": "%s: H%d/KV%d/d%d P=%d W=%d N=%d G=%d (T=%d), %d layers + verify "
                                "[%d,%d,%d] fp32" % (s.name, H, KV, d, P, s.W, s.N, s.G, T, L, s.G,
                                                      s.N - 1, s.V),
-                   "layers": L, "graph": bool(args.graph)},
+                   "layers": L, "graph": use_graph},
         "roofline": roof,
         "cpu_baseline": cpu,
         "verify_us": verify_us,

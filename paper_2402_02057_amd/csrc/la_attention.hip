@@ -50,6 +50,7 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float kNegInf = -__builtin_huge_valf();
 
@@ -60,7 +61,7 @@ struct AttnParams {
     const __bf16* step_k;
     const __bf16* step_v;
     __bf16* out;
-    float* partials;    // XS > 1: per workgroup, fragment-layout accumulators and (m, l)
+    void* partials;     // XS > 1: per workgroup, fragment-layout bf16 accumulators and fp32 (m, l)
     unsigned* tickets;  // XS > 1: one counter per (KV head, row block), zero between calls
     int P, W, N, G, T;
     int heads, kv_heads, group;
@@ -72,6 +73,11 @@ struct AttnParams {
     int total_wg;         // kv_heads * n_row_blocks * XS
     int wg_per_xcd;       // ceil(total_wg / 8)
     float scale_log2;     // log2(e) / sqrt(head_dim)
+    // Integer division costs dozens of instructions, and a wave issues about one instruction
+    // every four cycles: quotients by these small divisors are taken with a float reciprocal
+    // (exact while the dividend stays below 2^21, which the host checks).
+    float inv_XS, inv_row_blocks, inv_group, inv_W, inv_n1;
+    int chunks_lo, chunks_rem;  // n_chunks = XS * chunks_lo + chunks_rem
     int force_recompute;  // testing: treat every group as spread over several XCDs
 #ifdef LA_DEV_KNOBS
     int dev_mode;         // timing experiments only (results are wrong): see LA_DEV_MODE
@@ -87,7 +93,14 @@ struct RowVis {
     int cnt;
 };
 
-__device__ __forceinline__ RowVis row_visibility(int t, int W, int N)
+// floor(a / d) for 0 <= a < 2^21 given inv = 1.0f / d: (a + 0.5) / d is at least 0.5 / d away
+// from an integer, more than the rounding error of the two float operations.
+__device__ __forceinline__ int div_small(int a, float inv)
+{
+    return (int)(((float)a + 0.5f) * inv);
+}
+
+__device__ __forceinline__ RowVis row_visibility(int t, int W, int N, float inv_W, float inv_n1)
 {
     RowVis v;
     v.t = t;
@@ -96,11 +109,11 @@ __device__ __forceinline__ RowVis row_visibility(int t, int W, int N)
         v.e0 = 0; v.s1 = 1; v.cnt = 1;
     } else if (t <= n_look) {
         const int x = t - 1;
-        const int l = x / W, j = x - l * W;
+        const int l = div_small(x, inv_W), j = x - l * W;
         v.e0 = 1 + j; v.s1 = W; v.cnt = l + 1;
     } else {
         const int x = t - 1 - n_look;
-        const int k = x % (N - 1);
+        const int k = x - div_small(x, inv_n1) * (N - 1);
         v.e0 = 0; v.s1 = 1; v.cnt = k + 1;
     }
     return v;
@@ -120,6 +133,25 @@ __device__ __forceinline__ unsigned step_block_word(const RowVis& v, int key0)
     return w;
 }
 
+// Three-way maximum in one instruction; unlike fmaxf the compiler adds no NaN-quieting moves
+// around it (scores are MFMA results or -inf, never signalling NaNs).
+__device__ __forceinline__ float max3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// max of a value with the one held by the lane 32 away (the other 16 keys of the same row).
+// v_permlane32_swap exchanges the upper half of its first operand with the lower half of its
+// second: fed the same value twice it returns (lower half everywhere, upper half everywhere).
+__device__ __forceinline__ float max_across_halves(float x)
+{
+    const unsigned u = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 template <int N>
@@ -133,11 +165,13 @@ __device__ __forceinline__ void wait_vmcnt()
 // assembly so that the compiler's wait-count bookkeeping does not know of these loads: it would
 // otherwise make every later LDS read wait for ALL of them, including the chunks being
 // prefetched.  Completion is tracked by hand: s_waitcnt vmcnt(n) + workgroup barrier.
-__device__ __forceinline__ void dma16(const void* src, unsigned lds_base)
+// The address is a wave-uniform 64-bit base in scalar registers plus a 32-bit per-lane byte
+// offset: no 64-bit vector arithmetic per load.
+__device__ __forceinline__ void dma16_base(const void* base, unsigned lane_off, unsigned lds_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
-                 : "v"(src), "s"(lds_base)
+                 : "v"(lane_off), "s"(base), "s"(lds_base)
                  : "memory");
 }
 
@@ -171,12 +205,17 @@ struct Cfg {
     static constexpr int DB = D / 32;                     // 32-wide blocks of head_dim
     static constexpr int FRAG_FLOATS = DB * 16 * 64;      // one tile's accumulators
     static constexpr int TILE_FLOATS = FRAG_FLOATS + 128; // + m and l per lane
+    // a split's partial in global memory: per tile the accumulators as bf16 in fragment order
+    // ([8 values][lane], 16 bytes per lane and access) followed by (m, l) per lane in fp32
+    static constexpr int PART_ACC_BYTES = DB * 16 * 64 * 2;
+    static constexpr int PART_TILE_BYTES = PART_ACC_BYTES + 64 * 8;
+    static constexpr int PART_WG_BYTES = TILES * PART_TILE_BYTES;
     static constexpr int OUT_PITCH = RBYTES + 16;         // LDS pitch of the output transpose
     static constexpr int Q_BYTES = ROWS * RBYTES;         // the workgroup's query rows
     static constexpr int Q_OFFSET = NSTAGE * STAGE_BYTES; // they sit behind the stage ring
     static constexpr int QLPW = Q_BYTES / 1024 / NW;      // Q loads per wave
     static constexpr int LDS_MAIN = NSTAGE * STAGE_BYTES + Q_BYTES;
-    static constexpr int LDS_MERGE = (KS - 1) * RT * RW * TILE_FLOATS * 4;
+    static constexpr int LDS_MERGE = (KS / 2) * RT * RW * TILE_FLOATS * 4;
     static constexpr int LDS_OUT = ROWS * OUT_PITCH;
     static constexpr int LDS_BYTES =
         LDS_MAIN > LDS_MERGE ? (LDS_MAIN > LDS_OUT ? LDS_MAIN : LDS_OUT)
@@ -184,12 +223,12 @@ struct Cfg {
     static_assert(KB % KS == 0, "key blocks of a chunk must divide among the key-split waves");
     static_assert(WLOADS % NW == 0, "chunk loads must divide among the waves");
     static_assert((Q_BYTES / 1024) % NW == 0, "Q loads must divide among the waves");
-    static_assert(LPW * (NSTAGE - 1) + QLPW < 64, "vmcnt is a 6-bit counter");
+    static_assert(LPW * (NSTAGE - 1) < 64, "vmcnt is a 6-bit counter");
     static_assert(LDS_BYTES <= 160 * 1024 - 64, "LDS of a compute unit");
 };
 
 #ifdef LA_DEV_KNOBS
-#define LA_STAMP(k) do { if (p.dev_trace && threadIdx.x == 0) p.dev_trace[(size_t)blockIdx.x * 8 + (k)] = wall_clock64(); } while (0)
+#define LA_STAMP(k) do { if (p.dev_trace && (threadIdx.x & 63) == 0) p.dev_trace[((size_t)blockIdx.x * 8 + (threadIdx.x >> 6)) * 24 + (k)] = wall_clock64(); } while (0)
 #else
 #define LA_STAMP(k) do { } while (0)
 #endif
@@ -211,7 +250,7 @@ __device__ __forceinline__ void write_rows_from_lds(const AttnParams& p, const u
     for (int piece = tid; piece < rows_here * C::NCH; piece += C::NT) {
         const int r = piece / C::NCH, ch = piece % C::NCH;
         const int rr = rb * C::ROWS + r;
-        const int t = rr / p.group, hh = rr - t * p.group;
+        const int t = div_small(rr, p.inv_group), hh = rr - t * p.group;
         const f32x4 v = *reinterpret_cast<const f32x4*>(lds + r * C::OUT_PITCH + ch * 16);
         *reinterpret_cast<f32x4*>(p.out + ((size_t)t * p.heads + (size_t)kvh * p.group + hh) * D + ch * 8) = v;
     }
@@ -226,11 +265,15 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
     // Consecutive workgroup ids go round-robin over the 8 XCDs (each with its own L2); put
     // the workgroups that stream the same KV head on one XCD.
     LA_STAMP(0);
-    const int logical = (int)(blockIdx.x & 7) * p.wg_per_xcd + (int)(blockIdx.x >> 3);
+    int logical = (int)(blockIdx.x & 7) * p.wg_per_xcd + (int)(blockIdx.x >> 3);
+#ifdef LA_DEV_KNOBS
+    if (p.dev_mode >= 16) logical = (int)blockIdx.x;  // experiment: no XCD grouping (wrong combine!)
+#endif
     if (logical >= p.total_wg) return;
-    const int xs = logical % p.XS;
-    const int rb = (logical / p.XS) % p.n_row_blocks;
-    const int kvh = logical / (p.XS * p.n_row_blocks);
+    const int unit = div_small(logical, p.inv_XS);       // (kvh, rb) pair
+    const int xs = logical - unit * p.XS;
+    const int kvh = div_small(unit, p.inv_row_blocks);
+    const int rb = unit - kvh * p.n_row_blocks;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -245,38 +288,65 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
     const bool wave_active = row_base < p.R;            // else: only helps loading
 
     // ---- chunk range of this split
-    int c_begin = (int)(((long long)xs * p.n_chunks) / p.XS);
-    int c_end = (int)(((long long)(xs + 1) * p.n_chunks) / p.XS);
+    int c_begin = xs * p.chunks_lo + min(xs, p.chunks_rem);
+    int c_end = c_begin + p.chunks_lo + (xs < p.chunks_rem ? 1 : 0);
     bool direct = p.XS == 1;  // this pass covers every key of the rows: write `out` directly
 
-    // Issue the direct-to-LDS loads of chunk `c` into stage `st`.
+    // Per-lane part of a load's address.  A wave-load covers RPW = 64 / NCH consecutive rows of
+    // 16-byte pieces; with row = wl*RPW + lane_row the swizzle splits into a lane part and a part that
+    // depends only on the (wave-uniform) load index wl, so the byte offset of a lane is
+    // lane_off ^ (uni(wl) << 4) and the rest of the address is uniform.
+    const int lane_row = lane / C::NCH;
+    const int lane_lc0 = (lane % C::NCH) ^ (D == 128 ? (lane_row << 2) : (lane_row >> 1));
+    const unsigned lane_off = (unsigned)(lane_row * C::RBYTES + (lane_lc0 << 4));
+
+    // Issue the direct-to-LDS loads of chunk `c` into stage `st`: a wave-uniform 64-bit base
+    // plus a 32-bit lane offset per load.
     auto issue_chunk = [&](int c, int st) {
         const bool is_step = c >= p.n_prefix_chunks;
         const int key0 = (is_step ? c - p.n_prefix_chunks : c) * KC;
         const int limit = is_step ? p.T : p.P;
         const int last_row = min(KC, limit - key0) - 1;  // >= 0
-        const size_t stride = is_step ? (size_t)p.kv_heads * D : (size_t)D;
-        const __bf16* kbase = is_step ? p.step_k + ((size_t)key0 * p.kv_heads + kvh) * D
-                                      : p.k_cache + ((size_t)kvh * p.P + key0) * D;
-        const __bf16* vbase = is_step ? p.step_v + ((size_t)key0 * p.kv_heads + kvh) * D
-                                      : p.v_cache + ((size_t)kvh * p.P + key0) * D;
+        const unsigned stage_lds = lds_base + st * C::STAGE_BYTES;
+        // rows of the prefix cache are contiguous; step keys are strided by kv_heads
+        const unsigned stride_b = (unsigned)(is_step ? p.kv_heads * C::RBYTES : C::RBYTES);
+        const size_t first = is_step ? ((size_t)key0 * p.kv_heads + kvh) * D
+                                     : ((size_t)kvh * p.P + key0) * D;
+        const unsigned char* kbase = reinterpret_cast<const unsigned char*>((is_step ? p.step_k : p.k_cache) + first);
+        const unsigned char* vbase = reinterpret_cast<const unsigned char*>((is_step ? p.step_v : p.v_cache) + first);
+        if (!is_step && last_row == KC - 1) {
+            // a full chunk of the prefix cache: K and V are contiguous KV_BYTES regions
 #pragma unroll
-        for (int i = 0; i < C::LPW; ++i) {
-            const int wl = wave + i * C::NW;                  // wave-load index in the chunk
-            const bool is_v = wl >= C::WLOADS / 2;
-            const int piece = (is_v ? wl - C::WLOADS / 2 : wl) * 64 + lane;
-            const int row = piece / C::NCH;
-            const int pc = piece % C::NCH;
-            const int lc = pc ^ swizzle<D>(row);
-            const int srow = min(row, last_row);              // rows past the end repeat the last
-            const __bf16* src = (is_v ? vbase : kbase) + (size_t)srow * stride + lc * 8;
-            dma16(src, __builtin_amdgcn_readfirstlane(lds_base + st * C::STAGE_BYTES + wl * 1024));
+            for (int i = 0; i < C::LPW; ++i) {
+                const int wl = wave + i * C::NW;                  // wave-load index in the chunk
+                const bool is_v = wl >= C::WLOADS / 2;
+                const int wl2 = is_v ? wl - C::WLOADS / 2 : wl;   // index within K or V
+                const unsigned uni = D == 128 ? (unsigned)(wl2 & 3) : (unsigned)((wl2 & 1) << 2);
+                dma16_base((is_v ? vbase : kbase) + wl2 * 1024, lane_off ^ (uni << 4),
+                           __builtin_amdgcn_readfirstlane(stage_lds + wl * 1024));
+            }
+        } else {
+            // ragged end or strided step keys: rows past the end repeat the last one
+            // (the host checks that the row stride is below 2^24 bytes)
+#pragma unroll
+            for (int i = 0; i < C::LPW; ++i) {
+                const int wl = wave + i * C::NW;
+                const bool is_v = wl >= C::WLOADS / 2;
+                const int wl2 = is_v ? wl - C::WLOADS / 2 : wl;
+                const unsigned uni = D == 128 ? (unsigned)(wl2 & 3) : (unsigned)((wl2 & 1) << 2);
+                const int srow = min(wl2 * (64 / C::NCH) + lane_row, last_row);
+                const unsigned off = __umul24((unsigned)srow, stride_b) + (((unsigned)lane_lc0 ^ uni) << 4);
+                dma16_base(is_v ? vbase : kbase, off, __builtin_amdgcn_readfirstlane(stage_lds + wl * 1024));
+            }
         }
     };
 
     // Request Q and the first chunks before anything else: the stream from HBM is the critical
     // path.  The workgroup's query rows go to LDS (same swizzle as K) and are the oldest loads
     // in flight, so the first chunk's wait covers them.  Rows past the end repeat the last row.
+#ifdef LA_DEV_KNOBS
+    if (!(p.dev_mode & 32))
+#endif
     {
 #pragma unroll
         for (int i = 0; i < C::QLPW; ++i) {
@@ -285,13 +355,14 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
             const int row = piece / C::NCH, pc = piece % C::NCH;
             const int lc = pc ^ swizzle<D>(row);
             const int rr = min(rb * C::ROWS + row, p.R - 1);
-            const int t = rr / p.group, hh = rr - t * p.group;
-            const __bf16* src = p.q + ((size_t)t * p.heads + (size_t)kvh * p.group + hh) * D + lc * 8;
-            dma16(src, __builtin_amdgcn_readfirstlane(lds_base + C::Q_OFFSET + wl * 1024));
+            const int t = div_small(rr, p.inv_group), hh = rr - t * p.group;
+            // (the host checks that q spans less than 2^31 bytes)
+            const unsigned off = (unsigned)(((t * p.heads + kvh * p.group + hh) * D + lc * 8) * 2);
+            dma16_base(p.q, off, __builtin_amdgcn_readfirstlane(lds_base + C::Q_OFFSET + wl * 1024));
         }
     }
 #pragma unroll
-    for (int s = 0; s < NSTAGE - 1; ++s)
+    for (int s = 0; s < NSTAGE; ++s)
         if (s < c_end - c_begin) issue_chunk(c_begin + s, s);
     LA_STAMP(1);
 
@@ -300,7 +371,7 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
 #pragma unroll
     for (int rw = 0; rw < RW; ++rw) {
         const int rr = min(row_base + rw * 32 + l32, p.R - 1);
-        vis[rw] = row_visibility(rr / p.group, p.W, p.N);
+        vis[rw] = row_visibility(div_small(rr, p.inv_group), p.W, p.N, p.inv_W, p.inv_n1);
     }
     bf16x8 qreg[RW][D / 16];  // B operand of S^T = K Q^T: row l32, d = k16*16 + hi*8 .. +8
 
@@ -321,18 +392,21 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
         const int n_my = c_end - c_begin;
         if (pass > 0) {
 #pragma unroll
-            for (int s = 0; s < NSTAGE - 1; ++s)
+            for (int s = 0; s < NSTAGE; ++s)
                 if (s < n_my) issue_chunk(c_begin + s, s);
         }
 
         for (int it = 0; it < n_my; ++it) {
-            // wait for this wave's loads of chunk `it`; later chunks may stay in flight
-            const int later = min(n_my - 1 - it, NSTAGE - 2);
-            if (NSTAGE >= 4 && later >= 2) wait_vmcnt<(NSTAGE >= 4 ? 2 : 0) * C::LPW>();
-            else if (NSTAGE >= 3 && later >= 1) wait_vmcnt<(NSTAGE >= 3 ? 1 : 0) * C::LPW>();
+            // Wait for this wave's loads of chunk `it`; younger chunks may stay in flight.  Every
+            // stage is requested up front; chunk it+NSTAGE-1 is requested at iteration it >= 1,
+            // so NSTAGE-1 younger chunks are in flight at it = 0 and at most NSTAGE-2 afterwards.
+            const int later = min(n_my - 1 - it, it == 0 ? NSTAGE - 1 : NSTAGE - 2);
+            if (NSTAGE >= 4 && later >= 3) wait_vmcnt<(NSTAGE >= 4 ? 3 : 0) * C::LPW>();
+            else if (NSTAGE >= 3 && later >= 2) wait_vmcnt<(NSTAGE >= 3 ? 2 : 0) * C::LPW>();
+            else if (later >= 1) wait_vmcnt<C::LPW>();
             else wait_vmcnt<0>();
             __syncthreads();  // chunk `it` complete in LDS; everyone is done with chunk it-1
-            if (it == 0) LA_STAMP(2);
+            if (it < 8) LA_STAMP(8 + 2 * it);
             if (it == 0 && pass == 0) {
                 // Q has landed with the first chunk: move this wave's rows to registers
 #pragma unroll
@@ -345,11 +419,11 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                         qreg[rw][k16] = *reinterpret_cast<const bf16x8*>(qr + (((k16 * 2 + hi) ^ qsw) << 4));
                 }
             }
-            if (it + NSTAGE - 1 < n_my)
+            if (it >= 1 && it + NSTAGE - 1 < n_my)
                 issue_chunk(c_begin + it + NSTAGE - 1, (it + NSTAGE - 1) % NSTAGE);
             if (!wave_active) continue;
 #ifdef LA_DEV_KNOBS
-            if (p.dev_mode == 2) continue;  // loads only
+            if ((p.dev_mode & 15) == 2) continue;  // loads only
 #endif
 
             const int c = c_begin + it;
@@ -435,10 +509,10 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                             if (!((word >> bit) & 1u)) s[rw][i] = kNegInf;
                         }
                     }
-                    float mx = fmaxf(s[rw][0], s[rw][1]);
+                    float mx = max3(s[rw][0], s[rw][1], s[rw][2]);
 #pragma unroll
-                    for (int i = 2; i < 16; i += 2) mx = fmaxf(mx, fmaxf(s[rw][i], s[rw][i + 1]));
-                    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                    for (int i = 3; i < 15; i += 2) mx = max3(mx, s[rw][i], s[rw][i + 1]);
+                    mx = max_across_halves(fmaxf(mx, s[rw][15]));
                     // Scores stay unscaled; exp(x/sqrt(d)) = exp2(x * scale_log2).  The reference
                     // m_run only moves when the block maximum exceeds it by more than 2^8 in the
                     // exponent (or no key was seen yet): softmax is invariant to the reference, and
@@ -482,11 +556,12 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                         for (int rw = 0; rw < RW; ++rw)
                             o[rw][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kk][db], pf[rw][kk], o[rw][db], 0, 0, 0);
             }
+            if (it < 8) LA_STAMP(9 + 2 * it);
         }
 
         LA_STAMP(3);
 #ifdef LA_DEV_KNOBS
-        if (p.dev_mode == 1 || p.dev_mode == 2) {  // stop after the main loop
+        if ((p.dev_mode & 15) == 1 || (p.dev_mode & 15) == 2) {  // stop after the main loop
             if (l_run[0] == 123.456f) p.out[tid] = (__bf16)o[0][0][0];
             return;
         }
@@ -497,33 +572,39 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
 
         __syncthreads();  // all stages consumed: LDS is reused below
 
-        // ---- merge the KS waves of a row tile through LDS (fragment layout: [4 regs][lane])
+        // ---- merge the KS waves of a row tile through LDS, pairwise: at each step the waves
+        //      whose key index has the step's bit set hand their state to the wave `step` below
+        //      (fragment layout: [4 regs][lane], 16 bytes per lane and access)
         if (KS > 1) {
             float* mg = reinterpret_cast<float*>(lds);
-            if (ks > 0 && wave_active) {
 #pragma unroll
-                for (int rw = 0; rw < RW; ++rw) {
-                    float* dst = mg + (((ks - 1) * RT + rt) * RW + rw) * C::TILE_FLOATS;
-#pragma unroll
-                    for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-                        for (int i4 = 0; i4 < 4; ++i4) {
-                            f32x4 v = {o[rw][db][i4 * 4], o[rw][db][i4 * 4 + 1], o[rw][db][i4 * 4 + 2],
-                                       o[rw][db][i4 * 4 + 3]};
-                            *reinterpret_cast<f32x4*>(dst + ((db * 4 + i4) * 64 + lane) * 4) = v;
-                        }
-                    dst[C::FRAG_FLOATS + lane] = m_run[rw];
-                    dst[C::FRAG_FLOATS + 64 + lane] = l_run[rw];
-                }
-            }
-            __syncthreads();
-            if (ks == 0 && wave_active) {
-                for (int k2 = 1; k2 < KS; ++k2) {
+            for (int step = 1; step < KS; step <<= 1) {
+                const bool sender = (ks & (2 * step - 1)) == step;
+                const bool receiver = (ks & (2 * step - 1)) == 0;
+                // slot of the pair within this step: one per (receiver, tile)
+                float* slot = mg + (((ks >> 1) / step * RT + rt) * RW) * C::TILE_FLOATS;
+                if (sender && wave_active) {
 #pragma unroll
                     for (int rw = 0; rw < RW; ++rw) {
-                        const float* src = mg + (((k2 - 1) * RT + rt) * RW + rw) * C::TILE_FLOATS;
-                        const float m2 = src[C::FRAG_FLOATS + lane];
-                        const float l2 = src[C::FRAG_FLOATS + 64 + lane];
+                        float* dst = slot + rw * C::TILE_FLOATS;
+#pragma unroll
+                        for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                            for (int i4 = 0; i4 < 4; ++i4) {
+                                f32x4 v = {o[rw][db][i4 * 4], o[rw][db][i4 * 4 + 1], o[rw][db][i4 * 4 + 2],
+                                           o[rw][db][i4 * 4 + 3]};
+                                *reinterpret_cast<f32x4*>(dst + ((db * 4 + i4) * 64 + lane) * 4) = v;
+                            }
+                        *reinterpret_cast<f32x2*>(dst + C::FRAG_FLOATS + lane * 2) = f32x2{m_run[rw], l_run[rw]};
+                    }
+                }
+                __syncthreads();
+                if (receiver && wave_active) {
+#pragma unroll
+                    for (int rw = 0; rw < RW; ++rw) {
+                        const float* src = slot + rw * C::TILE_FLOATS;
+                        const f32x2 ml2 = *reinterpret_cast<const f32x2*>(src + C::FRAG_FLOATS + lane * 2);
+                        const float m2 = ml2[0], l2 = ml2[1];
                         const float m_new = fmaxf(m_run[rw], m2);
                         const float m_use = (m_new == kNegInf) ? 0.0f : m_new;
                         const float a1 = fast_exp2((m_run[rw] - m_use) * p.scale_log2);
@@ -541,29 +622,30 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                             }
                     }
                 }
+                __syncthreads();
             }
-            __syncthreads();
         }
         LA_STAMP(4);
         if (direct) break;
 
         // ---- split combine: store this split's partial, then take a ticket
-        const size_t wg_floats = (size_t)C::TILES * C::TILE_FLOATS;
-        float* group_base = p.partials + (size_t)((kvh * p.n_row_blocks + rb) * p.XS) * wg_floats;
+        unsigned char* group_base = reinterpret_cast<unsigned char*>(p.partials) +
+                                    (size_t)((kvh * p.n_row_blocks + rb) * p.XS) * C::PART_WG_BYTES;
         if (ks == 0 && wave_active) {
 #pragma unroll
             for (int rw = 0; rw < RW; ++rw) {
-                float* dst = group_base + (size_t)xs * wg_floats + (size_t)(rt * RW + rw) * C::TILE_FLOATS;
+                unsigned char* dst = group_base + (size_t)xs * C::PART_WG_BYTES +
+                                     (size_t)(rt * RW + rw) * C::PART_TILE_BYTES;
 #pragma unroll
                 for (int db = 0; db < C::DB; ++db)
 #pragma unroll
-                    for (int i4 = 0; i4 < 4; ++i4) {
-                        f32x4 v = {o[rw][db][i4 * 4], o[rw][db][i4 * 4 + 1], o[rw][db][i4 * 4 + 2],
-                                   o[rw][db][i4 * 4 + 3]};
-                        *reinterpret_cast<f32x4*>(dst + ((db * 4 + i4) * 64 + lane) * 4) = v;
+                    for (int i8 = 0; i8 < 2; ++i8) {
+                        bf16x8 v;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] = (__bf16)o[rw][db][i8 * 8 + e];
+                        *reinterpret_cast<bf16x8*>(dst + ((db * 2 + i8) * 64 + lane) * 16) = v;
                     }
-                dst[C::FRAG_FLOATS + lane] = m_run[rw];
-                dst[C::FRAG_FLOATS + 64 + lane] = l_run[rw];
+                *reinterpret_cast<f32x2*>(dst + C::PART_ACC_BYTES + lane * 8) = f32x2{m_run[rw], l_run[rw]};
             }
         }
         // Stores are acknowledged by the L2 of this XCD: wait for them, then publish.
@@ -599,8 +681,8 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
             //      at a time and requests all their partials before merging any, so that the
             //      usual case (at most 4 splits) costs one trip to the L2.
             constexpr int NSUB = C::TILES * C::DB;
-            constexpr int NU = RW == 1 ? 2 : 1;  // units in flight per wave
-            constexpr int MB = RW == 1 ? 4 : 2;  // splits requested at a time
+            constexpr int NU = (RW == 1 && NSUB > C::NW) ? 2 : 1;  // units in flight per wave
+            constexpr int MB = RW == 1 ? 4 : 2;                     // splits requested at a time
             for (int st0 = wave; st0 < NSUB; st0 += NU * C::NW) {
                 float m_acc[NU], l_acc[NU];
                 float acc[NU][16];
@@ -612,41 +694,50 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                     for (int i = 0; i < 16; ++i) acc[u][i] = 0.0f;
                 }
                 for (int s0 = 0; s0 < p.XS; s0 += MB) {
-                    float m2[NU][MB], l2[NU][MB];
-                    f32x4 v[NU][MB][4];
+                    // request everything of this batch, then merge: one trip to the L2
+                    f32x2 ml[NU][MB];
+                    bf16x8 v[NU][MB][2];
 #pragma unroll
                     for (int u = 0; u < NU; ++u) {
                         const int st = min(st0 + u * C::NW, NSUB - 1);
                         const int tile = st / C::DB, db = st - tile * C::DB;
-                        const float* src0 = group_base + (size_t)tile * C::TILE_FLOATS;
+                        const unsigned char* src0 = group_base + (size_t)tile * C::PART_TILE_BYTES;
 #pragma unroll
                         for (int w = 0; w < MB; ++w) {
                             const int s2 = min(s0 + w, p.XS - 1);
-                            const float* src = src0 + (size_t)s2 * wg_floats;
-                            m2[u][w] = src[C::FRAG_FLOATS + lane];
-                            l2[u][w] = src[C::FRAG_FLOATS + 64 + lane];
+                            const unsigned char* src = src0 + (size_t)s2 * C::PART_WG_BYTES;
+                            ml[u][w] = *reinterpret_cast<const f32x2*>(src + C::PART_ACC_BYTES + lane * 8);
 #pragma unroll
-                            for (int i4 = 0; i4 < 4; ++i4)
-                                v[u][w][i4] = *reinterpret_cast<const f32x4*>(src + ((db * 4 + i4) * 64 + lane) * 4);
+                            for (int i8 = 0; i8 < 2; ++i8)
+                                v[u][w][i8] = *reinterpret_cast<const bf16x8*>(src + ((db * 2 + i8) * 64 + lane) * 16);
                         }
                     }
 #pragma unroll
-                    for (int u = 0; u < NU; ++u)
+                    for (int u = 0; u < NU; ++u) {
+                        // batch maximum, then one weight per split: acc = acc * a0 + sum_w v_w * a_w
+                        float mb = m_acc[u];
+#pragma unroll
+                        for (int w = 0; w < MB; ++w)
+                            if (s0 + w < p.XS) mb = fmaxf(mb, ml[u][w][0]);
+                        const float m_use = (mb == kNegInf) ? 0.0f : mb;
+                        const float a0 = fast_exp2((m_acc[u] - m_use) * p.scale_log2);
+                        l_acc[u] *= a0;
+                        if (s0 > 0) {
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) acc[u][i] *= a0;
+                        }
+                        m_acc[u] = mb;
 #pragma unroll
                         for (int w = 0; w < MB; ++w) {
-                            if (s0 + w >= p.XS) break;
-                            const float m_new = fmaxf(m_acc[u], m2[u][w]);
-                            const float m_use = (m_new == kNegInf) ? 0.0f : m_new;
-                            const float a1 = fast_exp2((m_acc[u] - m_use) * p.scale_log2);
-                            const float a2 = fast_exp2((m2[u][w] - m_use) * p.scale_log2);
-                            l_acc[u] = l_acc[u] * a1 + l2[u][w] * a2;
-                            m_acc[u] = m_new;
+                            const float aw = s0 + w < p.XS ? fast_exp2((ml[u][w][0] - m_use) * p.scale_log2) : 0.0f;
+                            l_acc[u] = __builtin_fmaf(ml[u][w][1], aw, l_acc[u]);
 #pragma unroll
-                            for (int i4 = 0; i4 < 4; ++i4)
+                            for (int i8 = 0; i8 < 2; ++i8)
 #pragma unroll
-                                for (int e = 0; e < 4; ++e)
-                                    acc[u][i4 * 4 + e] = acc[u][i4 * 4 + e] * a1 + v[u][w][i4][e] * a2;
+                                for (int e = 0; e < 8; ++e)
+                                    acc[u][i8 * 8 + e] = __builtin_fmaf((float)v[u][w][i8][e], aw, acc[u][i8 * 8 + e]);
                         }
+                    }
                 }
 #pragma unroll
                 for (int u = 0; u < NU; ++u) {
@@ -664,7 +755,9 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                     }
                 }
             }
+            LA_STAMP(20);
             __syncthreads();
+            LA_STAMP(21);
             write_rows_from_lds<C>(p, lds, rb, kvh, tid);
             LA_STAMP(7);
             return;
@@ -703,25 +796,28 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
 // host side
 
 struct Plan {
-    int RW, RT, KS, XS, NS;   // NS = LDS stages (chunks in flight + 1)
+    int RW, RT, KS, XS, NS;   // NS = LDS stages
+    int KC;                   // keys per chunk
     int n_row_blocks;
     int n_prefix_chunks, n_chunks;
-    size_t partial_floats_per_wg;
+    size_t partial_bytes_per_wg;
 };
 
-constexpr int kKC = 64;
 
-// Most LDS stages (chunks in flight + 1) that fit beside the workgroup's Q rows.
-int max_stages(int D, int RW, int RT)
+// Most LDS stages that fit beside the workgroup's Q rows.
+int max_stages(int D, int RW, int RT, int KC)
 {
     const int tiles = RW * RT;
     if (D != 128) return 4;
+    if (KC == 128) return 2;
     return tiles <= 2 ? 4 : (tiles <= 4 ? 3 : 2);
 }
 
-bool plan_supported(int D, int RW, int RT, int KS, int NS)
+bool plan_supported(int D, int RW, int RT, int KS, int NS, int KC)
 {
-    if (NS != 2 && NS != max_stages(D, RW, RT)) return false;
+    if (KC == 128) return D == 128 && RW == 1 && RT == 2 && KS == 4 && NS == 2;
+    if (KC != 64) return false;
+    if (NS != 2 && NS != max_stages(D, RW, RT, KC)) return false;
     if (D == 128)
         return (RW == 1 && ((RT == 1 && KS == 2) || (RT == 2 && KS == 2) || (RT == 4 && KS == 1) ||
                             (RT == 2 && KS == 1))) ||
@@ -734,42 +830,47 @@ Plan make_plan(int P, int T, int group, int kv_heads, int D)
     Plan pl;
     const int R = T * group;
     const int tiles = (R + 31) / 32;
-    pl.n_prefix_chunks = (P + kKC - 1) / kKC;
-    pl.n_chunks = pl.n_prefix_chunks + (T + kKC - 1) / kKC;
+    pl.KC = 64;
+    // Few rows per KV head (memory-bound): 64-row workgroups whose wave pairs split the keys.
+    // Many rows (grouped-query models, wide windows): 128-row workgroups, one tile per wave.
+    // (64-row waves, RW = 2, are compiled and tested but were slower in every measurement.)
     if (tiles <= 1) { pl.RW = 1; pl.RT = 1; pl.KS = 2; }
     else if (tiles <= 4 || D != 128) { pl.RW = 1; pl.RT = 2; pl.KS = 2; }
-    else if (tiles <= 8) { pl.RW = 1; pl.RT = 4; pl.KS = 1; }
-    else { pl.RW = 2; pl.RT = 4; pl.KS = 1; }
+    else { pl.RW = 1; pl.RT = 4; pl.KS = 1; }
     pl.XS = 0;
     pl.NS = 0;
-    // developer override: LA_ATTN_PLAN="RW,RT,KS,XS,NS" (XS = 0 keeps the heuristic)
+    // developer override: LA_ATTN_PLAN="RW,RT,KS,XS,NS,KC" (XS = 0 keeps the heuristic)
     if (const char* env = getenv("LA_ATTN_PLAN")) {
-        int a = 0, b = 0, c = 0, d = 0, e = 0;
-        if (sscanf(env, "%d,%d,%d,%d,%d", &a, &b, &c, &d, &e) == 5 && plan_supported(D, a, b, c, e)) {
-            pl.RW = a; pl.RT = b; pl.KS = c; pl.XS = d; pl.NS = e;
+        int a = 0, b = 0, c = 0, d = 0, e = 0, f = 0;
+        if (sscanf(env, "%d,%d,%d,%d,%d,%d", &a, &b, &c, &d, &e, &f) == 6 &&
+            plan_supported(D, a, b, c, e, f)) {
+            pl.RW = a; pl.RT = b; pl.KS = c; pl.XS = d; pl.NS = e; pl.KC = f;
         }
     }
-    if (pl.NS == 0) pl.NS = max_stages(D, pl.RW, pl.RT);
+    if (pl.NS == 0) pl.NS = max_stages(D, pl.RW, pl.RT, pl.KC);
+    pl.n_prefix_chunks = (P + pl.KC - 1) / pl.KC;
+    pl.n_chunks = pl.n_prefix_chunks + (T + pl.KC - 1) / pl.KC;
     const int rows_wg = pl.RT * pl.RW * 32;
     pl.n_row_blocks = (R + rows_wg - 1) / rows_wg;
     if (pl.XS <= 0) {
-        // about one workgroup per compute unit, at least two chunks per workgroup
+        // One workgroup per compute unit and never more than 256 in all: a workgroup owns most
+        // of a compute unit's LDS, so a second round would only start when the first has ended.
         const int units = kv_heads * pl.n_row_blocks;
-        int xs = (256 + units - 1) / units;
+        int xs = 256 / units;
         if (xs > pl.n_chunks / 2) xs = pl.n_chunks / 2;
         pl.XS = xs < 1 ? 1 : xs;
     }
     if (pl.XS > pl.n_chunks) pl.XS = pl.n_chunks;
     if (pl.XS > 64) pl.XS = 64;
-    pl.partial_floats_per_wg = (size_t)pl.RT * pl.RW * ((size_t)(D / 32) * 16 * 64 + 128);
+    pl.partial_bytes_per_wg = (size_t)pl.RT * pl.RW * ((size_t)(D / 32) * 16 * 64 * 2 + 64 * 8);
     return pl;
 }
 
-template <int D, int RW, int RT, int KS, int NSTAGE>
+template <int D, int RW, int RT, int KS, int NSTAGE, int KC = 64>
 la_status launch_cfg(const AttnParams& prm, hipStream_t stream)
 {
-    using C = Cfg<D, RW, RT, KS, kKC, NSTAGE>;
-    auto kern = step_attention_kernel<D, RW, RT, KS, kKC, NSTAGE>;
+    using C = Cfg<D, RW, RT, KS, KC, NSTAGE>;
+    auto kern = step_attention_kernel<D, RW, RT, KS, KC, NSTAGE>;
     static bool attr_set[16] = {false};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return fail(LA_EHIP, "hipGetDevice failed");
@@ -793,7 +894,7 @@ size_t step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int
     const int T = 1 + (W + G) * (N - 1);
     const Plan pl = make_plan(P, T, heads / kv_heads, kv_heads, head_dim);
     if (pl.XS <= 1) return 0;
-    return (size_t)kv_heads * pl.n_row_blocks * pl.XS * pl.partial_floats_per_wg * sizeof(float);
+    return (size_t)kv_heads * pl.n_row_blocks * pl.XS * pl.partial_bytes_per_wg;
 }
 
 la_status launch_step_attention(const void* q, const void* k_cache, const void* v_cache,
@@ -802,7 +903,9 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
 {
     const int T = 1 + (W + G) * (N - 1);
     const int group = heads / kv_heads;
-    if ((long long)T * group > (1 << 24)) return fail(LA_EUNSUPPORTED, "la_step_attention: too many rows per KV head");
+    if ((long long)T * group >= (1 << 21) || (long long)T * heads * head_dim * 2 >= (1ll << 31) ||
+        (long long)kv_heads * head_dim * 2 >= (1 << 24))
+        return fail(LA_EUNSUPPORTED, "la_step_attention: step too large (T=%d, heads=%d)", T, heads);
     const Plan pl = make_plan(P, T, group, kv_heads, head_dim);
 
     AttnParams prm;
@@ -822,10 +925,17 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
     prm.n_row_blocks = pl.n_row_blocks;
     prm.XS = pl.XS;
     const long long total = (long long)kv_heads * pl.n_row_blocks * pl.XS;
-    if (total > (1 << 28)) return fail(LA_EUNSUPPORTED, "la_step_attention: too many workgroups");
+    if (total >= (1 << 21)) return fail(LA_EUNSUPPORTED, "la_step_attention: too many workgroups");
     prm.total_wg = (int)total;
     prm.wg_per_xcd = (int)((total + 7) / 8);
     prm.scale_log2 = 1.4426950408889634f / sqrtf((float)head_dim);
+    prm.inv_XS = 1.0f / (float)pl.XS;
+    prm.inv_row_blocks = 1.0f / (float)pl.n_row_blocks;
+    prm.inv_group = 1.0f / (float)group;
+    prm.inv_W = 1.0f / (float)(W > 0 ? W : 1);
+    prm.inv_n1 = 1.0f / (float)(N - 1);
+    prm.chunks_lo = pl.n_chunks / pl.XS;
+    prm.chunks_rem = pl.n_chunks % pl.XS;
     // testing hook: exercise the path taken when a split group is not on one XCD
     const char* fr = getenv("LA_FORCE_RECOMPUTE");
     prm.force_recompute = (fr && fr[0] == '1') ? 1 : 0;
@@ -840,11 +950,12 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
         const size_t ticket_bytes = (size_t)kv_heads * pl.n_row_blocks * sizeof(unsigned);
         prm.tickets = (unsigned*)zeroed_workspace(ticket_bytes, stream);
         if (!prm.tickets) return LA_ENOMEM;
-        const size_t bytes = (size_t)total * pl.partial_floats_per_wg * sizeof(float);
-        prm.partials = (float*)scratch_workspace(bytes);
+        const size_t bytes = (size_t)total * pl.partial_bytes_per_wg;
+        prm.partials = scratch_workspace(bytes);
         if (!prm.partials) return LA_ENOMEM;
     }
 
+    if (pl.KC == 128) return launch_cfg<128, 1, 2, 4, 2, 128>(prm, stream);
 #define LA_DISPATCH(D_, RW_, RT_, KS_, NSMAX_)                                       \
     if (head_dim == D_ && pl.RW == RW_ && pl.RT == RT_ && pl.KS == KS_) {           \
         if (pl.NS == 2) return launch_cfg<D_, RW_, RT_, KS_, 2>(prm, stream);       \
