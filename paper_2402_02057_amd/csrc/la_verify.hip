@@ -2,9 +2,11 @@
 // longest accepted prefix of every candidate n-gram (Sec. 2 "Guess-And-Verify"; the
 // accept/stop rule Algorithm 3 applies to each candidate), in one launch.
 //
-// The G*(N-1) logits rows are far fewer than the 256 compute units, so every row is cut
-// into segments and each workgroup scans one segment with 16-byte loads.  A segment's
-// winner is folded into one 64-bit key per row with atomicMax,
+// A workgroup of 16 waves scans one segment of one logits row - up to 32768 elements, so a
+// whole row of a 32000-entry vocabulary - with every 16-byte load requested before the first
+// comparison.  (Many small segments would fill the machine better, but each costs device-scope
+// atomics on a handful of addresses, and those serialise: measured, they dominated.)  A
+// segment's winner is folded into one 64-bit key per row with atomicMax,
 //     key = (order-preserving image of the fp32 value) << 32 | (0xFFFFFFFF - index),
 // so the largest value wins and, among equal values, the lowest index: the result does
 // not depend on the order in which workgroups finish.  Each candidate has a ticket counter;
@@ -19,8 +21,10 @@
 namespace la {
 namespace {
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / 64;
+constexpr int kVecPerThread = 8;                          // float4 loads in flight per thread
+constexpr int kMaxSeg = kThreads * kVecPerThread * 4;     // elements per segment
 
 __device__ __forceinline__ unsigned long long pack_key(float v, int idx)
 {
@@ -57,16 +61,22 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(
     float best = 0.0f;
     int best_idx = -1;
     if (kVec) {
-        const float4* p4 = reinterpret_cast<const float4*>(p);
-        const int q1 = v1 >> 2;  // V % 4 == 0 on this path
-        for (int i = (v0 >> 2) + tid; i < q1; i += kThreads) {
-            const float4 x = p4[i];
-            const int base = i << 2;
-            if (best_idx < 0) { best = x.x; best_idx = base; }
-            if (x.x > best) { best = x.x; best_idx = base; }
-            if (x.y > best) { best = x.y; best_idx = base + 1; }
-            if (x.z > best) { best = x.z; best_idx = base + 2; }
-            if (x.w > best) { best = x.w; best_idx = base + 3; }
+        const float4* p4 = reinterpret_cast<const float4*>(p) + (v0 >> 2);
+        const int nvec = (v1 - v0) >> 2;  // V % 4 == 0 on this path; nvec >= 1
+        float4 x[kVecPerThread];
+#pragma unroll
+        for (int j = 0; j < kVecPerThread; ++j) x[j] = p4[min(tid + j * kThreads, nvec - 1)];
+#pragma unroll
+        for (int j = 0; j < kVecPerThread; ++j) {
+            const int i = tid + j * kThreads;
+            if (i < nvec) {
+                const int base = v0 + (i << 2);
+                if (best_idx < 0) { best = x[j].x; best_idx = base; }
+                if (x[j].x > best) { best = x[j].x; best_idx = base; }
+                if (x[j].y > best) { best = x[j].y; best_idx = base + 1; }
+                if (x[j].z > best) { best = x[j].z; best_idx = base + 2; }
+                if (x[j].w > best) { best = x[j].w; best_idx = base + 3; }
+            }
         }
     } else {
         for (int i = v0 + tid; i < v1; i += kThreads) {
@@ -99,21 +109,35 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(
     __syncthreads();
     if (!last_flag) return;
 
-    // Last workgroup of candidate g: its N-1 keys are final.  Read them with atomics too.
-    if (tid == 0) {
+    // Last workgroup of candidate g: its N-1 keys are final.  The first wave reads them, one
+    // key per lane and all at once, with returning atomics (other workgroups updated them with
+    // device-scope atomics, which act at the memory side, not in this XCD's L2).
+    if (tid < 64) {
         const int g = row / n1;
         int len = 0;
-        bool run = true;
-        for (int k = 0; k < n1; ++k) {
-            const unsigned long long key = atomicMax(&keys[g * n1 + k], 0ull);
-            const int tok = (int)(0xFFFFFFFFu - (unsigned)key);
-            accepted[g * n1 + k] = tok;
-            run = run && (tok == cand_tokens[g * n1 + k]);
-            len += run ? 1 : 0;
+        bool run = true;  // still inside the leading run of matches
+        for (int k0 = 0; k0 < n1; k0 += 64) {
+            const int k = k0 + tid;
+            bool match = false;
+            if (k < n1) {
+                const unsigned long long key = atomicMax(&keys[g * n1 + k], 0ull);
+                const int tok = (int)(0xFFFFFFFFu - (unsigned)key);
+                accepted[g * n1 + k] = tok;
+                match = tok == cand_tokens[g * n1 + k];
+                atomicExch(&keys[g * n1 + k], 0ull);  // clean for the next call
+            }
+            const int here = min(64, n1 - k0);
+            const unsigned long long mask = __builtin_amdgcn_ballot_w64(match);
+            // number of leading set bits among the `here` lanes in use
+            const unsigned long long inv = ~mask & (here == 64 ? ~0ull : ((1ull << here) - 1ull));
+            const int lead = inv == 0ull ? here : (int)__builtin_ctzll(inv);
+            if (run) len += lead;
+            run = run && lead == here;
         }
-        accept_len[g] = len;
-        for (int k = 0; k < n1; ++k) atomicExch(&keys[g * n1 + k], 0ull);
-        atomicExch(&tickets[g], 0u);
+        if (tid == 0) {
+            accept_len[g] = len;
+            atomicExch(&tickets[g], 0u);
+        }
     }
 }
 
@@ -124,12 +148,8 @@ la_status launch_verify(const float* logits, const int* cand_tokens, int G, int 
 {
     const int n1 = N - 1;
     const int rows = G * n1;
-    // Segment length: at least 4096 elements (16 elements per thread), and enough segments
-    // to put about four workgroups on each of the 256 compute units.
-    int nseg = (V + 4095) / 4096;
-    const int want = (1024 + rows - 1) / rows;
-    if (nseg > want) nseg = want;
-    if (nseg < 1) nseg = 1;
+    // as few segments per row as the per-thread load budget allows
+    int nseg = (V + kMaxSeg - 1) / kMaxSeg;
     int seg_len = (V + nseg - 1) / nseg;
     seg_len = (seg_len + 3) & ~3;
     nseg = (V + seg_len - 1) / seg_len;
