@@ -24,6 +24,13 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 LAYERS = {"llama2-7b": 32, "llama2-13b": 40, "llama2-70b-gqa": 80}
 
+# HBM bytes per attention launch from rocprofv3 (FETCH_SIZE + WRITE_SIZE per dispatch, each scaled
+# by the same counter's reading for a 64 MiB copy): see profiles/attention_verify_<workload>.md.
+# None where no profile of the current kernel has been taken.
+MEASURED_TRAFFIC_BYTES = {
+    "llama2-7b": int((11708.5 * 65536.0 / 32786.8 + 5328.4 * 65536.0 / 65536.0) * 1024),
+}
+
 
 def visible_pairs(W, N, G):
     n1 = N - 1
@@ -161,7 +168,7 @@ def main():
         roof = {"bound": "mfma", "achieved": aflops / (attn_us * 1e-6) / 1e12,
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(args.workload)
     roof["kernel"] = "step_attention_kernel"
     roof["us_per_launch"] = attn_us
     roof["algorithmic_bytes"] = abytes
