@@ -160,6 +160,24 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// Wait until at most `later` * LPW of this wave's loads are still in flight (later < NS).
+template <int LPW, int NS>
+__device__ __forceinline__ void wait_chunks(int later)
+{
+    static_assert(LPW * (NS - 1) < 64, "vmcnt is a 6-bit counter");
+    switch (later) {
+    case 0: wait_vmcnt<0>(); break;
+    case 1: wait_vmcnt<(NS > 1 ? 1 : 0) * LPW>(); break;
+    case 2: wait_vmcnt<(NS > 2 ? 2 : 0) * LPW>(); break;
+    case 3: wait_vmcnt<(NS > 3 ? 3 : 0) * LPW>(); break;
+    case 4: wait_vmcnt<(NS > 4 ? 4 : 0) * LPW>(); break;
+    case 5: wait_vmcnt<(NS > 5 ? 5 : 0) * LPW>(); break;
+    case 6: wait_vmcnt<(NS > 6 ? 6 : 0) * LPW>(); break;
+    case 7: wait_vmcnt<(NS > 7 ? 7 : 0) * LPW>(); break;
+    default: wait_vmcnt<(NS > 8 ? 8 : 0) * LPW>(); break;
+    }
+}
+
 // One direct-to-LDS load: every lane fetches 16 bytes from its own global address, the wave's
 // 1 KB lands at LDS byte address `lds_base` + lane * 16 (M0 carries the base).  Written as
 // assembly so that the compiler's wait-count bookkeeping does not know of these loads: it would
@@ -169,9 +187,13 @@ __device__ __forceinline__ void wait_vmcnt()
 // offset: no 64-bit vector arithmetic per load.
 __device__ __forceinline__ void dma16_base(const void* base, unsigned lane_off, unsigned lds_base)
 {
+    // the base is the same in every lane; say so, or the operand may be given vector registers
+    const unsigned long long b = reinterpret_cast<unsigned long long>(base);
+    const unsigned long long lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)b);
+    const unsigned long long hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(b >> 32));
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
-                 : "v"(lane_off), "s"(base), "s"(lds_base)
+                 : "v"(lane_off), "s"((hi << 32) | lo), "s"(lds_base)
                  : "memory");
 }
 
@@ -195,7 +217,10 @@ struct Cfg {
     static constexpr int RBYTES = D * 2;
     static constexpr int NCH = D / 8;                     // 16-byte pieces per row
     static constexpr int KB = KC / 32;                    // 32-key blocks per chunk
-    static constexpr int KBW = KB / KS;                   // blocks per wave per chunk
+    // Key-split waves of a row tile: up to KB of them share a chunk (one or more blocks each);
+    // beyond that, groups of KB waves take consecutive chunks of the same iteration.
+    static constexpr int CPI = KS > KB ? KS / KB : 1;     // chunks consumed per iteration
+    static constexpr int KBW = KS >= KB ? 1 : KB / KS;    // blocks per wave per chunk
     static constexpr int KV_BYTES = KC * RBYTES;          // one of K or V of a chunk
     static constexpr int STAGE_BYTES = 2 * KV_BYTES;
     static constexpr int WLOADS = STAGE_BYTES / 1024;     // 64-lane x 16-byte loads per chunk
@@ -220,17 +245,20 @@ struct Cfg {
     static constexpr int LDS_BYTES =
         LDS_MAIN > LDS_MERGE ? (LDS_MAIN > LDS_OUT ? LDS_MAIN : LDS_OUT)
                              : (LDS_MERGE > LDS_OUT ? LDS_MERGE : LDS_OUT);
-    static_assert(KB % KS == 0, "key blocks of a chunk must divide among the key-split waves");
+    static_assert(KS >= KB ? KS % KB == 0 : KB % KS == 0, "key-split waves and blocks must divide");
+    static_assert(NSTAGE >= CPI, "an iteration's chunks must fit the ring");
     static_assert(WLOADS % NW == 0, "chunk loads must divide among the waves");
     static_assert((Q_BYTES / 1024) % NW == 0, "Q loads must divide among the waves");
-    static_assert(LPW * (NSTAGE - 1) < 64, "vmcnt is a 6-bit counter");
-    static_assert(LDS_BYTES <= 160 * 1024 - 64, "LDS of a compute unit");
+    static_assert(NSTAGE <= 9, "wait_chunks covers up to 8 younger chunks");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS of a compute unit");
 };
 
 #ifdef LA_DEV_KNOBS
 #define LA_STAMP(k) do { if (p.dev_trace && (threadIdx.x & 63) == 0) p.dev_trace[((size_t)blockIdx.x * 8 + (threadIdx.x >> 6)) * 24 + (k)] = wall_clock64(); } while (0)
+#define LA_CYC(k) do { if (p.dev_trace && (threadIdx.x & 63) == 0 && it == 1) p.dev_trace[((size_t)(4096 + blockIdx.x) * 8 + (threadIdx.x >> 6)) * 24 + (k)] = __builtin_readcyclecounter(); } while (0)
 #else
 #define LA_STAMP(k) do { } while (0)
+#define LA_CYC(k) do { } while (0)
 #endif
 
 // Id of the XCD (accelerator die, with its own L2) this wave runs on.
@@ -270,9 +298,11 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
     if (p.dev_mode >= 16) logical = (int)blockIdx.x;  // experiment: no XCD grouping (wrong combine!)
 #endif
     if (logical >= p.total_wg) return;
-    const int unit = div_small(logical, p.inv_XS);       // (kvh, rb) pair
+    // (the float arithmetic runs on the vector unit: tell the compiler the results are uniform,
+    // or every loop and branch that depends on them is compiled as divergent control flow)
+    const int unit = __builtin_amdgcn_readfirstlane(div_small(logical, p.inv_XS));  // (kvh, rb) pair
     const int xs = logical - unit * p.XS;
-    const int kvh = div_small(unit, p.inv_row_blocks);
+    const int kvh = __builtin_amdgcn_readfirstlane(div_small(unit, p.inv_row_blocks));
     const int rb = unit - kvh * p.n_row_blocks;
 
     const int tid = threadIdx.x;
@@ -377,7 +407,9 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
 
     f32x16 o[RW][C::DB];
     float m_run[RW], l_run[RW];
-    __shared__ unsigned s_role;  // after the ticket: 0 not last, 1 last and co-located, 2 recompute
+    // after the ticket: 0 not last, 1 last and co-located, 2 recompute.  It lives where the Q rows
+    // were (they are in registers by then), so that the stage ring can use every other byte.
+    volatile unsigned* s_role = reinterpret_cast<volatile unsigned*>(lds + C::Q_OFFSET);
 
     for (int pass = 0;; ++pass) {
 #pragma unroll
@@ -396,16 +428,17 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                 if (s < n_my) issue_chunk(c_begin + s, s);
         }
 
-        for (int it = 0; it < n_my; ++it) {
-            // Wait for this wave's loads of chunk `it`; younger chunks may stay in flight.  Every
-            // stage is requested up front; chunk it+NSTAGE-1 is requested at iteration it >= 1,
-            // so NSTAGE-1 younger chunks are in flight at it = 0 and at most NSTAGE-2 afterwards.
-            const int later = min(n_my - 1 - it, it == 0 ? NSTAGE - 1 : NSTAGE - 2);
-            if (NSTAGE >= 4 && later >= 3) wait_vmcnt<(NSTAGE >= 4 ? 3 : 0) * C::LPW>();
-            else if (NSTAGE >= 3 && later >= 2) wait_vmcnt<(NSTAGE >= 3 ? 2 : 0) * C::LPW>();
-            else if (later >= 1) wait_vmcnt<C::LPW>();
-            else wait_vmcnt<0>();
-            __syncthreads();  // chunk `it` complete in LDS; everyone is done with chunk it-1
+        const int n_iter = (n_my + C::CPI - 1) / C::CPI;
+        for (int it = 0; it < n_iter; ++it) {
+            // Iteration `it` consumes chunks it*CPI .. it*CPI+CPI-1.  Every stage is requested up
+            // front; the stages an iteration frees are refilled at the start of the next one.
+            // Wait for this wave's loads of the chunks needed now; younger ones stay in flight.
+            const int c_hi = min(n_my, (it + 1) * C::CPI) - 1;
+            const int issued = min(n_my, NSTAGE + (it > 0 ? (it - 1) * C::CPI : 0));
+            wait_chunks<C::LPW, NSTAGE>(issued - 1 - c_hi);  // 0 .. NSTAGE-1 younger chunks
+            LA_CYC(7);
+            __syncthreads();  // these chunks are complete in LDS; everyone is done with the last ones
+            LA_CYC(6);
             if (it < 8) LA_STAMP(8 + 2 * it);
             if (it == 0 && pass == 0) {
                 // Q has landed with the first chunk: move this wave's rows to registers
@@ -419,23 +452,30 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                         qreg[rw][k16] = *reinterpret_cast<const bf16x8*>(qr + (((k16 * 2 + hi) ^ qsw) << 4));
                 }
             }
-            if (it >= 1 && it + NSTAGE - 1 < n_my)
-                issue_chunk(c_begin + it + NSTAGE - 1, (it + NSTAGE - 1) % NSTAGE);
+            if (it >= 1) {
+#pragma unroll
+                for (int j = 0; j < C::CPI; ++j) {
+                    const int cn = (it - 1) * C::CPI + NSTAGE + j;
+                    if (cn < n_my) issue_chunk(c_begin + cn, cn % NSTAGE);
+                }
+            }
+            const int cl = it * C::CPI + (KS > C::KB ? ks / C::KB : 0);  // this wave's chunk
+            if (cl >= n_my) continue;
             if (!wave_active) continue;
 #ifdef LA_DEV_KNOBS
             if ((p.dev_mode & 15) == 2) continue;  // loads only
 #endif
 
-            const int c = c_begin + it;
+            const int c = c_begin + cl;
             const bool is_step = c >= p.n_prefix_chunks;
             const int chunk_key0 = (is_step ? c - p.n_prefix_chunks : c) * KC;
             const int limit = is_step ? p.T : p.P;
-            const unsigned char* kst = lds + (it % NSTAGE) * C::STAGE_BYTES;
+            const unsigned char* kst = lds + (cl % NSTAGE) * C::STAGE_BYTES;
             const unsigned char* vst = kst + C::KV_BYTES;
 
 #pragma unroll
             for (int kbw = 0; kbw < C::KBW; ++kbw) {
-                const int kb = ks + kbw * KS;
+                const int kb = KS >= C::KB ? ks % C::KB : ks + kbw * KS;
                 const int key0 = chunk_key0 + kb * 32;
                 if (key0 >= limit) continue;  // block entirely past the end (wave-uniform)
 
@@ -472,8 +512,10 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                         vf[kk][db] = u.v;
                     }
                 };
+                LA_CYC(0);
                 read_v(0);
                 __builtin_amdgcn_sched_barrier(0);
+                LA_CYC(1);
 
                 // ---- S^T block: 32 keys x 32 rows per tile
                 f32x16 s[RW];
@@ -487,6 +529,7 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                     for (int rw = 0; rw < RW; ++rw)
                         s[rw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[k16], qreg[rw][k16], s[rw], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
+                LA_CYC(2);
                 read_v(1);  // in flight during the softmax arithmetic
 
                 // ---- mask, running max, exponentials
@@ -513,6 +556,7 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
 #pragma unroll
                     for (int i = 3; i < 15; i += 2) mx = max3(mx, s[rw][i], s[rw][i + 1]);
                     mx = max_across_halves(fmaxf(mx, s[rw][15]));
+                    LA_CYC(3);
                     // Scores stay unscaled; exp(x/sqrt(d)) = exp2(x * scale_log2).  The reference
                     // m_run only moves when the block maximum exceeds it by more than 2^8 in the
                     // exponent (or no key was seen yet): softmax is invariant to the reference, and
@@ -546,6 +590,7 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                         for (int e = 0; e < 8; ++e) pf[rw][kk][e] = (__bf16)pv[kk * 8 + e];
                 }
                 __builtin_amdgcn_sched_barrier(0);
+                LA_CYC(4);
 
                 // ---- O^T += V^T P^T
 #pragma unroll
@@ -556,6 +601,7 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                         for (int rw = 0; rw < RW; ++rw)
                             o[rw][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kk][db], pf[rw][kk], o[rw][db], 0, 0, 0);
             }
+            LA_CYC(5);
             if (it < 8) LA_STAMP(9 + 2 * it);
         }
 
@@ -666,10 +712,10 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                 *ticket = 0u;  // everyone has arrived; clean for the next call
                 role = (sq * (unsigned)p.XS == sum * sum && !p.force_recompute) ? 1u : 2u;
             }
-            s_role = role;
+            *s_role = role;
         }
         __syncthreads();
-        const unsigned role = s_role;
+        const unsigned role = __builtin_amdgcn_readfirstlane(*s_role);  // same in every lane
         LA_STAMP(6);
         if (role == 0) return;
 #ifdef LA_DEV_KNOBS
@@ -809,14 +855,15 @@ int max_stages(int D, int RW, int RT, int KC)
 {
     const int tiles = RW * RT;
     if (D != 128) return 4;
-    if (KC == 128) return 2;
     return tiles <= 2 ? 4 : (tiles <= 4 ? 3 : 2);
 }
 
 bool plan_supported(int D, int RW, int RT, int KS, int NS, int KC)
 {
-    if (KC == 128) return D == 128 && RW == 1 && RT == 2 && KS == 4 && NS == 2;
+    if (KC == 32) return D == 128 && RW == 1 && RT == 2 && KS == 2 && NS == 9;
     if (KC != 64) return false;
+    if (KS == 4) return D == 128 && RW == 1 && RT == 2 && NS == 4;
+    if (RT == 4 && KS == 2) return D == 128 && RW == 1 && NS == 4;
     if (NS != 2 && NS != max_stages(D, RW, RT, KC)) return false;
     if (D == 128)
         return (RW == 1 && ((RT == 1 && KS == 2) || (RT == 2 && KS == 2) || (RT == 4 && KS == 1) ||
@@ -955,7 +1002,9 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
         if (!prm.partials) return LA_ENOMEM;
     }
 
-    if (pl.KC == 128) return launch_cfg<128, 1, 2, 4, 2, 128>(prm, stream);
+    if (pl.KC == 32) return launch_cfg<128, 1, 2, 2, 9, 32>(prm, stream);
+    if (pl.KS == 4) return launch_cfg<128, 1, 2, 4, 4>(prm, stream);
+    if (pl.RT == 4 && pl.KS == 2) return launch_cfg<128, 1, 4, 2, 4>(prm, stream);
 #define LA_DISPATCH(D_, RW_, RT_, KS_, NSMAX_)                                       \
     if (head_dim == D_ && pl.RW == RW_ && pl.RT == RT_ && pl.KS == KS_) {           \
         if (pl.NS == 2) return launch_cfg<D_, RW_, RT_, KS_, 2>(prm, stream);       \

@@ -180,7 +180,7 @@ def test_recompute_path_for_groups_not_on_one_xcd(monkeypatch):
 
 @pytest.mark.parametrize("plan", ["1,1,2,3,2,64", "1,2,2,5,4,64", "1,2,1,7,4,64", "1,4,1,2,2,64",
                                   "2,2,2,3,3,64", "2,4,1,4,2,64", "1,4,1,1,3,64", "1,2,2,1,2,64",
-                                  "1,2,4,3,2,128", "1,2,4,1,2,128", "1,1,2,2,4,64"])
+                                  "1,2,4,3,4,64", "1,2,4,1,4,64", "1,2,4,7,4,64", "1,1,2,2,4,64", "1,2,2,4,9,32", "1,2,2,1,9,32", "1,2,2,2,9,32", "1,4,2,3,4,64", "1,4,2,1,4,64", "1,4,2,8,4,64"])
 def test_every_kernel_variant(monkeypatch, plan):
     """Each compiled decomposition (rows per wave, row tiles, key-split waves, splits, stages)."""
     monkeypatch.setenv("LA_ATTN_PLAN", plan)
