@@ -8,7 +8,7 @@
 // (v_mfma_f32_32x32x16_bf16, fp32 accumulate) while K and V stream from HBM exactly once per
 // row block.
 //
-// Decomposition.  A workgroup owns (KV head, block of RT*RW 32-row tiles, one of XS ranges of
+// Decomposition.  A workgroup owns (KV head, block of RT 32-row tiles, one of XS ranges of
 // 64-key chunks).  Chunks are copied HBM -> LDS by direct-to-LDS loads into a ring of stages;
 // the 16-byte pieces of a row are stored XOR-swizzled so that both the K operand reads
 // (ds_read_b128, one key per lane) and the transposing V reads (ds_read_b64_tr_b16) are free
@@ -78,6 +78,7 @@ struct AttnParams {
     // (exact while the dividend stays below 2^21, which the host checks).
     float inv_XS, inv_row_blocks, inv_group, inv_W, inv_n1;
     int chunks_lo, chunks_rem;  // n_chunks = XS * chunks_lo + chunks_rem
+    int pre;              // chunks requested before the loop starts (1 .. stages)
     int force_recompute;  // testing: treat every group as spread over several XCDs
 #ifdef LA_DEV_KNOBS
     int dev_mode;         // timing experiments only (results are wrong): see LA_DEV_MODE
@@ -160,22 +161,19 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// Wait until at most `later` * LPW of this wave's loads are still in flight (later < NS).
-template <int LPW, int NS>
-__device__ __forceinline__ void wait_chunks(int later)
+// Wait until at most y * LPW of this wave's loads are still in flight, 0 <= y <= Y.  The
+// steady-state value (the largest) costs one comparison.
+template <int LPW, int Y>
+__device__ __forceinline__ void wait_young(int y)
 {
-    static_assert(LPW * (NS - 1) < 64, "vmcnt is a 6-bit counter");
-    switch (later) {
-    case 0: wait_vmcnt<0>(); break;
-    case 1: wait_vmcnt<(NS > 1 ? 1 : 0) * LPW>(); break;
-    case 2: wait_vmcnt<(NS > 2 ? 2 : 0) * LPW>(); break;
-    case 3: wait_vmcnt<(NS > 3 ? 3 : 0) * LPW>(); break;
-    case 4: wait_vmcnt<(NS > 4 ? 4 : 0) * LPW>(); break;
-    case 5: wait_vmcnt<(NS > 5 ? 5 : 0) * LPW>(); break;
-    case 6: wait_vmcnt<(NS > 6 ? 6 : 0) * LPW>(); break;
-    case 7: wait_vmcnt<(NS > 7 ? 7 : 0) * LPW>(); break;
-    default: wait_vmcnt<(NS > 8 ? 8 : 0) * LPW>(); break;
+    static_assert(LPW * Y < 64, "vmcnt is a 6-bit counter");
+    if constexpr (Y > 0) {
+        if (y < Y) {
+            wait_young<LPW, Y - 1>(y);
+            return;
+        }
     }
+    wait_vmcnt<Y * LPW>();
 }
 
 // One direct-to-LDS load: every lane fetches 16 bytes from its own global address, the wave's
@@ -210,7 +208,7 @@ __device__ __forceinline__ int swizzle(int row)
     return (row >> 1) & 7;
 }
 
-template <int D, int RW, int RT, int KS, int KC, int NSTAGE>
+template <int D, int RT, int KS, int KC, int NSTAGE>
 struct Cfg {
     static constexpr int NW = RT * KS;
     static constexpr int NT = NW * 64;
@@ -225,9 +223,11 @@ struct Cfg {
     static constexpr int STAGE_BYTES = 2 * KV_BYTES;
     static constexpr int WLOADS = STAGE_BYTES / 1024;     // 64-lane x 16-byte loads per chunk
     static constexpr int LPW = WLOADS / NW;               // loads per wave per chunk
-    static constexpr int TILES = RT * RW;                 // 32-row tiles per workgroup
+    static constexpr int TILES = RT;                      // 32-row tiles per workgroup, one per wave group
     static constexpr int ROWS = TILES * 32;
     static constexpr int DB = D / 32;                     // 32-wide blocks of head_dim
+    // After the key-split merge a wave owns SPW of its tile's DB (tile, 32-column) slices.
+    static constexpr int SPW = KS > 1 ? DB / KS : DB;
     static constexpr int FRAG_FLOATS = DB * 16 * 64;      // one tile's accumulators
     static constexpr int TILE_FLOATS = FRAG_FLOATS + 128; // + m and l per lane
     // a split's partial in global memory: per tile the accumulators as bf16 in fragment order
@@ -239,13 +239,19 @@ struct Cfg {
     static constexpr int Q_BYTES = ROWS * RBYTES;         // the workgroup's query rows
     static constexpr int Q_OFFSET = NSTAGE * STAGE_BYTES; // they sit behind the stage ring
     static constexpr int QLPW = Q_BYTES / 1024 / NW;      // Q loads per wave
+    static constexpr int LDS_LIMIT = 160 * 1024 - 16;    // room for the role flag
     static constexpr int LDS_MAIN = NSTAGE * STAGE_BYTES + Q_BYTES;
-    static constexpr int LDS_MERGE = (KS / 2) * RT * RW * TILE_FLOATS * 4;
+    static constexpr int LDS_MERGE = KS > 1 ? NW * TILE_FLOATS * 4 : 0;
     static constexpr int LDS_OUT = ROWS * OUT_PITCH;
-    static constexpr int LDS_BYTES =
-        LDS_MAIN > LDS_MERGE ? (LDS_MAIN > LDS_OUT ? LDS_MAIN : LDS_OUT)
-                             : (LDS_MERGE > LDS_OUT ? LDS_MERGE : LDS_OUT);
+    // the finished rows are staged behind the merge buffers if that fits, else on top of them
+    // (after one more barrier)
+    static constexpr int OUT_OFFSET = LDS_MERGE + LDS_OUT <= LDS_LIMIT ? LDS_MERGE : 0;
+    static constexpr bool OUT_BARRIER = KS > 1 && OUT_OFFSET == 0;
+    static constexpr int LDS_TAIL = OUT_OFFSET + LDS_OUT > LDS_MERGE ? OUT_OFFSET + LDS_OUT : LDS_MERGE;
+    static constexpr int ROLE_OFFSET = LDS_TAIL;  // one flag word, used once the ring is dead
+    static constexpr int LDS_BYTES = LDS_MAIN > LDS_TAIL + 16 ? LDS_MAIN : LDS_TAIL + 16;
     static_assert(KS >= KB ? KS % KB == 0 : KB % KS == 0, "key-split waves and blocks must divide");
+    static_assert(KS == 1 || DB % KS == 0, "key-split waves must divide the head_dim blocks");
     static_assert(NSTAGE >= CPI, "an iteration's chunks must fit the ring");
     static_assert(WLOADS % NW == 0, "chunk loads must divide among the waves");
     static_assert((Q_BYTES / 1024) % NW == 0, "Q loads must divide among the waves");
@@ -255,9 +261,15 @@ struct Cfg {
 
 #ifdef LA_DEV_KNOBS
 #define LA_STAMP(k) do { if (p.dev_trace && (threadIdx.x & 63) == 0) p.dev_trace[((size_t)blockIdx.x * 8 + (threadIdx.x >> 6)) * 24 + (k)] = wall_clock64(); } while (0)
+#define LA_CYCW(k) do { if (p.dev_trace && (threadIdx.x & 63) == 0) p.dev_trace[((size_t)blockIdx.x * 8 + (threadIdx.x >> 6)) * 24 + (k)] = __builtin_readcyclecounter(); } while (0)
+#ifdef LA_NO_CYC
+#define LA_CYC(k) do { } while (0)
+#else
 #define LA_CYC(k) do { if (p.dev_trace && (threadIdx.x & 63) == 0 && it == 1) p.dev_trace[((size_t)(4096 + blockIdx.x) * 8 + (threadIdx.x >> 6)) * 24 + (k)] = __builtin_readcyclecounter(); } while (0)
+#endif
 #else
 #define LA_STAMP(k) do { } while (0)
+#define LA_CYCW(k) do { } while (0)
 #define LA_CYC(k) do { } while (0)
 #endif
 
@@ -284,18 +296,90 @@ __device__ __forceinline__ void write_rows_from_lds(const AttnParams& p, const u
     }
 }
 
-template <int D, int RW, int RT, int KS, int KC, int NSTAGE>
+// Merge the KS key-split waves of a row tile, for the wave whose key index is MYKS.  Every
+// wave leaves the slices it does not own in LDS (fragment layout: [4 regs][lane], 16 bytes per
+// lane and access) with its (max, sum); after one barrier each wave sums its own SPW slices
+// over the KS states, in key order.  On return o[0 .. SPW-1] hold the merged slices
+// MYKS*SPW .. MYKS*SPW+SPW-1 and (m_run, l_run) the merged softmax state of the row.
+template <class C, int KS, int MYKS>
+__device__ __forceinline__ void merge_key_splits(unsigned char* lds, int rt, int lane, bool wave_active,
+                                                 f32x16 (&o)[C::DB], float& m_run, float& l_run,
+                                                 float scale_log2)
+{
+    constexpr int DB0 = MYKS * C::SPW;
+    float* mg = reinterpret_cast<float*>(lds) + rt * KS * C::TILE_FLOATS;  // this tile's states
+    if (wave_active) {
+        float* dst = mg + MYKS * C::TILE_FLOATS;
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db) {
+            if (db >= DB0 && db < DB0 + C::SPW) continue;  // stays in registers
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const f32x4 v = {o[db][i4 * 4], o[db][i4 * 4 + 1], o[db][i4 * 4 + 2], o[db][i4 * 4 + 3]};
+                *reinterpret_cast<f32x4*>(dst + ((db * 4 + i4) * 64 + lane) * 4) = v;
+            }
+        }
+        *reinterpret_cast<f32x2*>(dst + C::FRAG_FLOATS + lane * 2) = f32x2{m_run, l_run};
+    }
+    __syncthreads();
+    if (!wave_active) return;
+    f32x2 ml[KS];
+#pragma unroll
+    for (int k = 0; k < KS; ++k)
+        ml[k] = k == MYKS ? f32x2{m_run, l_run}
+                          : *reinterpret_cast<const f32x2*>(mg + k * C::TILE_FLOATS + C::FRAG_FLOATS + lane * 2);
+    f32x4 v[C::SPW][KS][4];
+#pragma unroll
+    for (int u = 0; u < C::SPW; ++u)
+#pragma unroll
+        for (int k = 0; k < KS; ++k)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4)
+                v[u][k][i4] = k == MYKS
+                                  ? f32x4{o[DB0 + u][i4 * 4], o[DB0 + u][i4 * 4 + 1], o[DB0 + u][i4 * 4 + 2],
+                                          o[DB0 + u][i4 * 4 + 3]}
+                                  : *reinterpret_cast<const f32x4*>(
+                                        mg + k * C::TILE_FLOATS + (((DB0 + u) * 4 + i4) * 64 + lane) * 4);
+    float m_all = ml[0][0];
+#pragma unroll
+    for (int k = 1; k < KS; ++k) m_all = fmaxf(m_all, ml[k][0]);
+    const float m_use = (m_all == kNegInf) ? 0.0f : m_all;
+    float a[KS];
+    float l = 0.0f;
+#pragma unroll
+    for (int k = 0; k < KS; ++k) {
+        a[k] = fast_exp2((ml[k][0] - m_use) * scale_log2);
+        l = __builtin_fmaf(ml[k][1], a[k], l);
+    }
+    m_run = m_all;
+    l_run = l;
+#pragma unroll
+    for (int u = 0; u < C::SPW; ++u)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float acc = v[u][0][i4][e] * a[0];
+#pragma unroll
+                for (int k = 1; k < KS; ++k) acc = __builtin_fmaf(v[u][k][i4][e], a[k], acc);
+                o[u][i4 * 4 + e] = acc;
+            }
+}
+
+template <int D, int RT, int KS, int KC, int NSTAGE>
 __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnParams p)
 {
-    using C = Cfg<D, RW, RT, KS, KC, NSTAGE>;
+    using C = Cfg<D, RT, KS, KC, NSTAGE>;
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
     // Consecutive workgroup ids go round-robin over the 8 XCDs (each with its own L2); put
     // the workgroups that stream the same KV head on one XCD.
     LA_STAMP(0);
+    LA_CYCW(22);
     int logical = (int)(blockIdx.x & 7) * p.wg_per_xcd + (int)(blockIdx.x >> 3);
 #ifdef LA_DEV_KNOBS
-    if (p.dev_mode >= 16) logical = (int)blockIdx.x;  // experiment: no XCD grouping (wrong combine!)
+    if (p.dev_mode & 16) logical = (int)blockIdx.x;  // experiment: no XCD grouping (wrong combine!)
+    if ((p.dev_mode & 64) && blockIdx.x >= 8) return;  // experiment: one workgroup per XCD only
 #endif
     if (logical >= p.total_wg) return;
     // (the float arithmetic runs on the vector unit: tell the compiler the results are uniform,
@@ -308,169 +392,205 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int rt = wave / KS;   // row tile group of this wave
+    const int rt = wave / KS;   // row tile of this wave
     const int ks = wave % KS;   // which key blocks of a chunk it takes
     const int hi = lane >> 5;   // upper half-wave
     const int l32 = lane & 31;
 
     const unsigned lds_base = lds_address(lds);
-    const int row_base = rb * C::ROWS + rt * (RW * 32);  // first row of this wave (in R space)
-    const bool wave_active = row_base < p.R;            // else: only helps loading
+    const int row_base = rb * C::ROWS + rt * 32;  // first row of this wave (in R space)
+    const bool wave_active = row_base < p.R;     // else: only helps loading
 
     // ---- chunk range of this split
     int c_begin = xs * p.chunks_lo + min(xs, p.chunks_rem);
     int c_end = c_begin + p.chunks_lo + (xs < p.chunks_rem ? 1 : 0);
     bool direct = p.XS == 1;  // this pass covers every key of the rows: write `out` directly
 
-    // Per-lane part of a load's address.  A wave-load covers RPW = 64 / NCH consecutive rows of
-    // 16-byte pieces; with row = wl*RPW + lane_row the swizzle splits into a lane part and a part that
-    // depends only on the (wave-uniform) load index wl, so the byte offset of a lane is
-    // lane_off ^ (uni(wl) << 4) and the rest of the address is uniform.
+    // ---- load addressing.  A wave-load moves 1 KB: RPW = 64 / NCH consecutive rows of 16-byte
+    // pieces.  The LDS side is linear; the swizzle is applied on the global side.  Wave-load j
+    // of this wave (j < LPW/2, the same for K and for V) covers chunk rows
+    // (wave + j*NW)*RPW .. +RPW-1.
+    static_assert(C::LPW % 2 == 0, "a wave loads as much of K as of V");
     const int lane_row = lane / C::NCH;
-    const int lane_lc0 = (lane % C::NCH) ^ (D == 128 ? (lane_row << 2) : (lane_row >> 1));
-    const unsigned lane_off = (unsigned)(lane_row * C::RBYTES + (lane_lc0 << 4));
+    const int lane_pc = lane % C::NCH;
+    int ld_row[C::LPW / 2];          // the chunk row this lane fetches in wave-load j
+    unsigned ld_piece[C::LPW / 2];   // byte offset of its 16-byte piece within that row
+#pragma unroll
+    for (int j = 0; j < C::LPW / 2; ++j) {
+        ld_row[j] = (wave + j * C::NW) * (64 / C::NCH) + lane_row;
+        ld_piece[j] = (unsigned)((lane_pc ^ swizzle<D>(ld_row[j])) << 4);
+    }
 
-    // Issue the direct-to-LDS loads of chunk `c` into stage `st`: a wave-uniform 64-bit base
-    // plus a 32-bit lane offset per load.
-    auto issue_chunk = [&](int c, int st) {
-        const bool is_step = c >= p.n_prefix_chunks;
-        const int key0 = (is_step ? c - p.n_prefix_chunks : c) * KC;
-        const int limit = is_step ? p.T : p.P;
-        const int last_row = min(KC, limit - key0) - 1;  // >= 0
-        const unsigned stage_lds = lds_base + st * C::STAGE_BYTES;
-        // rows of the prefix cache are contiguous; step keys are strided by kv_heads
-        const unsigned stride_b = (unsigned)(is_step ? p.kv_heads * C::RBYTES : C::RBYTES);
-        const size_t first = is_step ? ((size_t)key0 * p.kv_heads + kvh) * D
-                                     : ((size_t)kvh * p.P + key0) * D;
-        const unsigned char* kbase = reinterpret_cast<const unsigned char*>((is_step ? p.step_k : p.k_cache) + first);
-        const unsigned char* vbase = reinterpret_cast<const unsigned char*>((is_step ? p.step_v : p.v_cache) + first);
-        if (!is_step && last_row == KC - 1) {
-            // a full chunk of the prefix cache: K and V are contiguous KV_BYTES regions
-#pragma unroll
-            for (int i = 0; i < C::LPW; ++i) {
-                const int wl = wave + i * C::NW;                  // wave-load index in the chunk
-                const bool is_v = wl >= C::WLOADS / 2;
-                const int wl2 = is_v ? wl - C::WLOADS / 2 : wl;   // index within K or V
-                const unsigned uni = D == 128 ? (unsigned)(wl2 & 3) : (unsigned)((wl2 & 1) << 2);
-                dma16_base((is_v ? vbase : kbase) + wl2 * 1024, lane_off ^ (uni << 4),
-                           __builtin_amdgcn_readfirstlane(stage_lds + wl * 1024));
-            }
+    // This KV head's part of the four key/value tensors (wave-uniform).
+    const unsigned char* const kc_head = reinterpret_cast<const unsigned char*>(p.k_cache) + (size_t)kvh * p.P * C::RBYTES;
+    const unsigned char* const vc_head = reinterpret_cast<const unsigned char*>(p.v_cache) + (size_t)kvh * p.P * C::RBYTES;
+    const unsigned char* const sk_head = reinterpret_cast<const unsigned char*>(p.step_k) + (size_t)kvh * C::RBYTES;
+    const unsigned char* const sv_head = reinterpret_cast<const unsigned char*>(p.step_v) + (size_t)kvh * C::RBYTES;
+    const unsigned step_stride = (unsigned)(p.kv_heads * C::RBYTES);  // step keys are strided by kv_heads
+    const int n_prefix_chunks = p.n_prefix_chunks, n_P = p.P, n_T = p.T;
+
+    // ---- the stream of chunks to request, as running wave-uniform state: every scalar
+    //      instruction in the loop is paid by all waves of the workgroup, so nothing is
+    //      recomputed from the chunk index
+    const unsigned char* iss_k;   // K rows of the next chunk to request
+    const unsigned char* iss_v;   // V rows
+    int iss_rows;                 // rows from there to the end of the tensor (prefix cache or step)
+    unsigned iss_stride;          // bytes between rows (the host checks it is below 2^24)
+    int iss_prefix_left;          // prefix chunks still to request before the step keys start
+    unsigned iss_stage;           // LDS offset of the stage the next chunk goes to
+    auto seek = [&](int c) {      // next chunk to request := chunk c, into stage 0
+        if (c < n_prefix_chunks) {
+            const int key0 = c * KC;
+            iss_k = kc_head + (size_t)key0 * C::RBYTES;
+            iss_v = vc_head + (size_t)key0 * C::RBYTES;
+            iss_rows = n_P - key0;
+            iss_stride = C::RBYTES;
+            iss_prefix_left = n_prefix_chunks - c;
         } else {
-            // ragged end or strided step keys: rows past the end repeat the last one
-            // (the host checks that the row stride is below 2^24 bytes)
+            const int key0 = (c - n_prefix_chunks) * KC;
+            iss_k = sk_head + (size_t)key0 * step_stride;
+            iss_v = sv_head + (size_t)key0 * step_stride;
+            iss_rows = n_T - key0;
+            iss_stride = step_stride;
+            iss_prefix_left = 0;
+        }
+        iss_stage = 0;
+    };
+    // Request the next chunk: direct-to-LDS loads, a wave-uniform 64-bit base plus a 32-bit lane
+    // offset each.  Rows past the end of the tensor repeat its last row (they are masked later).
+    auto issue_next = [&]() {
+        const int last_row = min(KC, iss_rows) - 1;  // >= 0
+        const unsigned dst = lds_base + iss_stage + (unsigned)wave * 1024u;
 #pragma unroll
-            for (int i = 0; i < C::LPW; ++i) {
-                const int wl = wave + i * C::NW;
-                const bool is_v = wl >= C::WLOADS / 2;
-                const int wl2 = is_v ? wl - C::WLOADS / 2 : wl;
-                const unsigned uni = D == 128 ? (unsigned)(wl2 & 3) : (unsigned)((wl2 & 1) << 2);
-                const int srow = min(wl2 * (64 / C::NCH) + lane_row, last_row);
-                const unsigned off = __umul24((unsigned)srow, stride_b) + (((unsigned)lane_lc0 ^ uni) << 4);
-                dma16_base(is_v ? vbase : kbase, off, __builtin_amdgcn_readfirstlane(stage_lds + wl * 1024));
-            }
+        for (int j = 0; j < C::LPW / 2; ++j) {
+            const unsigned off = __umul24((unsigned)min(ld_row[j], last_row), iss_stride) + ld_piece[j];
+            dma16_base(iss_k, off, dst + j * C::NW * 1024);
+            dma16_base(iss_v, off, dst + C::KV_BYTES + j * C::NW * 1024);
+        }
+        iss_stage = iss_stage + C::STAGE_BYTES == (unsigned)(NSTAGE * C::STAGE_BYTES) ? 0u : iss_stage + C::STAGE_BYTES;
+        iss_rows -= KC;
+        if (--iss_prefix_left == 0) {  // the prefix cache is exhausted: go on with the step keys
+            iss_k = sk_head;
+            iss_v = sv_head;
+            iss_rows = n_T;
+            iss_stride = step_stride;
+        } else {
+            iss_k += (size_t)KC * iss_stride;
+            iss_v += (size_t)KC * iss_stride;
         }
     };
-
-    // Request Q and the first chunks before anything else: the stream from HBM is the critical
-    // path.  The workgroup's query rows go to LDS (same swizzle as K) and are the oldest loads
-    // in flight, so the first chunk's wait covers them.  Rows past the end repeat the last row.
-#ifdef LA_DEV_KNOBS
-    if (!(p.dev_mode & 32))
-#endif
-    {
+    // The workgroup's query rows go to LDS like a chunk (same swizzle as K); rows past the end
+    // repeat the last row.
+    auto issue_q = [&]() {
 #pragma unroll
         for (int i = 0; i < C::QLPW; ++i) {
             const int wl = wave + i * C::NW;
-            const int piece = wl * 64 + lane;
-            const int row = piece / C::NCH, pc = piece % C::NCH;
-            const int lc = pc ^ swizzle<D>(row);
+            const int row = wl * (64 / C::NCH) + lane_row;
+            const int lc = lane_pc ^ swizzle<D>(row);
             const int rr = min(rb * C::ROWS + row, p.R - 1);
             const int t = div_small(rr, p.inv_group), hh = rr - t * p.group;
             // (the host checks that q spans less than 2^31 bytes)
             const unsigned off = (unsigned)(((t * p.heads + kvh * p.group + hh) * D + lc * 8) * 2);
-            dma16_base(p.q, off, __builtin_amdgcn_readfirstlane(lds_base + C::Q_OFFSET + wl * 1024));
+            dma16_base(p.q, off, lds_base + C::Q_OFFSET + wl * 1024);
         }
-    }
+    };
+
+    // Requests first: the stream from HBM is the critical path.  The chunks of the first
+    // iteration, then Q (needed with them), then the rest of the `pre` chunks.
+    int n_my = c_end - c_begin;
+    int issued = 0;               // chunks of this pass requested so far
+    seek(c_begin);
+    auto issue_first = [&](bool with_q) {
+        const int upfront = min(n_my, p.pre);
 #pragma unroll
-    for (int s = 0; s < NSTAGE; ++s)
-        if (s < c_end - c_begin) issue_chunk(c_begin + s, s);
+        for (int s = 0; s < NSTAGE; ++s) {
+            if (s == C::CPI && with_q) issue_q();
+            if (s < upfront) issue_next();
+        }
+        issued = upfront;
+    };
+#ifdef LA_DEV_KNOBS
+    issue_first(!(p.dev_mode & 32));
+#else
+    issue_first(true);
+#endif
     LA_STAMP(1);
 
-    // which step keys each of this lane's rows may see
-    RowVis vis[RW];
-#pragma unroll
-    for (int rw = 0; rw < RW; ++rw) {
-        const int rr = min(row_base + rw * 32 + l32, p.R - 1);
-        vis[rw] = row_visibility(div_small(rr, p.inv_group), p.W, p.N, p.inv_W, p.inv_n1);
-    }
-    bf16x8 qreg[RW][D / 16];  // B operand of S^T = K Q^T: row l32, d = k16*16 + hi*8 .. +8
+    // which step keys this lane's row may see
+    const RowVis vis = row_visibility(div_small(min(row_base + l32, p.R - 1), p.inv_group), p.W, p.N,
+                                      p.inv_W, p.inv_n1);
+    bf16x8 qreg[D / 16];  // B operand of S^T = K Q^T: row l32, d = k16*16 + hi*8 .. +8
 
-    f32x16 o[RW][C::DB];
-    float m_run[RW], l_run[RW];
-    // after the ticket: 0 not last, 1 last and co-located, 2 recompute.  It lives where the Q rows
-    // were (they are in registers by then), so that the stage ring can use every other byte.
-    volatile unsigned* s_role = reinterpret_cast<volatile unsigned*>(lds + C::Q_OFFSET);
+    // o[db]: O^T accumulators of this wave's tile in the main loop; after the key-split merge,
+    // o[0 .. SPW-1] are the tile's 32-column slices db0 .. db0+SPW-1 summed over all key splits
+    f32x16 o[C::DB];
+    float m_run, l_run;
+    const int db0 = KS > 1 ? ks * C::SPW : 0;
+    const int cw = KS > C::KB ? ks / C::KB : 0;  // which of an iteration's chunks this wave takes
+    // after the ticket: 0 not last, 1 last and co-located, 2 recompute (a word of LDS, addressed as such)
+    typedef __attribute__((address_space(3))) unsigned lds_u32;
+    lds_u32* const s_role = (lds_u32*)(lds + C::ROLE_OFFSET);
 
     for (int pass = 0;; ++pass) {
+        m_run = kNegInf;
+        l_run = 0.0f;
 #pragma unroll
-        for (int rw = 0; rw < RW; ++rw) {
-            m_run[rw] = kNegInf;
-            l_run[rw] = 0.0f;
+        for (int db = 0; db < C::DB; ++db)
 #pragma unroll
-            for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) o[rw][db][i] = 0.0f;
-        }
-        const int n_my = c_end - c_begin;
+            for (int i = 0; i < 16; ++i) o[db][i] = 0.0f;
         if (pass > 0) {
-#pragma unroll
-            for (int s = 0; s < NSTAGE; ++s)
-                if (s < n_my) issue_chunk(c_begin + s, s);
+            n_my = c_end - c_begin;
+            seek(c_begin);
+            issue_first(false);
         }
 
-        const int n_iter = (n_my + C::CPI - 1) / C::CPI;
-        for (int it = 0; it < n_iter; ++it) {
-            // Iteration `it` consumes chunks it*CPI .. it*CPI+CPI-1.  Every stage is requested up
-            // front; the stages an iteration frees are refilled at the start of the next one.
+        // Iteration `it` consumes chunks done .. done+CPI-1 of this pass (done = it*CPI).
+        int cons_c = c_begin + cw;                     // the chunk this wave takes next
+        unsigned cons_stage = (unsigned)cw * C::STAGE_BYTES;  // and the LDS offset of its stage
+#ifdef LA_DEV_KNOBS
+        // timing experiment: run the loop many times over the chunks already in LDS (needs n_my <= pre)
+        for (int rep = 0, reps = (p.dev_mode & 128) ? 200 : 1; rep < reps; ++rep) {
+        cons_c = c_begin + cw;
+        cons_stage = (unsigned)cw * C::STAGE_BYTES;
+#endif
+        for (int it = 0, done = 0; done < n_my; ++it, done += C::CPI) {
             // Wait for this wave's loads of the chunks needed now; younger ones stay in flight.
-            const int c_hi = min(n_my, (it + 1) * C::CPI) - 1;
-            const int issued = min(n_my, NSTAGE + (it > 0 ? (it - 1) * C::CPI : 0));
-            wait_chunks<C::LPW, NSTAGE>(issued - 1 - c_hi);  // 0 .. NSTAGE-1 younger chunks
+            wait_young<C::LPW, NSTAGE - C::CPI>(issued - min(n_my, done + C::CPI));
             LA_CYC(7);
             __syncthreads();  // these chunks are complete in LDS; everyone is done with the last ones
             LA_CYC(6);
-            if (it < 8) LA_STAMP(8 + 2 * it);
+            if (it < 4) LA_STAMP(8 + 2 * it);
             if (it == 0 && pass == 0) {
-                // Q has landed with the first chunk: move this wave's rows to registers
+                // Q has landed with the first chunks: move this wave's rows to registers
+                const int qrow = rt * 32 + l32;
+                const unsigned char* qr = lds + C::Q_OFFSET + qrow * C::RBYTES;
+                const int qsw = swizzle<D>(qrow);
 #pragma unroll
-                for (int rw = 0; rw < RW; ++rw) {
-                    const int qrow = (rt * RW + rw) * 32 + l32;
-                    const unsigned char* qr = lds + C::Q_OFFSET + qrow * C::RBYTES;
-                    const int qsw = swizzle<D>(qrow);
-#pragma unroll
-                    for (int k16 = 0; k16 < D / 16; ++k16)
-                        qreg[rw][k16] = *reinterpret_cast<const bf16x8*>(qr + (((k16 * 2 + hi) ^ qsw) << 4));
-                }
+                for (int k16 = 0; k16 < D / 16; ++k16)
+                    qreg[k16] = *reinterpret_cast<const bf16x8*>(qr + (((k16 * 2 + hi) ^ qsw) << 4));
             }
-            if (it >= 1) {
-#pragma unroll
-                for (int j = 0; j < C::CPI; ++j) {
-                    const int cn = (it - 1) * C::CPI + NSTAGE + j;
-                    if (cn < n_my) issue_chunk(c_begin + cn, cn % NSTAGE);
+            // Up to CPI chunks are requested per iteration, into stages the last iteration freed:
+            // the ring has room up to chunk done + NSTAGE - 1.  A computing wave issues its first
+            // request behind a batch of MFMAs, which run on meanwhile.
+            const int room = min(n_my, done + NSTAGE);
+            int slots_left = C::CPI;
+            auto issue_slot = [&]() {
+                if (issued < room) {
+                    issue_next();
+                    ++issued;
                 }
-            }
-            const int cl = it * C::CPI + (KS > C::KB ? ks / C::KB : 0);  // this wave's chunk
-            if (cl >= n_my) continue;
-            if (!wave_active) continue;
+                --slots_left;
+            };
+            bool compute = done + cw < n_my && wave_active;
 #ifdef LA_DEV_KNOBS
-            if ((p.dev_mode & 15) == 2) continue;  // loads only
+            if ((p.dev_mode & 15) == 2) compute = false;  // loads only
+            if (rep > 0) slots_left = 0;
 #endif
-
-            const int c = c_begin + cl;
-            const bool is_step = c >= p.n_prefix_chunks;
-            const int chunk_key0 = (is_step ? c - p.n_prefix_chunks : c) * KC;
-            const int limit = is_step ? p.T : p.P;
-            const unsigned char* kst = lds + (cl % NSTAGE) * C::STAGE_BYTES;
+            if (compute) {
+            const bool is_step = cons_c >= n_prefix_chunks;
+            const int chunk_key0 = (cons_c - (is_step ? n_prefix_chunks : 0)) * KC;
+            const int limit = is_step ? n_T : n_P;
+            const unsigned char* kst = lds + cons_stage;
             const unsigned char* vst = kst + C::KV_BYTES;
 
 #pragma unroll
@@ -517,78 +637,72 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                 __builtin_amdgcn_sched_barrier(0);
                 LA_CYC(1);
 
-                // ---- S^T block: 32 keys x 32 rows per tile
-                f32x16 s[RW];
+                // ---- S^T block: 32 keys x 32 rows
+                f32x16 s;
 #pragma unroll
-                for (int rw = 0; rw < RW; ++rw)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) s[rw][i] = 0.0f;
+                for (int i = 0; i < 16; ++i) s[i] = 0.0f;
 #pragma unroll
                 for (int k16 = 0; k16 < D / 16; ++k16)
-#pragma unroll
-                    for (int rw = 0; rw < RW; ++rw)
-                        s[rw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[k16], qreg[rw][k16], s[rw], 0, 0, 0);
+                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[k16], qreg[k16], s, 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 LA_CYC(2);
+                if (slots_left > 0) issue_slot();
                 read_v(1);  // in flight during the softmax arithmetic
 
                 // ---- mask, running max, exponentials
                 const bool full = !is_step && (key0 + 32 <= limit);  // wave-uniform
-                bf16x8 pf[RW][2];
-#pragma unroll
-                for (int rw = 0; rw < RW; ++rw) {
-                    if (!full) {
-                        unsigned word;
-                        if (is_step) {
-                            word = step_block_word(vis[rw], key0);
-                        } else {
-                            const int n = limit - key0;  // 1..31
-                            word = (1u << n) - 1u;
-                        }
-                        word >>= hi * 4;
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            const int bit = (i >> 2) * 8 + (i & 3);  // hi*4 already shifted out
-                            if (!((word >> bit) & 1u)) s[rw][i] = kNegInf;
-                        }
+                if (!full) {
+                    unsigned word;
+                    if (is_step) {
+                        word = step_block_word(vis, key0);
+                    } else {
+                        const int n = limit - key0;  // 1..31
+                        word = (1u << n) - 1u;
                     }
-                    float mx = max3(s[rw][0], s[rw][1], s[rw][2]);
+                    word >>= hi * 4;
 #pragma unroll
-                    for (int i = 3; i < 15; i += 2) mx = max3(mx, s[rw][i], s[rw][i + 1]);
-                    mx = max_across_halves(fmaxf(mx, s[rw][15]));
-                    LA_CYC(3);
-                    // Scores stay unscaled; exp(x/sqrt(d)) = exp2(x * scale_log2).  The reference
-                    // m_run only moves when the block maximum exceeds it by more than 2^8 in the
-                    // exponent (or no key was seen yet): softmax is invariant to the reference, and
-                    // skipping small moves saves rescaling the accumulators nearly every time.
-                    const bool move = (mx - m_run[rw]) * p.scale_log2 > 8.0f || m_run[rw] == kNegInf;
-                    const float m_new = move ? mx : m_run[rw];
-                    const float m_use = (m_new == kNegInf) ? 0.0f : m_new;
-                    const float neg_mc = -m_use * p.scale_log2;
-                    if (__builtin_amdgcn_ballot_w64(move) != 0ull) {
-                        const float alpha = fast_exp2(__builtin_fmaf(m_run[rw], p.scale_log2, neg_mc));
-                        l_run[rw] *= alpha;
-#pragma unroll
-                        for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-                            for (int i = 0; i < 16; ++i) o[rw][db][i] *= alpha;
+                    for (int i = 0; i < 16; ++i) {
+                        const int bit = (i >> 2) * 8 + (i & 3);  // hi*4 already shifted out
+                        if (!((word >> bit) & 1u)) s[i] = kNegInf;
                     }
-                    m_run[rw] = m_new;
-                    float psum0 = 0.0f, psum1 = 0.0f;
-                    float pv[16];
-#pragma unroll
-                    for (int i = 0; i < 16; i += 2) {
-                        pv[i] = fast_exp2(__builtin_fmaf(s[rw][i], p.scale_log2, neg_mc));
-                        pv[i + 1] = fast_exp2(__builtin_fmaf(s[rw][i + 1], p.scale_log2, neg_mc));
-                        psum0 += pv[i];
-                        psum1 += pv[i + 1];
-                    }
-                    l_run[rw] += psum0 + psum1;
-#pragma unroll
-                    for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) pf[rw][kk][e] = (__bf16)pv[kk * 8 + e];
                 }
+                float mx = max3(s[0], s[1], s[2]);
+#pragma unroll
+                for (int i = 3; i < 15; i += 2) mx = max3(mx, s[i], s[i + 1]);
+                mx = max_across_halves(fmaxf(mx, s[15]));
+                LA_CYC(3);
+                // Scores stay unscaled; exp(x/sqrt(d)) = exp2(x * scale_log2).  The reference
+                // m_run only moves when the block maximum exceeds it by more than 2^8 in the
+                // exponent (or no key was seen yet): softmax is invariant to the reference, and
+                // skipping small moves saves rescaling the accumulators nearly every time.
+                const bool move = (mx - m_run) * p.scale_log2 > 8.0f || m_run == kNegInf;
+                const float m_new = move ? mx : m_run;
+                const float m_use = (m_new == kNegInf) ? 0.0f : m_new;
+                const float neg_mc = -m_use * p.scale_log2;
+                if (__builtin_amdgcn_ballot_w64(move) != 0ull) {
+                    const float alpha = fast_exp2(__builtin_fmaf(m_run, p.scale_log2, neg_mc));
+                    l_run *= alpha;
+#pragma unroll
+                    for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+                }
+                m_run = m_new;
+                float psum0 = 0.0f, psum1 = 0.0f;
+                float pv[16];
+#pragma unroll
+                for (int i = 0; i < 16; i += 2) {
+                    pv[i] = fast_exp2(__builtin_fmaf(s[i], p.scale_log2, neg_mc));
+                    pv[i + 1] = fast_exp2(__builtin_fmaf(s[i + 1], p.scale_log2, neg_mc));
+                    psum0 += pv[i];
+                    psum1 += pv[i + 1];
+                }
+                l_run += psum0 + psum1;
+                bf16x8 pf[2];
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) pf[kk][e] = (__bf16)pv[kk * 8 + e];
                 __builtin_amdgcn_sched_barrier(0);
                 LA_CYC(4);
 
@@ -597,79 +711,45 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                 for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
                     for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-                        for (int rw = 0; rw < RW; ++rw)
-                            o[rw][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kk][db], pf[rw][kk], o[rw][db], 0, 0, 0);
+                        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kk][db], pf[kk], o[db], 0, 0, 0);
             }
+            __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int j = 0; j < C::CPI; ++j)
+                if (slots_left > 0) issue_slot();
+            cons_c += C::CPI;
+            cons_stage += C::CPI * C::STAGE_BYTES;
+            if (cons_stage >= (unsigned)(NSTAGE * C::STAGE_BYTES)) cons_stage -= NSTAGE * C::STAGE_BYTES;
             LA_CYC(5);
-            if (it < 8) LA_STAMP(9 + 2 * it);
+            if (it < 4) LA_STAMP(9 + 2 * it);
         }
+#ifdef LA_DEV_KNOBS
+        }
+#endif
 
         LA_STAMP(3);
 #ifdef LA_DEV_KNOBS
         if ((p.dev_mode & 15) == 1 || (p.dev_mode & 15) == 2) {  // stop after the main loop
-            if (l_run[0] == 123.456f) p.out[tid] = (__bf16)o[0][0][0];
+            if (l_run == 123.456f) p.out[tid] = (__bf16)o[0][0];
             return;
         }
 #endif
         // the two half-waves of a row hold the sums over their own keys
-#pragma unroll
-        for (int rw = 0; rw < RW; ++rw) l_run[rw] += __shfl_xor(l_run[rw], 32, 64);
+        l_run += __shfl_xor(l_run, 32, 64);
 
         __syncthreads();  // all stages consumed: LDS is reused below
+        LA_STAMP(16);
 
-        // ---- merge the KS waves of a row tile through LDS, pairwise: at each step the waves
-        //      whose key index has the step's bit set hand their state to the wave `step` below
-        //      (fragment layout: [4 regs][lane], 16 bytes per lane and access)
+        // ---- merge the KS waves of a row tile; the key index is uniform in a wave, and branching
+        //      on it keeps every register index a compile-time constant
         if (KS > 1) {
-            float* mg = reinterpret_cast<float*>(lds);
-#pragma unroll
-            for (int step = 1; step < KS; step <<= 1) {
-                const bool sender = (ks & (2 * step - 1)) == step;
-                const bool receiver = (ks & (2 * step - 1)) == 0;
-                // slot of the pair within this step: one per (receiver, tile)
-                float* slot = mg + (((ks >> 1) / step * RT + rt) * RW) * C::TILE_FLOATS;
-                if (sender && wave_active) {
-#pragma unroll
-                    for (int rw = 0; rw < RW; ++rw) {
-                        float* dst = slot + rw * C::TILE_FLOATS;
-#pragma unroll
-                        for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-                            for (int i4 = 0; i4 < 4; ++i4) {
-                                f32x4 v = {o[rw][db][i4 * 4], o[rw][db][i4 * 4 + 1], o[rw][db][i4 * 4 + 2],
-                                           o[rw][db][i4 * 4 + 3]};
-                                *reinterpret_cast<f32x4*>(dst + ((db * 4 + i4) * 64 + lane) * 4) = v;
-                            }
-                        *reinterpret_cast<f32x2*>(dst + C::FRAG_FLOATS + lane * 2) = f32x2{m_run[rw], l_run[rw]};
-                    }
-                }
-                __syncthreads();
-                if (receiver && wave_active) {
-#pragma unroll
-                    for (int rw = 0; rw < RW; ++rw) {
-                        const float* src = slot + rw * C::TILE_FLOATS;
-                        const f32x2 ml2 = *reinterpret_cast<const f32x2*>(src + C::FRAG_FLOATS + lane * 2);
-                        const float m2 = ml2[0], l2 = ml2[1];
-                        const float m_new = fmaxf(m_run[rw], m2);
-                        const float m_use = (m_new == kNegInf) ? 0.0f : m_new;
-                        const float a1 = fast_exp2((m_run[rw] - m_use) * p.scale_log2);
-                        const float a2 = fast_exp2((m2 - m_use) * p.scale_log2);
-                        l_run[rw] = l_run[rw] * a1 + l2 * a2;
-                        m_run[rw] = m_new;
-#pragma unroll
-                        for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-                            for (int i4 = 0; i4 < 4; ++i4) {
-                                const f32x4 v = *reinterpret_cast<const f32x4*>(src + ((db * 4 + i4) * 64 + lane) * 4);
-#pragma unroll
-                                for (int e = 0; e < 4; ++e)
-                                    o[rw][db][i4 * 4 + e] = o[rw][db][i4 * 4 + e] * a1 + v[e] * a2;
-                            }
-                    }
-                }
-                __syncthreads();
-            }
+            const float sc = p.scale_log2;
+            if (ks == 0) merge_key_splits<C, KS, 0>(lds, rt, lane, wave_active, o, m_run, l_run, sc);
+            if (KS > 1 && ks == 1) merge_key_splits<C, KS, (KS > 1 ? 1 : 0)>(lds, rt, lane, wave_active, o, m_run, l_run, sc);
+            if (KS > 2 && ks == 2) merge_key_splits<C, KS, (KS > 2 ? 2 : 0)>(lds, rt, lane, wave_active, o, m_run, l_run, sc);
+            if (KS > 3 && ks == 3) merge_key_splits<C, KS, (KS > 3 ? 3 : 0)>(lds, rt, lane, wave_active, o, m_run, l_run, sc);
+            static_assert(KS <= 4, "one branch per key index");
         }
         LA_STAMP(4);
         if (direct) break;
@@ -677,22 +757,18 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
         // ---- split combine: store this split's partial, then take a ticket
         unsigned char* group_base = reinterpret_cast<unsigned char*>(p.partials) +
                                     (size_t)((kvh * p.n_row_blocks + rb) * p.XS) * C::PART_WG_BYTES;
-        if (ks == 0 && wave_active) {
+        if (wave_active) {
+            unsigned char* dst = group_base + (size_t)xs * C::PART_WG_BYTES + (size_t)rt * C::PART_TILE_BYTES;
 #pragma unroll
-            for (int rw = 0; rw < RW; ++rw) {
-                unsigned char* dst = group_base + (size_t)xs * C::PART_WG_BYTES +
-                                     (size_t)(rt * RW + rw) * C::PART_TILE_BYTES;
+            for (int u = 0; u < C::SPW; ++u)
 #pragma unroll
-                for (int db = 0; db < C::DB; ++db)
+                for (int i8 = 0; i8 < 2; ++i8) {
+                    bf16x8 v;
 #pragma unroll
-                    for (int i8 = 0; i8 < 2; ++i8) {
-                        bf16x8 v;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) v[e] = (__bf16)o[rw][db][i8 * 8 + e];
-                        *reinterpret_cast<bf16x8*>(dst + ((db * 2 + i8) * 64 + lane) * 16) = v;
-                    }
-                *reinterpret_cast<f32x2*>(dst + C::PART_ACC_BYTES + lane * 8) = f32x2{m_run[rw], l_run[rw]};
-            }
+                    for (int e = 0; e < 8; ++e) v[e] = (__bf16)o[u][i8 * 8 + e];
+                    *reinterpret_cast<bf16x8*>(dst + (((db0 + u) * 2 + i8) * 64 + lane) * 16) = v;
+                }
+            if (db0 == 0) *reinterpret_cast<f32x2*>(dst + C::PART_ACC_BYTES + lane * 8) = f32x2{m_run, l_run};
         }
         // Stores are acknowledged by the L2 of this XCD: wait for them, then publish.
         __builtin_amdgcn_s_waitcnt(0);
@@ -723,12 +799,13 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
 #endif
         if (role == 1) {
             // ---- last to arrive, all partials sit in the L2 this XCD shares: merge them in
-            //      index order.  Work unit: one (tile, 32-column block); a wave takes two units
-            //      at a time and requests all their partials before merging any, so that the
-            //      usual case (at most 4 splits) costs one trip to the L2.
+            //      index order.  Work unit: one (tile, 32-column) slice; a wave requests all the
+            //      partials of its units before merging any, so that the usual case (at most 4
+            //      splits) costs one trip to the L2.
             constexpr int NSUB = C::TILES * C::DB;
-            constexpr int NU = (RW == 1 && NSUB > C::NW) ? 2 : 1;  // units in flight per wave
-            constexpr int MB = RW == 1 ? 4 : 2;                     // splits requested at a time
+            constexpr int NU = NSUB > C::NW ? 2 : 1;  // units in flight per wave
+            constexpr int MB = 4;                     // splits requested at a time
+            LA_STAMP(17);
             for (int st0 = wave; st0 < NSUB; st0 += NU * C::NW) {
                 float m_acc[NU], l_acc[NU];
                 float acc[NU][16];
@@ -758,6 +835,7 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                                 v[u][w][i8] = *reinterpret_cast<const bf16x8*>(src + ((db * 2 + i8) * 64 + lane) * 16);
                         }
                     }
+                    LA_STAMP(18);
 #pragma unroll
                     for (int u = 0; u < NU; ++u) {
                         // batch maximum, then one weight per split: acc = acc * a0 + sum_w v_w * a_w
@@ -791,7 +869,7 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                     if (st >= NSUB) break;
                     const int tile = st / C::DB, db = st - tile * C::DB;
                     const float inv = 1.0f / l_acc[u];
-                    unsigned char* row_ptr = lds + (tile * 32 + l32) * C::OUT_PITCH;
+                    unsigned char* row_ptr = lds + C::OUT_OFFSET + (tile * 32 + l32) * C::OUT_PITCH;
 #pragma unroll
                     for (int i4 = 0; i4 < 4; ++i4) {
                         bf16x4 ov;
@@ -804,8 +882,9 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
             LA_STAMP(20);
             __syncthreads();
             LA_STAMP(21);
-            write_rows_from_lds<C>(p, lds, rb, kvh, tid);
+            write_rows_from_lds<C>(p, lds + C::OUT_OFFSET, rb, kvh, tid);
             LA_STAMP(7);
+            LA_CYCW(23);
             return;
         }
         // ---- role 2: the group was spread over several XCDs, whose L2s are not coherent with
@@ -817,59 +896,54 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
     }
 
     // ---- normalise, transpose through LDS, write bf16 rows with 16-byte stores
-    if (ks == 0 && wave_active) {
+    if (C::OUT_BARRIER) __syncthreads();  // the rows are staged where merge states are still being read
+    if (wave_active) {
+        const float inv = 1.0f / l_run;  // >= 1 visible key per row, so l > 0
+        unsigned char* row_ptr = lds + C::OUT_OFFSET + (rt * 32 + l32) * C::OUT_PITCH;
 #pragma unroll
-        for (int rw = 0; rw < RW; ++rw) {
-            const float inv = 1.0f / l_run[rw];  // >= 1 visible key per row, so l > 0
-            unsigned char* row_ptr = lds + ((rt * RW + rw) * 32 + l32) * C::OUT_PITCH;
+        for (int u = 0; u < C::SPW; ++u)
 #pragma unroll
-            for (int db = 0; db < C::DB; ++db)
+            for (int i4 = 0; i4 < 4; ++i4) {
+                bf16x4 v;
 #pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    bf16x4 v;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = (__bf16)(o[rw][db][i4 * 4 + e] * inv);
-                    const int dcol = db * 32 + i4 * 8 + hi * 4;
-                    *reinterpret_cast<bf16x4*>(row_ptr + dcol * 2) = v;
-                }
-        }
+                for (int e = 0; e < 4; ++e) v[e] = (__bf16)(o[u][i4 * 4 + e] * inv);
+                const int dcol = (db0 + u) * 32 + i4 * 8 + hi * 4;
+                *reinterpret_cast<bf16x4*>(row_ptr + dcol * 2) = v;
+            }
     }
     __syncthreads();
-    write_rows_from_lds<C>(p, lds, rb, kvh, tid);
+    write_rows_from_lds<C>(p, lds + C::OUT_OFFSET, rb, kvh, tid);
 }
 
 // ---------------------------------------------------------------------------------------
 // host side
 
 struct Plan {
-    int RW, RT, KS, XS, NS;   // NS = LDS stages
+    int RT, KS, XS, NS;       // NS = LDS stages
+    int PRE;                  // chunks requested before the loop (0 = all stages)
     int KC;                   // keys per chunk
     int n_row_blocks;
     int n_prefix_chunks, n_chunks;
     size_t partial_bytes_per_wg;
 };
 
-
 // Most LDS stages that fit beside the workgroup's Q rows.
-int max_stages(int D, int RW, int RT, int KC)
+int max_stages(int D, int RT)
 {
-    const int tiles = RW * RT;
     if (D != 128) return 4;
-    return tiles <= 2 ? 4 : (tiles <= 4 ? 3 : 2);
+    return RT <= 2 ? 4 : 3;
 }
 
-bool plan_supported(int D, int RW, int RT, int KS, int NS, int KC)
+bool plan_supported(int D, int RT, int KS, int NS, int KC)
 {
-    if (KC == 32) return D == 128 && RW == 1 && RT == 2 && KS == 2 && NS == 9;
+    if (KC == 32) return D == 128 && RT == 2 && KS == 2 && NS == 9;
     if (KC != 64) return false;
-    if (KS == 4) return D == 128 && RW == 1 && RT == 2 && NS == 4;
-    if (RT == 4 && KS == 2) return D == 128 && RW == 1 && NS == 4;
-    if (NS != 2 && NS != max_stages(D, RW, RT, KC)) return false;
+    if (KS == 4) return D == 128 && RT == 2 && NS == 4;
+    if (RT == 4 && KS == 2) return D == 128 && NS == 4;
+    if (NS != 2 && NS != max_stages(D, RT)) return false;
     if (D == 128)
-        return (RW == 1 && ((RT == 1 && KS == 2) || (RT == 2 && KS == 2) || (RT == 4 && KS == 1) ||
-                            (RT == 2 && KS == 1))) ||
-               (RW == 2 && ((RT == 2 && KS == 2) || (RT == 4 && KS == 1)));
-    return RW == 1 && ((RT == 1 && KS == 2) || (RT == 2 && KS == 2) || (RT == 4 && KS == 1));
+        return (RT == 1 && KS == 2) || (RT == 2 && KS == 2) || (RT == 4 && KS == 1) || (RT == 2 && KS == 1);
+    return (RT == 1 && KS == 2) || (RT == 2 && KS == 2) || (RT == 4 && KS == 1);
 }
 
 Plan make_plan(int P, int T, int group, int kv_heads, int D)
@@ -878,26 +952,31 @@ Plan make_plan(int P, int T, int group, int kv_heads, int D)
     const int R = T * group;
     const int tiles = (R + 31) / 32;
     pl.KC = 64;
-    // Few rows per KV head (memory-bound): 64-row workgroups whose wave pairs split the keys.
-    // Many rows (grouped-query models, wide windows): 128-row workgroups, one tile per wave.
-    // (64-row waves, RW = 2, are compiled and tested but were slower in every measurement.)
-    if (tiles <= 1) { pl.RW = 1; pl.RT = 1; pl.KS = 2; }
-    else if (tiles <= 4 || D != 128) { pl.RW = 1; pl.RT = 2; pl.KS = 2; }
-    else { pl.RW = 1; pl.RT = 4; pl.KS = 1; }
+    // Workgroups of eight waves, two per SIMD, so that one wave's MFMAs overlap the other's
+    // softmax arithmetic: 64 rows whose four waves per tile split the keys (measured best from the
+    // 7B shape up to grouped-query shapes with a few hundred rows per KV head), or 128 rows with two
+    // key-split waves per tile when there are many rows and a long prefix (more reuse of each
+    // chunk in LDS).  Head dimension 64 and single-tile problems keep four-wave workgroups.
+    if (tiles <= 1) { pl.RT = 1; pl.KS = 2; }
+    else if (D != 128) { pl.RT = 2; pl.KS = 2; }
+    else if (tiles >= 16 && (P + T) / pl.KC >= 64) { pl.RT = 4; pl.KS = 2; }
+    else { pl.RT = 2; pl.KS = 4; }
     pl.XS = 0;
     pl.NS = 0;
-    // developer override: LA_ATTN_PLAN="RW,RT,KS,XS,NS,KC" (XS = 0 keeps the heuristic)
+    pl.PRE = 0;
+    // developer override: LA_ATTN_PLAN="RT,KS,XS,NS,KC[,PRE]" (XS = 0, PRE = 0: heuristic)
     if (const char* env = getenv("LA_ATTN_PLAN")) {
-        int a = 0, b = 0, c = 0, d = 0, e = 0, f = 0;
-        if (sscanf(env, "%d,%d,%d,%d,%d,%d", &a, &b, &c, &d, &e, &f) == 6 &&
-            plan_supported(D, a, b, c, e, f)) {
-            pl.RW = a; pl.RT = b; pl.KS = c; pl.XS = d; pl.NS = e; pl.KC = f;
+        int b = 0, c = 0, d = 0, e = 0, f = 0, g = 0;
+        if (sscanf(env, "%d,%d,%d,%d,%d,%d", &b, &c, &d, &e, &f, &g) >= 5 &&
+            plan_supported(D, b, c, e, f)) {
+            pl.RT = b; pl.KS = c; pl.XS = d; pl.NS = e; pl.KC = f;
+            pl.PRE = g;
         }
     }
-    if (pl.NS == 0) pl.NS = max_stages(D, pl.RW, pl.RT, pl.KC);
+    if (pl.NS == 0) pl.NS = (pl.KS == 4 || (pl.RT == 4 && pl.KS == 2)) ? 4 : max_stages(D, pl.RT);
     pl.n_prefix_chunks = (P + pl.KC - 1) / pl.KC;
     pl.n_chunks = pl.n_prefix_chunks + (T + pl.KC - 1) / pl.KC;
-    const int rows_wg = pl.RT * pl.RW * 32;
+    const int rows_wg = pl.RT * 32;
     pl.n_row_blocks = (R + rows_wg - 1) / rows_wg;
     if (pl.XS <= 0) {
         // One workgroup per compute unit and never more than 256 in all: a workgroup owns most
@@ -909,15 +988,15 @@ Plan make_plan(int P, int T, int group, int kv_heads, int D)
     }
     if (pl.XS > pl.n_chunks) pl.XS = pl.n_chunks;
     if (pl.XS > 64) pl.XS = 64;
-    pl.partial_bytes_per_wg = (size_t)pl.RT * pl.RW * ((size_t)(D / 32) * 16 * 64 * 2 + 64 * 8);
+    pl.partial_bytes_per_wg = (size_t)pl.RT * ((size_t)(D / 32) * 16 * 64 * 2 + 64 * 8);
     return pl;
 }
 
-template <int D, int RW, int RT, int KS, int NSTAGE, int KC = 64>
+template <int D, int RT, int KS, int NSTAGE, int KC = 64>
 la_status launch_cfg(const AttnParams& prm, hipStream_t stream)
 {
-    using C = Cfg<D, RW, RT, KS, KC, NSTAGE>;
-    auto kern = step_attention_kernel<D, RW, RT, KS, KC, NSTAGE>;
+    using C = Cfg<D, RT, KS, KC, NSTAGE>;
+    auto kern = step_attention_kernel<D, RT, KS, KC, NSTAGE>;
     static bool attr_set[16] = {false};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return fail(LA_EHIP, "hipGetDevice failed");
@@ -983,6 +1062,11 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
     prm.inv_n1 = 1.0f / (float)(N - 1);
     prm.chunks_lo = pl.n_chunks / pl.XS;
     prm.chunks_rem = pl.n_chunks % pl.XS;
+    // Chunks requested before the loop: the first iteration's and one more.  Requesting every
+    // stage up front delays the first chunk (each request costs issue time); fewer leave the
+    // second iteration waiting.
+    const int kb = pl.KC / 32, cpi = pl.KS > kb ? pl.KS / kb : 1;  // chunks per iteration
+    prm.pre = (pl.PRE >= cpi && pl.PRE <= pl.NS) ? pl.PRE : (cpi + 1 < pl.NS ? cpi + 1 : pl.NS);
     // testing hook: exercise the path taken when a split group is not on one XCD
     const char* fr = getenv("LA_FORCE_RECOMPUTE");
     prm.force_recompute = (fr && fr[0] == '1') ? 1 : 0;
@@ -1002,26 +1086,24 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
         if (!prm.partials) return LA_ENOMEM;
     }
 
-    if (pl.KC == 32) return launch_cfg<128, 1, 2, 2, 9, 32>(prm, stream);
-    if (pl.KS == 4) return launch_cfg<128, 1, 2, 4, 4>(prm, stream);
-    if (pl.RT == 4 && pl.KS == 2) return launch_cfg<128, 1, 4, 2, 4>(prm, stream);
-#define LA_DISPATCH(D_, RW_, RT_, KS_, NSMAX_)                                       \
-    if (head_dim == D_ && pl.RW == RW_ && pl.RT == RT_ && pl.KS == KS_) {           \
-        if (pl.NS == 2) return launch_cfg<D_, RW_, RT_, KS_, 2>(prm, stream);       \
-        return launch_cfg<D_, RW_, RT_, KS_, NSMAX_>(prm, stream);                  \
+    if (pl.KC == 32) return launch_cfg<128, 2, 2, 9, 32>(prm, stream);
+    if (pl.KS == 4) return launch_cfg<128, 2, 4, 4>(prm, stream);
+    if (pl.RT == 4 && pl.KS == 2) return launch_cfg<128, 4, 2, 4>(prm, stream);
+#define LA_DISPATCH(D_, RT_, KS_, NSMAX_)                                        \
+    if (head_dim == D_ && pl.RT == RT_ && pl.KS == KS_) {                       \
+        if (pl.NS == 2) return launch_cfg<D_, RT_, KS_, 2>(prm, stream);        \
+        return launch_cfg<D_, RT_, KS_, NSMAX_>(prm, stream);                   \
     }
-    LA_DISPATCH(128, 1, 1, 2, 4)
-    LA_DISPATCH(128, 1, 2, 2, 4)
-    LA_DISPATCH(128, 1, 2, 1, 4)
-    LA_DISPATCH(128, 1, 4, 1, 3)
-    LA_DISPATCH(128, 2, 2, 2, 3)
-    LA_DISPATCH(128, 2, 4, 1, 2)
-    LA_DISPATCH(64, 1, 1, 2, 4)
-    LA_DISPATCH(64, 1, 2, 2, 4)
-    LA_DISPATCH(64, 1, 4, 1, 4)
+    LA_DISPATCH(128, 1, 2, 4)
+    LA_DISPATCH(128, 2, 2, 4)
+    LA_DISPATCH(128, 2, 1, 4)
+    LA_DISPATCH(128, 4, 1, 3)
+    LA_DISPATCH(64, 1, 2, 4)
+    LA_DISPATCH(64, 2, 2, 4)
+    LA_DISPATCH(64, 4, 1, 4)
 #undef LA_DISPATCH
-    return fail(LA_EUNSUPPORTED, "la_step_attention: no kernel for head_dim=%d plan (%d,%d,%d)",
-                head_dim, pl.RW, pl.RT, pl.KS);
+    return fail(LA_EUNSUPPORTED, "la_step_attention: no kernel for head_dim=%d plan (%d,%d)",
+                head_dim, pl.RT, pl.KS);
 }
 
 }  // namespace la

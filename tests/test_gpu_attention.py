@@ -178,16 +178,33 @@ def test_recompute_path_for_groups_not_on_one_xcd(monkeypatch):
     check(x, 333, 15, 5, 15, 4, 4, 128, "recompute-small")
 
 
-@pytest.mark.parametrize("plan", ["1,1,2,3,2,64", "1,2,2,5,4,64", "1,2,1,7,4,64", "1,4,1,2,2,64",
-                                  "2,2,2,3,3,64", "2,4,1,4,2,64", "1,4,1,1,3,64", "1,2,2,1,2,64",
-                                  "1,2,4,3,4,64", "1,2,4,1,4,64", "1,2,4,7,4,64", "1,1,2,2,4,64", "1,2,2,4,9,32", "1,2,2,1,9,32", "1,2,2,2,9,32", "1,4,2,3,4,64", "1,4,2,1,4,64", "1,4,2,8,4,64"])
+# plan = "row tiles, key-split waves, splits, stages, keys per chunk[, chunks requested up front]"
+PLANS_D128 = ["1,2,3,2,64", "2,2,5,4,64", "2,1,7,4,64", "4,1,2,2,64", "4,1,1,3,64", "2,2,1,2,64",
+              "2,4,3,4,64", "2,4,1,4,64", "2,4,7,4,64", "1,2,2,4,64", "2,2,4,9,32", "2,2,1,9,32",
+              "2,2,2,9,32", "4,2,3,4,64", "4,2,1,4,64", "4,2,8,4,64",
+              "2,2,3,4,64,1", "2,2,1,4,64,2", "2,4,2,4,64,2", "2,4,1,4,64,3", "4,1,3,3,64,1",
+              "2,2,3,9,32,2", "4,2,2,4,64,1"]
+PLANS_D64 = ["1,2,3,2,64", "1,2,1,4,64", "2,2,4,4,64", "2,2,1,2,64", "4,1,2,4,64", "4,1,1,2,64",
+             "2,2,3,4,64,1", "4,1,2,4,64,2"]
+
+
+@pytest.mark.parametrize("plan", PLANS_D128)
 def test_every_kernel_variant(monkeypatch, plan):
-    """Each compiled decomposition (rows per wave, row tiles, key-split waves, splits, stages)."""
+    """Each compiled decomposition (row tiles, key-split waves, splits, stages, up-front depth)."""
     monkeypatch.setenv("LA_ATTN_PLAN", plan)
     x = rand_inputs(123, 777, 9, 5, 9, 8, 2, 128)      # R = 292 rows per KV head
     check(x, 777, 9, 5, 9, 8, 2, 128, "plan " + plan)
     x = rand_inputs(124, 130, 2, 3, 1, 2, 2, 128)      # R = 7
     check(x, 130, 2, 3, 1, 2, 2, 128, "plan " + plan)
+
+
+@pytest.mark.parametrize("plan", PLANS_D64)
+def test_every_kernel_variant_head_dim_64(monkeypatch, plan):
+    monkeypatch.setenv("LA_ATTN_PLAN", plan)
+    x = rand_inputs(125, 700, 7, 5, 7, 6, 2, 64)       # R = 171 rows per KV head
+    check(x, 700, 7, 5, 7, 6, 2, 64, "plan " + plan)
+    x = rand_inputs(126, 65, 2, 3, 1, 2, 2, 64)        # R = 7
+    check(x, 65, 2, 3, 1, 2, 2, 64, "plan " + plan)
 
 
 def test_errors_surface_as_exceptions():
