@@ -47,6 +47,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -143,6 +144,13 @@ __device__ __forceinline__ float max3(float a, float b, float c)
     return r;
 }
 
+__device__ __forceinline__ float max2(float a, float b)
+{
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
 // max of a value with the one held by the lane 32 away (the other 16 keys of the same row).
 // v_permlane32_swap exchanges the upper half of its first operand with the lower half of its
 // second: fed the same value twice it returns (lower half everywhere, upper half everywhere).
@@ -150,7 +158,7 @@ __device__ __forceinline__ float max_across_halves(float x)
 {
     const unsigned u = __float_as_uint(x);
     const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    return max2(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -235,21 +243,13 @@ struct Cfg {
     static constexpr int PART_ACC_BYTES = DB * 16 * 64 * 2;
     static constexpr int PART_TILE_BYTES = PART_ACC_BYTES + 64 * 8;
     static constexpr int PART_WG_BYTES = TILES * PART_TILE_BYTES;
-    static constexpr int OUT_PITCH = RBYTES + 16;         // LDS pitch of the output transpose
     static constexpr int Q_BYTES = ROWS * RBYTES;         // the workgroup's query rows
     static constexpr int Q_OFFSET = NSTAGE * STAGE_BYTES; // they sit behind the stage ring
     static constexpr int QLPW = Q_BYTES / 1024 / NW;      // Q loads per wave
-    static constexpr int LDS_LIMIT = 160 * 1024 - 16;    // room for the role flag
     static constexpr int LDS_MAIN = NSTAGE * STAGE_BYTES + Q_BYTES;
     static constexpr int LDS_MERGE = KS > 1 ? NW * TILE_FLOATS * 4 : 0;
-    static constexpr int LDS_OUT = ROWS * OUT_PITCH;
-    // the finished rows are staged behind the merge buffers if that fits, else on top of them
-    // (after one more barrier)
-    static constexpr int OUT_OFFSET = LDS_MERGE + LDS_OUT <= LDS_LIMIT ? LDS_MERGE : 0;
-    static constexpr bool OUT_BARRIER = KS > 1 && OUT_OFFSET == 0;
-    static constexpr int LDS_TAIL = OUT_OFFSET + LDS_OUT > LDS_MERGE ? OUT_OFFSET + LDS_OUT : LDS_MERGE;
-    static constexpr int ROLE_OFFSET = LDS_TAIL;  // one flag word, used once the ring is dead
-    static constexpr int LDS_BYTES = LDS_MAIN > LDS_TAIL + 16 ? LDS_MAIN : LDS_TAIL + 16;
+    static constexpr int ROLE_OFFSET = LDS_MERGE;  // one flag word, used once the ring is dead
+    static constexpr int LDS_BYTES = LDS_MAIN > LDS_MERGE + 16 ? LDS_MAIN : LDS_MERGE + 16;
     static_assert(KS >= KB ? KS % KB == 0 : KB % KS == 0, "key-split waves and blocks must divide");
     static_assert(KS == 1 || DB % KS == 0, "key-split waves must divide the head_dim blocks");
     static_assert(NSTAGE >= CPI, "an iteration's chunks must fit the ring");
@@ -281,18 +281,23 @@ __device__ __forceinline__ unsigned xcc_id()
     return v & 0xfu;
 }
 
-// Copy the workgroup's finished rows (bf16, pitch C::OUT_PITCH in LDS) to `out`, 16 bytes a lane.
+// Write one finished (tile, 32-column) slice: lane (l32, hi) holds, for query row tile*32 + l32 of
+// the workgroup, columns db*32 + i4*8 + hi*4 .. +3 in vals[i4*4 .. +3].  The two half-waves of a
+// row fill 16 contiguous bytes per i4, 64 per slice.
 template <class C, int D = C::RBYTES / 2>
-__device__ __forceinline__ void write_rows_from_lds(const AttnParams& p, const unsigned char* lds,
-                                                    int rb, int kvh, int tid)
+__device__ __forceinline__ void store_slice(const AttnParams& p, int rb, int kvh, int tile, int db, int l32,
+                                            int hi, const f32x16& vals, float inv)
 {
-    const int rows_here = min(C::ROWS, p.R - rb * C::ROWS);
-    for (int piece = tid; piece < rows_here * C::NCH; piece += C::NT) {
-        const int r = piece / C::NCH, ch = piece % C::NCH;
-        const int rr = rb * C::ROWS + r;
-        const int t = div_small(rr, p.inv_group), hh = rr - t * p.group;
-        const f32x4 v = *reinterpret_cast<const f32x4*>(lds + r * C::OUT_PITCH + ch * 16);
-        *reinterpret_cast<f32x4*>(p.out + ((size_t)t * p.heads + (size_t)kvh * p.group + hh) * D + ch * 8) = v;
+    const int rr = rb * C::ROWS + tile * 32 + l32;
+    if (rr >= p.R) return;
+    const int t = div_small(rr, p.inv_group), hh = rr - t * p.group;
+    __bf16* row = p.out + ((size_t)t * p.heads + (size_t)kvh * p.group + hh) * D + db * 32 + hi * 4;
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (__bf16)(vals[i4 * 4 + e] * inv);
+        *reinterpret_cast<bf16x4*>(row + i4 * 8) = v;
     }
 }
 
@@ -302,9 +307,9 @@ __device__ __forceinline__ void write_rows_from_lds(const AttnParams& p, const u
 // over the KS states, in key order.  On return o[0 .. SPW-1] hold the merged slices
 // MYKS*SPW .. MYKS*SPW+SPW-1 and (m_run, l_run) the merged softmax state of the row.
 template <class C, int KS, int MYKS>
-__device__ __forceinline__ void merge_key_splits(unsigned char* lds, int rt, int lane, bool wave_active,
-                                                 f32x16 (&o)[C::DB], float& m_run, float& l_run,
-                                                 float scale_log2)
+__device__ __forceinline__ void merge_key_splits(const AttnParams& p, unsigned char* lds, int rt, int lane,
+                                                 bool wave_active, f32x16 (&o)[C::DB], float& m_run,
+                                                 float& l_run, float scale_log2)
 {
     constexpr int DB0 = MYKS * C::SPW;
     float* mg = reinterpret_cast<float*>(lds) + rt * KS * C::TILE_FLOATS;  // this tile's states
@@ -321,7 +326,9 @@ __device__ __forceinline__ void merge_key_splits(unsigned char* lds, int rt, int
         }
         *reinterpret_cast<f32x2*>(dst + C::FRAG_FLOATS + lane * 2) = f32x2{m_run, l_run};
     }
+    LA_STAMP(2);
     __syncthreads();
+    LA_STAMP(19);
     if (!wave_active) return;
     f32x2 ml[KS];
 #pragma unroll
@@ -531,6 +538,34 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
     typedef __attribute__((address_space(3))) unsigned lds_u32;
     lds_u32* const s_role = (lds_u32*)(lds + C::ROLE_OFFSET);
 
+    // LDS read offsets of this lane relative to the start of a stage; the loop adds only the stage.
+    //   K operand: key row kb*32 + l32, pieces k16*2 + hi (swizzled).
+    //   V^T operand: k-slot e of half `hi` of 16-key step kk is key kb*32 + kk*16 + (e/4)*8 + hi*4 + e%4
+    //   (the layout S^T leaves P in).  A 16-lane block reads 4 keys x 16 columns; the transposing
+    //   read hands lane n column n.  The swizzle of those rows does not depend on kb or kk.
+    const int kb_first = KS >= C::KB ? ks % C::KB : ks;  // this wave's (first) block of a chunk
+    unsigned k_off[D / 16], v_off[2][C::DB];
+    {
+        const int krow = kb_first * 32 + l32;
+        const int ksw = swizzle<D>(krow);
+#pragma unroll
+        for (int k16 = 0; k16 < D / 16; ++k16)
+            k_off[k16] = (unsigned)(krow * C::RBYTES + (((k16 * 2 + hi) ^ ksw) << 4));
+        const int b16 = lane >> 4, i16 = lane & 15;
+        const int jj = i16 >> 2, q4 = i16 & 3;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int vrow = kb_first * 32 + hi * 4 + jj + r * 8;  // e = 0..3 (r = 0), 4..7 (r = 1); kk = 0
+            const int sw = swizzle<D>(vrow);
+#pragma unroll
+            for (int db = 0; db < C::DB; ++db) {
+                const int col = db * 32 + (b16 & 1) * 16 + q4 * 4;
+                const int lc = col >> 3, within = (col & 7) * 2;
+                v_off[r][db] = (unsigned)(C::KV_BYTES + vrow * C::RBYTES + ((lc ^ sw) << 4) + within);
+            }
+        }
+    }
+
     for (int pass = 0;; ++pass) {
         m_run = kNegInf;
         l_run = 0.0f;
@@ -590,8 +625,6 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
             const bool is_step = cons_c >= n_prefix_chunks;
             const int chunk_key0 = (cons_c - (is_step ? n_prefix_chunks : 0)) * KC;
             const int limit = is_step ? n_T : n_P;
-            const unsigned char* kst = lds + cons_stage;
-            const unsigned char* vst = kst + C::KV_BYTES;
 
 #pragma unroll
             for (int kbw = 0; kbw < C::KBW; ++kbw) {
@@ -601,29 +634,17 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
 
                 // ---- operands: all K pieces of the block, and the V pieces of its first 16 keys,
                 //      are requested from LDS before the first MFMA (LDS answers in order)
-                const int krow = kb * 32 + l32;
-                const unsigned char* kr = kst + krow * C::RBYTES;
-                const int ksw = swizzle<D>(krow);
+                const unsigned char* blk = lds + (cons_stage + (unsigned)(kbw * KS * 32 * C::RBYTES));
                 bf16x8 kf[D / 16];
 #pragma unroll
                 for (int k16 = 0; k16 < D / 16; ++k16)
-                    kf[k16] = *reinterpret_cast<const bf16x8*>(kr + (((k16 * 2 + hi) ^ ksw) << 4));
-                // V^T operand: k-slot e of half `hi` of 16-key step kk is key
-                // kb*32 + kk*16 + (e/4)*8 + hi*4 + e%4 (the layout S^T leaves P in).  A 16-lane
-                // block reads 4 keys x 16 columns; the transposing read hands lane n column n.
-                const int b16 = lane >> 4, i16 = lane & 15;
-                const int jj = i16 >> 2, q4 = i16 & 3;
+                    kf[k16] = *reinterpret_cast<const bf16x8*>(blk + k_off[k16]);
                 bf16x8 vf[2][C::DB];
                 auto read_v = [&](int kk) {
-                    const int vrow0 = kb * 32 + kk * 16 + hi * 4 + jj;  // e = 0..3
-                    const int vrow1 = vrow0 + 8;                        // e = 4..7
-                    const int sw0 = swizzle<D>(vrow0), sw1 = swizzle<D>(vrow1);
 #pragma unroll
                     for (int db = 0; db < C::DB; ++db) {
-                        const int col = db * 32 + (b16 & 1) * 16 + q4 * 4;
-                        const int lc = col >> 3, within = (col & 7) * 2;
-                        const unsigned char* a0 = vst + vrow0 * C::RBYTES + ((lc ^ sw0) << 4) + within;
-                        const unsigned char* a1 = vst + vrow1 * C::RBYTES + ((lc ^ sw1) << 4) + within;
+                        const unsigned char* a0 = blk + v_off[0][db] + kk * 16 * C::RBYTES;
+                        const unsigned char* a1 = blk + v_off[1][db] + kk * 16 * C::RBYTES;
                         union { struct { short4v a, b; } s; bf16x8 v; } u;
                         u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                             (short4v __attribute__((address_space(3)))*)a0);
@@ -669,7 +690,7 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                 float mx = max3(s[0], s[1], s[2]);
 #pragma unroll
                 for (int i = 3; i < 15; i += 2) mx = max3(mx, s[i], s[i + 1]);
-                mx = max_across_halves(fmaxf(mx, s[15]));
+                mx = max_across_halves(max2(mx, s[15]));
                 LA_CYC(3);
                 // Scores stay unscaled; exp(x/sqrt(d)) = exp2(x * scale_log2).  The reference
                 // m_run only moves when the block maximum exceeds it by more than 2^8 in the
@@ -677,7 +698,7 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                 // skipping small moves saves rescaling the accumulators nearly every time.
                 const bool move = (mx - m_run) * p.scale_log2 > 8.0f || m_run == kNegInf;
                 const float m_new = move ? mx : m_run;
-                const float m_use = (m_new == kNegInf) ? 0.0f : m_new;
+                const float m_use = (m_new == kNegInf) ? 0.0f : m_new;  // the row has seen no key at all
                 const float neg_mc = -m_use * p.scale_log2;
                 if (__builtin_amdgcn_ballot_w64(move) != 0ull) {
                     const float alpha = fast_exp2(__builtin_fmaf(m_run, p.scale_log2, neg_mc));
@@ -688,21 +709,24 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                         for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
                 }
                 m_run = m_new;
-                float psum0 = 0.0f, psum1 = 0.0f;
-                float pv[16];
-#pragma unroll
-                for (int i = 0; i < 16; i += 2) {
-                    pv[i] = fast_exp2(__builtin_fmaf(s[i], p.scale_log2, neg_mc));
-                    pv[i + 1] = fast_exp2(__builtin_fmaf(s[i + 1], p.scale_log2, neg_mc));
-                    psum0 += pv[i];
-                    psum1 += pv[i + 1];
-                }
-                l_run += psum0 + psum1;
+                // P in bf16, as the PV product uses it; the row sum adds up those same rounded
+                // values (two per instruction), so that numerator and denominator agree
                 bf16x8 pf[2];
 #pragma unroll
-                for (int kk = 0; kk < 2; ++kk)
+                for (int i = 0; i < 16; ++i)
+                    pf[i >> 3][i & 7] = (__bf16)fast_exp2(__builtin_fmaf(s[i], p.scale_log2, neg_mc));
+                {
+                    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+                    float psum0 = 0.0f, psum1 = 0.0f;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) pf[kk][e] = (__bf16)pv[kk * 8 + e];
+                    for (int kk = 0; kk < 2; ++kk) {
+                        psum0 = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{pf[kk][0], pf[kk][1]}, ones, psum0, false);
+                        psum1 = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{pf[kk][2], pf[kk][3]}, ones, psum1, false);
+                        psum0 = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{pf[kk][4], pf[kk][5]}, ones, psum0, false);
+                        psum1 = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{pf[kk][6], pf[kk][7]}, ones, psum1, false);
+                    }
+                    l_run += psum0 + psum1;
+                }
                 __builtin_amdgcn_sched_barrier(0);
                 LA_CYC(4);
 
@@ -745,10 +769,10 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
         //      on it keeps every register index a compile-time constant
         if (KS > 1) {
             const float sc = p.scale_log2;
-            if (ks == 0) merge_key_splits<C, KS, 0>(lds, rt, lane, wave_active, o, m_run, l_run, sc);
-            if (KS > 1 && ks == 1) merge_key_splits<C, KS, (KS > 1 ? 1 : 0)>(lds, rt, lane, wave_active, o, m_run, l_run, sc);
-            if (KS > 2 && ks == 2) merge_key_splits<C, KS, (KS > 2 ? 2 : 0)>(lds, rt, lane, wave_active, o, m_run, l_run, sc);
-            if (KS > 3 && ks == 3) merge_key_splits<C, KS, (KS > 3 ? 3 : 0)>(lds, rt, lane, wave_active, o, m_run, l_run, sc);
+            if (ks == 0) merge_key_splits<C, KS, 0>(p, lds, rt, lane, wave_active, o, m_run, l_run, sc);
+            if (KS > 1 && ks == 1) merge_key_splits<C, KS, (KS > 1 ? 1 : 0)>(p, lds, rt, lane, wave_active, o, m_run, l_run, sc);
+            if (KS > 2 && ks == 2) merge_key_splits<C, KS, (KS > 2 ? 2 : 0)>(p, lds, rt, lane, wave_active, o, m_run, l_run, sc);
+            if (KS > 3 && ks == 3) merge_key_splits<C, KS, (KS > 3 ? 3 : 0)>(p, lds, rt, lane, wave_active, o, m_run, l_run, sc);
             static_assert(KS <= 4, "one branch per key index");
         }
         LA_STAMP(4);
@@ -868,21 +892,13 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                     const int st = st0 + u * C::NW;
                     if (st >= NSUB) break;
                     const int tile = st / C::DB, db = st - tile * C::DB;
-                    const float inv = 1.0f / l_acc[u];
-                    unsigned char* row_ptr = lds + C::OUT_OFFSET + (tile * 32 + l32) * C::OUT_PITCH;
+                    f32x16 vals;
 #pragma unroll
-                    for (int i4 = 0; i4 < 4; ++i4) {
-                        bf16x4 ov;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(acc[u][i4 * 4 + e] * inv);
-                        *reinterpret_cast<bf16x4*>(row_ptr + (db * 32 + i4 * 8 + hi * 4) * 2) = ov;
-                    }
+                    for (int i = 0; i < 16; ++i) vals[i] = acc[u][i];
+                    store_slice<C>(p, rb, kvh, tile, db, l32, hi, vals, 1.0f / l_acc[u]);
                 }
             }
             LA_STAMP(20);
-            __syncthreads();
-            LA_STAMP(21);
-            write_rows_from_lds<C>(p, lds + C::OUT_OFFSET, rb, kvh, tid);
             LA_STAMP(7);
             LA_CYCW(23);
             return;
@@ -895,24 +911,12 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
         direct = true;
     }
 
-    // ---- normalise, transpose through LDS, write bf16 rows with 16-byte stores
-    if (C::OUT_BARRIER) __syncthreads();  // the rows are staged where merge states are still being read
+    // ---- normalise and write this wave's slices (>= 1 visible key per row, so l > 0)
     if (wave_active) {
-        const float inv = 1.0f / l_run;  // >= 1 visible key per row, so l > 0
-        unsigned char* row_ptr = lds + C::OUT_OFFSET + (rt * 32 + l32) * C::OUT_PITCH;
+        const float inv = 1.0f / l_run;
 #pragma unroll
-        for (int u = 0; u < C::SPW; ++u)
-#pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                bf16x4 v;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = (__bf16)(o[u][i4 * 4 + e] * inv);
-                const int dcol = (db0 + u) * 32 + i4 * 8 + hi * 4;
-                *reinterpret_cast<bf16x4*>(row_ptr + dcol * 2) = v;
-            }
+        for (int u = 0; u < C::SPW; ++u) store_slice<C>(p, rb, kvh, rt, db0 + u, l32, hi, o[u], inv);
     }
-    __syncthreads();
-    write_rows_from_lds<C>(p, lds + C::OUT_OFFSET, rb, kvh, tid);
 }
 
 // ---------------------------------------------------------------------------------------
