@@ -26,9 +26,11 @@ LAYERS = {"llama2-7b": 32, "llama2-13b": 40, "llama2-70b-gqa": 80}
 
 # HBM bytes per attention launch from rocprofv3 (FETCH_SIZE + WRITE_SIZE per dispatch, each scaled
 # by the same counter's reading for a 64 MiB copy): see profiles/attention_verify_<workload>.md.
-# None where no profile of the current kernel has been taken.
+# (FETCH_SIZE reads half the bytes of a plain copy on this part, WRITE_SIZE all of them.)
 MEASURED_TRAFFIC_BYTES = {
-    "llama2-7b": int((11708.5 * 65536.0 / 32786.8 + 5328.4 * 65536.0 / 65536.0) * 1024),
+    "llama2-7b": int((11737.9 * 65536.0 / 32785.2 + 5328.4) * 1024),
+    "llama2-13b": int((23512.2 * 65536.0 / 32786.0 + 3879.2) * 1024),
+    "llama2-70b-gqa": int((10837.0 * 65536.0 / 32787.2 + 5000.5) * 1024),
 }
 
 
