@@ -15,7 +15,12 @@
  * row's own token chain, against a library softmax-attention for the
  * one-token decode special case, and against isolation / permutation
  * invariants; the verification reduction against exhaustive enumeration on
- * tiny vocabularies, a library argmax, and the paper's Algorithm 3.
+ * tiny vocabularies, a library argmax, and the paper's Algorithm 3; the
+ * end-of-step reduction (accepted token list, best candidate, new window
+ * tokens) against the same exhaustive enumeration written from the words of
+ * Sec. 3.2, a literal walk through Algorithm 3 on a prefix-deterministic toy
+ * model (whose output must also equal plain greedy decoding), and a library
+ * argmax.
  *
  * Row / key order of one step (same for q, step_k, step_v, out):
  *   r = 0                               the current input token, relative position 0
@@ -244,3 +249,60 @@ int la_oracle_verify(const float *logits, const int32_t *cand_tokens, int G, int
     }
     return 0;
 }
+
+/*
+ * The end of a greedy lookahead step in one call (Algorithm 3 in full, and the new window
+ * tokens of Algorithm 2's lookahead branch).  Plain definition, scalar loops.
+ *
+ *   logits_cur   [V]          model output at the current token: judges slot 0 of every candidate
+ *   logits_look  [W][V]       outputs at the W newest lookahead tokens (one per column)
+ *   logits_cand  [G][N-1][V]  row (g,k): output at candidate g's token k; judges slot k+1, and
+ *                             row (g,N-2) gives the bonus token when all N-1 slots were accepted
+ *   cand_tokens  [G][N-1]
+ * out:
+ *   accept_len[g]  leading slots s with argmax(judge(g,s)) == cand_tokens[g][s]
+ *   best           lowest g with the largest accept_len (-1 if G == 0); L = that length
+ *   out_tokens     cand_tokens[best][0..L-1], then argmax(judge(best, L)): the correction
+ *                  token (L < N-1) or the bonus token (L == N-1); n_out = L + 1
+ *   new_window[j]  argmax of logits_look[j]
+ * argmax = lowest index of the maximum.
+ */
+static int argmax_row(const float *row, int V)
+{
+    int best = 0;
+    for (int v = 1; v < V; ++v)
+        if (row[v] > row[best]) best = v;
+    return best;
+}
+
+int la_oracle_verify_step(const float *logits_cur, const float *logits_look, const float *logits_cand,
+                          const int32_t *cand_tokens, int W, int N, int G, int V, int32_t *out_tokens,
+                          int32_t *n_out, int32_t *best, int32_t *new_window, int32_t *accept_len)
+{
+    if (W < 0 || G < 0 || N < 2 || V < 1) return -1;
+    const int n1 = N - 1;
+    for (int j = 0; j < W; ++j) new_window[j] = argmax_row(logits_look + (size_t)j * V, V);
+    const int cur_token = argmax_row(logits_cur, V);
+    int best_g = -1, best_len = 0;
+    for (int g = 0; g < G; ++g) {
+        int len = 0;
+        while (len < n1) {
+            const int judged = len == 0 ? cur_token
+                                        : argmax_row(logits_cand + ((size_t)g * n1 + (len - 1)) * V, V);
+            if (judged != cand_tokens[g * n1 + len]) break;
+            ++len;
+        }
+        accept_len[g] = len;
+        if (best_g < 0 || len > best_len) {
+            best_g = g;
+            best_len = len;
+        }
+    }
+    *best = best_g;
+    for (int s = 0; s < best_len; ++s) out_tokens[s] = cand_tokens[best_g * n1 + s];
+    out_tokens[best_len] = best_len == 0 ? cur_token
+                                         : argmax_row(logits_cand + ((size_t)best_g * n1 + (best_len - 1)) * V, V);
+    *n_out = best_len + 1;
+    return 0;
+}
+

@@ -31,6 +31,8 @@ def _load():
         lib.la_oracle_step_attention.restype = i
         lib.la_oracle_verify.argtypes = [p, p, i, i, i, p, p]
         lib.la_oracle_verify.restype = i
+        lib.la_oracle_verify_step.argtypes = [p, p, p, p, i, i, i, i, p, p, p, p, p]
+        lib.la_oracle_verify_step.restype = i
         _lib = lib
     return _lib
 
@@ -92,6 +94,31 @@ def verify(logits, cand_tokens, G, N, V):
     if rc != 0:
         raise ValueError("la_oracle_verify: bad shape (rc=%d)" % rc)
     return accept_len, accepted
+
+
+def verify_step(logits_cur, logits_look, logits_cand, cand_tokens, W, N, G, V):
+    """The end of a greedy step: (out_tokens list, best, new_window int32 [W], accept_len int32 [G]).
+
+    logits_cur fp32 [V], logits_look fp32 [W, V], logits_cand fp32 [G, N-1, V], cand_tokens int32
+    [G, N-1]; see la_oracle_verify_step in la_oracle.c.
+    """
+    cur = np.ascontiguousarray(logits_cur)
+    look = np.ascontiguousarray(logits_look).reshape(W, V)
+    cnd = np.ascontiguousarray(logits_cand).reshape(G, N - 1, V)
+    cand = np.ascontiguousarray(cand_tokens).reshape(G, N - 1)
+    assert cur.dtype == look.dtype == cnd.dtype == np.float32 and cur.shape == (V,)
+    assert cand.dtype == np.int32
+    out = np.zeros((N,), dtype=np.int32)
+    n_out = np.zeros((1,), dtype=np.int32)
+    best = np.zeros((1,), dtype=np.int32)
+    window = np.zeros((W,), dtype=np.int32)
+    accept_len = np.zeros((G,), dtype=np.int32)
+    rc = _load().la_oracle_verify_step(cur.ctypes.data, look.ctypes.data, cnd.ctypes.data, cand.ctypes.data,
+                                       W, N, G, V, out.ctypes.data, n_out.ctypes.data, best.ctypes.data,
+                                       window.ctypes.data, accept_len.ctypes.data)
+    if rc != 0:
+        raise ValueError("la_oracle_verify_step: bad shape (rc=%d)" % rc)
+    return [int(t) for t in out[:int(n_out[0])]], int(best[0]), window, accept_len
 
 
 def greedy_verification(candidates, dist_argmax):
