@@ -94,6 +94,13 @@ def main():
     cand = torch.from_numpy(cand_h).cuda()
     alen = torch.empty((s.G,), dtype=torch.int32, device="cuda")
     acc = torch.empty((s.G, s.N - 1), dtype=torch.int32, device="cuda")
+    # the whole end of a greedy step in one launch (timed on its own, not part of `value`)
+    vs_h = wl.verify_step_inputs(s)
+    vs = [torch.from_numpy(x).cuda() for x in vs_h[:4]]
+    vs_out = [torch.empty((n,), dtype=torch.int32, device="cuda") for n in (s.N, 1, 1, s.W, s.G)]
+
+    def verify_step():
+        binding.la_verify_step(vs[0], vs[1], vs[2], vs[3], s.W, s.N, s.G, s.V, *vs_out)
 
     def attention_layers():
         for x, o in zip(layers, outs):
@@ -133,20 +140,26 @@ def main():
 
     # ---- dominant kernel (attention) and the verify kernel, by HIP events on the launch stream
     reps = max(10, min(args.steps, 100))
-    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-    attn_ms, ver_ms = [], []
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    attn_ms, ver_ms, vs_ms = [], [], []
     if use_graph:
         # the L attention launches alone, and the verify launch alone, as graphs
         ga, gv = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
         with torch.cuda.graph(ga):
             attention_layers()
         with torch.cuda.graph(gv):
-            for _ in range(8):
+            for _ in range(32):
                 binding.la_verify(logits, cand, s.G, s.N, s.V, alen, acc)
-        run_attn, run_ver, ver_calls = ga.replay, gv.replay, 8
+        verify_step()
+        gs = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gs):
+            for _ in range(32):
+                verify_step()
+        run_attn, run_ver, run_vs, ver_calls = ga.replay, gv.replay, gs.replay, 32
     else:
         run_attn = attention_layers
         run_ver = lambda: binding.la_verify(logits, cand, s.G, s.N, s.V, alen, acc)
+        run_vs = verify_step
         ver_calls = 1
     for _ in range(reps):
         e[0].record()
@@ -154,11 +167,16 @@ def main():
         e[1].record()
         run_ver()
         e[2].record()
+        run_vs()
+        e[3].record()
         torch.cuda.synchronize()
         attn_ms.append(e[0].elapsed_time(e[1]))
         ver_ms.append(e[1].elapsed_time(e[2]) / ver_calls)
+        vs_ms.append(e[2].elapsed_time(e[3]) / ver_calls)
     attn_us = float(np.median(attn_ms)) * 1e3 / L       # per launch, launch gaps included
     verify_us = float(np.median(ver_ms)) * 1e3
+    verify_step_us = float(np.median(vs_ms)) * 1e3
+    verify_step_bytes = (1 + s.W + s.G * (s.N - 1)) * s.V * 4
     abytes = algorithmic_bytes(s)
     aflops = algorithmic_flops(s)
     t_hbm = abytes / (HBM_PEAK_GBS * 1e9)
@@ -191,6 +209,11 @@ def main():
     err = float(np.abs(outs[0].float().cpu().numpy().astype(np.float64) - want).max())
     want_len, want_acc = orc.verify(logits_h, cand_h, s.G, s.N, s.V)
     exact = bool(np.array_equal(alen.cpu().numpy(), want_len) and np.array_equal(acc.cpu().numpy(), want_acc))
+    w_out, w_best, w_window, w_len = orc.verify_step(*vs_h[:4], s.W, s.N, s.G, s.V)
+    n = int(vs_out[1].item())
+    exact_step = bool(vs_out[0].cpu().numpy()[:n].tolist() == w_out and int(vs_out[2].item()) == w_best and
+                      np.array_equal(vs_out[3].cpu().numpy(), w_window) and
+                      np.array_equal(vs_out[4].cpu().numpy(), w_len))
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -224,12 +247,16 @@ def main():
         "roofline": roof,
         "cpu_baseline": cpu,
         "verify_us": verify_us,
+        "verify_step": {"us": verify_step_us, "algorithmic_bytes": verify_step_bytes,
+                        "gbs": verify_step_bytes / (verify_step_us * 1e-6) / 1e9,
+                        "frac_of_hbm_peak": verify_step_bytes / (verify_step_us * 1e-6) / 1e9 / HBM_PEAK_GBS},
         "attention_tflops": aflops / (attn_us * 1e-6) / 1e12,
         "attention_gbs": abytes / (attn_us * 1e-6) / 1e9,
-        "parity": {"attention_max_abs_err_layer0": err, "verify_bit_exact": exact},
+        "parity": {"attention_max_abs_err_layer0": err, "verify_bit_exact": exact,
+                   "verify_step_bit_exact": exact_step},
     }
     print(json.dumps(line))
-    if err > 2e-2 or not exact:
+    if err > 2e-2 or not exact or not exact_step:
         print("bench.py: PARITY FAILURE", file=sys.stderr)
         sys.exit(1)
 

@@ -53,7 +53,7 @@ extern "C" {
 typedef int la_status;
 #define LA_OK 0
 #define LA_EINVAL (-1)       /* null pointer, negative size, N < 2, misaligned buffer */
-#define LA_EUNSUPPORTED (-2) /* head_dim not 64 or 128, heads % kv_heads != 0, group too large */
+#define LA_EUNSUPPORTED (-2) /* head_dim not 64 or 128, heads % kv_heads != 0, step too large */
 #define LA_ENOMEM (-3)       /* workspace allocation failed */
 #define LA_EHIP (-4)         /* a HIP call or the launch failed (see la_last_error) */
 
@@ -91,6 +91,34 @@ la_status la_step_attention(const void* q, const void* k_cache, const void* v_ca
  */
 la_status la_verify(const float* logits, const int* cand_tokens, int G, int N, int V,
                     int* accept_len, int* accepted, void* stream);
+
+/*
+ * The end of a greedy lookahead step in one launch: Algorithm 3 in full (Sec. 3.2: a
+ * candidate's tokens are accepted while they equal the model's greedy tokens, the longest
+ * run wins, and the model's own token at the first unaccepted slot follows - the
+ * correction token, or the bonus token after a full match, so that a step always moves
+ * by at least one token), and the new window tokens of Algorithm 2's lookahead branch
+ * (the greedy token at each of the W newest lookahead positions).
+ *
+ *   logits_cur   fp32 [V]          model output at the current token: judges slot 0 of
+ *                                  every candidate
+ *   logits_look  fp32 [W][V]       outputs at the W newest lookahead tokens (level N-2,
+ *                                  columns 0..W-1); may be NULL iff W == 0
+ *   logits_cand  fp32 [G][N-1][V]  row (g,k): output at candidate g's token k: judges slot
+ *                                  k+1; row (g,N-2) gives the bonus token; NULL iff G == 0
+ *   cand_tokens  int32 [G][N-1]
+ *   out_tokens   int32 [N]   out: the accepted tokens, n_out of them
+ *   n_out        int32 [1]   out: 1..N
+ *   best         int32 [1]   out: the winning candidate - the lowest index among those with
+ *                            the longest accepted run (the order Algorithm 3 scans them in);
+ *                            -1 if G == 0
+ *   new_window   int32 [W]   out
+ *   accept_len   int32 [G]   out: accepted run of every candidate; may be NULL
+ * Argmax = lowest index of the maximum; values must not be NaN.  1 + W + G(N-1) <= 12288.
+ */
+la_status la_verify_step(const float* logits_cur, const float* logits_look, const float* logits_cand,
+                         const int* cand_tokens, int W, int N, int G, int V, int* out_tokens, int* n_out,
+                         int* best, int* new_window, int* accept_len, void* stream);
 
 /* Bytes of device workspace la_step_attention needs for this shape (0 if none). */
 long long la_step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int kv_heads,

@@ -35,6 +35,8 @@ def load():
     lib.la_step_attention.restype = i
     lib.la_verify.argtypes = [p, p, i, i, i, p, p, p]
     lib.la_verify.restype = i
+    lib.la_verify_step.argtypes = [p, p, p, p, i, i, i, i, p, p, p, p, p, p]
+    lib.la_verify_step.restype = i
     lib.la_step_attention_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
     lib.la_step_attention_workspace_bytes.restype = ctypes.c_longlong
     lib.la_shutdown.argtypes = []
@@ -47,7 +49,7 @@ def load():
     return lib
 
 
-EXPORTS = ("la_step_attention", "la_verify", "la_step_attention_workspace_bytes", "la_shutdown",
+EXPORTS = ("la_step_attention", "la_verify", "la_verify_step", "la_step_attention_workspace_bytes", "la_shutdown",
            "la_last_error", "la_version")
 
 
@@ -109,6 +111,24 @@ def la_verify(logits, cand_tokens, G, N, V, accept_len, accepted, stream=None):
         _ptr(accepted, torch.int32, (G, N - 1), "accepted"), _stream(stream))
     _check(rc)
     return accept_len, accepted
+
+
+def la_verify_step(logits_cur, logits_look, logits_cand, cand_tokens, W, N, G, V, out_tokens, n_out, best,
+                   new_window, accept_len=None, stream=None):
+    """out_tokens[N], n_out[1], best[1], new_window[W], accept_len[G] (int32) <- the end of a greedy
+    step (accepted tokens of the best candidate plus correction or bonus token; new window tokens);
+    asynchronous."""
+    rc = load().la_verify_step(
+        _ptr(logits_cur, torch.float32, (V,), "logits_cur"),
+        _ptr(logits_look, torch.float32, (W, V), "logits_look", allow_empty_null=True),
+        _ptr(logits_cand, torch.float32, (G, N - 1, V), "logits_cand", allow_empty_null=True),
+        _ptr(cand_tokens, torch.int32, (G, N - 1), "cand_tokens", allow_empty_null=True), W, N, G, V,
+        _ptr(out_tokens, torch.int32, (N,), "out_tokens"), _ptr(n_out, torch.int32, (1,), "n_out"),
+        _ptr(best, torch.int32, (1,), "best"),
+        _ptr(new_window, torch.int32, (W,), "new_window", allow_empty_null=True),
+        _ptr(accept_len, torch.int32, (G,), "accept_len", allow_empty_null=True), _stream(stream))
+    _check(rc)
+    return out_tokens, n_out, best, new_window, accept_len
 
 
 def la_step_attention_workspace_bytes(P, W, N, G, heads, kv_heads, head_dim):

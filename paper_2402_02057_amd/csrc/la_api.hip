@@ -155,6 +155,24 @@ la_status la_verify(const float* logits, const int* cand_tokens, int G, int N, i
     return la::launch_verify(logits, cand_tokens, G, N, V, accept_len, accepted, (hipStream_t)stream);
 }
 
+la_status la_verify_step(const float* logits_cur, const float* logits_look, const float* logits_cand,
+                         const int* cand_tokens, int W, int N, int G, int V, int* out_tokens, int* n_out,
+                         int* best, int* new_window, int* accept_len, void* stream)
+{
+    if (W < 0 || G < 0 || N < 2 || V < 1)
+        return la::fail(LA_EINVAL, "la_verify_step: need W >= 0, G >= 0, N >= 2, V >= 1 (got W=%d G=%d N=%d V=%d)",
+                        W, G, N, V);
+    if (!logits_cur || !out_tokens || !n_out || !best || (W > 0 && (!logits_look || !new_window)) ||
+        (G > 0 && (!logits_cand || !cand_tokens)))
+        return la::fail(LA_EINVAL, "la_verify_step: null pointer");
+    if (((uintptr_t)logits_cur | (uintptr_t)logits_look | (uintptr_t)logits_cand | (uintptr_t)cand_tokens |
+         (uintptr_t)out_tokens | (uintptr_t)n_out | (uintptr_t)best | (uintptr_t)new_window |
+         (uintptr_t)accept_len) & 3)
+        return la::fail(LA_EINVAL, "la_verify_step: buffers must be 4-byte aligned");
+    return la::launch_verify_step(logits_cur, logits_look, logits_cand, cand_tokens, W, N, G, V, out_tokens,
+                                  n_out, best, new_window, accept_len, (hipStream_t)stream);
+}
+
 long long la_step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int kv_heads,
                                             int head_dim)
 {
@@ -168,6 +186,6 @@ void la_shutdown(void) { la::free_workspaces(); }
 
 const char* la_last_error(void) { return la::g_error; }
 
-int la_version(void) { return 1000; }
+int la_version(void) { return 1001; }
 
 }  // extern "C"

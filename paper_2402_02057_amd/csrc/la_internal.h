@@ -22,6 +22,9 @@ void free_workspaces();
 // Launchers (defined next to their kernels).
 la_status launch_verify(const float* logits, const int* cand_tokens, int G, int N, int V,
                         int* accept_len, int* accepted, hipStream_t stream);
+la_status launch_verify_step(const float* logits_cur, const float* logits_look, const float* logits_cand,
+                             const int* cand_tokens, int W, int N, int G, int V, int* out_tokens, int* n_out,
+                             int* best, int* new_window, int* accept_len, hipStream_t stream);
 la_status launch_step_attention(const void* q, const void* k_cache, const void* v_cache,
                                 const void* step_k, const void* step_v, int P, int W, int N, int G,
                                 int heads, int kv_heads, int head_dim, void* out,

@@ -125,3 +125,48 @@ def verify_inputs(s: StepShape, extra=0):
                 other = (int(cand[g, k]) + 1 + int(rng.integers(0, V - 1))) % V
                 logits[g, k, other] = PLANT_VALUE
     return logits, cand, lens
+
+
+def verify_step_inputs(s: StepShape, extra=0):
+    """Inputs of the end-of-step reduction: (logits_cur fp32 [V], logits_look fp32 [W, V],
+    logits_cand fp32 [G, N-1, V], cand_tokens int32 [G, N-1], planted accept lengths or None).
+
+    Row (g, k) of logits_cand is the model output at candidate g's token k: it judges slot k + 1
+    (slot 0 is judged by logits_cur, the same for every candidate) and row (g, N-2) is the bonus
+    row.  With `planted`, candidate g gets the accept length (g + shift) mod N: its slot-0 token is
+    the peak of logits_cur iff that length is positive, the rows judging its next slots peak at its
+    tokens, the row judging the first rejected slot peaks elsewhere, and on odd g the later rows
+    peak at the candidate's tokens again.
+    """
+    W, G, n1, V = s.W, s.G, s.N - 1, s.V
+    rng = np.random.default_rng(seed_for(s.config, _LOGITS, extra + 7))
+    cur = rng.standard_normal(size=(V,), dtype=np.float32)
+    look = rng.standard_normal(size=(W, V), dtype=np.float32)
+    cnd = rng.standard_normal(size=(G, n1, V), dtype=np.float32)
+    rng = np.random.default_rng(seed_for(s.config, _CAND, extra + 7))
+    cand = rng.integers(0, V, size=(G, n1)).astype(np.int32)
+    if not s.planted:
+        return cur, look, cnd, cand, None
+    rng = np.random.default_rng(seed_for(s.config, _PLAN, extra + 7))
+    shift = int(rng.integers(0, s.N))
+    a0 = int(rng.integers(0, V))
+    cur[a0] = PLANT_VALUE
+    for j in range(W):
+        look[j, int(rng.integers(0, V))] = PLANT_VALUE
+    lens = np.zeros((G,), dtype=np.int32)
+    for g in range(G):
+        L = (g + shift) % s.N
+        lens[g] = L
+        if L >= 1:
+            cand[g, 0] = a0
+        elif cand[g, 0] == a0:
+            cand[g, 0] = (a0 + 1) % V
+        for slot in range(1, n1):            # judged by row (g, slot - 1)
+            if slot < L or (slot > L and g % 2 == 1):
+                cnd[g, slot - 1, cand[g, slot]] = PLANT_VALUE
+            elif slot == L:
+                other = (int(cand[g, slot]) + 1 + int(rng.integers(0, V - 1))) % V
+                cnd[g, slot - 1, other] = PLANT_VALUE
+        cnd[g, n1 - 1, int(rng.integers(0, V))] = PLANT_VALUE   # bonus row
+    return cur, look, cnd, cand, lens
+

@@ -49,6 +49,10 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
     assert lib.la_verify(None, None, 0, 3, 10, None, None, None) == 0      # G = 0: no-op
     assert lib.la_verify(None, None, 2, 3, 10, None, None, None) == -1
     assert lib.la_verify(None, None, 2, 1, 10, None, None, None) == -1
+    assert lib.la_verify_step(None, None, None, None, 0, 3, 0, 10, None, None, None, None, None, None) == -1
+    assert b"null" in lib.la_last_error()
+    assert lib.la_verify_step(None, None, None, None, 0, 1, 0, 10, None, None, None, None, None, None) == -1
+    assert b"N >= 2" in lib.la_last_error()
 
 
 def test_workspace_query(lib):
