@@ -655,7 +655,6 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                 };
                 LA_CYC(0);
                 read_v(0);
-                __builtin_amdgcn_sched_barrier(0);
                 LA_CYC(1);
 
                 // ---- S^T block: 32 keys x 32 rows
@@ -665,7 +664,6 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
 #pragma unroll
                 for (int k16 = 0; k16 < D / 16; ++k16)
                     s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[k16], qreg[k16], s, 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
                 LA_CYC(2);
                 if (slots_left > 0) issue_slot();
                 read_v(1);  // in flight during the softmax arithmetic
@@ -727,7 +725,6 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                     }
                     l_run += psum0 + psum1;
                 }
-                __builtin_amdgcn_sched_barrier(0);
                 LA_CYC(4);
 
                 // ---- O^T += V^T P^T
@@ -737,7 +734,6 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                     for (int db = 0; db < C::DB; ++db)
                         o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kk][db], pf[kk], o[db], 0, 0, 0);
             }
-            __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
             for (int j = 0; j < C::CPI; ++j)
