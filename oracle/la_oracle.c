@@ -20,7 +20,11 @@
  * tokens) against the same exhaustive enumeration written from the words of
  * Sec. 3.2, a literal walk through Algorithm 3 on a prefix-deterministic toy
  * model (whose output must also equal plain greedy decoding), and a library
- * argmax.
+ * argmax; sampling verification (Algorithm 4) against the exact law of its
+ * decision tree computed independently in the test (which is also checked
+ * to give every emitted token the model's own distribution: Theorem A of
+ * App. B), hand-computed accept/reject regions, the zero-temperature limit
+ * (greedy verification) and a library softmax + inverse-CDF search.
  *
  * Row / key order of one step (same for q, step_k, step_v, out):
  *   r = 0                               the current input token, relative position 0
@@ -303,6 +307,107 @@ int la_oracle_verify_step(const float *logits_cur, const float *logits_look, con
     out_tokens[best_len] = best_len == 0 ? cur_token
                                          : argmax_row(logits_cand + ((size_t)best_g * n1 + (best_len - 1)) * V, V);
     *n_out = best_len + 1;
+    return 0;
+}
+
+/*
+ * Sampling verification (Algorithm 4), step by step in the algorithm's order, fp64.
+ *
+ *   logits_cur   [V]          model output at the current token (the first of the N
+ *                             distributions of every candidate)
+ *   logits_cand  [G][N-1][V]  row (g,k): output at candidate g's token k (distribution k+2)
+ *   cand_tokens  [G][N-1]
+ *   u_test       [N-1][G]     the uniform draws of the accept tests: u_test[i][j] is the one
+ *                             drawn for the j-th candidate examined at position i
+ *   u_final                   the draw that samples the last token
+ *   temperature > 0           distributions are softmax(logits / temperature)
+ *
+ * At each position the surviving candidates are examined in order; candidate token s is
+ * accepted if the draw is below P(s), where P starts as the model's distribution at this
+ * position (all survivors share the accepted prefix, the first survivor's row is used) and,
+ * after every rejection, has the rejected token's probability set to zero and is renormalised.
+ * After an acceptance only the later candidates with the same token survive.  If no candidate
+ * is accepted, one token is sampled from the residual P and the walk stops; after N-1
+ * acceptances one token is sampled from the first survivor's N-th distribution.
+ *
+ * Readings: the test "r <= P(s)" is taken as r < P(s) for r in [0,1) (same probability; a
+ * token of probability zero is never accepted); sampling is by inverse CDF in index order:
+ * the first v whose cumulative probability exceeds u.  G == 0: one token sampled from the
+ * current token's distribution.
+ */
+static void softmax_row(const float *row, int V, double inv_t, double *P)
+{
+    double m = (double)row[0] * inv_t;
+    for (int v = 1; v < V; ++v)
+        if ((double)row[v] * inv_t > m) m = (double)row[v] * inv_t;
+    double z = 0.0;
+    for (int v = 0; v < V; ++v) {
+        P[v] = exp((double)row[v] * inv_t - m);
+        z += P[v];
+    }
+    for (int v = 0; v < V; ++v) P[v] /= z;
+}
+
+static int sample_inverse_cdf(const double *P, int V, double u)
+{
+    double c = 0.0;
+    int last_positive = 0;
+    for (int v = 0; v < V; ++v) {
+        if (P[v] > 0.0) last_positive = v;
+        c += P[v];
+        if (c > u) return v;
+    }
+    return last_positive;  /* rounding left the total a hair below u */
+}
+
+int la_oracle_verify_sample(const float *logits_cur, const float *logits_cand, const int32_t *cand_tokens,
+                            const float *u_test, float u_final, float temperature, int N, int G, int V,
+                            int32_t *out_tokens, int32_t *n_out)
+{
+    if (G < 0 || N < 2 || V < 1 || !(temperature > 0.0f)) return -1;
+    const int n1 = N - 1;
+    const double inv_t = 1.0 / (double)temperature;
+    double *P = (double *)malloc((size_t)V * sizeof(double));
+    int *alive = (int *)malloc((size_t)(G > 0 ? G : 1) * sizeof(int));
+    if (!P || !alive) { free(P); free(alive); return -2; }
+    int n_alive = G, len = 0;
+    for (int g = 0; g < G; ++g) alive[g] = g;
+
+    for (int i = 0; i < n1 && n_alive > 0; ++i) {
+        /* the i-th distribution of the first survivor */
+        const int g0 = alive[0];
+        softmax_row(i == 0 ? logits_cur : logits_cand + ((size_t)g0 * n1 + (i - 1)) * V, V, inv_t, P);
+        int accepted = 0;
+        for (int j = 0; j < n_alive; ++j) {
+            const int s = cand_tokens[alive[j] * n1 + i];
+            const double r = (double)u_test[i * G + j];
+            if (r < P[s]) {
+                out_tokens[len++] = s;
+                accepted = 1;
+                int m = 0;
+                for (int k = j; k < n_alive; ++k)
+                    if (cand_tokens[alive[k] * n1 + i] == s) alive[m++] = alive[k];
+                n_alive = m;
+                break;
+            }
+            /* rejected: this token is ruled out, renormalise */
+            P[s] = 0.0;
+            double z = 0.0;
+            for (int v = 0; v < V; ++v) z += P[v];
+            for (int v = 0; v < V; ++v) P[v] /= z;
+        }
+        if (!accepted) {
+            out_tokens[len++] = sample_inverse_cdf(P, V, (double)u_final);
+            *n_out = len;
+            free(P); free(alive);
+            return 0;
+        }
+    }
+    /* every position accepted (or no candidates at all): one more token from the model */
+    softmax_row(len == 0 ? logits_cur : logits_cand + ((size_t)alive[0] * n1 + (len - 1)) * V, V, inv_t, P);
+    out_tokens[len++] = sample_inverse_cdf(P, V, (double)u_final);
+    *n_out = len;
+    free(P); free(alive);
     return 0;
 }
 

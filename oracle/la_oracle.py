@@ -33,6 +33,9 @@ def _load():
         lib.la_oracle_verify.restype = i
         lib.la_oracle_verify_step.argtypes = [p, p, p, p, i, i, i, i, p, p, p, p, p]
         lib.la_oracle_verify_step.restype = i
+        f = ctypes.c_float
+        lib.la_oracle_verify_sample.argtypes = [p, p, p, p, f, f, i, i, i, p, p]
+        lib.la_oracle_verify_sample.restype = i
         _lib = lib
     return _lib
 
@@ -119,6 +122,28 @@ def verify_step(logits_cur, logits_look, logits_cand, cand_tokens, W, N, G, V):
     if rc != 0:
         raise ValueError("la_oracle_verify_step: bad shape (rc=%d)" % rc)
     return [int(t) for t in out[:int(n_out[0])]], int(best[0]), window, accept_len
+
+
+def verify_sample(logits_cur, logits_cand, cand_tokens, u_test, u_final, temperature, N, G, V):
+    """Algorithm 4 (sampling verification): the list of 1..N accepted tokens.
+
+    logits_cur fp32 [V], logits_cand fp32 [G, N-1, V], cand_tokens int32 [G, N-1], u_test fp32
+    [N-1, G] (draw of the j-th candidate examined at position i), u_final the draw of the last
+    token; see la_oracle_verify_sample in la_oracle.c.
+    """
+    cur = np.ascontiguousarray(logits_cur)
+    cnd = np.ascontiguousarray(logits_cand).reshape(G, N - 1, V)
+    cand = np.ascontiguousarray(cand_tokens).reshape(G, N - 1)
+    ut = np.ascontiguousarray(u_test, dtype=np.float32).reshape(N - 1, G)
+    assert cur.dtype == cnd.dtype == np.float32 and cur.shape == (V,) and cand.dtype == np.int32
+    out = np.zeros((N,), dtype=np.int32)
+    n_out = np.zeros((1,), dtype=np.int32)
+    rc = _load().la_oracle_verify_sample(cur.ctypes.data, cnd.ctypes.data, cand.ctypes.data, ut.ctypes.data,
+                                         float(u_final), float(temperature), N, G, V, out.ctypes.data,
+                                         n_out.ctypes.data)
+    if rc != 0:
+        raise ValueError("la_oracle_verify_sample: bad arguments (rc=%d)" % rc)
+    return [int(t) for t in out[:int(n_out[0])]]
 
 
 def greedy_verification(candidates, dist_argmax):
