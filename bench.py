@@ -102,6 +102,14 @@ def main():
     def verify_step():
         binding.la_verify_step(vs[0], vs[1], vs[2], vs[3], s.W, s.N, s.G, s.V, *vs_out)
 
+    # sampling verification (Algorithm 4), also timed on its own
+    sm_h = wl.verify_sample_inputs(s)
+    sm = [torch.from_numpy(x).cuda() for x in sm_h]
+    sm_out = [torch.empty((n,), dtype=torch.int32, device="cuda") for n in (s.N, 1)]
+
+    def verify_sample():
+        binding.la_verify_sample(sm[0], sm[1], sm[2], sm[3], sm[4], 1.0, s.N, s.G, s.V, *sm_out)
+
     def attention_layers():
         for x, o in zip(layers, outs):
             binding.la_step_attention(x["q"], x["k_cache"], x["v_cache"], x["step_k"], x["step_v"],
@@ -140,8 +148,8 @@ def main():
 
     # ---- dominant kernel (attention) and the verify kernel, by HIP events on the launch stream
     reps = max(10, min(args.steps, 100))
-    e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
-    attn_ms, ver_ms, vs_ms = [], [], []
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+    attn_ms, ver_ms, vs_ms, sm_ms = [], [], [], []
     if use_graph:
         # the L attention launches alone, and the verify launch alone, as graphs
         ga, gv = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
@@ -155,11 +163,17 @@ def main():
         with torch.cuda.graph(gs):
             for _ in range(32):
                 verify_step()
-        run_attn, run_ver, run_vs, ver_calls = ga.replay, gv.replay, gs.replay, 32
+        verify_sample()
+        gm = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gm):
+            for _ in range(32):
+                verify_sample()
+        run_attn, run_ver, run_vs, run_sm, ver_calls = ga.replay, gv.replay, gs.replay, gm.replay, 32
     else:
         run_attn = attention_layers
         run_ver = lambda: binding.la_verify(logits, cand, s.G, s.N, s.V, alen, acc)
         run_vs = verify_step
+        run_sm = verify_sample
         ver_calls = 1
     for _ in range(reps):
         e[0].record()
@@ -169,14 +183,19 @@ def main():
         e[2].record()
         run_vs()
         e[3].record()
+        run_sm()
+        e[4].record()
         torch.cuda.synchronize()
         attn_ms.append(e[0].elapsed_time(e[1]))
         ver_ms.append(e[1].elapsed_time(e[2]) / ver_calls)
         vs_ms.append(e[2].elapsed_time(e[3]) / ver_calls)
+        sm_ms.append(e[3].elapsed_time(e[4]) / ver_calls)
     attn_us = float(np.median(attn_ms)) * 1e3 / L       # per launch, launch gaps included
     verify_us = float(np.median(ver_ms)) * 1e3
     verify_step_us = float(np.median(vs_ms)) * 1e3
     verify_step_bytes = (1 + s.W + s.G * (s.N - 1)) * s.V * 4
+    verify_sample_us = float(np.median(sm_ms)) * 1e3
+    verify_sample_bytes = (2 + s.G * (s.N - 1)) * s.V * 4   # every row once, one row again for the draw
     abytes = algorithmic_bytes(s)
     aflops = algorithmic_flops(s)
     t_hbm = abytes / (HBM_PEAK_GBS * 1e9)
@@ -215,6 +234,10 @@ def main():
                       np.array_equal(vs_out[3].cpu().numpy(), w_window) and
                       np.array_equal(vs_out[4].cpu().numpy(), w_len))
 
+    w_tokens = orc.verify_sample(*sm_h[:4], float(sm_h[4][0]), 1.0, s.N, s.G, s.V)
+    n = int(sm_out[1].item())
+    sample_equal = bool(sm_out[0].cpu().numpy()[:n].tolist() == w_tokens)   # fp32 vs fp64: near-ties may differ
+
     cpu = None
     if not args.no_cpu_baseline:
         # the oracle as it stands, on the host cores: repeated layer-steps of layer 0's inputs
@@ -250,10 +273,13 @@ def main():
         "verify_step": {"us": verify_step_us, "algorithmic_bytes": verify_step_bytes,
                         "gbs": verify_step_bytes / (verify_step_us * 1e-6) / 1e9,
                         "frac_of_hbm_peak": verify_step_bytes / (verify_step_us * 1e-6) / 1e9 / HBM_PEAK_GBS},
+        "verify_sample": {"us": verify_sample_us, "algorithmic_bytes": verify_sample_bytes,
+                          "gbs": verify_sample_bytes / (verify_sample_us * 1e-6) / 1e9,
+                          "frac_of_hbm_peak": verify_sample_bytes / (verify_sample_us * 1e-6) / 1e9 / HBM_PEAK_GBS},
         "attention_tflops": aflops / (attn_us * 1e-6) / 1e12,
         "attention_gbs": abytes / (attn_us * 1e-6) / 1e9,
         "parity": {"attention_max_abs_err_layer0": err, "verify_bit_exact": exact,
-                   "verify_step_bit_exact": exact_step},
+                   "verify_step_bit_exact": exact_step, "verify_sample_equals_oracle": sample_equal},
     }
     print(json.dumps(line))
     if err > 2e-2 or not exact or not exact_step:

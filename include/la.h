@@ -120,6 +120,35 @@ la_status la_verify_step(const float* logits_cur, const float* logits_look, cons
                          const int* cand_tokens, int W, int N, int G, int V, int* out_tokens, int* n_out,
                          int* best, int* new_window, int* accept_len, void* stream);
 
+/*
+ * Sampling verification in one launch (Algorithm 4; App. B shows that every token it emits
+ * follows the model's own distribution).  Distributions are softmax(logits / temperature).
+ * Position by position the surviving candidates are examined in order: candidate token s is
+ * accepted if its draw is below P(s), where P starts as the first survivor's distribution at
+ * that position and, after every rejection, has the rejected token's probability set to zero
+ * and is renormalised; after an acceptance only the later candidates with the same token
+ * survive.  If none is accepted one token is drawn from the residual P and the walk stops;
+ * after N-1 acceptances one token is drawn from the first survivor's N-th distribution.
+ *
+ *   logits_cur   fp32 [V]          model output at the current token (distribution 1 of every
+ *                                  candidate)
+ *   logits_cand  fp32 [G][N-1][V]  row (g,k): output at candidate g's token k (its distribution
+ *                                  k+2); NULL iff G == 0
+ *   cand_tokens  int32 [G][N-1]
+ *   u_test       fp32 [N-1][G]     uniform draws in [0,1): u_test[i][j] serves the j-th candidate
+ *                                  examined at position i; NULL iff G == 0
+ *   u_final      fp32 [1]          the draw for the last token (inverse CDF in index order)
+ *   temperature  > 0 (host value)
+ *   out_tokens   int32 [N]   out: n_out tokens
+ *   n_out        int32 [1]   out: 1..N
+ * The accept test is "draw < P(s)" (a token of probability zero is never accepted).  Arithmetic
+ * is fp32: a draw within rounding of P(s), or of a step of the cumulative distribution, may fall
+ * on either side.  G <= 1024.
+ */
+la_status la_verify_sample(const float* logits_cur, const float* logits_cand, const int* cand_tokens,
+                           const float* u_test, const float* u_final, float temperature, int N, int G, int V,
+                           int* out_tokens, int* n_out, void* stream);
+
 /* Bytes of device workspace la_step_attention needs for this shape (0 if none). */
 long long la_step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int kv_heads,
                                             int head_dim);

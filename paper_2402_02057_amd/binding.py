@@ -37,6 +37,8 @@ def load():
     lib.la_verify.restype = i
     lib.la_verify_step.argtypes = [p, p, p, p, i, i, i, i, p, p, p, p, p, p]
     lib.la_verify_step.restype = i
+    lib.la_verify_sample.argtypes = [p, p, p, p, p, ctypes.c_float, i, i, i, p, p, p]
+    lib.la_verify_sample.restype = i
     lib.la_step_attention_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
     lib.la_step_attention_workspace_bytes.restype = ctypes.c_longlong
     lib.la_shutdown.argtypes = []
@@ -49,7 +51,7 @@ def load():
     return lib
 
 
-EXPORTS = ("la_step_attention", "la_verify", "la_verify_step", "la_step_attention_workspace_bytes", "la_shutdown",
+EXPORTS = ("la_step_attention", "la_verify", "la_verify_step", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown",
            "la_last_error", "la_version")
 
 
@@ -129,6 +131,21 @@ def la_verify_step(logits_cur, logits_look, logits_cand, cand_tokens, W, N, G, V
         _ptr(accept_len, torch.int32, (G,), "accept_len", allow_empty_null=True), _stream(stream))
     _check(rc)
     return out_tokens, n_out, best, new_window, accept_len
+
+
+def la_verify_sample(logits_cur, logits_cand, cand_tokens, u_test, u_final, temperature, N, G, V, out_tokens,
+                     n_out, stream=None):
+    """out_tokens[N], n_out[1] (int32) <- sampling verification (Algorithm 4); asynchronous."""
+    rc = load().la_verify_sample(
+        _ptr(logits_cur, torch.float32, (V,), "logits_cur"),
+        _ptr(logits_cand, torch.float32, (G, N - 1, V), "logits_cand", allow_empty_null=True),
+        _ptr(cand_tokens, torch.int32, (G, N - 1), "cand_tokens", allow_empty_null=True),
+        _ptr(u_test, torch.float32, (N - 1, G), "u_test", allow_empty_null=True),
+        _ptr(u_final, torch.float32, (1,), "u_final"), float(temperature), N, G, V,
+        _ptr(out_tokens, torch.int32, (N,), "out_tokens"), _ptr(n_out, torch.int32, (1,), "n_out"),
+        _stream(stream))
+    _check(rc)
+    return out_tokens, n_out
 
 
 def la_step_attention_workspace_bytes(P, W, N, G, heads, kv_heads, head_dim):

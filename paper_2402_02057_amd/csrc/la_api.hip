@@ -173,6 +173,24 @@ la_status la_verify_step(const float* logits_cur, const float* logits_look, cons
                                   n_out, best, new_window, accept_len, (hipStream_t)stream);
 }
 
+la_status la_verify_sample(const float* logits_cur, const float* logits_cand, const int* cand_tokens,
+                           const float* u_test, const float* u_final, float temperature, int N, int G, int V,
+                           int* out_tokens, int* n_out, void* stream)
+{
+    if (G < 0 || N < 2 || V < 1 || !(temperature > 0.0f))
+        return la::fail(LA_EINVAL,
+                        "la_verify_sample: need G >= 0, N >= 2, V >= 1, temperature > 0 (got G=%d N=%d V=%d T=%g)",
+                        G, N, V, (double)temperature);
+    if (G > 1024) return la::fail(LA_EUNSUPPORTED, "la_verify_sample: at most 1024 candidates (got %d)", G);
+    if (!logits_cur || !u_final || !out_tokens || !n_out || (G > 0 && (!logits_cand || !cand_tokens || !u_test)))
+        return la::fail(LA_EINVAL, "la_verify_sample: null pointer");
+    if (((uintptr_t)logits_cur | (uintptr_t)logits_cand | (uintptr_t)cand_tokens | (uintptr_t)u_test |
+         (uintptr_t)u_final | (uintptr_t)out_tokens | (uintptr_t)n_out) & 3)
+        return la::fail(LA_EINVAL, "la_verify_sample: buffers must be 4-byte aligned");
+    return la::launch_verify_sample(logits_cur, logits_cand, cand_tokens, u_test, u_final, temperature, N, G, V,
+                                    out_tokens, n_out, (hipStream_t)stream);
+}
+
 long long la_step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int kv_heads,
                                             int head_dim)
 {
@@ -186,6 +204,6 @@ void la_shutdown(void) { la::free_workspaces(); }
 
 const char* la_last_error(void) { return la::g_error; }
 
-int la_version(void) { return 1001; }
+int la_version(void) { return 1002; }
 
 }  // extern "C"

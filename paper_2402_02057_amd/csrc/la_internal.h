@@ -25,6 +25,9 @@ la_status launch_verify(const float* logits, const int* cand_tokens, int G, int 
 la_status launch_verify_step(const float* logits_cur, const float* logits_look, const float* logits_cand,
                              const int* cand_tokens, int W, int N, int G, int V, int* out_tokens, int* n_out,
                              int* best, int* new_window, int* accept_len, hipStream_t stream);
+la_status launch_verify_sample(const float* logits_cur, const float* logits_cand, const int* cand_tokens,
+                               const float* u_test, const float* u_final, float temperature, int N, int G,
+                               int V, int* out_tokens, int* n_out, hipStream_t stream);
 la_status launch_step_attention(const void* q, const void* k_cache, const void* v_cache,
                                 const void* step_k, const void* step_v, int P, int W, int N, int G,
                                 int heads, int kv_heads, int head_dim, void* out,

@@ -170,3 +170,42 @@ def verify_step_inputs(s: StepShape, extra=0):
         cnd[g, n1 - 1, int(rng.integers(0, V))] = PLANT_VALUE   # bonus row
     return cur, look, cnd, cand, lens
 
+
+
+def verify_sample_inputs(s: StepShape, extra=0, temperature=1.0):
+    """Inputs of sampling verification: (logits_cur fp32 [V], logits_cand fp32 [G, N-1, V],
+    cand_tokens int32 [G, N-1], u_test fp32 [N-1, G], u_final fp32 [1]).
+
+    Logits are N(0,1) draws with a few tokens per row raised so that a handful of tokens carry
+    most of the probability (as a language model's rows do); candidate g follows the peaked
+    tokens for (g + shift) mod N positions, so that accept tests meet both large and small
+    probabilities.  Rows of candidates that share a token prefix are made identical, as a real
+    model's would be.  Draws are uniform in [0, 1).
+    """
+    G, n1, V = s.G, s.N - 1, s.V
+    rng = np.random.default_rng(seed_for(s.config, _LOGITS, extra + 13))
+    top = min(V, 4)
+
+    def peaked_row():
+        row = rng.standard_normal(size=(V,), dtype=np.float32)
+        idx = rng.choice(V, size=top, replace=False)
+        row[idx] += np.float32(9.0) + rng.standard_normal(top).astype(np.float32)
+        return row, idx
+    cur, cur_top = peaked_row()
+    cnd = np.zeros((G, n1, V), dtype=np.float32)
+    cand = np.zeros((G, n1), dtype=np.int32)
+    shift = int(rng.integers(0, s.N))
+    rows_by_prefix = {}
+    for g in range(G):
+        follow = (g + shift) % s.N
+        prefix, tops = (), cur_top
+        for k in range(n1):
+            tokn = int(tops[int(rng.integers(0, len(tops)))]) if k < follow else int(rng.integers(0, V))
+            cand[g, k] = tokn
+            prefix = prefix + (tokn,)
+            if prefix not in rows_by_prefix:
+                rows_by_prefix[prefix] = peaked_row()
+            cnd[g, k], tops = rows_by_prefix[prefix]
+    u_test = rng.random(size=(n1, G), dtype=np.float32)
+    u_final = rng.random(size=(1,), dtype=np.float32)
+    return cur, cnd, cand, u_test, u_final

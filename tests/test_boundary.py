@@ -53,6 +53,10 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
     assert b"null" in lib.la_last_error()
     assert lib.la_verify_step(None, None, None, None, 0, 1, 0, 10, None, None, None, None, None, None) == -1
     assert b"N >= 2" in lib.la_last_error()
+    assert lib.la_verify_sample(None, None, None, None, None, 1.0, 3, 0, 10, None, None, None) == -1
+    assert b"null" in lib.la_last_error()
+    assert lib.la_verify_sample(None, None, None, None, None, 0.0, 3, 0, 10, None, None, None) == -1
+    assert b"temperature" in lib.la_last_error()
 
 
 def test_workspace_query(lib):
