@@ -209,3 +209,53 @@ def verify_sample_inputs(s: StepShape, extra=0, temperature=1.0):
     u_test = rng.random(size=(n1, G), dtype=np.float32)
     u_final = rng.random(size=(1,), dtype=np.float32)
     return cur, cnd, cand, u_test, u_final
+
+
+# ---- a toy language model for driving the decoding loop end to end --------------------------
+
+TOY_VOCAB = 32       # token 0 is the begin-of-sequence token and is never generated
+TOY_HEAD_DIM = 64
+TOY_SENTINEL = 32    # the coordinate of the key that only the begin-of-sequence token carries
+
+
+def toy_lm_tables(seed=0):
+    """Seeded tables of a one-layer attention-only toy language model (inputs, like weights).
+
+    The model looks for one particular other token in what a position may see: `wanted[c]` is the
+    token that position holding token c looks for, `next_token[2 c + found]` the greedy
+    continuation, `logits[2 c + found]` an fp32 row of N(0,1) noise with a peak of 12 at that
+    continuation.  `q`, `k`, `v` are the attention tables (float32 holding bf16-exact values,
+    [vocab, 64]) with which one softmax-attention head computes `found`: a query matches the
+    wanted token's key with score 32 and the begin-of-sequence key with score 16 (everything else
+    0), values carry 1 in coordinate 0 for ordinary tokens and in coordinate 1 for the
+    begin-of-sequence token, so that found <=> out[0] > 0.5 with a wide margin.
+    """
+    rng = np.random.default_rng(BASE_SEED + 9000 + seed)
+    V, d = TOY_VOCAB, TOY_HEAD_DIM
+    wanted = rng.integers(1, V, size=V).astype(np.int32)
+    next_token = rng.integers(1, V, size=2 * V).astype(np.int32)
+    logits = rng.standard_normal(size=(2 * V, V)).astype(np.float32)
+    logits[np.arange(2 * V), next_token] = PLANT_VALUE
+    q = np.zeros((V, d), dtype=np.float32)
+    k = np.zeros((V, d), dtype=np.float32)
+    v = np.zeros((V, d), dtype=np.float32)
+    for c in range(V):
+        q[c, wanted[c]] = 16.0
+        q[c, TOY_SENTINEL] = 8.0
+        if c == 0:
+            k[c, TOY_SENTINEL] = 16.0
+            v[c, 1] = 1.0
+        else:
+            k[c, c] = 16.0
+            v[c, 0] = 1.0
+    return {"wanted": wanted, "next_token": next_token, "logits": logits, "q": q, "k": k, "v": v}
+
+
+def window_random_token(seed, step, column):
+    """The "random" tokens Algorithm 2 fills the window with, as a counter-based generator so
+    that every implementation of the loop draws the same ones: a token in [1, TOY_VOCAB)."""
+    h = (seed * 0x9E3779B97F4A7C15 + step * 0xBF58476D1CE4E5B9 + column * 0x94D049BB133111EB) % (1 << 64)
+    h ^= h >> 31
+    h = (h * 0xD6E8FEB86659FD93) % (1 << 64)
+    h ^= h >> 29
+    return 1 + h % (TOY_VOCAB - 1)
