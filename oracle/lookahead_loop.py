@@ -52,17 +52,26 @@ def greedy_decode(model, prompt, n_tokens):
     return out
 
 
-def lookahead_decode(model, prompt, W, N, G, n_tokens, seed=0):
+def lookahead_decode(model, prompt, W, N, G, n_tokens, seed=0, prompt_as_reference=False):
     """(tokens, steps, trace): Algorithm 2 with greedy verification until n_tokens are out.
 
     trace is one record per step: the step's tokens in row order, the accepted tokens, the index
     of the winning candidate and the new window level, for step-by-step comparison.
+    With prompt_as_reference the pool starts with every n-gram of the prompt (the augmentation of
+    the ablation study, Sec. 5.4): candidates may come from anywhere, the output cannot change.
     """
     n1 = N - 1
     V = model.vocab
     seq = list(prompt)                     # x^0 followed by the accepted tokens; seq[-1] is the current token
     window = [[wl.window_random_token(seed, l - n1, j) for j in range(W)] for l in range(n1)]
     pool = {}
+    if prompt_as_reference:
+        for i in range(len(prompt) - N + 1):
+            bucket = pool.setdefault(int(prompt[i]), [])
+            tail = tuple(int(t) for t in prompt[i + 1:i + N])
+            if tail in bucket:
+                bucket.remove(tail)
+            bucket.append(tail)
     out, trace, steps = [], [], 0
     index = 0                              # Algorithm 2's loop index i - 1 (tokens decided so far, skips included)
     while len(out) < n_tokens:

@@ -1,0 +1,165 @@
+"""Host side of a Lookahead Decoding run (Algorithm 2 of arXiv 2402.02057) driving the HIP kernels.
+
+Everything per-token runs on the device: the model's forward pass over the step's
+T = 1 + (W + G)(N - 1) tokens (its attention is `la_step_attention`) and the end of the step
+(`la_verify_step`: Algorithm 3 and the window's new tokens).  The host keeps what the paper keeps
+on the host: the 2D window of Jacobi iterates (Sec. 3.1) and the n-gram pool (Sec. 3.2).
+
+`model` is any object with
+    vocab                               vocabulary size
+    forward_step(tokens, W, N, G)       fp32 device tensor [T, vocab]: the model output at every
+                                        row of the step (row order of include/la.h), attending to
+                                        its own KV cache as the prefix
+    append(tokens)                      append tokens to the KV cache
+`ToyAttentionLM` below is such a model: one attention head over seeded tables, enough to run the
+loop end to end on the GPU and check it against plain greedy decoding.
+
+    python -m paper_2402_02057_amd.lookahead      # demo: tokens per step and time per step
+"""
+import time
+
+import torch
+
+from . import binding, workloads as wl
+
+
+class NgramPool:
+    """n-grams collected from the Jacobi trajectory, by first token; most recent last."""
+
+    def __init__(self):
+        self._tails = {}
+
+    def add(self, gram):
+        bucket = self._tails.setdefault(gram[0], [])
+        tail = tuple(gram[1:])
+        if tail in bucket:
+            bucket.remove(tail)
+        bucket.append(tail)
+
+    def lookup(self, first_token, limit):
+        """At most `limit` tails of n-grams starting with first_token, the most recent ones."""
+        return self._tails.get(first_token, [])[-limit:] if limit > 0 else []
+
+
+class LookaheadDecoder:
+    """Greedy Lookahead Decoding.  `prompt` must hold at least one token; its last token is the
+    first current token, the others go to the model's KV cache.  With prompt_as_reference the
+    pool starts with the prompt's own n-grams."""
+
+    def __init__(self, model, prompt, W, N, G, seed=0, random_token=wl.window_random_token,
+                 prompt_as_reference=False):
+        if N < 2 or W < 0 or G < 0 or not prompt:
+            raise ValueError("need N >= 2, W >= 0, G >= 0 and a non-empty prompt")
+        self.model, self.W, self.N, self.G, self.seed = model, W, N, G, seed
+        self.random_token = random_token
+        n1 = N - 1
+        self.window = [[random_token(seed, l - n1, j) for j in range(W)] for l in range(n1)]
+        self.pool = NgramPool()
+        if prompt_as_reference:     # the prompt's own n-grams as first candidates (ablation study, Sec. 5.4)
+            for i in range(len(prompt) - N + 1):
+                self.pool.add(tuple(int(t) for t in prompt[i:i + N]))
+        self.current = int(prompt[-1])
+        model.append([int(t) for t in prompt[:-1]])
+        self.index = 0          # Algorithm 2's loop index: tokens decided so far
+        self.steps = 0
+        dev = "cuda"
+        self._out = torch.empty((N,), dtype=torch.int32, device=dev)
+        self._n_out = torch.empty((1,), dtype=torch.int32, device=dev)
+        self._best = torch.empty((1,), dtype=torch.int32, device=dev)
+        self._new = torch.empty((W,), dtype=torch.int32, device=dev)
+
+    def step(self):
+        """One decoding step; returns (accepted tokens, step tokens, winning candidate, new level)."""
+        W, N, n1 = self.W, self.N, self.N - 1
+        cur = self.current
+        tails = self.pool.lookup(cur, self.G)
+        g = len(tails)
+        tokens = [cur] + [t for level in self.window for t in level] + [t for tail in tails for t in tail]
+        logits = self.model.forward_step(tokens, W, N, g)
+        V = self.model.vocab
+        look = logits[1 + (n1 - 1) * W:1 + n1 * W] if W else None        # newest level of the window
+        cand_logits = logits[1 + W * n1:].view(g, n1, V) if g else None
+        cand = torch.tensor(tails, dtype=torch.int32, device=logits.device).view(g, n1) if g else None
+        binding.la_verify_step(logits[0], look, cand_logits, cand, W, N, g, V, self._out, self._n_out,
+                               self._best, self._new if W else None, None)
+        n = int(self._n_out.item())                                       # (synchronises)
+        accepted = self._out[:n].tolist()
+        new = self._new.tolist() if W else []
+        for j in range(W):
+            self.pool.add(tuple(self.window[l][j] for l in range(n1)) + (new[j],))
+        self.window = self.window[1:] + [new]
+        for extra in range(1, n):   # skipped loop indices: a "random" level each (Algorithm 2)
+            self.window = self.window[1:] + [[self.random_token(self.seed, self.index + extra, j)
+                                              for j in range(W)]]
+        self.index += n
+        self.model.append([cur] + accepted[:-1])
+        self.current = accepted[-1]
+        self.steps += 1
+        return accepted, tokens, int(self._best.item()), new
+
+    def generate(self, n_tokens):
+        out = []
+        while len(out) < n_tokens:
+            out.extend(self.step()[0])
+        return out[:n_tokens]
+
+
+class ToyAttentionLM:
+    """One attention head over the seeded tables of workloads.toy_lm_tables: a position's output
+    depends on its token and on whether the token it looks for is among the positions it may see,
+    which the head finds out with `la_step_attention` (head_dim 64)."""
+
+    def __init__(self, seed=0, max_len=8192, device="cuda"):
+        t = wl.toy_lm_tables(seed)
+        self.vocab = wl.TOY_VOCAB
+        d = wl.TOY_HEAD_DIM
+
+        def table(x):
+            return torch.from_numpy(x).to(device).to(torch.bfloat16).view(self.vocab, 1, d)
+        self._q, self._k, self._v = table(t["q"]), table(t["k"]), table(t["v"])
+        self._logits = torch.from_numpy(t["logits"]).to(device)
+        self._k_cache = torch.zeros((1, max_len, d), dtype=torch.bfloat16, device=device)
+        self._v_cache = torch.zeros((1, max_len, d), dtype=torch.bfloat16, device=device)
+        self.length = 0
+        self.device = device
+
+    def append(self, tokens):
+        if not tokens:
+            return
+        idx = torch.tensor(tokens, dtype=torch.long, device=self.device)
+        n = len(tokens)
+        if self.length + n > self._k_cache.shape[1]:
+            raise ValueError("KV cache full")
+        self._k_cache[0, self.length:self.length + n] = self._k[idx, 0]
+        self._v_cache[0, self.length:self.length + n] = self._v[idx, 0]
+        self.length += n
+
+    def forward_step(self, tokens, W, N, G):
+        idx = torch.tensor(tokens, dtype=torch.long, device=self.device)
+        T, P, d = len(tokens), self.length, wl.TOY_HEAD_DIM
+        assert T == 1 + (W + G) * (N - 1)
+        out = torch.empty((T, 1, d), dtype=torch.bfloat16, device=self.device)
+        binding.la_step_attention(self._q[idx].contiguous(), self._k_cache[:, :P] if P else None,
+                                  self._v_cache[:, :P] if P else None, self._k[idx].contiguous(),
+                                  self._v[idx].contiguous(), P, W, N, G, 1, 1, d, out)
+        found = (out[:, 0, 0].float() > 0.5).long()
+        return self._logits[idx * 2 + found].contiguous()
+
+
+def _demo():
+    torch.cuda.set_device(0)
+    for W, N, G in ((5, 4, 5), (15, 5, 15)):
+        model = ToyAttentionLM(0)
+        dec = LookaheadDecoder(model, [0, 5, 9], W, N, G)
+        dec.generate(32)                      # warm-up
+        torch.cuda.synchronize()
+        t0, s0 = time.perf_counter(), dec.steps
+        n = len(dec.generate(512))
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        print("W=%d N=%d G=%d: %d tokens in %d steps (S = %.2f), %.0f us per step (host loop included)"
+              % (W, N, G, n, dec.steps - s0, n / (dec.steps - s0), dt / (dec.steps - s0) * 1e6))
+
+
+if __name__ == "__main__":
+    _demo()

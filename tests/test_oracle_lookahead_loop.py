@@ -62,3 +62,22 @@ def test_random_window_tokens_are_valid_and_spread():
     toks = [wl.window_random_token(s, i, j) for s in range(3) for i in range(-4, 60) for j in range(8)]
     assert min(toks) >= 1 and max(toks) < wl.TOY_VOCAB
     assert len(set(toks)) == wl.TOY_VOCAB - 1
+
+
+def test_prompt_as_reference_changes_the_steps_but_never_the_output():
+    """Sec. 5.4: the prompt's own n-grams as candidates.  With no lookahead branch (W = 0) the pool
+    holds nothing else: a prompt that already contains the continuation compresses the steps, any
+    other prompt leaves one token per step; the tokens are the greedy ones either way."""
+    model = loop.ToyModel(3)
+    head = [0, 5, 9]
+    seen = loop.greedy_decode(model, head, 80)
+    prompt = head + seen                          # the continuation goes on cycling through these
+    want = loop.greedy_decode(model, prompt, 60)
+    plain, steps_plain, _ = loop.lookahead_decode(model, prompt, 0, 4, 3, 60, seed=3)
+    assert plain == want and steps_plain == 60
+    got, steps, trace = loop.lookahead_decode(model, prompt, 0, 4, 3, 60, seed=3, prompt_as_reference=True)
+    assert got == want and steps < 40
+    assert all(len(t["tokens"]) == 1 + len(t["tokens"][1:]) and (len(t["tokens"]) - 1) % 3 == 0 for t in trace)
+    # with a lookahead branch as well: still the same tokens
+    got, steps_both, _ = loop.lookahead_decode(model, prompt, 5, 4, 5, 60, seed=3, prompt_as_reference=True)
+    assert got == want and steps_both <= 60
