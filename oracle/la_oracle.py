@@ -2,6 +2,8 @@
 
 Test infrastructure only (tests, the smoke check, the benchmark's cpu_baseline leg).
 bf16 tensors travel as numpy uint16 bit patterns; nothing here touches the GPU library.
+`kv_commit` (appending the accepted tokens to the KV cache) is plain numpy; its pin is that the
+cache after any run of lookahead steps equals the cache of plain autoregressive decoding.
 """
 import ctypes
 
@@ -178,3 +180,24 @@ def greedy_verification(candidates, dist_argmax):
         alive = [g for g in alive[hit:] if candidates[g][i] == target]
     out.append(dist_argmax[alive[0]][n1])
     return out
+
+
+def kv_commit(k_cache, v_cache, step_k, step_v, P, W, N, G, best, n_out):
+    """Append the accepted tokens of a greedy step to the KV cache, in place (numpy arrays
+    [kv_heads, capacity, d] and step tensors [T, kv_heads, d] of any dtype).
+
+    Sec. 3.3 evaluates every step token at the position it would hold in the sequence (the current
+    token at 0, candidate token k at 1 + k), so the keys and values the step computed for the
+    accepted tokens ARE their cache rows: the current token goes to row P, the i-th accepted
+    candidate token (i = 1 .. n_out - 1) of candidate `best` to row P + i.  The last emitted token
+    (Algorithm 3's correction or bonus token) has no keys yet.  Returns the new prefix length.
+    """
+    n1 = N - 1
+    assert 1 <= n_out <= N and (n_out == 1 or 0 <= best < G)
+    assert P + n_out <= k_cache.shape[1]
+    for i in range(n_out):
+        row = 0 if i == 0 else 1 + W * n1 + best * n1 + (i - 1)
+        for h in range(k_cache.shape[0]):
+            k_cache[h, P + i, :] = step_k[row, h, :]
+            v_cache[h, P + i, :] = step_v[row, h, :]
+    return P + n_out
