@@ -196,6 +196,34 @@ def main():
     verify_step_bytes = (1 + s.W + s.G * (s.N - 1)) * s.V * 4
     verify_sample_us = float(np.median(sm_ms)) * 1e3
     verify_sample_bytes = (2 + s.G * (s.N - 1)) * s.V * 4   # every row once, one row again for the draw
+    # appending the accepted rows to an in-place cache (la_kv_commit), timed on its own: it follows
+    # the best / n_out that verify_step left on the device
+    cap = P + 64
+    kc_cap = torch.zeros((KV, cap, d), dtype=torch.bfloat16, device="cuda")
+    vc_cap = torch.zeros((KV, cap, d), dtype=torch.bfloat16, device="cuda")
+    kc_cap[:, :P], vc_cap[:, :P] = layers[0]["k_cache"], layers[0]["v_cache"]
+
+    def kv_commit():
+        binding.la_kv_commit(kc_cap, vc_cap, layers[0]["step_k"], layers[0]["step_v"], P, s.W, s.N, s.G, KV, d,
+                             vs_out[2], vs_out[1])
+    kv_commit()
+    run_kc, kc_calls = kv_commit, 1
+    if use_graph:
+        gk = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gk):
+            for _ in range(32):
+                kv_commit()
+        run_kc, kc_calls = gk.replay, 32
+    kc_ms = []
+    for _ in range(reps):
+        e[0].record()
+        run_kc()
+        e[1].record()
+        torch.cuda.synchronize()
+        kc_ms.append(e[0].elapsed_time(e[1]) / kc_calls)
+    kv_commit_us = float(np.median(kc_ms)) * 1e3
+    n_commit = int(vs_out[1].item())
+    kv_commit_bytes = n_commit * KV * d * 2 * 2 * 2      # rows x (K, V) x (read, write)
     abytes = algorithmic_bytes(s)
     aflops = algorithmic_flops(s)
     t_hbm = abytes / (HBM_PEAK_GBS * 1e9)
@@ -233,6 +261,12 @@ def main():
     exact_step = bool(vs_out[0].cpu().numpy()[:n].tolist() == w_out and int(vs_out[2].item()) == w_best and
                       np.array_equal(vs_out[3].cpu().numpy(), w_window) and
                       np.array_equal(vs_out[4].cpu().numpy(), w_len))
+
+    ok_h = np.zeros((KV, cap, d), np.uint16)
+    ov_h = np.zeros((KV, cap, d), np.uint16)
+    ok_h[:, :P], ov_h[:, :P] = host0["k_cache"], host0["v_cache"]
+    orc.kv_commit(ok_h, ov_h, host0["step_k"], host0["step_v"], P, s.W, s.N, s.G, w_best, len(w_out))
+    exact_commit = bool(np.array_equal(binding.bf16_bits(kc_cap), ok_h) and np.array_equal(binding.bf16_bits(vc_cap), ov_h))
 
     w_tokens = orc.verify_sample(*sm_h[:4], float(sm_h[4][0]), 1.0, s.N, s.G, s.V)
     n = int(sm_out[1].item())
@@ -276,13 +310,15 @@ def main():
         "verify_sample": {"us": verify_sample_us, "algorithmic_bytes": verify_sample_bytes,
                           "gbs": verify_sample_bytes / (verify_sample_us * 1e-6) / 1e9,
                           "frac_of_hbm_peak": verify_sample_bytes / (verify_sample_us * 1e-6) / 1e9 / HBM_PEAK_GBS},
+        "kv_commit": {"us": kv_commit_us, "rows": n_commit, "algorithmic_bytes": kv_commit_bytes},
         "attention_tflops": aflops / (attn_us * 1e-6) / 1e12,
         "attention_gbs": abytes / (attn_us * 1e-6) / 1e9,
         "parity": {"attention_max_abs_err_layer0": err, "verify_bit_exact": exact,
-                   "verify_step_bit_exact": exact_step, "verify_sample_equals_oracle": sample_equal},
+                   "verify_step_bit_exact": exact_step, "verify_sample_equals_oracle": sample_equal,
+                   "kv_commit_bit_exact": exact_commit},
     }
     print(json.dumps(line))
-    if err > 2e-2 or not exact or not exact_step:
+    if err > 2e-2 or not exact or not exact_step or not exact_commit:
         print("bench.py: PARITY FAILURE", file=sys.stderr)
         sys.exit(1)
 

@@ -77,6 +77,38 @@ la_status la_step_attention(const void* q, const void* k_cache, const void* v_ca
                             int heads, int kv_heads, int head_dim, void* out, void* stream);
 
 /*
+ * The same step over a cache allocated for more keys than it holds, as a decoding loop keeps
+ * it (rows are appended in place, see la_kv_commit):
+ *   k_cache, v_cache  bf16 [kv_heads][capacity][head_dim]; rows 0..P-1 of every head are the
+ *                     prefix, the rest is never read.  capacity >= P.
+ * Everything else as la_step_attention, which is the case capacity == P.
+ */
+la_status la_step_attention_cap(const void* q, const void* k_cache, const void* v_cache, long long capacity,
+                                const void* step_k, const void* step_v, int P, int W, int N, int G,
+                                int heads, int kv_heads, int head_dim, void* out, void* stream);
+
+/*
+ * Append the tokens a greedy step accepted to the KV cache, on the device, from the result
+ * la_verify_step left there.  The step's keys and values of those rows are already what the
+ * next steps need (Sec. 3.3: candidate token k is evaluated at relative position 1+k, the
+ * position it holds once accepted), so this is a copy:
+ *   cache row P        <- step row 0 (the current token)
+ *   cache row P + i    <- step row 1 + W(N-1) + best(N-1) + (i-1), i = 1 .. n_out-1
+ * The last of the n_out emitted tokens is the next current token; its keys do not exist yet.
+ * Afterwards the prefix holds P + n_out keys.
+ *
+ *   k_cache, v_cache  bf16 [kv_heads][capacity][head_dim], in/out; P + N <= capacity (the
+ *                     count is known only on the device, so room for a full match is required)
+ *   step_k, step_v    bf16 [T][kv_heads][head_dim] of the step just verified
+ *   best, n_out       int32 [1] each, as written by la_verify_step (values outside -1..G-1
+ *                     and 1..N are clamped, never followed out of bounds)
+ *   head_dim: any multiple of 8 up to 1024.
+ */
+la_status la_kv_commit(void* k_cache, void* v_cache, long long capacity, const void* step_k,
+                       const void* step_v, int P, int W, int N, int G, int kv_heads, int head_dim,
+                       const int* best, const int* n_out, void* stream);
+
+/*
  * Greedy verification reduction (Sec. 2 "Guess-And-Verify": accept a draft
  * token while it equals the model's greedy token, stop at the first mismatch;
  * Algorithm 3 runs it over G candidates).

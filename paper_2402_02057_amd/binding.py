@@ -33,6 +33,11 @@ def load():
     i, p = ctypes.c_int, ctypes.c_void_p
     lib.la_step_attention.argtypes = [p, p, p, p, p, i, i, i, i, i, i, i, p, p]
     lib.la_step_attention.restype = i
+    ll = ctypes.c_longlong
+    lib.la_step_attention_cap.argtypes = [p, p, p, ll, p, p, i, i, i, i, i, i, i, p, p]
+    lib.la_step_attention_cap.restype = i
+    lib.la_kv_commit.argtypes = [p, p, ll, p, p, i, i, i, i, i, i, p, p, p]
+    lib.la_kv_commit.restype = i
     lib.la_verify.argtypes = [p, p, i, i, i, p, p, p]
     lib.la_verify.restype = i
     lib.la_verify_step.argtypes = [p, p, p, p, i, i, i, i, p, p, p, p, p, p]
@@ -51,7 +56,7 @@ def load():
     return lib
 
 
-EXPORTS = ("la_step_attention", "la_verify", "la_verify_step", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown",
+EXPORTS = ("la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_verify", "la_verify_step", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown",
            "la_last_error", "la_version")
 
 
@@ -102,6 +107,41 @@ def la_step_attention(q, k_cache, v_cache, step_k, step_v, P, W, N, G, heads, kv
         _ptr(out, bf, (T, heads, head_dim), "out"), _stream(stream))
     _check(rc)
     return out
+
+
+def la_step_attention_cap(q, k_cache, v_cache, step_k, step_v, P, W, N, G, heads, kv_heads, head_dim, out,
+                          stream=None):
+    """la_step_attention over caches [kv_heads, capacity, head_dim] whose first P rows per head are
+    the prefix (capacity is read from the tensors); asynchronous."""
+    T = 1 + (W + G) * (N - 1)
+    bf = torch.bfloat16
+    capacity = int(k_cache.shape[1])
+    rc = load().la_step_attention_cap(
+        _ptr(q, bf, (T, heads, head_dim), "q"),
+        _ptr(k_cache, bf, (kv_heads, capacity, head_dim), "k_cache"),
+        _ptr(v_cache, bf, (kv_heads, capacity, head_dim), "v_cache"), capacity,
+        _ptr(step_k, bf, (T, kv_heads, head_dim), "step_k"),
+        _ptr(step_v, bf, (T, kv_heads, head_dim), "step_v"),
+        P, W, N, G, heads, kv_heads, head_dim,
+        _ptr(out, bf, (T, heads, head_dim), "out"), _stream(stream))
+    _check(rc)
+    return out
+
+
+def la_kv_commit(k_cache, v_cache, step_k, step_v, P, W, N, G, kv_heads, head_dim, best, n_out, stream=None):
+    """Append the rows of the tokens la_verify_step accepted (device-side best, n_out) to the caches
+    [kv_heads, capacity, head_dim] at row P; asynchronous."""
+    T = 1 + (W + G) * (N - 1)
+    bf = torch.bfloat16
+    capacity = int(k_cache.shape[1])
+    rc = load().la_kv_commit(
+        _ptr(k_cache, bf, (kv_heads, capacity, head_dim), "k_cache"),
+        _ptr(v_cache, bf, (kv_heads, capacity, head_dim), "v_cache"), capacity,
+        _ptr(step_k, bf, (T, kv_heads, head_dim), "step_k"),
+        _ptr(step_v, bf, (T, kv_heads, head_dim), "step_v"),
+        P, W, N, G, kv_heads, head_dim,
+        _ptr(best, torch.int32, (1,), "best"), _ptr(n_out, torch.int32, (1,), "n_out"), _stream(stream))
+    _check(rc)
 
 
 def la_verify(logits, cand_tokens, G, N, V, accept_len, accepted, stream=None):

@@ -114,29 +114,75 @@ void free_workspaces()
 
 extern "C" {
 
+namespace {
+
+la_status step_attention_checked(const char* name, const void* q, const void* k_cache, const void* v_cache,
+                                 long long capacity, const void* step_k, const void* step_v, int P, int W,
+                                 int N, int G, int heads, int kv_heads, int head_dim, void* out, void* stream)
+{
+    if (P < 0 || W < 0 || G < 0 || N < 2 || heads < 1 || kv_heads < 1)
+        return la::fail(LA_EINVAL, "%s: need P,W,G >= 0, N >= 2, heads,kv_heads >= 1 "
+                                   "(got P=%d W=%d N=%d G=%d heads=%d kv_heads=%d)",
+                        name, P, W, N, G, heads, kv_heads);
+    if (head_dim != 64 && head_dim != 128)
+        return la::fail(LA_EUNSUPPORTED, "%s: head_dim %d is not 64 or 128", name, head_dim);
+    if (heads % kv_heads != 0)
+        return la::fail(LA_EUNSUPPORTED, "%s: heads %d not a multiple of kv_heads %d", name, heads, kv_heads);
+    const long long T = 1 + (long long)(W + G) * (N - 1);
+    if (T > (1 << 20) || (long long)P > (1ll << 30))
+        return la::fail(LA_EINVAL, "%s: step of %lld rows / prefix %d too large", name, T, P);
+    if (capacity < P || capacity > (1ll << 40))
+        return la::fail(LA_EINVAL, "%s: capacity %lld does not hold the %d prefix keys", name, capacity, P);
+    if (!q || !step_k || !step_v || !out || (P > 0 && (!k_cache || !v_cache)))
+        return la::fail(LA_EINVAL, "%s: null pointer", name);
+    const uintptr_t bits = (uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache |
+                           (uintptr_t)step_k | (uintptr_t)step_v | (uintptr_t)out;
+    if (bits & 15) return la::fail(LA_EINVAL, "%s: buffers must be 16-byte aligned", name);
+    return la::launch_step_attention(q, k_cache, v_cache, capacity, step_k, step_v, P, W, N, G, heads,
+                                     kv_heads, head_dim, out, (hipStream_t)stream);
+}
+
+}  // namespace
+
 la_status la_step_attention(const void* q, const void* k_cache, const void* v_cache,
                             const void* step_k, const void* step_v, int P, int W, int N, int G,
                             int heads, int kv_heads, int head_dim, void* out, void* stream)
 {
-    if (P < 0 || W < 0 || G < 0 || N < 2 || heads < 1 || kv_heads < 1)
-        return la::fail(LA_EINVAL, "la_step_attention: need P,W,G >= 0, N >= 2, heads,kv_heads >= 1 "
-                                   "(got P=%d W=%d N=%d G=%d heads=%d kv_heads=%d)",
-                        P, W, N, G, heads, kv_heads);
-    if (head_dim != 64 && head_dim != 128)
-        return la::fail(LA_EUNSUPPORTED, "la_step_attention: head_dim %d is not 64 or 128", head_dim);
-    if (heads % kv_heads != 0)
-        return la::fail(LA_EUNSUPPORTED, "la_step_attention: heads %d not a multiple of kv_heads %d",
-                        heads, kv_heads);
-    const long long T = 1 + (long long)(W + G) * (N - 1);
-    if (T > (1 << 20) || (long long)P > (1ll << 30))
-        return la::fail(LA_EINVAL, "la_step_attention: step of %lld rows / prefix %d too large", T, P);
-    if (!q || !step_k || !step_v || !out || (P > 0 && (!k_cache || !v_cache)))
-        return la::fail(LA_EINVAL, "la_step_attention: null pointer");
-    const uintptr_t bits = (uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache |
-                           (uintptr_t)step_k | (uintptr_t)step_v | (uintptr_t)out;
-    if (bits & 15) return la::fail(LA_EINVAL, "la_step_attention: buffers must be 16-byte aligned");
-    return la::launch_step_attention(q, k_cache, v_cache, step_k, step_v, P, W, N, G, heads,
-                                     kv_heads, head_dim, out, (hipStream_t)stream);
+    return step_attention_checked("la_step_attention", q, k_cache, v_cache, P, step_k, step_v, P, W, N, G,
+                                  heads, kv_heads, head_dim, out, stream);
+}
+
+la_status la_step_attention_cap(const void* q, const void* k_cache, const void* v_cache, long long capacity,
+                                const void* step_k, const void* step_v, int P, int W, int N, int G,
+                                int heads, int kv_heads, int head_dim, void* out, void* stream)
+{
+    return step_attention_checked("la_step_attention_cap", q, k_cache, v_cache, capacity, step_k, step_v, P,
+                                  W, N, G, heads, kv_heads, head_dim, out, stream);
+}
+
+la_status la_kv_commit(void* k_cache, void* v_cache, long long capacity, const void* step_k,
+                       const void* step_v, int P, int W, int N, int G, int kv_heads, int head_dim,
+                       const int* best, const int* n_out, void* stream)
+{
+    if (P < 0 || W < 0 || G < 0 || N < 2 || kv_heads < 1)
+        return la::fail(LA_EINVAL, "la_kv_commit: need P,W,G >= 0, N >= 2, kv_heads >= 1 "
+                                   "(got P=%d W=%d N=%d G=%d kv_heads=%d)", P, W, N, G, kv_heads);
+    if (head_dim < 8 || head_dim % 8 != 0 || head_dim > 1024)
+        return la::fail(LA_EUNSUPPORTED, "la_kv_commit: head_dim %d is not a multiple of 8 in 8..1024", head_dim);
+    if (1 + (long long)(W + G) * (N - 1) > (1 << 20) || N > 65535)
+        return la::fail(LA_EINVAL, "la_kv_commit: step too large");
+    // up to N rows are appended; the count is only known on the device
+    if (capacity > (1ll << 40) || (long long)P + N > capacity)
+        return la::fail(LA_EINVAL, "la_kv_commit: capacity %lld cannot take N = %d more rows after P = %d",
+                        capacity, N, P);
+    if (!k_cache || !v_cache || !step_k || !step_v || !best || !n_out)
+        return la::fail(LA_EINVAL, "la_kv_commit: null pointer");
+    if (((uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)step_k | (uintptr_t)step_v) & 15)
+        return la::fail(LA_EINVAL, "la_kv_commit: caches and step tensors must be 16-byte aligned");
+    if (((uintptr_t)best | (uintptr_t)n_out) & 3)
+        return la::fail(LA_EINVAL, "la_kv_commit: best and n_out must be 4-byte aligned");
+    return la::launch_kv_commit(k_cache, v_cache, capacity, step_k, step_v, P, W, N, G, kv_heads, head_dim,
+                                best, n_out, (hipStream_t)stream);
 }
 
 la_status la_verify(const float* logits, const int* cand_tokens, int G, int N, int V,
@@ -204,6 +250,6 @@ void la_shutdown(void) { la::free_workspaces(); }
 
 const char* la_last_error(void) { return la::g_error; }
 
-int la_version(void) { return 1002; }
+int la_version(void) { return 1003; }
 
 }  // extern "C"

@@ -65,6 +65,7 @@ struct AttnParams {
     void* partials;     // XS > 1: per workgroup, fragment-layout bf16 accumulators and fp32 (m, l)
     unsigned* tickets;  // XS > 1: one counter per (KV head, row block), zero between calls
     int P, W, N, G, T;
+    long long cache_rows;  // rows between the caches of consecutive KV heads (>= P)
     int heads, kv_heads, group;
     int R;                // T * group query rows per KV head
     int n_prefix_chunks;  // ceil(P / KC)
@@ -429,8 +430,8 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
     }
 
     // This KV head's part of the four key/value tensors (wave-uniform).
-    const unsigned char* const kc_head = reinterpret_cast<const unsigned char*>(p.k_cache) + (size_t)kvh * p.P * C::RBYTES;
-    const unsigned char* const vc_head = reinterpret_cast<const unsigned char*>(p.v_cache) + (size_t)kvh * p.P * C::RBYTES;
+    const unsigned char* const kc_head = reinterpret_cast<const unsigned char*>(p.k_cache) + (size_t)kvh * (size_t)p.cache_rows * C::RBYTES;
+    const unsigned char* const vc_head = reinterpret_cast<const unsigned char*>(p.v_cache) + (size_t)kvh * (size_t)p.cache_rows * C::RBYTES;
     const unsigned char* const sk_head = reinterpret_cast<const unsigned char*>(p.step_k) + (size_t)kvh * C::RBYTES;
     const unsigned char* const sv_head = reinterpret_cast<const unsigned char*>(p.step_v) + (size_t)kvh * C::RBYTES;
     const unsigned step_stride = (unsigned)(p.kv_heads * C::RBYTES);  // step keys are strided by kv_heads
@@ -533,7 +534,11 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
     f32x16 o[C::DB];
     float m_run, l_run;
     const int db0 = KS > 1 ? ks * C::SPW : 0;
-    const int cw = KS > C::KB ? ks / C::KB : 0;  // which of an iteration's chunks this wave takes
+    // Which of an iteration's chunks this wave takes.  Waves w and w + NW/2 (equal key index,
+    // different tiles when RT = 2) share a SIMD: odd tiles take the chunks in rotated order, so
+    // that a last iteration with fewer chunks than CPI leaves one busy wave on every SIMD
+    // instead of two on half of them.
+    const int cw = KS > C::KB ? (ks / C::KB + rt) % C::CPI : 0;
     // after the ticket: 0 not last, 1 last and co-located, 2 recompute (a word of LDS, addressed as such)
     typedef __attribute__((address_space(3))) unsigned lds_u32;
     lds_u32* const s_role = (lds_u32*)(lds + C::ROLE_OFFSET);
@@ -1024,8 +1029,9 @@ size_t step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int
 }
 
 la_status launch_step_attention(const void* q, const void* k_cache, const void* v_cache,
-                                const void* step_k, const void* step_v, int P, int W, int N, int G,
-                                int heads, int kv_heads, int head_dim, void* out, hipStream_t stream)
+                                long long capacity, const void* step_k, const void* step_v, int P, int W,
+                                int N, int G, int heads, int kv_heads, int head_dim, void* out,
+                                hipStream_t stream)
 {
     const int T = 1 + (W + G) * (N - 1);
     const int group = heads / kv_heads;
@@ -1044,6 +1050,7 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
     prm.partials = nullptr;
     prm.tickets = nullptr;
     prm.P = P; prm.W = W; prm.N = N; prm.G = G; prm.T = T;
+    prm.cache_rows = capacity;
     prm.heads = heads; prm.kv_heads = kv_heads; prm.group = group;
     prm.R = T * group;
     prm.n_prefix_chunks = pl.n_prefix_chunks;

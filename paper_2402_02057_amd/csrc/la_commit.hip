@@ -1,0 +1,69 @@
+// Appending the accepted tokens of a step to the KV cache (the step's own keys and values of
+// those rows become prefix rows of the next step: Sec. 3.3 evaluates the candidates at the
+// positions they will hold once accepted, so nothing is recomputed).
+//
+// A copy of at most N rows per KV head, driven by the device-side result of la_verify_step:
+// one workgroup per appended row, 16 bytes per thread and trip.
+#include "la_internal.h"
+
+namespace la {
+namespace {
+
+struct CommitParams {
+    unsigned char* k_cache;
+    unsigned char* v_cache;
+    const unsigned char* step_k;
+    const unsigned char* step_v;
+    const int* best;
+    const int* n_out;
+    long long capacity;   // rows per KV head in the cache
+    int P, W, N, G, kv_heads;
+    int row_bytes;        // head_dim * 2
+};
+
+__global__ __launch_bounds__(256) void kv_commit_kernel(CommitParams p)
+{
+    const int i = blockIdx.x;               // i-th appended row: cache row P + i
+    int n = *p.n_out;
+    n = n < 1 ? 1 : (n > p.N ? p.N : n);    // (a valid result is 1..N; never index past the step)
+    if (i >= n) return;
+    int src = 0;                            // step row it comes from: the current token ...
+    if (i > 0) {                            // ... or token i-1 of the winning candidate
+        int g = *p.best;
+        g = g < 0 ? 0 : (g >= p.G ? p.G - 1 : g);
+        if (p.G == 0) return;               // (cannot happen with n > 1)
+        src = 1 + p.W * (p.N - 1) + g * (p.N - 1) + (i - 1);
+    }
+    const int pieces = p.row_bytes / 16;    // 16-byte pieces per head row
+    for (int x = threadIdx.x; x < p.kv_heads * pieces; x += blockDim.x) {
+        const int h = x / pieces, c = x - h * pieces;
+        const size_t from = ((size_t)src * p.kv_heads + h) * p.row_bytes + (size_t)c * 16;
+        const size_t to = ((size_t)h * (size_t)p.capacity + (size_t)(p.P + i)) * p.row_bytes + (size_t)c * 16;
+        *reinterpret_cast<uint4*>(p.k_cache + to) = *reinterpret_cast<const uint4*>(p.step_k + from);
+        *reinterpret_cast<uint4*>(p.v_cache + to) = *reinterpret_cast<const uint4*>(p.step_v + from);
+    }
+}
+
+}  // namespace
+
+la_status launch_kv_commit(void* k_cache, void* v_cache, long long capacity, const void* step_k,
+                           const void* step_v, int P, int W, int N, int G, int kv_heads, int head_dim,
+                           const int* best, const int* n_out, hipStream_t stream)
+{
+    CommitParams p;
+    p.k_cache = (unsigned char*)k_cache;
+    p.v_cache = (unsigned char*)v_cache;
+    p.step_k = (const unsigned char*)step_k;
+    p.step_v = (const unsigned char*)step_v;
+    p.best = best;
+    p.n_out = n_out;
+    p.capacity = capacity;
+    p.P = P; p.W = W; p.N = N; p.G = G; p.kv_heads = kv_heads;
+    p.row_bytes = head_dim * 2;
+    hipLaunchKernelGGL(kv_commit_kernel, dim3((unsigned)N), dim3(256), 0, stream, p);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(LA_EHIP, "la_kv_commit launch: %s", hipGetErrorString(e));
+    return LA_OK;
+}
+
+}  // namespace la

@@ -2,7 +2,8 @@
 
 Everything per-token runs on the device: the model's forward pass over the step's
 T = 1 + (W + G)(N - 1) tokens (its attention is `la_step_attention`) and the end of the step
-(`la_verify_step`: Algorithm 3 and the window's new tokens).  The host keeps what the paper keeps
+(`la_verify_step`: Algorithm 3 and the window's new tokens; `la_kv_commit`: the accepted tokens'
+keys and values go to the KV cache).  The host keeps what the paper keeps
 on the host: the 2D window of Jacobi iterates (Sec. 3.1) and the n-gram pool (Sec. 3.2).
 
 `model` is any object with
@@ -10,7 +11,11 @@ on the host: the 2D window of Jacobi iterates (Sec. 3.1) and the n-gram pool (Se
     forward_step(tokens, W, N, G)       fp32 device tensor [T, vocab]: the model output at every
                                         row of the step (row order of include/la.h), attending to
                                         its own KV cache as the prefix
-    append(tokens)                      append tokens to the KV cache
+    commit(best, n_out)                 append the accepted tokens of the step just run to the KV
+                                        cache from the device-side result of la_verify_step
+                                        (int32 tensors; `la_kv_commit`), without waiting for it
+    advance(n)                          the host's count of what commit appended
+    append(tokens)                      prefill: append tokens to the KV cache
 `ToyAttentionLM` below is such a model: one attention head over seeded tables, enough to run the
 loop end to end on the GPU and check it against plain greedy decoding.
 
@@ -82,6 +87,7 @@ class LookaheadDecoder:
         cand = torch.tensor(tails, dtype=torch.int32, device=logits.device).view(g, n1) if g else None
         binding.la_verify_step(logits[0], look, cand_logits, cand, W, N, g, V, self._out, self._n_out,
                                self._best, self._new if W else None, None)
+        self.model.commit(self._best, self._n_out)                        # queued behind the verification
         n = int(self._n_out.item())                                       # (synchronises)
         accepted = self._out[:n].tolist()
         new = self._new.tolist() if W else []
@@ -92,7 +98,7 @@ class LookaheadDecoder:
             self.window = self.window[1:] + [[self.random_token(self.seed, self.index + extra, j)
                                               for j in range(W)]]
         self.index += n
-        self.model.append([cur] + accepted[:-1])
+        self.model.advance(n)       # the cache now holds cur and accepted[:-1]
         self.current = accepted[-1]
         self.steps += 1
         return accepted, tokens, int(self._best.item()), new
@@ -138,12 +144,22 @@ class ToyAttentionLM:
         idx = torch.tensor(tokens, dtype=torch.long, device=self.device)
         T, P, d = len(tokens), self.length, wl.TOY_HEAD_DIM
         assert T == 1 + (W + G) * (N - 1)
+        if P + N > self._k_cache.shape[1]:
+            raise ValueError("KV cache full")
         out = torch.empty((T, 1, d), dtype=torch.bfloat16, device=self.device)
-        binding.la_step_attention(self._q[idx].contiguous(), self._k_cache[:, :P] if P else None,
-                                  self._v_cache[:, :P] if P else None, self._k[idx].contiguous(),
-                                  self._v[idx].contiguous(), P, W, N, G, 1, 1, d, out)
+        self._step = (self._k[idx].contiguous(), self._v[idx].contiguous(), W, N, G)
+        binding.la_step_attention_cap(self._q[idx].contiguous(), self._k_cache, self._v_cache, self._step[0],
+                                      self._step[1], P, W, N, G, 1, 1, d, out)
         found = (out[:, 0, 0].float() > 0.5).long()
         return self._logits[idx * 2 + found].contiguous()
+
+    def commit(self, best, n_out):
+        step_k, step_v, W, N, G = self._step
+        binding.la_kv_commit(self._k_cache, self._v_cache, step_k, step_v, self.length, W, N, G, 1,
+                             wl.TOY_HEAD_DIM, best, n_out)
+
+    def advance(self, n):
+        self.length += n
 
 
 def _demo():
