@@ -4,6 +4,8 @@ Test infrastructure only (tests, the smoke check, the benchmark's cpu_baseline l
 bf16 tensors travel as numpy uint16 bit patterns; nothing here touches the GPU library.
 `kv_commit` (appending the accepted tokens to the KV cache) is plain numpy; its pin is that the
 cache after any run of lookahead steps equals the cache of plain autoregressive decoding.
+`gather_pages` / `kv_commit_paged` define what a paged cache stands for (pinned as the inverse of
+a scatter written in the test, and against the packed append).
 """
 import ctypes
 
@@ -200,4 +202,37 @@ def kv_commit(k_cache, v_cache, step_k, step_v, P, W, N, G, best, n_out):
         for h in range(k_cache.shape[0]):
             k_cache[h, P + i, :] = step_k[row, h, :]
             v_cache[h, P + i, :] = step_v[row, h, :]
+    return P + n_out
+
+
+def gather_pages(pages, block_table, P, page_size):
+    """The packed prefix cache [kv_heads, P, d] that a paged cache stands for.
+
+    pages is [n_pages, kv_heads, page_size, d] (any dtype); key t of the sequence lives in page
+    block_table[t // page_size] at slot t % page_size.  Plain loops: this is the definition the
+    paged entry points are checked against (attention over a paged cache = attention over the
+    packed cache it stands for)."""
+    n_pages, kv_heads, ps, d = pages.shape
+    assert ps == page_size
+    out = np.zeros((kv_heads, P, d), dtype=pages.dtype)
+    for t in range(P):
+        page = int(block_table[t // page_size])
+        assert 0 <= page < n_pages
+        for h in range(kv_heads):
+            out[h, t, :] = pages[page, h, t % page_size, :]
+    return out
+
+
+def kv_commit_paged(k_pages, v_pages, block_table, page_size, step_k, step_v, P, W, N, G, best, n_out):
+    """kv_commit for a paged cache, in place: row P + i of the sequence is slot (P + i) % page_size
+    of page block_table[(P + i) // page_size].  Returns the new prefix length."""
+    n1 = N - 1
+    assert 1 <= n_out <= N and (n_out == 1 or 0 <= best < G)
+    for i in range(n_out):
+        row = 0 if i == 0 else 1 + W * n1 + best * n1 + (i - 1)
+        t = P + i
+        page = int(block_table[t // page_size])
+        for h in range(k_pages.shape[1]):
+            k_pages[page, h, t % page_size, :] = step_k[row, h, :]
+            v_pages[page, h, t % page_size, :] = step_v[row, h, :]
     return P + n_out
