@@ -109,6 +109,25 @@ la_status la_kv_commit(void* k_cache, void* v_cache, long long capacity, const v
                        const int* best, const int* n_out, void* stream);
 
 /*
+ * The same step and the same append over a PAGED cache, as a serving system keeps it:
+ *   k_pages, v_pages  bf16 [n_pages][kv_heads][page_size][head_dim]; 16-byte aligned
+ *   block_table       int32 [ceil(P / page_size)] (for the append: ceil((P + N) / page_size)):
+ *                     prefix key t of every KV head sits in page block_table[t / page_size] at
+ *                     slot t % page_size.  Entries outside 0..n_pages-1 are clamped into that
+ *                     range (wrong results, never an access outside the pages).
+ *   page_size         a multiple of 64
+ * The result is that of la_step_attention / la_kv_commit over the packed cache the table
+ * stands for.  Pages the table does not name are never touched.
+ */
+la_status la_step_attention_paged(const void* q, const void* k_pages, const void* v_pages, const int* block_table,
+                                  int page_size, int n_pages, const void* step_k, const void* step_v, int P,
+                                  int W, int N, int G, int heads, int kv_heads, int head_dim, void* out,
+                                  void* stream);
+la_status la_kv_commit_paged(void* k_pages, void* v_pages, const int* block_table, int page_size, int n_pages,
+                             const void* step_k, const void* step_v, int P, int W, int N, int G, int kv_heads,
+                             int head_dim, const int* best, const int* n_out, void* stream);
+
+/*
  * Greedy verification reduction (Sec. 2 "Guess-And-Verify": accept a draft
  * token while it equals the model's greedy token, stop at the first mismatch;
  * Algorithm 3 runs it over G candidates).

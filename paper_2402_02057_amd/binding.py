@@ -38,6 +38,10 @@ def load():
     lib.la_step_attention_cap.restype = i
     lib.la_kv_commit.argtypes = [p, p, ll, p, p, i, i, i, i, i, i, p, p, p]
     lib.la_kv_commit.restype = i
+    lib.la_step_attention_paged.argtypes = [p, p, p, p, i, i, p, p, i, i, i, i, i, i, i, p, p]
+    lib.la_step_attention_paged.restype = i
+    lib.la_kv_commit_paged.argtypes = [p, p, p, i, i, p, p, i, i, i, i, i, i, p, p, p]
+    lib.la_kv_commit_paged.restype = i
     lib.la_verify.argtypes = [p, p, i, i, i, p, p, p]
     lib.la_verify.restype = i
     lib.la_verify_step.argtypes = [p, p, p, p, i, i, i, i, p, p, p, p, p, p]
@@ -56,7 +60,7 @@ def load():
     return lib
 
 
-EXPORTS = ("la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_verify", "la_verify_step", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown",
+EXPORTS = ("la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_verify", "la_verify_step", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown",
            "la_last_error", "la_version")
 
 
@@ -137,6 +141,50 @@ def la_kv_commit(k_cache, v_cache, step_k, step_v, P, W, N, G, kv_heads, head_di
     rc = load().la_kv_commit(
         _ptr(k_cache, bf, (kv_heads, capacity, head_dim), "k_cache"),
         _ptr(v_cache, bf, (kv_heads, capacity, head_dim), "v_cache"), capacity,
+        _ptr(step_k, bf, (T, kv_heads, head_dim), "step_k"),
+        _ptr(step_v, bf, (T, kv_heads, head_dim), "step_v"),
+        P, W, N, G, kv_heads, head_dim,
+        _ptr(best, torch.int32, (1,), "best"), _ptr(n_out, torch.int32, (1,), "n_out"), _stream(stream))
+    _check(rc)
+
+
+def _pages(k_pages, v_pages, block_table, kv_heads, head_dim, rows):
+    n_pages, page_size = int(k_pages.shape[0]), int(k_pages.shape[2])
+    shape = (n_pages, kv_heads, page_size, head_dim)
+    need = (rows + page_size - 1) // page_size
+    if need > 0 and (block_table is None or block_table.numel() < need):
+        raise ValueError("block_table must hold at least %d entries" % need)
+    bt = None if block_table is None else _ptr(block_table, torch.int32, (block_table.numel(),), "block_table",
+                                               allow_empty_null=True)
+    return (_ptr(k_pages, torch.bfloat16, shape, "k_pages"), _ptr(v_pages, torch.bfloat16, shape, "v_pages"), bt,
+            page_size, n_pages)
+
+
+def la_step_attention_paged(q, k_pages, v_pages, block_table, step_k, step_v, P, W, N, G, heads, kv_heads,
+                            head_dim, out, stream=None):
+    """la_step_attention over pages [n_pages, kv_heads, page_size, head_dim] named by the int32
+    block_table (>= ceil(P / page_size) entries); asynchronous."""
+    T = 1 + (W + G) * (N - 1)
+    bf = torch.bfloat16
+    kp, vp, bt, page_size, n_pages = _pages(k_pages, v_pages, block_table, kv_heads, head_dim, P)
+    rc = load().la_step_attention_paged(
+        _ptr(q, bf, (T, heads, head_dim), "q"), kp, vp, bt, page_size, n_pages,
+        _ptr(step_k, bf, (T, kv_heads, head_dim), "step_k"),
+        _ptr(step_v, bf, (T, kv_heads, head_dim), "step_v"),
+        P, W, N, G, heads, kv_heads, head_dim,
+        _ptr(out, bf, (T, heads, head_dim), "out"), _stream(stream))
+    _check(rc)
+    return out
+
+
+def la_kv_commit_paged(k_pages, v_pages, block_table, step_k, step_v, P, W, N, G, kv_heads, head_dim, best,
+                       n_out, stream=None):
+    """la_kv_commit into pages; block_table needs >= ceil((P + N) / page_size) entries; asynchronous."""
+    T = 1 + (W + G) * (N - 1)
+    bf = torch.bfloat16
+    kp, vp, bt, page_size, n_pages = _pages(k_pages, v_pages, block_table, kv_heads, head_dim, P + N)
+    rc = load().la_kv_commit_paged(
+        kp, vp, bt, page_size, n_pages,
         _ptr(step_k, bf, (T, kv_heads, head_dim), "step_k"),
         _ptr(step_v, bf, (T, kv_heads, head_dim), "step_v"),
         P, W, N, G, kv_heads, head_dim,

@@ -116,9 +116,11 @@ extern "C" {
 
 namespace {
 
+// block_table == nullptr: packed caches with `capacity` rows per head; else pages.
 la_status step_attention_checked(const char* name, const void* q, const void* k_cache, const void* v_cache,
-                                 long long capacity, const void* step_k, const void* step_v, int P, int W,
-                                 int N, int G, int heads, int kv_heads, int head_dim, void* out, void* stream)
+                                 long long capacity, const int* block_table, int page_size, int n_pages,
+                                 const void* step_k, const void* step_v, int P, int W, int N, int G, int heads,
+                                 int kv_heads, int head_dim, void* out, void* stream)
 {
     if (P < 0 || W < 0 || G < 0 || N < 2 || heads < 1 || kv_heads < 1)
         return la::fail(LA_EINVAL, "%s: need P,W,G >= 0, N >= 2, heads,kv_heads >= 1 "
@@ -131,15 +133,26 @@ la_status step_attention_checked(const char* name, const void* q, const void* k_
     const long long T = 1 + (long long)(W + G) * (N - 1);
     if (T > (1 << 20) || (long long)P > (1ll << 30))
         return la::fail(LA_EINVAL, "%s: step of %lld rows / prefix %d too large", name, T, P);
-    if (capacity < P || capacity > (1ll << 40))
+    if (!block_table && (capacity < P || capacity > (1ll << 40)))
         return la::fail(LA_EINVAL, "%s: capacity %lld does not hold the %d prefix keys", name, capacity, P);
     if (!q || !step_k || !step_v || !out || (P > 0 && (!k_cache || !v_cache)))
         return la::fail(LA_EINVAL, "%s: null pointer", name);
+    if (((uintptr_t)block_table) & 3) return la::fail(LA_EINVAL, "%s: block_table must be 4-byte aligned", name);
     const uintptr_t bits = (uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache |
                            (uintptr_t)step_k | (uintptr_t)step_v | (uintptr_t)out;
     if (bits & 15) return la::fail(LA_EINVAL, "%s: buffers must be 16-byte aligned", name);
-    return la::launch_step_attention(q, k_cache, v_cache, capacity, step_k, step_v, P, W, N, G, heads,
-                                     kv_heads, head_dim, out, (hipStream_t)stream);
+    return la::launch_step_attention(q, k_cache, v_cache, capacity, block_table, page_size, n_pages, step_k,
+                                     step_v, P, W, N, G, heads, kv_heads, head_dim, out, (hipStream_t)stream);
+}
+
+// page geometry shared by the paged entry points
+la_status check_pages(const char* name, const int* block_table, int page_size, int n_pages, long long rows)
+{
+    if (page_size < 64 || page_size % 64 != 0 || page_size > (1 << 20))
+        return la::fail(LA_EUNSUPPORTED, "%s: page_size %d is not a multiple of 64 in 64..2^20", name, page_size);
+    if (n_pages < 1) return la::fail(LA_EINVAL, "%s: n_pages %d < 1", name, n_pages);
+    if (rows > 0 && !block_table) return la::fail(LA_EINVAL, "%s: block_table is null", name);
+    return LA_OK;
 }
 
 }  // namespace
@@ -148,16 +161,52 @@ la_status la_step_attention(const void* q, const void* k_cache, const void* v_ca
                             const void* step_k, const void* step_v, int P, int W, int N, int G,
                             int heads, int kv_heads, int head_dim, void* out, void* stream)
 {
-    return step_attention_checked("la_step_attention", q, k_cache, v_cache, P, step_k, step_v, P, W, N, G,
-                                  heads, kv_heads, head_dim, out, stream);
+    return step_attention_checked("la_step_attention", q, k_cache, v_cache, P, nullptr, 0, 0, step_k, step_v,
+                                  P, W, N, G, heads, kv_heads, head_dim, out, stream);
 }
 
 la_status la_step_attention_cap(const void* q, const void* k_cache, const void* v_cache, long long capacity,
                                 const void* step_k, const void* step_v, int P, int W, int N, int G,
                                 int heads, int kv_heads, int head_dim, void* out, void* stream)
 {
-    return step_attention_checked("la_step_attention_cap", q, k_cache, v_cache, capacity, step_k, step_v, P,
-                                  W, N, G, heads, kv_heads, head_dim, out, stream);
+    return step_attention_checked("la_step_attention_cap", q, k_cache, v_cache, capacity, nullptr, 0, 0, step_k,
+                                  step_v, P, W, N, G, heads, kv_heads, head_dim, out, stream);
+}
+
+la_status la_step_attention_paged(const void* q, const void* k_pages, const void* v_pages, const int* block_table,
+                                  int page_size, int n_pages, const void* step_k, const void* step_v, int P,
+                                  int W, int N, int G, int heads, int kv_heads, int head_dim, void* out,
+                                  void* stream)
+{
+    const la_status st = check_pages("la_step_attention_paged", block_table, page_size, n_pages, P);
+    if (st != LA_OK) return st;
+    // with an empty prefix the table is never read
+    return step_attention_checked("la_step_attention_paged", q, k_pages, v_pages, 0, P > 0 ? block_table : nullptr,
+                                  page_size, n_pages, step_k, step_v, P, W, N, G, heads, kv_heads, head_dim, out,
+                                  stream);
+}
+
+la_status la_kv_commit_paged(void* k_pages, void* v_pages, const int* block_table, int page_size, int n_pages,
+                             const void* step_k, const void* step_v, int P, int W, int N, int G, int kv_heads,
+                             int head_dim, const int* best, const int* n_out, void* stream)
+{
+    if (P < 0 || W < 0 || G < 0 || N < 2 || kv_heads < 1)
+        return la::fail(LA_EINVAL, "la_kv_commit_paged: need P,W,G >= 0, N >= 2, kv_heads >= 1 "
+                                   "(got P=%d W=%d N=%d G=%d kv_heads=%d)", P, W, N, G, kv_heads);
+    if (head_dim < 8 || head_dim % 8 != 0 || head_dim > 1024)
+        return la::fail(LA_EUNSUPPORTED, "la_kv_commit_paged: head_dim %d is not a multiple of 8 in 8..1024", head_dim);
+    if (1 + (long long)(W + G) * (N - 1) > (1 << 20) || N > 65535 || (long long)P > (1ll << 30))
+        return la::fail(LA_EINVAL, "la_kv_commit_paged: step or prefix too large");
+    const la_status st = check_pages("la_kv_commit_paged", block_table, page_size, n_pages, (long long)P + N);
+    if (st != LA_OK) return st;
+    if (!k_pages || !v_pages || !step_k || !step_v || !best || !n_out)
+        return la::fail(LA_EINVAL, "la_kv_commit_paged: null pointer");
+    if (((uintptr_t)k_pages | (uintptr_t)v_pages | (uintptr_t)step_k | (uintptr_t)step_v) & 15)
+        return la::fail(LA_EINVAL, "la_kv_commit_paged: pages and step tensors must be 16-byte aligned");
+    if (((uintptr_t)best | (uintptr_t)n_out | (uintptr_t)block_table) & 3)
+        return la::fail(LA_EINVAL, "la_kv_commit_paged: best, n_out and block_table must be 4-byte aligned");
+    return la::launch_kv_commit(k_pages, v_pages, 0, block_table, page_size, n_pages, step_k, step_v, P, W, N, G,
+                                kv_heads, head_dim, best, n_out, (hipStream_t)stream);
 }
 
 la_status la_kv_commit(void* k_cache, void* v_cache, long long capacity, const void* step_k,
@@ -181,8 +230,8 @@ la_status la_kv_commit(void* k_cache, void* v_cache, long long capacity, const v
         return la::fail(LA_EINVAL, "la_kv_commit: caches and step tensors must be 16-byte aligned");
     if (((uintptr_t)best | (uintptr_t)n_out) & 3)
         return la::fail(LA_EINVAL, "la_kv_commit: best and n_out must be 4-byte aligned");
-    return la::launch_kv_commit(k_cache, v_cache, capacity, step_k, step_v, P, W, N, G, kv_heads, head_dim,
-                                best, n_out, (hipStream_t)stream);
+    return la::launch_kv_commit(k_cache, v_cache, capacity, nullptr, 0, 0, step_k, step_v, P, W, N, G, kv_heads,
+                                head_dim, best, n_out, (hipStream_t)stream);
 }
 
 la_status la_verify(const float* logits, const int* cand_tokens, int G, int N, int V,
@@ -250,6 +299,6 @@ void la_shutdown(void) { la::free_workspaces(); }
 
 const char* la_last_error(void) { return la::g_error; }
 
-int la_version(void) { return 1003; }
+int la_version(void) { return 1004; }
 
 }  // extern "C"

@@ -65,7 +65,15 @@ struct AttnParams {
     void* partials;     // XS > 1: per workgroup, fragment-layout bf16 accumulators and fp32 (m, l)
     unsigned* tickets;  // XS > 1: one counter per (KV head, row block), zero between calls
     int P, W, N, G, T;
-    long long cache_rows;  // rows between the caches of consecutive KV heads (>= P)
+    long long cache_rows;  // rows between the caches of consecutive KV heads (>= P; paged: the page size)
+    // Paged cache (block_table != nullptr): k_cache / v_cache are [n_pages][kv_heads][page][head_dim]
+    // and prefix key t sits in page block_table[t / page] at slot t % page.
+    const int* block_table;
+    long long page_bytes;  // bytes of one page (all KV heads)
+    int page_chunks;       // chunks per page
+    int n_pages;           // table entries are clamped to 0 .. n_pages-1
+    int table_last;        // last valid index of block_table
+    float inv_page_chunks;
     int heads, kv_heads, group;
     int R;                // T * group query rows per KV head
     int n_prefix_chunks;  // ceil(P / KC)
@@ -374,7 +382,9 @@ __device__ __forceinline__ void merge_key_splits(const AttnParams& p, unsigned c
             }
 }
 
-template <int D, int RT, int KS, int KC, int NSTAGE>
+// PAGED: the prefix cache is reached through a block table (a kernel of its own: the walk then
+// needs a dozen more scalar registers, which the packed kernel would otherwise pay for in spills).
+template <int D, int RT, int KS, int KC, int NSTAGE, bool PAGED = false>
 __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnParams p)
 {
     using C = Cfg<D, RT, KS, KC, NSTAGE>;
@@ -446,12 +456,54 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
     unsigned iss_stride;          // bytes between rows (the host checks it is below 2^24)
     int iss_prefix_left;          // prefix chunks still to request before the step keys start
     unsigned iss_stage;           // LDS offset of the stage the next chunk goes to
+    // paged cache: chunks left in the current page, its index in the block table, and a queue of
+    // the raw entries of the next four pages.  The entries are fetched with scalar loads written
+    // as assembly, each batch followed by its own wait: left to the compiler they become vector
+    // loads (it cannot prove that the kernel's stores leave the table alone), whose wait is a wait
+    // for every direct-to-LDS load in flight.  The queue is refilled at the end of an iteration,
+    // where no LDS read is pending and the wave is about to wait for its chunks anyway; a page
+    // crossing in between only moves registers.  Entries are clamped when used.
+    const int* const table = PAGED ? p.block_table : nullptr;
+    constexpr int kNoPage = 1 << 30;  // page countdown that never reaches zero: packed cache, step keys
+    int iss_page_left = kNoPage, iss_page = 0;
+    int iss_ent0 = 0, iss_ent1 = 0, iss_ent2 = 0, iss_ent3 = 0;  // entries of pages iss_page+1 .. iss_page+iss_q
+    int iss_q = 0;
+    auto table_offset = [&](int i) {  // byte offset of entry i, never past the end of the table
+        return (unsigned)__builtin_amdgcn_readfirstlane(min(i, p.table_last) * 4);
+    };
+    auto page_offset = [&](int raw) {  // clamped: a bad table can give wrong results, not a fault
+        return (size_t)min(max(raw, 0), p.n_pages - 1) * (size_t)p.page_bytes;
+    };
+    auto refill_entries = [&]() {
+        asm volatile("s_load_dword %0, %4, %5\n\ts_load_dword %1, %4, %6\n\ts_load_dword %2, %4, %7\n\t"
+                     "s_load_dword %3, %4, %8\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&s"(iss_ent0), "=&s"(iss_ent1), "=&s"(iss_ent2), "=&s"(iss_ent3)
+                     : "s"(table), "s"(table_offset(iss_page + 1)), "s"(table_offset(iss_page + 2)),
+                       "s"(table_offset(iss_page + 3)), "s"(table_offset(iss_page + 4))
+                     : "memory");
+        iss_q = 4;
+    };
     auto seek = [&](int c) {      // next chunk to request := chunk c, into stage 0
+        iss_page_left = kNoPage;
         if (c < n_prefix_chunks) {
-            const int key0 = c * KC;
-            iss_k = kc_head + (size_t)key0 * C::RBYTES;
-            iss_v = vc_head + (size_t)key0 * C::RBYTES;
+            int key0 = c * KC;
             iss_rows = n_P - key0;
+            size_t page_off = 0;
+            if (table) {
+                iss_page = div_small(c, p.inv_page_chunks);
+                const int within = c - iss_page * p.page_chunks;
+                int first;
+                asm volatile("s_load_dword %0, %1, %2\n\ts_waitcnt lgkmcnt(0)"
+                             : "=&s"(first)
+                             : "s"(table), "s"(table_offset(iss_page))
+                             : "memory");
+                refill_entries();
+                page_off = page_offset(first);
+                iss_page_left = p.page_chunks - within;
+                key0 = within * KC;
+            }
+            iss_k = kc_head + page_off + (size_t)key0 * C::RBYTES;
+            iss_v = vc_head + page_off + (size_t)key0 * C::RBYTES;
             iss_stride = C::RBYTES;
             iss_prefix_left = n_prefix_chunks - c;
         } else {
@@ -482,6 +534,18 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
             iss_v = sv_head;
             iss_rows = n_T;
             iss_stride = step_stride;
+            iss_page_left = kNoPage;
+        } else if (--iss_page_left == 0) {  // paged cache: the next chunk starts the next page
+            if (iss_q == 0) refill_entries();  // (only when more chunks are requested in a row than the queue holds)
+            ++iss_page;
+            const size_t page_off = page_offset(iss_ent0);
+            iss_k = kc_head + page_off;
+            iss_v = vc_head + page_off;
+            iss_ent0 = iss_ent1;
+            iss_ent1 = iss_ent2;
+            iss_ent2 = iss_ent3;
+            --iss_q;
+            iss_page_left = p.page_chunks;
         } else {
             iss_k += (size_t)KC * iss_stride;
             iss_v += (size_t)KC * iss_stride;
@@ -510,9 +574,13 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
     seek(c_begin);
     auto issue_first = [&](bool with_q) {
         const int upfront = min(n_my, p.pre);
+        // (paged cache: Q does not depend on the block table, so it goes first and the wait for
+        // the table's first entries overlaps its issue)
+        const bool q_first = table != nullptr;
+        if (q_first && with_q) issue_q();
 #pragma unroll
         for (int s = 0; s < NSTAGE; ++s) {
-            if (s == C::CPI && with_q) issue_q();
+            if (s == C::CPI && with_q && !q_first) issue_q();
             if (s < upfront) issue_next();
         }
         issued = upfront;
@@ -743,6 +811,7 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
 #pragma unroll
             for (int j = 0; j < C::CPI; ++j)
                 if (slots_left > 0) issue_slot();
+            if (table && iss_q < 4) refill_entries();
             cons_c += C::CPI;
             cons_stage += C::CPI * C::STAGE_BYTES;
             if (cons_stage >= (unsigned)(NSTAGE * C::STAGE_BYTES)) cons_stage -= NSTAGE * C::STAGE_BYTES;
@@ -951,7 +1020,15 @@ bool plan_supported(int D, int RT, int KS, int NS, int KC)
     return (RT == 1 && KS == 2) || (RT == 2 && KS == 2) || (RT == 4 && KS == 1);
 }
 
-Plan make_plan(int P, int T, int group, int kv_heads, int D)
+// Plans compiled for a paged cache: the ones the heuristic below picks.
+bool paged_plan_supported(int D, int RT, int KS, int NS, int KC)
+{
+    if (KC != 64 || NS != 4) return false;
+    if (D == 128) return (RT == 2 && KS == 4) || (RT == 4 && KS == 2) || (RT == 1 && KS == 2) || (RT == 2 && KS == 2);
+    return (RT == 1 && KS == 2) || (RT == 2 && KS == 2);
+}
+
+Plan make_plan(int P, int T, int group, int kv_heads, int D, bool paged = false)
 {
     Plan pl;
     const int R = T * group;
@@ -973,7 +1050,7 @@ Plan make_plan(int P, int T, int group, int kv_heads, int D)
     if (const char* env = getenv("LA_ATTN_PLAN")) {
         int b = 0, c = 0, d = 0, e = 0, f = 0, g = 0;
         if (sscanf(env, "%d,%d,%d,%d,%d,%d", &b, &c, &d, &e, &f, &g) >= 5 &&
-            plan_supported(D, b, c, e, f)) {
+            plan_supported(D, b, c, e, f) && (!paged || paged_plan_supported(D, b, c, e, f))) {
             pl.RT = b; pl.KS = c; pl.XS = d; pl.NS = e; pl.KC = f;
             pl.PRE = g;
         }
@@ -997,11 +1074,11 @@ Plan make_plan(int P, int T, int group, int kv_heads, int D)
     return pl;
 }
 
-template <int D, int RT, int KS, int NSTAGE, int KC = 64>
+template <int D, int RT, int KS, int NSTAGE, int KC = 64, bool PAGED = false>
 la_status launch_cfg(const AttnParams& prm, hipStream_t stream)
 {
     using C = Cfg<D, RT, KS, KC, NSTAGE>;
-    auto kern = step_attention_kernel<D, RT, KS, KC, NSTAGE>;
+    auto kern = step_attention_kernel<D, RT, KS, KC, NSTAGE, PAGED>;
     static bool attr_set[16] = {false};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return fail(LA_EHIP, "hipGetDevice failed");
@@ -1029,16 +1106,16 @@ size_t step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int
 }
 
 la_status launch_step_attention(const void* q, const void* k_cache, const void* v_cache,
-                                long long capacity, const void* step_k, const void* step_v, int P, int W,
-                                int N, int G, int heads, int kv_heads, int head_dim, void* out,
-                                hipStream_t stream)
+                                long long capacity, const int* block_table, int page_size, int n_pages,
+                                const void* step_k, const void* step_v, int P, int W, int N, int G,
+                                int heads, int kv_heads, int head_dim, void* out, hipStream_t stream)
 {
     const int T = 1 + (W + G) * (N - 1);
     const int group = heads / kv_heads;
     if ((long long)T * group >= (1 << 21) || (long long)T * heads * head_dim * 2 >= (1ll << 31) ||
         (long long)kv_heads * head_dim * 2 >= (1 << 24))
         return fail(LA_EUNSUPPORTED, "la_step_attention: step too large (T=%d, heads=%d)", T, heads);
-    const Plan pl = make_plan(P, T, group, kv_heads, head_dim);
+    const Plan pl = make_plan(P, T, group, kv_heads, head_dim, block_table != nullptr);
 
     AttnParams prm;
     prm.q = (const __bf16*)q;
@@ -1050,7 +1127,16 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
     prm.partials = nullptr;
     prm.tickets = nullptr;
     prm.P = P; prm.W = W; prm.N = N; prm.G = G; prm.T = T;
-    prm.cache_rows = capacity;
+    if (block_table && (pl.n_prefix_chunks >= (1 << 21) || page_size % pl.KC != 0))
+        return fail(LA_EUNSUPPORTED, "la_step_attention_paged: prefix of %d keys / page of %d not supported", P, page_size);
+    prm.cache_rows = block_table ? page_size : capacity;
+    prm.block_table = block_table;
+    prm.page_bytes = (long long)kv_heads * page_size * head_dim * 2;
+    prm.page_chunks = block_table ? page_size / pl.KC : 1;
+    prm.n_pages = n_pages;
+    prm.table_last = block_table ? (P + page_size - 1) / page_size - 1 : 0;
+    if (prm.table_last < 0) prm.table_last = 0;
+    prm.inv_page_chunks = 1.0f / (float)prm.page_chunks;
     prm.heads = heads; prm.kv_heads = kv_heads; prm.group = group;
     prm.R = T * group;
     prm.n_prefix_chunks = pl.n_prefix_chunks;
@@ -1093,6 +1179,19 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
         if (!prm.partials) return LA_ENOMEM;
     }
 
+    if (block_table) {
+        if (!paged_plan_supported(head_dim, pl.RT, pl.KS, pl.NS, pl.KC))
+            return fail(LA_EUNSUPPORTED, "la_step_attention_paged: no kernel for head_dim=%d plan (%d,%d,%d)",
+                        head_dim, pl.RT, pl.KS, pl.NS);
+        if (head_dim == 128) {
+            if (pl.KS == 4) return launch_cfg<128, 2, 4, 4, 64, true>(prm, stream);
+            if (pl.RT == 4) return launch_cfg<128, 4, 2, 4, 64, true>(prm, stream);
+            if (pl.RT == 1) return launch_cfg<128, 1, 2, 4, 64, true>(prm, stream);
+            return launch_cfg<128, 2, 2, 4, 64, true>(prm, stream);
+        }
+        if (pl.RT == 1) return launch_cfg<64, 1, 2, 4, 64, true>(prm, stream);
+        return launch_cfg<64, 2, 2, 4, 64, true>(prm, stream);
+    }
     if (pl.KC == 32) return launch_cfg<128, 2, 2, 9, 32>(prm, stream);
     if (pl.KS == 4) return launch_cfg<128, 2, 4, 4>(prm, stream);
     if (pl.RT == 4 && pl.KS == 2) return launch_cfg<128, 4, 2, 4>(prm, stream);

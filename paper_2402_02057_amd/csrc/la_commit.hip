@@ -17,6 +17,8 @@ struct CommitParams {
     const int* best;
     const int* n_out;
     long long capacity;   // rows per KV head in the cache
+    const int* block_table;  // paged cache (else nullptr): [n_pages][kv_heads][page_size][head_dim]
+    int page_size, n_pages;
     int P, W, N, G, kv_heads;
     int row_bytes;        // head_dim * 2
 };
@@ -38,7 +40,16 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(CommitParams p)
     for (int x = threadIdx.x; x < p.kv_heads * pieces; x += blockDim.x) {
         const int h = x / pieces, c = x - h * pieces;
         const size_t from = ((size_t)src * p.kv_heads + h) * p.row_bytes + (size_t)c * 16;
-        const size_t to = ((size_t)h * (size_t)p.capacity + (size_t)(p.P + i)) * p.row_bytes + (size_t)c * 16;
+        size_t to_row;
+        if (p.block_table) {   // (the host checked that the table covers P + N rows; entries are clamped)
+            const int t = p.P + i;
+            int page = p.block_table[t / p.page_size];
+            page = page < 0 ? 0 : (page >= p.n_pages ? p.n_pages - 1 : page);
+            to_row = ((size_t)page * p.kv_heads + h) * (size_t)p.page_size + (size_t)(t % p.page_size);
+        } else {
+            to_row = (size_t)h * (size_t)p.capacity + (size_t)(p.P + i);
+        }
+        const size_t to = to_row * p.row_bytes + (size_t)c * 16;
         *reinterpret_cast<uint4*>(p.k_cache + to) = *reinterpret_cast<const uint4*>(p.step_k + from);
         *reinterpret_cast<uint4*>(p.v_cache + to) = *reinterpret_cast<const uint4*>(p.step_v + from);
     }
@@ -46,9 +57,10 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(CommitParams p)
 
 }  // namespace
 
-la_status launch_kv_commit(void* k_cache, void* v_cache, long long capacity, const void* step_k,
-                           const void* step_v, int P, int W, int N, int G, int kv_heads, int head_dim,
-                           const int* best, const int* n_out, hipStream_t stream)
+la_status launch_kv_commit(void* k_cache, void* v_cache, long long capacity, const int* block_table,
+                           int page_size, int n_pages, const void* step_k, const void* step_v, int P, int W,
+                           int N, int G, int kv_heads, int head_dim, const int* best, const int* n_out,
+                           hipStream_t stream)
 {
     CommitParams p;
     p.k_cache = (unsigned char*)k_cache;
@@ -58,6 +70,9 @@ la_status launch_kv_commit(void* k_cache, void* v_cache, long long capacity, con
     p.best = best;
     p.n_out = n_out;
     p.capacity = capacity;
+    p.block_table = block_table;
+    p.page_size = page_size;
+    p.n_pages = n_pages;
     p.P = P; p.W = W; p.N = N; p.G = G; p.kv_heads = kv_heads;
     p.row_bytes = head_dim * 2;
     hipLaunchKernelGGL(kv_commit_kernel, dim3((unsigned)N), dim3(256), 0, stream, p);
