@@ -1160,6 +1160,10 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
     // second iteration waiting.
     const int kb = pl.KC / 32, cpi = pl.KS > kb ? pl.KS / kb : 1;  // chunks per iteration
     prm.pre = (pl.PRE >= cpi && pl.PRE <= pl.NS) ? pl.PRE : (cpi + 1 < pl.NS ? cpi + 1 : pl.NS);
+    // Long walks with one chunk per iteration (the 128-row plan): the start-up cost is amortised
+    // and a full ring keeps three chunks in flight instead of two (measured 6-8 % at 50 chunks
+    // per workgroup, a loss at 8).
+    if (pl.PRE == 0 && cpi == 1 && prm.chunks_lo >= 16) prm.pre = pl.NS;
     // testing hook: exercise the path taken when a split group is not on one XCD
     const char* fr = getenv("LA_FORCE_RECOMPUTE");
     prm.force_recompute = (fr && fr[0] == '1') ? 1 : 0;

@@ -113,9 +113,11 @@ class LookaheadDecoder:
 class ToyAttentionLM:
     """One attention head over the seeded tables of workloads.toy_lm_tables: a position's output
     depends on its token and on whether the token it looks for is among the positions it may see,
-    which the head finds out with `la_step_attention` (head_dim 64)."""
+    which the head finds out with `la_step_attention` (head_dim 64).  The KV cache is kept in place
+    (`la_step_attention_cap` / `la_kv_commit`) or, with page_size, in pages named by a shuffled
+    block table (`la_step_attention_paged` / `la_kv_commit_paged`)."""
 
-    def __init__(self, seed=0, max_len=8192, device="cuda"):
+    def __init__(self, seed=0, max_len=8192, device="cuda", page_size=None):
         t = wl.toy_lm_tables(seed)
         self.vocab = wl.TOY_VOCAB
         d = wl.TOY_HEAD_DIM
@@ -124,8 +126,18 @@ class ToyAttentionLM:
             return torch.from_numpy(x).to(device).to(torch.bfloat16).view(self.vocab, 1, d)
         self._q, self._k, self._v = table(t["q"]), table(t["k"]), table(t["v"])
         self._logits = torch.from_numpy(t["logits"]).to(device)
-        self._k_cache = torch.zeros((1, max_len, d), dtype=torch.bfloat16, device=device)
-        self._v_cache = torch.zeros((1, max_len, d), dtype=torch.bfloat16, device=device)
+        self.page_size = page_size
+        if page_size:
+            n_pages = (max_len + page_size - 1) // page_size
+            self.capacity = n_pages * page_size
+            self._k_cache = torch.zeros((n_pages, 1, page_size, d), dtype=torch.bfloat16, device=device)
+            self._v_cache = torch.zeros_like(self._k_cache)
+            gen = torch.Generator().manual_seed(seed)
+            self.block_table = torch.randperm(n_pages, generator=gen).to(torch.int32).to(device)
+        else:
+            self.capacity = max_len
+            self._k_cache = torch.zeros((1, max_len, d), dtype=torch.bfloat16, device=device)
+            self._v_cache = torch.zeros((1, max_len, d), dtype=torch.bfloat16, device=device)
         self.length = 0
         self.device = device
 
@@ -134,29 +146,43 @@ class ToyAttentionLM:
             return
         idx = torch.tensor(tokens, dtype=torch.long, device=self.device)
         n = len(tokens)
-        if self.length + n > self._k_cache.shape[1]:
+        if self.length + n > self.capacity:
             raise ValueError("KV cache full")
-        self._k_cache[0, self.length:self.length + n] = self._k[idx, 0]
-        self._v_cache[0, self.length:self.length + n] = self._v[idx, 0]
+        if self.page_size:
+            pos = torch.arange(self.length, self.length + n, device=self.device)
+            page = self.block_table[pos // self.page_size].long()
+            self._k_cache[page, 0, pos % self.page_size] = self._k[idx, 0]
+            self._v_cache[page, 0, pos % self.page_size] = self._v[idx, 0]
+        else:
+            self._k_cache[0, self.length:self.length + n] = self._k[idx, 0]
+            self._v_cache[0, self.length:self.length + n] = self._v[idx, 0]
         self.length += n
 
     def forward_step(self, tokens, W, N, G):
         idx = torch.tensor(tokens, dtype=torch.long, device=self.device)
         T, P, d = len(tokens), self.length, wl.TOY_HEAD_DIM
         assert T == 1 + (W + G) * (N - 1)
-        if P + N > self._k_cache.shape[1]:
+        if P + N > self.capacity:
             raise ValueError("KV cache full")
         out = torch.empty((T, 1, d), dtype=torch.bfloat16, device=self.device)
         self._step = (self._k[idx].contiguous(), self._v[idx].contiguous(), W, N, G)
-        binding.la_step_attention_cap(self._q[idx].contiguous(), self._k_cache, self._v_cache, self._step[0],
-                                      self._step[1], P, W, N, G, 1, 1, d, out)
+        if self.page_size:
+            binding.la_step_attention_paged(self._q[idx].contiguous(), self._k_cache, self._v_cache,
+                                            self.block_table, self._step[0], self._step[1], P, W, N, G, 1, 1, d, out)
+        else:
+            binding.la_step_attention_cap(self._q[idx].contiguous(), self._k_cache, self._v_cache, self._step[0],
+                                          self._step[1], P, W, N, G, 1, 1, d, out)
         found = (out[:, 0, 0].float() > 0.5).long()
         return self._logits[idx * 2 + found].contiguous()
 
     def commit(self, best, n_out):
         step_k, step_v, W, N, G = self._step
-        binding.la_kv_commit(self._k_cache, self._v_cache, step_k, step_v, self.length, W, N, G, 1,
-                             wl.TOY_HEAD_DIM, best, n_out)
+        if self.page_size:
+            binding.la_kv_commit_paged(self._k_cache, self._v_cache, self.block_table, step_k, step_v, self.length,
+                                       W, N, G, 1, wl.TOY_HEAD_DIM, best, n_out)
+        else:
+            binding.la_kv_commit(self._k_cache, self._v_cache, step_k, step_v, self.length, W, N, G, 1,
+                                 wl.TOY_HEAD_DIM, best, n_out)
 
     def advance(self, n):
         self.length += n

@@ -66,3 +66,16 @@ def test_prompt_as_reference_matches_the_oracle(W, N, G):
         assert (tokens, accepted, best, new) == (rec["tokens"], rec["accepted"], rec["best"], rec["window"]), step
         got.extend(accepted)
     assert got[:60] == want == ref.greedy_decode(cpu, prompt, 60) and dec.steps == want_steps
+
+
+@pytest.mark.parametrize("page_size", [64, 128])
+def test_loop_over_a_paged_cache(page_size):
+    """The same run with the KV cache in shuffled pages: the paged step and the paged append must
+    leave the sequence untouched while the prefix grows across many page boundaries."""
+    seed = 4
+    prompt = [0, 7, 2, 7]
+    dec = lookahead.LookaheadDecoder(lookahead.ToyAttentionLM(seed, max_len=2048, page_size=page_size), prompt, 6, 4, 6,
+                                     seed=seed)
+    got = dec.generate(700)
+    assert got == ref.greedy_decode(ref.ToyModel(seed), prompt, 700)
+    assert 700 / dec.steps > 1.5
