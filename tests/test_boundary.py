@@ -59,6 +59,29 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
     assert b"temperature" in lib.la_last_error()
 
 
+def test_cache_forms_report_argument_errors_without_a_gpu(lib):
+    A = 4096    # any aligned non-null value: nothing is dereferenced before validation ends
+    # in-place cache: capacity below the prefix, and no room for N more rows
+    rc = lib.la_step_attention_cap(A, A, A, 10, A, A, 11, 1, 3, 1, 4, 4, 128, A, None)
+    assert rc == -1 and b"capacity" in lib.la_last_error()
+    rc = lib.la_kv_commit(A, A, 12, A, A, 10, 1, 3, 1, 4, 128, A, A, None)
+    assert rc == -1 and b"capacity" in lib.la_last_error()
+    assert lib.la_kv_commit(A, A, 64, A, A, 10, 1, 1, 1, 4, 128, A, A, None) == -1      # N < 2
+    assert lib.la_kv_commit(A, A, 64, A, A, 10, 1, 3, 1, 4, 100, A, A, None) == -2      # head_dim % 8
+    assert lib.la_kv_commit(A, A, 64, A, A, 10, 1, 3, 1, 4, 128, None, A, None) == -1   # best is null
+    assert lib.la_kv_commit(A, A + 8, 64, A, A, 10, 1, 3, 1, 4, 128, A, A, None) == -1  # misaligned cache
+    # paged cache: page size, page count, table
+    rc = lib.la_step_attention_paged(A, A, A, A, 96, 4, A, A, 10, 1, 3, 1, 4, 4, 128, A, None)
+    assert rc == -2 and b"page_size" in lib.la_last_error()
+    rc = lib.la_step_attention_paged(A, A, A, A, 64, 0, A, A, 10, 1, 3, 1, 4, 4, 128, A, None)
+    assert rc == -1 and b"n_pages" in lib.la_last_error()
+    rc = lib.la_step_attention_paged(A, A, A, None, 64, 4, A, A, 10, 1, 3, 1, 4, 4, 128, A, None)
+    assert rc == -1 and b"block_table" in lib.la_last_error()
+    rc = lib.la_kv_commit_paged(A, A, None, 64, 4, A, A, 0, 1, 3, 1, 4, 128, A, A, None)
+    assert rc == -1 and b"block_table" in lib.la_last_error()      # the append always reads the table
+    assert lib.la_kv_commit_paged(A, A, A, 48, 4, A, A, 0, 1, 3, 1, 4, 128, A, A, None) == -2
+
+
 def test_workspace_query(lib):
     assert binding.la_step_attention_workspace_bytes(1024, 15, 5, 15, 32, 32, 128) > 0
     assert binding.la_step_attention_workspace_bytes(0, 0, 2, 0, 1, 1, 128) == 0
