@@ -28,7 +28,7 @@ LAYERS = {"llama2-7b": 32, "llama2-13b": 40, "llama2-70b-gqa": 80}
 # by the same counter's reading for a 64 MiB copy): see profiles/attention_verify_<workload>.md.
 # (FETCH_SIZE reads half the bytes of a plain copy on this part, WRITE_SIZE all of them.)
 MEASURED_TRAFFIC_BYTES = {
-    "llama2-7b": int((11734.1 * 65536.0 / 32786.4 + 5328.4) * 1024),
+    "llama2-7b": int((11726.0 * 65536.0 / 32782.9 + 5328.4) * 1024),
     "llama2-13b": int((23519.9 * 65536.0 / 32786.4 + 3879.3) * 1024),
     "llama2-70b-gqa": int((10842.2 * 65536.0 / 32783.2 + 5000.5) * 1024),
 }
