@@ -52,11 +52,16 @@ def greedy_decode(model, prompt, n_tokens):
     return out
 
 
-def lookahead_decode(model, prompt, W, N, G, n_tokens, seed=0, prompt_as_reference=False):
+def lookahead_decode(model, prompt, W, N, G, n_tokens, seed=0, prompt_as_reference=False, temperature=None):
     """(tokens, steps, trace): Algorithm 2 with greedy verification until n_tokens are out.
 
     trace is one record per step: the step's tokens in row order, the accepted tokens, the index
     of the winning candidate and the new window level, for step-by-step comparison.
+    With a temperature the verification branch samples (Algorithm 4) while the lookahead branch
+    stays greedy, as Sec. 3.2 prescribes: how the candidates were made does not matter to the
+    output distribution.  The uniform draws come from the counter-based generator, indexed by the
+    step and by (position, order of examination); `best` is then the first candidate that starts
+    with the accepted tokens (-1 if none was accepted).
     With prompt_as_reference the pool starts with every n-gram of the prompt (the augmentation of
     the ablation study, Sec. 5.4): candidates may come from anywhere, the output cannot change.
     """
@@ -91,7 +96,17 @@ def lookahead_decode(model, prompt, W, N, G, n_tokens, seed=0, prompt_as_referen
         for g, tail in enumerate(tails):
             for k in range(n1):
                 cnd[g, k] = model.logits(tail[k], prefix_set | set(tail[:k + 1]))
-        accepted, best, new, _ = orc.verify_step(logits_cur, look, cnd, cand, W, N, len(tails), V)
+        if temperature is None:
+            accepted, best, new, _ = orc.verify_step(logits_cur, look, cnd, cand, W, N, len(tails), V)
+        else:
+            g = len(tails)
+            _, _, new, _ = orc.verify_step(logits_cur, look, cnd[:0], cand[:0], W, N, 0, V)   # window: greedy
+            u_test = np.array([wl.uniform_draw(seed, steps, i * g + j) for i in range(n1) for j in range(g)],
+                              dtype=np.float32).reshape(n1, g)
+            u_final = wl.uniform_draw(seed, steps, 1 << 20)
+            accepted = orc.verify_sample(logits_cur, cnd, cand, u_test, u_final, temperature, N, g, V)
+            k = len(accepted) - 1
+            best = next((i for i, tail in enumerate(tails) if list(tail[:k]) == accepted[:k]), -1) if k else -1
         step_tokens = [cur] + [t for level in window for t in level] + [t for tail in tails for t in tail]
         trace.append({"tokens": step_tokens, "accepted": list(accepted), "best": best, "window": new.tolist()})
         # ---- pool update: one n-gram per column

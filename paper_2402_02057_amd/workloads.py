@@ -259,3 +259,15 @@ def window_random_token(seed, step, column):
     h = (h * 0xD6E8FEB86659FD93) % (1 << 64)
     h ^= h >> 29
     return 1 + h % (TOY_VOCAB - 1)
+
+
+def uniform_draw(seed, step, index):
+    """The uniform draws of sampling verification inside a decoding loop, as a counter-based
+    generator (every implementation of the loop makes the same ones): a float32 in [0, 1)."""
+    h = (seed * 0xD1342543DE82EF95 + step * 0x9E3779B97F4A7C15 + index * 0xC2B2AE3D27D4EB4F + 0x165667B19E3779F9) % (1 << 64)
+    h ^= h >> 32
+    h = (h * 0xD6E8FEB86659FD93) % (1 << 64)
+    h ^= h >> 32
+    h = (h * 0xD6E8FEB86659FD93) % (1 << 64)
+    h ^= h >> 32
+    return np.float32((h >> 40) / float(1 << 24))

@@ -81,3 +81,70 @@ def test_prompt_as_reference_changes_the_steps_but_never_the_output():
     # with a lookahead branch as well: still the same tokens
     got, steps_both, _ = loop.lookahead_decode(model, prompt, 5, 4, 5, 60, seed=3, prompt_as_reference=True)
     assert got == want and steps_both <= 60
+
+
+# ---- the loop with sampling verification (Algorithm 4 inside Algorithm 2)
+
+def softmax(x, temperature):
+    z = np.asarray(x, dtype=np.float64) / temperature
+    e = np.exp(z - z.max())
+    return e / e.sum()
+
+
+def test_sampling_loop_at_vanishing_temperature_is_greedy_decoding():
+    for seed, (W, N, G) in enumerate([(5, 4, 5), (3, 3, 2), (0, 3, 3), (6, 5, 6)]):
+        model = loop.ToyModel(seed)
+        prompt = [0, 5, 9, 5, 2, 9]
+        got, steps, _ = loop.lookahead_decode(model, prompt, W, N, G, 80, seed=seed, temperature=0.02,
+                                              prompt_as_reference=True)
+        assert got == loop.greedy_decode(model, prompt, 80)
+        assert steps < 80 or W == 0
+
+
+def test_sampling_loop_follows_the_models_distribution():
+    """Theorem A end to end: over many seeds (= many sets of uniform draws) the first two tokens
+    the loop emits follow p(t1) p(t2 | t1) of plain autoregressive sampling, although candidates
+    from the pool are accepted along the way.  The prompt is its own reference, so that the very
+    first step already verifies candidates."""
+    model = loop.ToyModel(1)
+    temperature = 5.0
+    W, N, G = 3, 3, 3
+    head = [0, 4]
+    cur = 7
+    # n-grams that start with the current token, continuing with likely tokens
+    p1 = softmax(model.logits(cur, set(head) | {cur}), temperature)
+    likely = [int(t) for t in np.argsort(-p1)[:3]]
+    prompt = head[:]
+    for t in likely:
+        nxt = int(np.argmax(model.logits(t, set(prompt) | {cur, t})))
+        prompt += [cur, t, nxt]
+    prompt += [cur]
+    base = set(prompt)
+    p1 = softmax(model.logits(cur, base), temperature)
+    n = 12000
+    counts = np.zeros((model.vocab, model.vocab))
+    multi = 0
+    for s in range(n):
+        got, _, trace = loop.lookahead_decode(model, prompt, W, N, G, 2, seed=s, temperature=temperature,
+                                              prompt_as_reference=True)
+        counts[got[0], got[1]] += 1
+        multi += len(trace[0]["accepted"]) > 1
+    assert multi > n // 10                           # candidates were accepted in the first step
+    for t1 in range(model.vocab):
+        p2 = softmax(model.logits(t1, base | {t1}), temperature)
+        for t2 in range(model.vocab):
+            p = p1[t1] * p2[t2]
+            sigma = np.sqrt(p * (1 - p) / n)
+            assert abs(counts[t1, t2] / n - p) <= 5 * sigma + 2e-4, (t1, t2, counts[t1, t2] / n, p)
+    # and the marginal of the first token, where the counts are large
+    for t1 in range(model.vocab):
+        p = p1[t1]
+        assert abs(counts[t1].sum() / n - p) <= 5 * np.sqrt(p * (1 - p) / n) + 1e-4
+
+
+def test_uniform_draws_are_uniform():
+    u = np.array([wl.uniform_draw(3, s, i) for s in range(200) for i in range(100)])
+    assert u.dtype == np.float32 and u.min() >= 0.0 and u.max() < 1.0
+    hist, _ = np.histogram(u, bins=20, range=(0, 1))
+    assert abs(hist / len(u) - 0.05).max() < 0.006
+    assert abs(np.corrcoef(u[:-1], u[1:])[0, 1]) < 0.02
