@@ -49,14 +49,17 @@ class NgramPool:
 class LookaheadDecoder:
     """Greedy Lookahead Decoding.  `prompt` must hold at least one token; its last token is the
     first current token, the others go to the model's KV cache.  With prompt_as_reference the
-    pool starts with the prompt's own n-grams."""
+    pool starts with the prompt's own n-grams.  With a temperature the candidates are verified by
+    sampling (Algorithm 4, `la_verify_sample`) while the lookahead branch stays greedy (Sec. 3.2);
+    `uniform(seed, step, index)` supplies the draws."""
 
     def __init__(self, model, prompt, W, N, G, seed=0, random_token=wl.window_random_token,
-                 prompt_as_reference=False):
+                 prompt_as_reference=False, temperature=None, uniform=wl.uniform_draw):
         if N < 2 or W < 0 or G < 0 or not prompt:
             raise ValueError("need N >= 2, W >= 0, G >= 0 and a non-empty prompt")
         self.model, self.W, self.N, self.G, self.seed = model, W, N, G, seed
         self.random_token = random_token
+        self.temperature, self.uniform = temperature, uniform
         n1 = N - 1
         self.window = [[random_token(seed, l - n1, j) for j in range(W)] for l in range(n1)]
         self.pool = NgramPool()
@@ -85,11 +88,29 @@ class LookaheadDecoder:
         look = logits[1 + (n1 - 1) * W:1 + n1 * W] if W else None        # newest level of the window
         cand_logits = logits[1 + W * n1:].view(g, n1, V) if g else None
         cand = torch.tensor(tails, dtype=torch.int32, device=logits.device).view(g, n1) if g else None
-        binding.la_verify_step(logits[0], look, cand_logits, cand, W, N, g, V, self._out, self._n_out,
-                               self._best, self._new if W else None, None)
-        self.model.commit(self._best, self._n_out)                        # queued behind the verification
-        n = int(self._n_out.item())                                       # (synchronises)
-        accepted = self._out[:n].tolist()
+        if self.temperature is None:
+            binding.la_verify_step(logits[0], look, cand_logits, cand, W, N, g, V, self._out, self._n_out,
+                                   self._best, self._new if W else None, None)
+            self.model.commit(self._best, self._n_out)                    # queued behind the verification
+            n = int(self._n_out.item())                                   # (synchronises)
+            accepted = self._out[:n].tolist()
+        else:
+            # the window's new level: greedy tokens of the lookahead rows (no candidates in this call)
+            binding.la_verify_step(logits[0], look, None, None, W, N, 0, V, self._out, self._n_out, self._best,
+                                   self._new if W else None, None)
+            step = self.steps + 1
+            u_test = torch.tensor([float(self.uniform(self.seed, step, i * g + j)) for i in range(n1) for j in range(g)],
+                                  dtype=torch.float32).view(n1, g).to(logits.device) if g else None
+            u_final = torch.tensor([float(self.uniform(self.seed, step, 1 << 20))], dtype=torch.float32).to(logits.device)
+            binding.la_verify_sample(logits[0], cand_logits, cand, u_test, u_final, self.temperature, N, g, V,
+                                     self._out, self._n_out)
+            n = int(self._n_out.item())
+            accepted = self._out[:n].tolist()
+            # any candidate that starts with the accepted tokens has their keys and values
+            k = n - 1
+            best = next((i for i, tail in enumerate(tails) if list(tail[:k]) == accepted[:k]), -1) if k else -1
+            self._best.fill_(best)
+            self.model.commit(self._best, self._n_out)
         new = self._new.tolist() if W else []
         for j in range(W):
             self.pool.add(tuple(self.window[l][j] for l in range(n1)) + (new[j],))

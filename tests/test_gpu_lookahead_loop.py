@@ -79,3 +79,35 @@ def test_loop_over_a_paged_cache(page_size):
     got = dec.generate(700)
     assert got == ref.greedy_decode(ref.ToyModel(seed), prompt, 700)
     assert 700 / dec.steps > 1.5
+
+
+@pytest.mark.parametrize("W,N,G,temperature,seed", [(5, 4, 5, 3.0, 0), (3, 3, 3, 5.0, 1), (8, 5, 8, 2.0, 2), (0, 3, 3, 4.0, 3)])
+def test_sampling_loop_matches_the_oracle_step_by_step(W, N, G, temperature, seed):
+    """Sampling verification inside the loop, same counter-based draws on both sides.  The kernel
+    decides in fp32 and the oracle in fp64: a draw within rounding of its threshold may fall on
+    either side, after which the two runs differ for good; with these seeds none does."""
+    print("case", dict(W=W, N=N, G=G, temperature=temperature, seed=seed), flush=True)
+    cpu = ref.ToyModel(seed)
+    head = [0, 6, 3]
+    prompt = head + ref.greedy_decode(cpu, head, 24)      # its own n-grams are the first candidates
+    want, want_steps, trace = ref.lookahead_decode(cpu, prompt, W, N, G, 120, seed=seed, temperature=temperature,
+                                                   prompt_as_reference=True)
+    dec = lookahead.LookaheadDecoder(lookahead.ToyAttentionLM(seed), prompt, W, N, G, seed=seed,
+                                     temperature=temperature, prompt_as_reference=True)
+    got, multi = [], 0
+    for step, rec in enumerate(trace):
+        accepted, tokens, best, new = dec.step()
+        assert tokens == rec["tokens"], step
+        assert (accepted, best, new) == (rec["accepted"], rec["best"], rec["window"]), step
+        got.extend(accepted)
+        multi += len(accepted) > 1
+    assert got[:120] == want and dec.steps == want_steps
+    assert want != ref.greedy_decode(cpu, prompt, 120)     # it did sample
+
+
+def test_sampling_loop_at_vanishing_temperature_is_greedy():
+    seed = 2
+    prompt = [0, 5, 9, 5]
+    dec = lookahead.LookaheadDecoder(lookahead.ToyAttentionLM(seed), prompt, 6, 4, 6, seed=seed, temperature=0.02)
+    assert dec.generate(300) == ref.greedy_decode(ref.ToyModel(seed), prompt, 300)
+    assert 300 / dec.steps > 1.5
