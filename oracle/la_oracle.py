@@ -4,7 +4,9 @@ Test infrastructure only (tests, the smoke check, the benchmark's cpu_baseline l
 bf16 tensors travel as numpy uint16 bit patterns; nothing here touches the GPU library.
 `kv_commit` (appending the accepted tokens to the KV cache) is plain numpy; its pin is that the
 cache after any run of lookahead steps equals the cache of plain autoregressive decoding.
-`gather_pages` / `kv_commit_paged` define what a paged cache stands for (pinned as the inverse of
+`step_attention_rows` is the step over a subset of its rows (one device's share under lookahead
+parallelism), dense numpy with the explicit mask, pinned by equality with the full step on closed
+subsets.  `gather_pages` / `kv_commit_paged` define what a paged cache stands for (pinned as the inverse of
 a scatter written in the test, and against the packed append).
 """
 import ctypes
@@ -236,3 +238,37 @@ def kv_commit_paged(k_pages, v_pages, block_table, page_size, step_k, step_v, P,
             k_pages[page, h, t % page_size, :] = step_k[row, h, :]
             v_pages[page, h, t % page_size, :] = step_v[row, h, :]
     return P + n_out
+
+
+def step_attention_rows(q, k_cache, v_cache, step_k, step_v, row_ids, P, W, N, G, heads, kv_heads, head_dim):
+    """Lookahead-step attention over a SUBSET of the step's rows (one device's share under
+    lookahead parallelism, Sec. 3.4): fp64 [n, heads, head_dim] from bf16 bit patterns.
+
+    q is [n, heads, d] and step_k / step_v are [n, kv_heads, d]: local row a is row row_ids[a] of
+    the full (W, N, G) layout and may see local key b iff full row row_ids[a] may see full row
+    row_ids[b] (the mask of Sec. 3.3 restricted to the subset), plus all P prefix keys.  Dense
+    numpy with the explicit boolean mask; no blocking."""
+    ids = np.asarray(row_ids, dtype=np.int64)
+    n = len(ids)
+    mask = step_mask(W, N, G)[np.ix_(ids, ids)]
+    f = lambda a, shape: bf16_to_f64(_u16(a, shape))
+    qf = f(q, (n, heads, head_dim))
+    kc, vc = f(k_cache, (kv_heads, P, head_dim)), f(v_cache, (kv_heads, P, head_dim))
+    sk, sv = f(step_k, (n, kv_heads, head_dim)), f(step_v, (n, kv_heads, head_dim))
+    group = heads // kv_heads
+    out = np.zeros((n, heads, head_dim))
+    scale = 1.0 / np.sqrt(head_dim)
+    for h in range(heads):
+        kv = h // group
+        keys = np.concatenate([kc[kv], sk[:, kv]], axis=0)          # [P + n, d]
+        vals = np.concatenate([vc[kv], sv[:, kv]], axis=0)
+        s = qf[:, h] @ keys.T * scale                                # [n, P + n]
+        vis = np.concatenate([np.ones((n, P), dtype=bool), mask], axis=1)
+        s = np.where(vis, s, -np.inf)
+        p = np.exp(s - s.max(axis=1, keepdims=True))
+        out[:, h] = (p / p.sum(axis=1, keepdims=True)) @ vals
+    return out
+
+
+def bf16_to_f64(bits):
+    return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
