@@ -128,6 +128,23 @@ la_status la_kv_commit_paged(void* k_pages, void* v_pages, const int* block_tabl
                              int head_dim, const int* best, const int* n_out, void* stream);
 
 /*
+ * The step over a SUBSET of its rows: one device's share under lookahead parallelism
+ * (Sec. 3.4), which keeps the current token and the oldest window level everywhere and deals
+ * the columns of the newer levels and the candidates out to the devices; such a share needs no
+ * key of another share, so every device runs this call on its own rows and the outputs are
+ * those of the full step.
+ *   row_ids  int32 [n_rows]  which rows of the (W, N, G) layout the step holds, in the order of
+ *                            q / step_k / step_v / out; 1 <= n_rows <= 1024.  Ids outside the
+ *                            layout are clamped into it.
+ *   q, out   bf16 [n_rows][heads][head_dim];  step_k, step_v  bf16 [n_rows][kv_heads][head_dim]
+ * Local row a attends to the P prefix keys and to local key b iff row row_ids[a] of the full
+ * layout may see row row_ids[b].  Everything else as la_step_attention (packed cache).
+ */
+la_status la_step_attention_rows(const void* q, const void* k_cache, const void* v_cache, const void* step_k,
+                                 const void* step_v, const int* row_ids, int n_rows, int P, int W, int N, int G,
+                                 int heads, int kv_heads, int head_dim, void* out, void* stream);
+
+/*
  * Greedy verification reduction (Sec. 2 "Guess-And-Verify": accept a draft
  * token while it equals the model's greedy token, stop at the first mismatch;
  * Algorithm 3 runs it over G candidates).

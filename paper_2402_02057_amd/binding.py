@@ -38,6 +38,8 @@ def load():
     lib.la_step_attention_cap.restype = i
     lib.la_kv_commit.argtypes = [p, p, ll, p, p, i, i, i, i, i, i, p, p, p]
     lib.la_kv_commit.restype = i
+    lib.la_step_attention_rows.argtypes = [p, p, p, p, p, p, i, i, i, i, i, i, i, i, p, p]
+    lib.la_step_attention_rows.restype = i
     lib.la_step_attention_paged.argtypes = [p, p, p, p, i, i, p, p, i, i, i, i, i, i, i, p, p]
     lib.la_step_attention_paged.restype = i
     lib.la_kv_commit_paged.argtypes = [p, p, p, i, i, p, p, i, i, i, i, i, i, p, p, p]
@@ -60,7 +62,7 @@ def load():
     return lib
 
 
-EXPORTS = ("la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_verify", "la_verify_step", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown",
+EXPORTS = ("la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_step_attention_rows", "la_verify", "la_verify_step", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown",
            "la_last_error", "la_version")
 
 
@@ -146,6 +148,24 @@ def la_kv_commit(k_cache, v_cache, step_k, step_v, P, W, N, G, kv_heads, head_di
         P, W, N, G, kv_heads, head_dim,
         _ptr(best, torch.int32, (1,), "best"), _ptr(n_out, torch.int32, (1,), "n_out"), _stream(stream))
     _check(rc)
+
+
+def la_step_attention_rows(q, k_cache, v_cache, step_k, step_v, row_ids, P, W, N, G, heads, kv_heads, head_dim, out,
+                           stream=None):
+    """la_step_attention over the rows `row_ids` (int32 tensor) of the (W, N, G) layout: a device's
+    share under lookahead parallelism; asynchronous."""
+    n = int(row_ids.numel())
+    bf = torch.bfloat16
+    rc = load().la_step_attention_rows(
+        _ptr(q, bf, (n, heads, head_dim), "q"),
+        _ptr(k_cache, bf, (kv_heads, P, head_dim), "k_cache", allow_empty_null=True),
+        _ptr(v_cache, bf, (kv_heads, P, head_dim), "v_cache", allow_empty_null=True),
+        _ptr(step_k, bf, (n, kv_heads, head_dim), "step_k"),
+        _ptr(step_v, bf, (n, kv_heads, head_dim), "step_v"),
+        _ptr(row_ids, torch.int32, (n,), "row_ids"), n, P, W, N, G, heads, kv_heads, head_dim,
+        _ptr(out, bf, (n, heads, head_dim), "out"), _stream(stream))
+    _check(rc)
+    return out
 
 
 def _pages(k_pages, v_pages, block_table, kv_heads, head_dim, rows):

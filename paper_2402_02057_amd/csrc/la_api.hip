@@ -120,7 +120,8 @@ namespace {
 la_status step_attention_checked(const char* name, const void* q, const void* k_cache, const void* v_cache,
                                  long long capacity, const int* block_table, int page_size, int n_pages,
                                  const void* step_k, const void* step_v, int P, int W, int N, int G, int heads,
-                                 int kv_heads, int head_dim, void* out, void* stream)
+                                 int kv_heads, int head_dim, void* out, void* stream, const int* row_ids = nullptr,
+                                 int n_rows = 0)
 {
     if (P < 0 || W < 0 || G < 0 || N < 2 || heads < 1 || kv_heads < 1)
         return la::fail(LA_EINVAL, "%s: need P,W,G >= 0, N >= 2, heads,kv_heads >= 1 "
@@ -141,8 +142,9 @@ la_status step_attention_checked(const char* name, const void* q, const void* k_
     const uintptr_t bits = (uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache |
                            (uintptr_t)step_k | (uintptr_t)step_v | (uintptr_t)out;
     if (bits & 15) return la::fail(LA_EINVAL, "%s: buffers must be 16-byte aligned", name);
-    return la::launch_step_attention(q, k_cache, v_cache, capacity, block_table, page_size, n_pages, step_k,
-                                     step_v, P, W, N, G, heads, kv_heads, head_dim, out, (hipStream_t)stream);
+    return la::launch_step_attention(q, k_cache, v_cache, capacity, block_table, page_size, n_pages, row_ids,
+                                     n_rows, step_k, step_v, P, W, N, G, heads, kv_heads, head_dim, out,
+                                     (hipStream_t)stream);
 }
 
 // page geometry shared by the paged entry points
@@ -171,6 +173,19 @@ la_status la_step_attention_cap(const void* q, const void* k_cache, const void* 
 {
     return step_attention_checked("la_step_attention_cap", q, k_cache, v_cache, capacity, nullptr, 0, 0, step_k,
                                   step_v, P, W, N, G, heads, kv_heads, head_dim, out, stream);
+}
+
+la_status la_step_attention_rows(const void* q, const void* k_cache, const void* v_cache, const void* step_k,
+                                 const void* step_v, const int* row_ids, int n_rows, int P, int W, int N, int G,
+                                 int heads, int kv_heads, int head_dim, void* out, void* stream)
+{
+    const long long T = 1 + (long long)(W > 0 ? W : 0) * (N - 1) + (long long)(G > 0 ? G : 0) * (N - 1);
+    if (n_rows < 1 || n_rows > 1024 || (N >= 2 && n_rows > T))
+        return la::fail(LA_EINVAL, "la_step_attention_rows: n_rows %d not in 1..min(1024, rows of the step)", n_rows);
+    if (!row_ids || ((uintptr_t)row_ids & 3))
+        return la::fail(LA_EINVAL, "la_step_attention_rows: row_ids is null or misaligned");
+    return step_attention_checked("la_step_attention_rows", q, k_cache, v_cache, P, nullptr, 0, 0, step_k, step_v, P,
+                                  W, N, G, heads, kv_heads, head_dim, out, stream, row_ids, n_rows);
 }
 
 la_status la_step_attention_paged(const void* q, const void* k_pages, const void* v_pages, const int* block_table,
@@ -299,6 +314,6 @@ void la_shutdown(void) { la::free_workspaces(); }
 
 const char* la_last_error(void) { return la::g_error; }
 
-int la_version(void) { return 1004; }
+int la_version(void) { return 1005; }
 
 }  // extern "C"

@@ -52,6 +52,7 @@ typedef short short4v __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float kNegInf = -__builtin_huge_valf();
 
@@ -69,6 +70,7 @@ struct AttnParams {
     // Paged cache (block_table != nullptr): k_cache / v_cache are [n_pages][kv_heads][page][head_dim]
     // and prefix key t sits in page block_table[t / page] at slot t % page.
     const int* block_table;
+    const int* row_ids;    // row-subset variant: T ids of rows of the full (W, N, G) layout, else nullptr
     long long page_bytes;  // bytes of one page (all KV heads)
     int page_chunks;       // chunks per page
     int n_pages;           // table entries are clamped to 0 .. n_pages-1
@@ -144,6 +146,38 @@ __device__ __forceinline__ unsigned step_block_word(const RowVis& v, int key0)
     return w;
 }
 
+// Row-subset variant: a row of the full layout as (branch, coordinates), and the pairwise rule
+// of Sec. 3.3 written out (the closed-form words above assume consecutive step keys).
+struct RowPos {
+    int cls;  // 0 current token, 1 lookahead (a = level, b = column), 2 candidate (a = candidate, b = token)
+    int a, b;
+};
+
+__device__ __forceinline__ RowPos row_position(int t, int W, int N, float inv_W, float inv_n1)
+{
+    RowPos r;
+    const int n_look = W * (N - 1);
+    if (t == 0) {
+        r.cls = 0; r.a = 0; r.b = 0;
+    } else if (t <= n_look) {
+        const int x = t - 1;
+        r.cls = 1; r.a = div_small(x, inv_W); r.b = x - r.a * W;
+    } else {
+        const int x = t - 1 - n_look;
+        r.cls = 2; r.a = div_small(x, inv_n1); r.b = x - r.a * (N - 1);
+    }
+    return r;
+}
+
+__device__ __forceinline__ bool visible_pair(const RowPos& q, int tk, int W, int N, float inv_W, float inv_n1)
+{
+    if (tk == 0) return true;  // everyone sees the current token
+    const RowPos k = row_position(tk, W, N, inv_W, inv_n1);
+    if (q.cls != k.cls) return false;
+    if (q.cls == 1) return (k.a == 0 && k.b <= q.b) || (k.b == q.b && k.a <= q.a);
+    return q.cls == 2 && k.a == q.a && k.b <= q.b;
+}
+
 // Three-way maximum in one instruction; unlike fmaxf the compiler adds no NaN-quieting moves
 // around it (scores are MFMA results or -inf, never signalling NaNs).
 __device__ __forceinline__ float max3(float a, float b, float c)
@@ -212,6 +246,18 @@ __device__ __forceinline__ void dma16_base(const void* base, unsigned lane_off, 
                  : "memory");
 }
 
+// The same with 4 bytes per lane (256 bytes per wave).
+__device__ __forceinline__ void dma4_base(const void* base, unsigned lane_off, unsigned lds_base)
+{
+    const unsigned long long b = reinterpret_cast<unsigned long long>(base);
+    const unsigned long long lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)b);
+    const unsigned long long hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(b >> 32));
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 :
+                 : "v"(lane_off), "s"((hi << 32) | lo), "s"(lds_base)
+                 : "memory");
+}
+
 __device__ __forceinline__ unsigned lds_address(const void* p)
 {
     return (unsigned)(size_t)(const __attribute__((address_space(3))) void*)p;
@@ -265,6 +311,10 @@ struct Cfg {
     static_assert(WLOADS % NW == 0, "chunk loads must divide among the waves");
     static_assert((Q_BYTES / 1024) % NW == 0, "Q loads must divide among the waves");
     static_assert(NSTAGE <= 9, "wait_chunks covers up to 8 younger chunks");
+    // row-subset variant: the ids of up to ROWSET_MAX rows, staged behind everything else
+    static constexpr int ROWSET_MAX = 1024;
+    static constexpr int ROWIDS_OFFSET = LDS_BYTES;
+    static constexpr int ROWIDS_BYTES = ROWSET_MAX * 4;
     static_assert(LDS_BYTES <= 160 * 1024, "LDS of a compute unit");
 };
 
@@ -384,7 +434,9 @@ __device__ __forceinline__ void merge_key_splits(const AttnParams& p, unsigned c
 
 // PAGED: the prefix cache is reached through a block table (a kernel of its own: the walk then
 // needs a dozen more scalar registers, which the packed kernel would otherwise pay for in spills).
-template <int D, int RT, int KS, int KC, int NSTAGE, bool PAGED = false>
+// ROWSET: the step holds a subset of the rows of the (W, N, G) layout (one device's share under
+// lookahead parallelism, Sec. 3.4); row ids come from p.row_ids and the mask is evaluated pair by pair.
+template <int D, int RT, int KS, int KC, int NSTAGE, bool PAGED = false, bool ROWSET = false>
 __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnParams p)
 {
     using C = Cfg<D, RT, KS, KC, NSTAGE>;
@@ -565,6 +617,15 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
             const unsigned off = (unsigned)(((t * p.heads + kvh * p.group + hh) * D + lc * 8) * 2);
             dma16_base(p.q, off, lds_base + C::Q_OFFSET + wl * 1024);
         }
+        if constexpr (ROWSET) {  // the row ids travel with Q (entries past the end repeat the last one)
+            static_assert(C::ROWSET_MAX % (C::NW * 64) == 0, "whole rounds of wave-loads");
+#pragma unroll
+            for (int r = 0; r < C::ROWSET_MAX / (C::NW * 64); ++r) {
+                const int slot = r * C::NW + wave;
+                const int idx = min(slot * 64 + lane, n_T - 1);
+                dma4_base(p.row_ids, (unsigned)idx * 4u, lds_base + C::ROWIDS_OFFSET + slot * 256);
+            }
+        }
     };
 
     // Requests first: the stream from HBM is the critical path.  The chunks of the first
@@ -593,8 +654,9 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
     LA_STAMP(1);
 
     // which step keys this lane's row may see
-    const RowVis vis = row_visibility(div_small(min(row_base + l32, p.R - 1), p.inv_group), p.W, p.N,
-                                      p.inv_W, p.inv_n1);
+    const int t_lane = div_small(min(row_base + l32, p.R - 1), p.inv_group);  // step row of this lane's query row
+    const RowVis vis = row_visibility(t_lane, p.W, p.N, p.inv_W, p.inv_n1);
+    RowPos qpos = {0, 0, 0};  // row-subset variant: filled once the ids have landed
     bf16x8 qreg[D / 16];  // B operand of S^T = K Q^T: row l32, d = k16*16 + hi*8 .. +8
 
     // o[db]: O^T accumulators of this wave's tile in the main loop; after the key-split merge,
@@ -676,6 +738,11 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
 #pragma unroll
                 for (int k16 = 0; k16 < D / 16; ++k16)
                     qreg[k16] = *reinterpret_cast<const bf16x8*>(qr + (((k16 * 2 + hi) ^ qsw) << 4));
+                if constexpr (ROWSET) {
+                    const int t_full = 1 + (p.W + p.G) * (p.N - 1);
+                    const int tq = *reinterpret_cast<const int*>(lds + C::ROWIDS_OFFSET + t_lane * 4);
+                    qpos = row_position(min(max(tq, 0), t_full - 1), p.W, p.N, p.inv_W, p.inv_n1);
+                }
             }
             // Up to CPI chunks are requested per iteration, into stages the last iteration freed:
             // the ring has room up to chunk done + NSTAGE - 1.  A computing wave issues its first
@@ -704,6 +771,35 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                 const int kb = KS >= C::KB ? ks % C::KB : ks + kbw * KS;
                 const int key0 = chunk_key0 + kb * 32;
                 if (key0 >= limit) continue;  // block entirely past the end (wave-uniform)
+
+                // ---- which of this lane's 16 keys of the block its row may see (bit (i/4)*8 + i%4 for
+                //      score register i).  A step block that no row of the tile sees at all is
+                //      skipped before anything is read: with wide windows most step blocks are.
+                const bool full = !is_step && (key0 + 32 <= limit);  // wave-uniform
+                unsigned word = 0xFFFFFFFFu;
+                if (!full) {
+                    if (is_step && ROWSET) {
+                        // pair by pair over this lane's 16 keys of the block (ids from LDS, four at a time)
+                        word = 0;
+#pragma unroll
+                        for (int grp = 0; grp < 4; ++grp) {
+                            const int c0 = key0 + grp * 8 + hi * 4;
+                            const i32x4 g4 = *reinterpret_cast<const i32x4*>(lds + C::ROWIDS_OFFSET + c0 * 4);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const bool ok = c0 + e < n_T && visible_pair(qpos, g4[e], p.W, p.N, p.inv_W, p.inv_n1);
+                                word |= (ok ? 1u : 0u) << (grp * 8 + hi * 4 + e);
+                            }
+                        }
+                    } else if (is_step) {
+                        word = step_block_word(vis, key0);
+                    } else {
+                        const int n = limit - key0;  // 1..31
+                        word = (1u << n) - 1u;
+                    }
+                    word = (word >> (hi * 4)) & 0x0F0F0F0Fu;
+                    if (is_step && __builtin_amdgcn_ballot_w64(word != 0u) == 0ull) continue;
+                }
 
                 // ---- operands: all K pieces of the block, and the V pieces of its first 16 keys,
                 //      are requested from LDS before the first MFMA (LDS answers in order)
@@ -742,16 +838,7 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
                 read_v(1);  // in flight during the softmax arithmetic
 
                 // ---- mask, running max, exponentials
-                const bool full = !is_step && (key0 + 32 <= limit);  // wave-uniform
                 if (!full) {
-                    unsigned word;
-                    if (is_step) {
-                        word = step_block_word(vis, key0);
-                    } else {
-                        const int n = limit - key0;  // 1..31
-                        word = (1u << n) - 1u;
-                    }
-                    word >>= hi * 4;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int bit = (i >> 2) * 8 + (i & 3);  // hi*4 already shifted out
@@ -1028,7 +1115,14 @@ bool paged_plan_supported(int D, int RT, int KS, int NS, int KC)
     return (RT == 1 && KS == 2) || (RT == 2 && KS == 2);
 }
 
-Plan make_plan(int P, int T, int group, int kv_heads, int D, bool paged = false)
+// Plans compiled for a row subset: as for a paged cache, without the 128-row plan (the ids need
+// 4 KB of LDS that it does not leave).
+bool rowset_plan_supported(int D, int RT, int KS, int NS, int KC)
+{
+    return paged_plan_supported(D, RT, KS, NS, KC) && RT != 4;
+}
+
+Plan make_plan(int P, int T, int group, int kv_heads, int D, bool paged = false, bool rowset = false)
 {
     Plan pl;
     const int R = T * group;
@@ -1041,7 +1135,7 @@ Plan make_plan(int P, int T, int group, int kv_heads, int D, bool paged = false)
     // chunk in LDS).  Head dimension 64 and single-tile problems keep four-wave workgroups.
     if (tiles <= 1) { pl.RT = 1; pl.KS = 2; }
     else if (D != 128) { pl.RT = 2; pl.KS = 2; }
-    else if (tiles >= 16 && (P + T) / pl.KC >= 64) { pl.RT = 4; pl.KS = 2; }
+    else if (tiles >= 16 && (P + T) / pl.KC >= 64 && !rowset) { pl.RT = 4; pl.KS = 2; }
     else { pl.RT = 2; pl.KS = 4; }
     pl.XS = 0;
     pl.NS = 0;
@@ -1050,7 +1144,8 @@ Plan make_plan(int P, int T, int group, int kv_heads, int D, bool paged = false)
     if (const char* env = getenv("LA_ATTN_PLAN")) {
         int b = 0, c = 0, d = 0, e = 0, f = 0, g = 0;
         if (sscanf(env, "%d,%d,%d,%d,%d,%d", &b, &c, &d, &e, &f, &g) >= 5 &&
-            plan_supported(D, b, c, e, f) && (!paged || paged_plan_supported(D, b, c, e, f))) {
+            plan_supported(D, b, c, e, f) && (!paged || paged_plan_supported(D, b, c, e, f)) &&
+            (!rowset || rowset_plan_supported(D, b, c, e, f))) {
             pl.RT = b; pl.KS = c; pl.XS = d; pl.NS = e; pl.KC = f;
             pl.PRE = g;
         }
@@ -1074,22 +1169,24 @@ Plan make_plan(int P, int T, int group, int kv_heads, int D, bool paged = false)
     return pl;
 }
 
-template <int D, int RT, int KS, int NSTAGE, int KC = 64, bool PAGED = false>
+template <int D, int RT, int KS, int NSTAGE, int KC = 64, bool PAGED = false, bool ROWSET = false>
 la_status launch_cfg(const AttnParams& prm, hipStream_t stream)
 {
     using C = Cfg<D, RT, KS, KC, NSTAGE>;
-    auto kern = step_attention_kernel<D, RT, KS, KC, NSTAGE, PAGED>;
+    constexpr int kLds = C::LDS_BYTES + (ROWSET ? C::ROWIDS_BYTES : 0);
+    static_assert(kLds <= 160 * 1024, "LDS of a compute unit");
+    auto kern = step_attention_kernel<D, RT, KS, KC, NSTAGE, PAGED, ROWSET>;
     static bool attr_set[16] = {false};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return fail(LA_EHIP, "hipGetDevice failed");
     if (!attr_set[dev]) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-        if (e != hipSuccess) return fail(LA_EHIP, "hipFuncSetAttribute(%d bytes LDS): %s", C::LDS_BYTES, hipGetErrorString(e));
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+        if (e != hipSuccess) return fail(LA_EHIP, "hipFuncSetAttribute(%d bytes LDS): %s", kLds, hipGetErrorString(e));
         attr_set[dev] = true;
     }
     const unsigned grid = (unsigned)prm.wg_per_xcd * 8u;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), C::LDS_BYTES, stream, prm);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), kLds, stream, prm);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(LA_EHIP, "la_step_attention launch: %s", hipGetErrorString(e));
     return LA_OK;
@@ -1107,15 +1204,16 @@ size_t step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int
 
 la_status launch_step_attention(const void* q, const void* k_cache, const void* v_cache,
                                 long long capacity, const int* block_table, int page_size, int n_pages,
-                                const void* step_k, const void* step_v, int P, int W, int N, int G,
-                                int heads, int kv_heads, int head_dim, void* out, hipStream_t stream)
+                                const int* row_ids, int n_rows, const void* step_k, const void* step_v, int P,
+                                int W, int N, int G, int heads, int kv_heads, int head_dim, void* out,
+                                hipStream_t stream)
 {
-    const int T = 1 + (W + G) * (N - 1);
+    const int T = row_ids ? n_rows : 1 + (W + G) * (N - 1);
     const int group = heads / kv_heads;
     if ((long long)T * group >= (1 << 21) || (long long)T * heads * head_dim * 2 >= (1ll << 31) ||
         (long long)kv_heads * head_dim * 2 >= (1 << 24))
         return fail(LA_EUNSUPPORTED, "la_step_attention: step too large (T=%d, heads=%d)", T, heads);
-    const Plan pl = make_plan(P, T, group, kv_heads, head_dim, block_table != nullptr);
+    const Plan pl = make_plan(P, T, group, kv_heads, head_dim, block_table != nullptr, row_ids != nullptr);
 
     AttnParams prm;
     prm.q = (const __bf16*)q;
@@ -1131,6 +1229,7 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
         return fail(LA_EUNSUPPORTED, "la_step_attention_paged: prefix of %d keys / page of %d not supported", P, page_size);
     prm.cache_rows = block_table ? page_size : capacity;
     prm.block_table = block_table;
+    prm.row_ids = row_ids;
     prm.page_bytes = (long long)kv_heads * page_size * head_dim * 2;
     prm.page_chunks = block_table ? page_size / pl.KC : 1;
     prm.n_pages = n_pages;
@@ -1183,6 +1282,18 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
         if (!prm.partials) return LA_ENOMEM;
     }
 
+    if (row_ids) {
+        if (block_table || n_rows > 1024 || !rowset_plan_supported(head_dim, pl.RT, pl.KS, pl.NS, pl.KC))
+            return fail(LA_EUNSUPPORTED, "la_step_attention_rows: no kernel for head_dim=%d plan (%d,%d,%d), %d rows",
+                        head_dim, pl.RT, pl.KS, pl.NS, n_rows);
+        if (head_dim == 128) {
+            if (pl.KS == 4) return launch_cfg<128, 2, 4, 4, 64, false, true>(prm, stream);
+            if (pl.RT == 1) return launch_cfg<128, 1, 2, 4, 64, false, true>(prm, stream);
+            return launch_cfg<128, 2, 2, 4, 64, false, true>(prm, stream);
+        }
+        if (pl.RT == 1) return launch_cfg<64, 1, 2, 4, 64, false, true>(prm, stream);
+        return launch_cfg<64, 2, 2, 4, 64, false, true>(prm, stream);
+    }
     if (block_table) {
         if (!paged_plan_supported(head_dim, pl.RT, pl.KS, pl.NS, pl.KC))
             return fail(LA_EUNSUPPORTED, "la_step_attention_paged: no kernel for head_dim=%d plan (%d,%d,%d)",

@@ -30,11 +30,13 @@ la_status launch_verify_sample(const float* logits_cur, const float* logits_cand
                                int V, int* out_tokens, int* n_out, hipStream_t stream);
 // `capacity`: rows between the caches of consecutive KV heads (P for a packed cache).
 // `block_table` != nullptr: the caches are pages [n_pages][kv_heads][page_size][head_dim]
-// (page_size a multiple of 64) and `capacity` is not used.
+// (page_size a multiple of 64) and `capacity` is not used.  `row_ids` != nullptr: the step holds
+// n_rows rows of the (W, N, G) layout (packed cache only).
 la_status launch_step_attention(const void* q, const void* k_cache, const void* v_cache,
                                 long long capacity, const int* block_table, int page_size, int n_pages,
-                                const void* step_k, const void* step_v, int P, int W, int N, int G,
-                                int heads, int kv_heads, int head_dim, void* out, hipStream_t stream);
+                                const int* row_ids, int n_rows, const void* step_k, const void* step_v, int P,
+                                int W, int N, int G, int heads, int kv_heads, int head_dim, void* out,
+                                hipStream_t stream);
 la_status launch_kv_commit(void* k_cache, void* v_cache, long long capacity, const int* block_table,
                            int page_size, int n_pages, const void* step_k, const void* step_v, int P, int W,
                            int N, int G, int kv_heads, int head_dim, const int* best, const int* n_out,

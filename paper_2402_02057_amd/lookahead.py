@@ -28,6 +28,20 @@ import torch
 from . import binding, workloads as wl
 
 
+def lp_share(W, N, G, parts, part):
+    """Rows of the (W, N, G) step that device `part` of `parts` holds under lookahead parallelism
+    (Sec. 3.4): the current token and the oldest window level on every device (computed
+    redundantly, which spares all communication inside the forward pass), the columns of the newer
+    levels and the candidates dealt round-robin.  For `la_step_attention_rows`."""
+    n1 = N - 1
+    rows = [0] + [1 + j for j in range(W)]
+    for level in range(1, n1):
+        rows += [1 + level * W + j for j in range(part, W, parts)]
+    for g in range(part, G, parts):
+        rows += [1 + W * n1 + g * n1 + k for k in range(n1)]
+    return rows
+
+
 class NgramPool:
     """n-grams collected from the Jacobi trajectory, by first token; most recent last."""
 
