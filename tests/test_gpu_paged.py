@@ -154,3 +154,11 @@ def test_every_paged_plan():
             del os.environ["LA_ATTN_PLAN"]
         got = out.float().cpu().numpy().astype(np.float64)
         assert np.isfinite(got).all() and np.abs(got - want).max() <= TOL, plan
+
+
+def test_paged_recompute_path(monkeypatch):
+    """The fallback of a split group that is not on one XCD (the last workgroup walks every chunk
+    again, through the block table) with a paged cache."""
+    monkeypatch.setenv("LA_FORCE_RECOMPUTE", "1")
+    test_paged_attention_matches_the_oracle(1000, 128, 10, 5, 10, 8, 8, 128)
+    test_paged_attention_matches_the_oracle(1024, 64, 15, 5, 15, 32, 32, 128)
