@@ -145,6 +145,32 @@ la_status la_step_attention_rows(const void* q, const void* k_cache, const void*
                                  int heads, int kv_heads, int head_dim, void* out, void* stream);
 
 /*
+ * Several independent steps (sequences decoding side by side, or the sequences of a ragged
+ * batch) in ONE launch: the same result as n_seqs calls of la_step_attention with the same
+ * W, N, G and head geometry, one per descriptor, in any order.  A single decode-sized step
+ * cannot fill the GPU (it is bound by latencies, not by bandwidth); a batch can: key ranges are
+ * split only as far as the whole batch needs, and one step's tail overlaps the next one's head.
+ *
+ *   seqs    HOST array of n_seqs descriptors (read before the call returns); the pointers in
+ *           them are device pointers with the shapes and alignment la_step_attention asks for
+ *   n_seqs  1..1024 (launched sixteen at a time, longest prefix first)
+ * Outputs of different descriptors must not overlap.
+ */
+typedef struct la_step_desc {
+    const void* q;        /* bf16 [T][heads][head_dim] */
+    const void* k_cache;  /* bf16 [kv_heads][P][head_dim]; may be NULL iff P == 0 */
+    const void* v_cache;
+    const void* step_k;   /* bf16 [T][kv_heads][head_dim] */
+    const void* step_v;
+    void* out;            /* bf16 [T][heads][head_dim] */
+    int P;                /* prefix length of this sequence */
+    int reserved;         /* must be 0 */
+} la_step_desc;
+
+la_status la_step_attention_batch(const la_step_desc* seqs, int n_seqs, int W, int N, int G, int heads,
+                                  int kv_heads, int head_dim, void* stream);
+
+/*
  * Greedy verification reduction (Sec. 2 "Guess-And-Verify": accept a draft
  * token while it equals the model's greedy token, stop at the first mismatch;
  * Algorithm 3 runs it over G candidates).

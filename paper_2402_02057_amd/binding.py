@@ -16,6 +16,13 @@ LA_OK = 0
 _lib = None
 
 
+class StepDesc(ctypes.Structure):
+    """la_step_desc of include/la.h."""
+    _fields_ = [("q", ctypes.c_void_p), ("k_cache", ctypes.c_void_p), ("v_cache", ctypes.c_void_p),
+                ("step_k", ctypes.c_void_p), ("step_v", ctypes.c_void_p), ("out", ctypes.c_void_p),
+                ("P", ctypes.c_int), ("reserved", ctypes.c_int)]
+
+
 class LaError(RuntimeError):
     def __init__(self, code, message):
         super().__init__("la error %d: %s" % (code, message))
@@ -38,6 +45,8 @@ def load():
     lib.la_step_attention_cap.restype = i
     lib.la_kv_commit.argtypes = [p, p, ll, p, p, i, i, i, i, i, i, p, p, p]
     lib.la_kv_commit.restype = i
+    lib.la_step_attention_batch.argtypes = [p, i, i, i, i, i, i, i, p]
+    lib.la_step_attention_batch.restype = i
     lib.la_step_attention_rows.argtypes = [p, p, p, p, p, p, i, i, i, i, i, i, i, i, p, p]
     lib.la_step_attention_rows.restype = i
     lib.la_step_attention_paged.argtypes = [p, p, p, p, i, i, p, p, i, i, i, i, i, i, i, p, p]
@@ -62,7 +71,7 @@ def load():
     return lib
 
 
-EXPORTS = ("la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_step_attention_rows", "la_verify", "la_verify_step", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown",
+EXPORTS = ("la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_step_attention_rows", "la_step_attention_batch", "la_verify", "la_verify_step", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown",
            "la_last_error", "la_version")
 
 
@@ -148,6 +157,25 @@ def la_kv_commit(k_cache, v_cache, step_k, step_v, P, W, N, G, kv_heads, head_di
         P, W, N, G, kv_heads, head_dim,
         _ptr(best, torch.int32, (1,), "best"), _ptr(n_out, torch.int32, (1,), "n_out"), _stream(stream))
     _check(rc)
+
+
+def la_step_attention_batch(seqs, W, N, G, heads, kv_heads, head_dim, stream=None):
+    """Several steps in one launch.  `seqs` is a list of dicts with q, k_cache, v_cache, step_k,
+    step_v, out (tensors as for la_step_attention) and P; asynchronous."""
+    T = 1 + (W + G) * (N - 1)
+    bf = torch.bfloat16
+    descs = (StepDesc * len(seqs))()
+    for d, x in zip(descs, seqs):
+        P = int(x["P"])
+        d.q = _ptr(x["q"], bf, (T, heads, head_dim), "q")
+        d.k_cache = _ptr(x["k_cache"], bf, (kv_heads, P, head_dim), "k_cache", allow_empty_null=True)
+        d.v_cache = _ptr(x["v_cache"], bf, (kv_heads, P, head_dim), "v_cache", allow_empty_null=True)
+        d.step_k = _ptr(x["step_k"], bf, (T, kv_heads, head_dim), "step_k")
+        d.step_v = _ptr(x["step_v"], bf, (T, kv_heads, head_dim), "step_v")
+        d.out = _ptr(x["out"], bf, (T, heads, head_dim), "out")
+        d.P, d.reserved = P, 0
+    _check(load().la_step_attention_batch(ctypes.cast(descs, ctypes.c_void_p), len(seqs), W, N, G, heads, kv_heads,
+                                          head_dim, _stream(stream)))
 
 
 def la_step_attention_rows(q, k_cache, v_cache, step_k, step_v, row_ids, P, W, N, G, heads, kv_heads, head_dim, out,

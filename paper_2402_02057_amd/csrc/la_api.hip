@@ -175,6 +175,35 @@ la_status la_step_attention_cap(const void* q, const void* k_cache, const void* 
                                   step_v, P, W, N, G, heads, kv_heads, head_dim, out, stream);
 }
 
+la_status la_step_attention_batch(const la_step_desc* seqs, int n_seqs, int W, int N, int G, int heads,
+                                  int kv_heads, int head_dim, void* stream)
+{
+    if (!seqs || n_seqs < 1 || n_seqs > 1024)
+        return la::fail(LA_EINVAL, "la_step_attention_batch: need 1..1024 descriptors (got %d)", n_seqs);
+    if (W < 0 || G < 0 || N < 2 || heads < 1 || kv_heads < 1)
+        return la::fail(LA_EINVAL, "la_step_attention_batch: need W,G >= 0, N >= 2, heads,kv_heads >= 1 "
+                                   "(got W=%d N=%d G=%d heads=%d kv_heads=%d)", W, N, G, heads, kv_heads);
+    if (head_dim != 64 && head_dim != 128)
+        return la::fail(LA_EUNSUPPORTED, "la_step_attention_batch: head_dim %d is not 64 or 128", head_dim);
+    if (heads % kv_heads != 0)
+        return la::fail(LA_EUNSUPPORTED, "la_step_attention_batch: heads %d not a multiple of kv_heads %d", heads,
+                        kv_heads);
+    if (1 + (long long)(W + G) * (N - 1) > (1 << 20))
+        return la::fail(LA_EINVAL, "la_step_attention_batch: step too large");
+    for (int i = 0; i < n_seqs; ++i) {
+        const la_step_desc& d = seqs[i];
+        if (d.P < 0 || (long long)d.P > (1ll << 30) || d.reserved != 0)
+            return la::fail(LA_EINVAL, "la_step_attention_batch: descriptor %d: bad P or reserved field", i);
+        if (!d.q || !d.step_k || !d.step_v || !d.out || (d.P > 0 && (!d.k_cache || !d.v_cache)))
+            return la::fail(LA_EINVAL, "la_step_attention_batch: descriptor %d: null pointer", i);
+        const uintptr_t bits = (uintptr_t)d.q | (uintptr_t)d.k_cache | (uintptr_t)d.v_cache | (uintptr_t)d.step_k |
+                               (uintptr_t)d.step_v | (uintptr_t)d.out;
+        if (bits & 15)
+            return la::fail(LA_EINVAL, "la_step_attention_batch: descriptor %d: buffers must be 16-byte aligned", i);
+    }
+    return la::launch_step_attention_batch(seqs, n_seqs, W, N, G, heads, kv_heads, head_dim, (hipStream_t)stream);
+}
+
 la_status la_step_attention_rows(const void* q, const void* k_cache, const void* v_cache, const void* step_k,
                                  const void* step_v, const int* row_ids, int n_rows, int P, int W, int N, int G,
                                  int heads, int kv_heads, int head_dim, void* out, void* stream)
@@ -314,6 +343,6 @@ void la_shutdown(void) { la::free_workspaces(); }
 
 const char* la_last_error(void) { return la::g_error; }
 
-int la_version(void) { return 1005; }
+int la_version(void) { return 1006; }
 
 }  // extern "C"

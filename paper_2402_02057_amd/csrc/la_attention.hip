@@ -436,8 +436,10 @@ __device__ __forceinline__ void merge_key_splits(const AttnParams& p, unsigned c
 // needs a dozen more scalar registers, which the packed kernel would otherwise pay for in spills).
 // ROWSET: the step holds a subset of the rows of the (W, N, G) layout (one device's share under
 // lookahead parallelism, Sec. 3.4); row ids come from p.row_ids and the mask is evaluated pair by pair.
+// The body is shared by the one-step kernel and the batched one: `xcd` is the XCD this workgroup
+// runs on (its id modulo 8) and `slot` its index among the step's workgroups on that XCD.
 template <int D, int RT, int KS, int KC, int NSTAGE, bool PAGED = false, bool ROWSET = false>
-__global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnParams p)
+__device__ __forceinline__ void step_attention_body(const AttnParams& p, const int xcd, const int slot)
 {
     using C = Cfg<D, RT, KS, KC, NSTAGE>;
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
@@ -446,7 +448,7 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
     // the workgroups that stream the same KV head on one XCD.
     LA_STAMP(0);
     LA_CYCW(22);
-    int logical = (int)(blockIdx.x & 7) * p.wg_per_xcd + (int)(blockIdx.x >> 3);
+    int logical = xcd * p.wg_per_xcd + slot;
 #ifdef LA_DEV_KNOBS
     if (p.dev_mode & 16) logical = (int)blockIdx.x;  // experiment: no XCD grouping (wrong combine!)
     if ((p.dev_mode & 64) && blockIdx.x >= 8) return;  // experiment: one workgroup per XCD only
@@ -1076,6 +1078,33 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
     }
 }
 
+template <int D, int RT, int KS, int KC, int NSTAGE, bool PAGED = false, bool ROWSET = false>
+__global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnParams p)
+{
+    step_attention_body<D, RT, KS, KC, NSTAGE, PAGED, ROWSET>(p, (int)(blockIdx.x & 7), (int)(blockIdx.x >> 3));
+}
+
+// Several independent steps (sequences) in one launch: on every XCD, step i owns the slots
+// slot0[i] .. slot0[i+1]-1.  Workgroups are handed out in id order, so the steps start in the
+// order given (longest first) and the tail of one overlaps the head of the next.
+constexpr int kMaxBatch = 16;
+struct BatchParams {
+    AttnParams seq[kMaxBatch];
+    int slot0[kMaxBatch + 1];
+    int n;
+};
+
+template <int D, int RT, int KS, int KC, int NSTAGE>
+__global__ __launch_bounds__(RT* KS * 64) void step_attention_batch_kernel(const BatchParams bp)
+{
+    const int slot = (int)(blockIdx.x >> 3);
+    int i = 0;
+#pragma unroll
+    for (int k = 1; k < kMaxBatch; ++k)
+        if (k < bp.n && slot >= bp.slot0[k]) i = k;
+    step_attention_body<D, RT, KS, KC, NSTAGE>(bp.seq[i], (int)(blockIdx.x & 7), slot - bp.slot0[i]);
+}
+
 // ---------------------------------------------------------------------------------------
 // host side
 
@@ -1202,20 +1231,15 @@ size_t step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int
     return (size_t)kv_heads * pl.n_row_blocks * pl.XS * pl.partial_bytes_per_wg;
 }
 
-la_status launch_step_attention(const void* q, const void* k_cache, const void* v_cache,
-                                long long capacity, const int* block_table, int page_size, int n_pages,
-                                const int* row_ids, int n_rows, const void* step_k, const void* step_v, int P,
-                                int W, int N, int G, int heads, int kv_heads, int head_dim, void* out,
-                                hipStream_t stream)
-{
-    const int T = row_ids ? n_rows : 1 + (W + G) * (N - 1);
-    const int group = heads / kv_heads;
-    if ((long long)T * group >= (1 << 21) || (long long)T * heads * head_dim * 2 >= (1ll << 31) ||
-        (long long)kv_heads * head_dim * 2 >= (1 << 24))
-        return fail(LA_EUNSUPPORTED, "la_step_attention: step too large (T=%d, heads=%d)", T, heads);
-    const Plan pl = make_plan(P, T, group, kv_heads, head_dim, block_table != nullptr, row_ids != nullptr);
+namespace {
 
-    AttnParams prm;
+// Everything of a launch's parameters that follows from the arguments and the plan (no workspace).
+la_status build_params(AttnParams& prm, const Plan& pl, const void* q, const void* k_cache, const void* v_cache,
+                       long long capacity, const int* block_table, int page_size, int n_pages, const int* row_ids,
+                       int T, const void* step_k, const void* step_v, int P, int W, int N, int G, int heads,
+                       int kv_heads, int head_dim, void* out)
+{
+    const int group = heads / kv_heads;
     prm.q = (const __bf16*)q;
     prm.k_cache = (const __bf16*)k_cache;
     prm.v_cache = (const __bf16*)v_cache;
@@ -1272,6 +1296,28 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
     const char* tp = getenv("LA_DEV_TRACE_PTR");
     prm.dev_trace = tp ? (long long*)strtoull(tp, nullptr, 16) : nullptr;
 #endif
+    return LA_OK;
+}
+
+}  // namespace
+
+la_status launch_step_attention(const void* q, const void* k_cache, const void* v_cache,
+                                long long capacity, const int* block_table, int page_size, int n_pages,
+                                const int* row_ids, int n_rows, const void* step_k, const void* step_v, int P,
+                                int W, int N, int G, int heads, int kv_heads, int head_dim, void* out,
+                                hipStream_t stream)
+{
+    const int T = row_ids ? n_rows : 1 + (W + G) * (N - 1);
+    const int group = heads / kv_heads;
+    if ((long long)T * group >= (1 << 21) || (long long)T * heads * head_dim * 2 >= (1ll << 31) ||
+        (long long)kv_heads * head_dim * 2 >= (1 << 24))
+        return fail(LA_EUNSUPPORTED, "la_step_attention: step too large (T=%d, heads=%d)", T, heads);
+    const Plan pl = make_plan(P, T, group, kv_heads, head_dim, block_table != nullptr, row_ids != nullptr);
+    AttnParams prm;
+    const la_status st = build_params(prm, pl, q, k_cache, v_cache, capacity, block_table, page_size, n_pages, row_ids,
+                                      T, step_k, step_v, P, W, N, G, heads, kv_heads, head_dim, out);
+    if (st != LA_OK) return st;
+    const long long total = prm.total_wg;
 
     if (pl.XS > 1) {
         const size_t ticket_bytes = (size_t)kv_heads * pl.n_row_blocks * sizeof(unsigned);
@@ -1325,6 +1371,132 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
 #undef LA_DISPATCH
     return fail(LA_EUNSUPPORTED, "la_step_attention: no kernel for head_dim=%d plan (%d,%d)",
                 head_dim, pl.RT, pl.KS);
+}
+
+// ---- several steps in one launch
+
+namespace {
+
+template <int D, int RT, int KS, int NSTAGE>
+la_status launch_batch_cfg(const BatchParams& bp, unsigned grid, hipStream_t stream)
+{
+    using C = Cfg<D, RT, KS, 64, NSTAGE>;
+    auto kern = step_attention_batch_kernel<D, RT, KS, 64, NSTAGE>;
+    static bool attr_set[16] = {false};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return fail(LA_EHIP, "hipGetDevice failed");
+    if (!attr_set[dev]) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+        if (e != hipSuccess) return fail(LA_EHIP, "hipFuncSetAttribute(%d bytes LDS): %s", C::LDS_BYTES, hipGetErrorString(e));
+        attr_set[dev] = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), C::LDS_BYTES, stream, bp);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(LA_EHIP, "la_step_attention_batch launch: %s", hipGetErrorString(e));
+    return LA_OK;
+}
+
+}  // namespace
+
+static_assert(sizeof(BatchParams) <= 4000, "the batch travels as a kernel argument");
+
+la_status launch_step_attention_batch(const la_step_desc* seqs, int n_seqs, int W, int N, int G, int heads,
+                                      int kv_heads, int head_dim, hipStream_t stream)
+{
+    const int T = 1 + (W + G) * (N - 1);
+    const int group = heads / kv_heads;
+    if ((long long)T * group >= (1 << 21) || (long long)T * heads * head_dim * 2 >= (1ll << 31) ||
+        (long long)kv_heads * head_dim * 2 >= (1 << 24))
+        return fail(LA_EUNSUPPORTED, "la_step_attention_batch: step too large (T=%d, heads=%d)", T, heads);
+    // longest first: workgroups are handed out in id order
+    int order[1024];
+    if (n_seqs > 1024) return fail(LA_EUNSUPPORTED, "la_step_attention_batch: at most 1024 steps per call");
+    for (int i = 0; i < n_seqs; ++i) order[i] = i;
+    for (int i = 1; i < n_seqs; ++i)
+        for (int j = i; j > 0 && seqs[order[j]].P > seqs[order[j - 1]].P; --j) {
+            const int t = order[j]; order[j] = order[j - 1]; order[j - 1] = t;
+        }
+    for (int first = 0; first < n_seqs; first += kMaxBatch) {
+        const int n = n_seqs - first < kMaxBatch ? n_seqs - first : kMaxBatch;
+        if (n == 1) {  // nothing to share a launch with: the one-step path and its own decomposition
+            const la_step_desc& d = seqs[order[first]];
+            const la_status st = launch_step_attention(d.q, d.k_cache, d.v_cache, d.P, nullptr, 0, 0, nullptr, 0,
+                                                       d.step_k, d.step_v, d.P, W, N, G, heads, kv_heads, head_dim,
+                                                       d.out, stream);
+            if (st != LA_OK) return st;
+            continue;
+        }
+        // One decomposition (row tiles, key-split waves) for the whole launch; the key ranges are
+        // cut so that every workgroup gets about the same number of chunks, with enough
+        // workgroups for two rounds over the 256 compute units.
+        Plan pl[kMaxBatch];
+        bool all_big = true;
+        long long work = 0;
+        for (int i = 0; i < n; ++i) {
+            pl[i] = make_plan(seqs[order[first + i]].P, T, group, kv_heads, head_dim);
+            all_big = all_big && pl[i].RT == 4 && pl[i].KS == 2;
+        }
+        int RT = pl[0].RT, KS = pl[0].KS;
+        for (int i = 1; i < n; ++i)
+            if (pl[i].RT != RT || pl[i].KS != KS) { RT = 2; KS = 4; }
+        if (head_dim == 128 && !all_big && !(RT == 2 && KS == 4)) { RT = 2; KS = 4; }
+        if (head_dim == 64) { RT = 2; KS = 2; }
+        const int rows_wg = RT * 32;
+        const int n_row_blocks = (T * group + rows_wg - 1) / rows_wg;
+        for (int i = 0; i < n; ++i) work += (long long)kv_heads * n_row_blocks * pl[i].n_chunks;
+        // One round of workgroups when the steps are alike (a second round only waits for the
+        // first); half a round more when their lengths differ, to even out the ends (measured).
+        bool alike = true;
+        for (int i = 1; i < n; ++i) alike = alike && pl[i].n_chunks == pl[0].n_chunks;
+        const long long wgs = alike ? 256 : 384;
+        long long target = (work + wgs - 1) / wgs;   // chunks per workgroup
+        if (target < 4) target = 4;
+        BatchParams bp;
+        bp.n = n;
+        size_t partial_bytes = 0, ticket_count = 0;
+        int slot = 0;
+        for (int i = 0; i < n; ++i) {
+            const la_step_desc& d = seqs[order[first + i]];
+            Plan& q = pl[i];
+            q.RT = RT; q.KS = KS; q.NS = 4; q.KC = 64; q.PRE = 0;
+            q.n_row_blocks = n_row_blocks;
+            q.partial_bytes_per_wg = (size_t)RT * ((size_t)(head_dim / 32) * 16 * 64 * 2 + 64 * 8);
+            int xs = (int)((q.n_chunks + target - 1) / target);
+            if (xs > q.n_chunks / 2) xs = q.n_chunks / 2;
+            if (xs > 64) xs = 64;
+            q.XS = xs < 1 ? 1 : xs;
+            const la_status st = build_params(bp.seq[i], q, d.q, d.k_cache, d.v_cache, d.P, nullptr, 0, 0, nullptr, T,
+                                              d.step_k, d.step_v, d.P, W, N, G, heads, kv_heads, head_dim, d.out);
+            if (st != LA_OK) return st;
+            bp.slot0[i] = slot;
+            slot += bp.seq[i].wg_per_xcd;
+            if (q.XS > 1) {
+                partial_bytes += (size_t)bp.seq[i].total_wg * q.partial_bytes_per_wg;
+                ticket_count += (size_t)kv_heads * n_row_blocks;
+            }
+        }
+        for (int i = n; i <= kMaxBatch; ++i) bp.slot0[i] = slot;
+        if (partial_bytes) {
+            unsigned* tickets = (unsigned*)zeroed_workspace(ticket_count * sizeof(unsigned), stream);
+            unsigned char* partials = (unsigned char*)scratch_workspace(partial_bytes);
+            if (!tickets || !partials) return LA_ENOMEM;
+            for (int i = 0; i < n; ++i) {
+                if (pl[i].XS <= 1) continue;
+                bp.seq[i].tickets = tickets;
+                bp.seq[i].partials = partials;
+                tickets += (size_t)kv_heads * n_row_blocks;
+                partials += (size_t)bp.seq[i].total_wg * pl[i].partial_bytes_per_wg;
+            }
+        }
+        const unsigned grid = (unsigned)slot * 8u;
+        la_status st;
+        if (head_dim == 128 && RT == 4) st = launch_batch_cfg<128, 4, 2, 4>(bp, grid, stream);
+        else if (head_dim == 128) st = launch_batch_cfg<128, 2, 4, 4>(bp, grid, stream);
+        else st = launch_batch_cfg<64, 2, 2, 4>(bp, grid, stream);
+        if (st != LA_OK) return st;
+    }
+    return LA_OK;
 }
 
 }  // namespace la

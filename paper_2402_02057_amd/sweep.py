@@ -1,11 +1,12 @@
 """Timing of the ragged long-context sweep: 8 sequences (32/8 grouped-query heads, head_dim 128,
 prefix lengths drawn once by seed from [512, 16384]), N = 5, G = W for W in {5, 10, 15, 20, 30},
-one la_step_attention call per sequence, the 8 calls replayed as one HIP graph.
+once as one la_step_attention call per sequence and once as a single la_step_attention_batch
+launch, each replayed as a HIP graph of four repetitions.
 
     python -m paper_2402_02057_amd.sweep
 
-Prints, per W, the time of the 8 calls, their algorithmic bytes and flops and the fraction of the
-roofline (the larger of bytes / 8 TB/s and flops / 2.5 PFLOP/s over the measured time).
+Prints, per W, both times, the algorithmic bytes and flops and the fraction of the roofline
+(the larger of bytes / 8 TB/s and flops / 2.5 PFLOP/s over the measured time).
 """
 import numpy as np
 import torch
@@ -32,32 +33,43 @@ def main():
             seqs.append((s, rb(T, H, d), rb(KV, P, d), rb(KV, P, d), rb(T, KV, d), rb(T, KV, d),
                          torch.empty((T, H, d), device="cuda", dtype=torch.bfloat16)))
 
-        def run():
+        descs = [dict(q=q, k_cache=k, v_cache=v, step_k=sk, step_v=sv, out=o, P=s.P) for s, q, k, v, sk, sv, o in seqs]
+        s0 = seqs[0][0]
+
+        def calls():
             for s, q, k, v, sk, sv, o in seqs:
                 binding.la_step_attention(q, k, v, sk, sv, s.P, s.W, s.N, s.G, s.heads, s.kv_heads, s.head_dim, o)
-        run()
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
+
+        def batch():
+            binding.la_step_attention_batch(descs, s0.W, s0.N, s0.G, s0.heads, s0.kv_heads, s0.head_dim)
+
+        def measure(run, reps=4):
             run()
-        graph.replay()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        times = []
-        for _ in range(20):
-            e0.record()
-            graph.replay()
-            e1.record()
             torch.cuda.synchronize()
-            times.append(e0.elapsed_time(e1) * 1e-3)
-        t = float(np.median(times))
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for _ in range(reps):
+                    run()
+            graph.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            times = []
+            for _ in range(20):
+                e0.record()
+                graph.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                times.append(e0.elapsed_time(e1) * 1e-3 / reps)
+            return float(np.median(times))
+        t, tb = measure(calls), measure(batch)
         nbytes = sum(2 * s.P * s.kv_heads * s.head_dim * 2 + 2 * s.T * s.kv_heads * s.head_dim * 2 +
                      2 * s.T * s.heads * s.head_dim * 2 for s, *_ in seqs)
         flops = sum(4 * s.head_dim * s.heads * s.T * (s.P + s.T) for s, *_ in seqs)
         t_hbm, t_mfma = nbytes / HBM_PEAK, flops / MFMA_BF16_PEAK
-        print("W=%2d (T=%3d): 8 calls %6.1f us | %.1f MB, %.1f GFLOP | roofline %.1f us (%s) -> %.1f %%"
-              % (W, seqs[0][0].T, t * 1e6, nbytes / 1e6, flops / 1e9, max(t_hbm, t_mfma) * 1e6,
-                 "HBM" if t_hbm > t_mfma else "MFMA", 100 * max(t_hbm, t_mfma) / t), flush=True)
+        roof = max(t_hbm, t_mfma)
+        print("W=%2d (T=%3d): 8 calls %6.1f us (%.1f %%), one launch %6.1f us (%.1f %%) | %.1f MB, %.1f GFLOP | "
+              "roofline %.1f us (%s)" % (W, s0.T, t * 1e6, 100 * roof / t, tb * 1e6, 100 * roof / tb, nbytes / 1e6,
+                                         flops / 1e9, roof * 1e6, "HBM" if t_hbm > t_mfma else "MFMA"), flush=True)
 
 
 if __name__ == "__main__":

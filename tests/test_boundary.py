@@ -82,6 +82,31 @@ def test_cache_forms_report_argument_errors_without_a_gpu(lib):
     assert lib.la_kv_commit_paged(A, A, A, 48, 4, A, A, 0, 1, 3, 1, 4, 128, A, A, None) == -2
 
 
+def test_batch_reports_argument_errors_without_a_gpu(lib):
+    import ctypes
+    A = 4096
+    d = (binding.StepDesc * 2)()
+    for x in d:
+        x.q = x.step_k = x.step_v = x.out = x.k_cache = x.v_cache = A
+        x.P, x.reserved = 10, 0
+    ptr = ctypes.cast(d, ctypes.c_void_p)
+    assert lib.la_step_attention_batch(ptr, 0, 1, 3, 1, 4, 4, 128, None) == -1
+    assert lib.la_step_attention_batch(None, 2, 1, 3, 1, 4, 4, 128, None) == -1
+    assert lib.la_step_attention_batch(ptr, 2, 1, 1, 1, 4, 4, 128, None) == -1          # N < 2
+    assert lib.la_step_attention_batch(ptr, 2, 1, 3, 1, 4, 4, 96, None) == -2           # head_dim
+    d[1].P = -1
+    rc = lib.la_step_attention_batch(ptr, 2, 1, 3, 1, 4, 4, 128, None)
+    assert rc == -1 and b"descriptor 1" in lib.la_last_error()
+    d[1].P = 10
+    d[1].out = A + 2
+    rc = lib.la_step_attention_batch(ptr, 2, 1, 3, 1, 4, 4, 128, None)
+    assert rc == -1 and b"aligned" in lib.la_last_error()
+    d[1].out = A
+    d[0].k_cache = None
+    rc = lib.la_step_attention_batch(ptr, 2, 1, 3, 1, 4, 4, 128, None)
+    assert rc == -1 and b"descriptor 0" in lib.la_last_error()
+
+
 def test_workspace_query(lib):
     assert binding.la_step_attention_workspace_bytes(1024, 15, 5, 15, 32, 32, 128) > 0
     assert binding.la_step_attention_workspace_bytes(0, 0, 2, 0, 1, 1, 128) == 0
