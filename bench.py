@@ -222,6 +222,32 @@ def main():
         torch.cuda.synchronize()
         kc_ms.append(e[0].elapsed_time(e[1]) / kc_calls)
     kv_commit_us = float(np.median(kc_ms)) * 1e3
+
+    # several independent steps in one launch (la_step_attention_batch), timed on its own: the first
+    # eight layers' inputs stand for eight sequences.  Not part of `value` (one sequence per step).
+    nb = min(8, L)
+    descs = [dict(q=x["q"], k_cache=x["k_cache"], v_cache=x["v_cache"], step_k=x["step_k"], step_v=x["step_v"],
+                  out=torch.empty_like(o), P=P) for x, o in zip(layers[:nb], outs[:nb])]
+
+    def batch():
+        binding.la_step_attention_batch(descs, s.W, s.N, s.G, H, KV, d)
+    batch()
+    run_b, b_calls = batch, 1
+    if use_graph:
+        gb = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gb):
+            for _ in range(8):
+                batch()
+        run_b, b_calls = gb.replay, 8
+    b_ms = []
+    for _ in range(reps):
+        e[0].record()
+        run_b()
+        e[1].record()
+        torch.cuda.synchronize()
+        b_ms.append(e[0].elapsed_time(e[1]) / b_calls)
+    batch_us = float(np.median(b_ms)) * 1e3
+    batch_equal = all(float((dsc["out"].float() - o.float()).abs().max()) <= 2e-2 for dsc, o in zip(descs, outs[:nb]))
     n_commit = int(vs_out[1].item())
     kv_commit_bytes = n_commit * KV * d * 2 * 2 * 2      # rows x (K, V) x (read, write)
     abytes = algorithmic_bytes(s)
@@ -311,14 +337,16 @@ def main():
                           "gbs": verify_sample_bytes / (verify_sample_us * 1e-6) / 1e9,
                           "frac_of_hbm_peak": verify_sample_bytes / (verify_sample_us * 1e-6) / 1e9 / HBM_PEAK_GBS},
         "kv_commit": {"us": kv_commit_us, "rows": n_commit, "algorithmic_bytes": kv_commit_bytes},
+        "batch": {"steps_per_launch": nb, "us_per_launch": batch_us, "us_per_step": batch_us / nb,
+                  "frac_of_roofline": max(t_hbm, t_mfma) * nb / (batch_us * 1e-6)},
         "attention_tflops": aflops / (attn_us * 1e-6) / 1e12,
         "attention_gbs": abytes / (attn_us * 1e-6) / 1e9,
         "parity": {"attention_max_abs_err_layer0": err, "verify_bit_exact": exact,
                    "verify_step_bit_exact": exact_step, "verify_sample_equals_oracle": sample_equal,
-                   "kv_commit_bit_exact": exact_commit},
+                   "kv_commit_bit_exact": exact_commit, "batch_matches_single_calls": batch_equal},
     }
     print(json.dumps(line))
-    if err > 2e-2 or not exact or not exact_step or not exact_commit:
+    if err > 2e-2 or not exact or not exact_step or not exact_commit or not batch_equal:
         print("bench.py: PARITY FAILURE", file=sys.stderr)
         sys.exit(1)
 
