@@ -74,3 +74,11 @@ def test_argument_errors():
         binding.la_step_attention_batch([seq], 1, 3, 1, 3, 2, 64)      # 3 query heads on 2 KV heads
     with pytest.raises(binding.LaError):
         binding.la_step_attention_batch([], 1, 3, 1, 2, 2, 64)         # no descriptors
+
+
+@pytest.mark.parametrize("plan", ["2", "4"])
+def test_both_batch_decompositions(monkeypatch, plan):
+    """64-row and 128-row workgroups (LA_BATCH_PLAN overrides the choice the library makes)."""
+    monkeypatch.setenv("LA_BATCH_PLAN", plan)
+    run_batch([1024, 900, 64, 3000], 15, 5, 15, 32, 32, 128, seed=3, check_oracle={2, 3})
+    run_batch([500, 2000], 4, 5, 4, 32, 8, 128, seed=4, check_oracle={0})
