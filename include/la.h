@@ -4,7 +4,7 @@
  * Lookahead Decoding (arXiv 2402.02057) evaluates, in ONE model forward per
  * decoding step, the current input token, a W x (N-1) window of Jacobi
  * lookahead tokens and G candidate n-grams against the prefix KV cache
- * (Sec. 3, Sec. 3.3 "Decode, Predict, and Verify in The Same Step"), then
+ * (Sec. 3, Sec. 3.3), then
  * verifies the candidates greedily (Sec. 3.2, Algorithm 3).  This library is
  * the attention of that forward and the verification reduction.  The n-gram
  * pool, the window update, projections, RoPE and the LM head are the
@@ -171,7 +171,7 @@ la_status la_step_attention_batch(const la_step_desc* seqs, int n_seqs, int W, i
                                   int kv_heads, int head_dim, void* stream);
 
 /*
- * Greedy verification reduction (Sec. 2 "Guess-And-Verify": accept a draft
+ * Greedy verification reduction (Sec. 2, the guess-and-verify paragraph: accept a draft
  * token while it equals the model's greedy token, stop at the first mismatch;
  * Algorithm 3 runs it over G candidates).
  *

@@ -224,7 +224,7 @@ int la_oracle_step_attention(const uint16_t *q, const uint16_t *k_cache, const u
 }
 
 /*
- * Greedy verification reduction (Sec. 2 "Guess-And-Verify": accept while the
+ * Greedy verification reduction (Sec. 2, the guess-and-verify paragraph: accept while the
  * model's greedy choice equals the draft token, stop at the first mismatch;
  * Algorithm 3 applies it to G candidates at once).
  *

@@ -1,5 +1,5 @@
 // Greedy verification reduction for gfx950: per-row argmax over the vocabulary and the
-// longest accepted prefix of every candidate n-gram (Sec. 2 "Guess-And-Verify"; the
+// longest accepted prefix of every candidate n-gram (Sec. 2, the guess-and-verify paragraph; the
 // accept/stop rule Algorithm 3 applies to each candidate), in one launch.
 //
 // A workgroup of 16 waves scans one segment of one logits row - up to 32768 elements, so a
