@@ -7,7 +7,10 @@ the 256 MB Infinity Cache cannot hold what is streamed), followed by one la_veri
 the step's verification logits.  Inputs are seeded synthetic tensors resident in HBM before
 the timed region.  The reported value is microseconds per layer-step (step time / L).
 
-Prints ONE JSON line; see the design doc for the roofline and cpu_baseline fields.
+Prints ONE JSON line.  `roofline`: algorithmic bytes (or flops) of one attention launch over its
+measured time against the MI355X peak that bounds the shape (HBM 8 TB/s or bf16 MFMA 2.5 PFLOP/s),
+plus the HBM traffic the counters saw.  `cpu_baseline`: the CPU oracle timed on the host cores.
+The other objects time the remaining entry points on their own.
 """
 import argparse
 import json
@@ -64,8 +67,8 @@ def main():
                     help="also run a plain 64 MiB device copy a few times (reference for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only; --gpus %d is not supported "
-              "(see DESIGN.md, 'More than one GPU')" % args.gpus, file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the hot path is one GPU's share; nothing here "
+              "shards across GPUs); --gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
