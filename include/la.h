@@ -39,7 +39,10 @@
  * workspace per device (split partials, tickets), grown on demand with
  * hipMalloc - so the first call at a new size may allocate - and shared by
  * all calls on that device: calls issued to one stream are ordered; calls on
- * different streams of the same device must not overlap in time.
+ * different streams of the same device must not overlap in time.  The calls may
+ * be recorded into a HIP graph once a call of the same (or a larger) shape has
+ * run outside the capture: that one sizes and clears the workspace, the kernels
+ * leave it cleared.
  *
  * Errors are returned, never thrown; on error nothing has been launched.
  */

@@ -1,0 +1,92 @@
+"""The entry points inside a HIP graph: every replay, with other work and new input contents
+between the replays, must give what the same calls give eagerly (the tickets and packed keys the
+kernels keep in the library's workspace have to come back to zero after every launch, also when
+the launch is a graph node)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2402_02057_amd import binding, workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def test_replays_equal_eager_calls():
+    s = wl.LLAMA2_7B
+    W, N, G, V, H, KV, d, P, T = s.W, s.N, s.G, s.V, s.heads, s.kv_heads, s.head_dim, s.P, s.T
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+
+    def rb(*shape):
+        return torch.randn(shape, device="cuda", generator=gen).bfloat16()
+    q, kc, vc, sk, sv = rb(T, H, d), rb(KV, P, d), rb(KV, P, d), rb(T, KV, d), rb(T, KV, d)
+    q2, kc2, vc2, sk2, sv2 = rb(T, H, d), rb(KV, 700, d), rb(KV, 700, d), rb(T, KV, d), rb(T, KV, d)
+    logits_cur = torch.randn(V, device="cuda", generator=gen)
+    logits_look = torch.randn(W, V, device="cuda", generator=gen)
+    logits_cand = torch.randn(G, N - 1, V, device="cuda", generator=gen)
+    cand = torch.randint(0, V, (G, N - 1), device="cuda", generator=gen, dtype=torch.int32)
+    u_test = torch.rand(N - 1, G, device="cuda", generator=gen)
+    u_final = torch.rand(1, device="cuda", generator=gen)
+    cap = P + 16
+    kcap, vcap = torch.zeros((KV, cap, d), dtype=torch.bfloat16, device="cuda"), torch.zeros((KV, cap, d), dtype=torch.bfloat16, device="cuda")
+    i32 = dict(dtype=torch.int32, device="cuda")
+
+    def outputs():
+        return dict(out=torch.empty((T, H, d), dtype=torch.bfloat16, device="cuda"),
+                    b0=torch.empty((T, H, d), dtype=torch.bfloat16, device="cuda"),
+                    b1=torch.empty((T, H, d), dtype=torch.bfloat16, device="cuda"),
+                    alen=torch.empty(G, **i32), acc=torch.empty((G, N - 1), **i32),
+                    toks=torch.empty(N, **i32), n_out=torch.empty(1, **i32), best=torch.empty(1, **i32),
+                    new=torch.empty(W, **i32), alen2=torch.empty(G, **i32),
+                    stoks=torch.empty(N, **i32), sn=torch.empty(1, **i32))
+
+    def calls(o):
+        binding.la_step_attention(q, kc, vc, sk, sv, P, W, N, G, H, KV, d, o["out"])
+        binding.la_step_attention_batch([dict(q=q, k_cache=kc, v_cache=vc, step_k=sk, step_v=sv, out=o["b0"], P=P),
+                                         dict(q=q2, k_cache=kc2, v_cache=vc2, step_k=sk2, step_v=sv2, out=o["b1"], P=700)],
+                                        W, N, G, H, KV, d)
+        binding.la_verify(logits_cand, cand, G, N, V, o["alen"], o["acc"])
+        binding.la_verify_step(logits_cur, logits_look, logits_cand, cand, W, N, G, V, o["toks"], o["n_out"], o["best"],
+                               o["new"], o["alen2"])
+        binding.la_verify_sample(logits_cur, logits_cand, cand, u_test, u_final, 1.0, N, G, V, o["stoks"], o["sn"])
+        binding.la_kv_commit(kcap, vcap, sk, sv, P, W, N, G, KV, d, o["best"], o["n_out"])
+
+    def plant():
+        """New contents in the same buffers: random logits with a few candidate tokens made greedy."""
+        for t in (q, kc, vc, sk, sv, q2, kc2, sk2):
+            t.copy_(torch.randn(t.shape, device="cuda", generator=gen).bfloat16())
+        for t in (logits_cur, logits_look, logits_cand):
+            t.copy_(torch.randn(t.shape, device="cuda", generator=gen))
+        u_test.copy_(torch.rand(u_test.shape, device="cuda", generator=gen))
+        logits_cur[cand[0, 0].long()] = 30.0
+        logits_cand[0, 0, cand[0, 1].long()] = 30.0
+        kcap.zero_()
+        vcap.zero_()
+
+    eager = outputs()
+    calls(eager)                      # (the first call sizes the library's workspace: not under capture)
+    torch.cuda.synchronize()
+    captured = outputs()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        calls(captured)
+    for replay in range(4):
+        plant()
+        calls(eager)
+        torch.cuda.synchronize()
+        want_cache = kcap.clone()
+        kcap.zero_()
+        vcap.zero_()
+        scratch = torch.randn(1 << 20, device="cuda", generator=gen).sum()     # unrelated work in between
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in eager:
+            a, b = eager[name], captured[name]
+            if name in ("toks", "stoks"):
+                n = int(eager["n_out" if name == "toks" else "sn"].item())
+                a, b = a[:n], b[:n]
+            assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a,
+                               b.view(torch.int16) if b.dtype == torch.bfloat16 else b), (replay, name)
+        assert torch.equal(kcap.view(torch.int16), want_cache.view(torch.int16)), replay
+        assert int(eager["n_out"].item()) >= 2
+        del scratch
