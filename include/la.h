@@ -174,6 +174,25 @@ la_status la_step_attention_batch(const la_step_desc* seqs, int n_seqs, int W, i
                                   int kv_heads, int head_dim, void* stream);
 
 /*
+ * The same over a paged cache, as a serving system holds it: all sequences share one pool of
+ * pages (k_pages, v_pages, page_size, n_pages as for la_step_attention_paged) and every
+ * descriptor names its sequence's block table.
+ */
+typedef struct la_step_desc_paged {
+    const void* q;
+    const int* block_table;  /* int32 [ceil(P / page_size)], device; may be NULL iff P == 0 */
+    const void* step_k;
+    const void* step_v;
+    void* out;
+    int P;
+    int reserved;            /* must be 0 */
+} la_step_desc_paged;
+
+la_status la_step_attention_batch_paged(const la_step_desc_paged* seqs, int n_seqs, const void* k_pages,
+                                        const void* v_pages, int page_size, int n_pages, int W, int N, int G,
+                                        int heads, int kv_heads, int head_dim, void* stream);
+
+/*
  * Greedy verification reduction (Sec. 2, the guess-and-verify paragraph: accept a draft
  * token while it equals the model's greedy token, stop at the first mismatch;
  * Algorithm 3 runs it over G candidates).

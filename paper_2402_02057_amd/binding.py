@@ -23,6 +23,12 @@ class StepDesc(ctypes.Structure):
                 ("P", ctypes.c_int), ("reserved", ctypes.c_int)]
 
 
+class StepDescPaged(ctypes.Structure):
+    """la_step_desc_paged of include/la.h."""
+    _fields_ = [("q", ctypes.c_void_p), ("block_table", ctypes.c_void_p), ("step_k", ctypes.c_void_p),
+                ("step_v", ctypes.c_void_p), ("out", ctypes.c_void_p), ("P", ctypes.c_int), ("reserved", ctypes.c_int)]
+
+
 class LaError(RuntimeError):
     def __init__(self, code, message):
         super().__init__("la error %d: %s" % (code, message))
@@ -47,6 +53,8 @@ def load():
     lib.la_kv_commit.restype = i
     lib.la_step_attention_batch.argtypes = [p, i, i, i, i, i, i, i, p]
     lib.la_step_attention_batch.restype = i
+    lib.la_step_attention_batch_paged.argtypes = [p, i, p, p, i, i, i, i, i, i, i, i, p]
+    lib.la_step_attention_batch_paged.restype = i
     lib.la_step_attention_rows.argtypes = [p, p, p, p, p, p, i, i, i, i, i, i, i, i, p, p]
     lib.la_step_attention_rows.restype = i
     lib.la_step_attention_paged.argtypes = [p, p, p, p, i, i, p, p, i, i, i, i, i, i, i, p, p]
@@ -71,7 +79,7 @@ def load():
     return lib
 
 
-EXPORTS = ("la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_step_attention_rows", "la_step_attention_batch", "la_verify", "la_verify_step", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown",
+EXPORTS = ("la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown",
            "la_last_error", "la_version")
 
 
@@ -176,6 +184,31 @@ def la_step_attention_batch(seqs, W, N, G, heads, kv_heads, head_dim, stream=Non
         d.P, d.reserved = P, 0
     _check(load().la_step_attention_batch(ctypes.cast(descs, ctypes.c_void_p), len(seqs), W, N, G, heads, kv_heads,
                                           head_dim, _stream(stream)))
+
+
+def la_step_attention_batch_paged(seqs, k_pages, v_pages, W, N, G, heads, kv_heads, head_dim, stream=None):
+    """Several steps over one paged cache in one launch.  `seqs`: dicts with q, block_table (int32
+    tensor, >= ceil(P / page_size) entries, or None if P == 0), step_k, step_v, out, P; asynchronous."""
+    T = 1 + (W + G) * (N - 1)
+    bf = torch.bfloat16
+    n_pages, page_size = int(k_pages.shape[0]), int(k_pages.shape[2])
+    shape = (n_pages, kv_heads, page_size, head_dim)
+    descs = (StepDescPaged * len(seqs))()
+    for d, x in zip(descs, seqs):
+        P = int(x["P"])
+        need = (P + page_size - 1) // page_size
+        bt = x.get("block_table")
+        if need > 0 and (bt is None or bt.numel() < need):
+            raise ValueError("block_table must hold at least %d entries" % need)
+        d.q = _ptr(x["q"], bf, (T, heads, head_dim), "q")
+        d.block_table = None if bt is None else _ptr(bt, torch.int32, (bt.numel(),), "block_table", allow_empty_null=True)
+        d.step_k = _ptr(x["step_k"], bf, (T, kv_heads, head_dim), "step_k")
+        d.step_v = _ptr(x["step_v"], bf, (T, kv_heads, head_dim), "step_v")
+        d.out = _ptr(x["out"], bf, (T, heads, head_dim), "out")
+        d.P, d.reserved = P, 0
+    _check(load().la_step_attention_batch_paged(ctypes.cast(descs, ctypes.c_void_p), len(seqs),
+                                                _ptr(k_pages, bf, shape, "k_pages"), _ptr(v_pages, bf, shape, "v_pages"),
+                                                page_size, n_pages, W, N, G, heads, kv_heads, head_dim, _stream(stream)))
 
 
 def la_step_attention_rows(q, k_cache, v_cache, step_k, step_v, row_ids, P, W, N, G, heads, kv_heads, head_dim, out,

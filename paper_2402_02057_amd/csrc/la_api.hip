@@ -175,33 +175,72 @@ la_status la_step_attention_cap(const void* q, const void* k_cache, const void* 
                                   step_v, P, W, N, G, heads, kv_heads, head_dim, out, stream);
 }
 
+namespace {
+
+la_status batch_common_checks(const char* name, const void* seqs, int n_seqs, int W, int N, int G, int heads,
+                              int kv_heads, int head_dim)
+{
+    if (!seqs || n_seqs < 1 || n_seqs > 1024)
+        return la::fail(LA_EINVAL, "%s: need 1..1024 descriptors (got %d)", name, n_seqs);
+    if (W < 0 || G < 0 || N < 2 || heads < 1 || kv_heads < 1)
+        return la::fail(LA_EINVAL, "%s: need W,G >= 0, N >= 2, heads,kv_heads >= 1 "
+                                   "(got W=%d N=%d G=%d heads=%d kv_heads=%d)", name, W, N, G, heads, kv_heads);
+    if (head_dim != 64 && head_dim != 128)
+        return la::fail(LA_EUNSUPPORTED, "%s: head_dim %d is not 64 or 128", name, head_dim);
+    if (heads % kv_heads != 0)
+        return la::fail(LA_EUNSUPPORTED, "%s: heads %d not a multiple of kv_heads %d", name, heads, kv_heads);
+    if (1 + (long long)(W + G) * (N - 1) > (1 << 20)) return la::fail(LA_EINVAL, "%s: step too large", name);
+    return LA_OK;
+}
+
+}  // namespace
+
 la_status la_step_attention_batch(const la_step_desc* seqs, int n_seqs, int W, int N, int G, int heads,
                                   int kv_heads, int head_dim, void* stream)
 {
-    if (!seqs || n_seqs < 1 || n_seqs > 1024)
-        return la::fail(LA_EINVAL, "la_step_attention_batch: need 1..1024 descriptors (got %d)", n_seqs);
-    if (W < 0 || G < 0 || N < 2 || heads < 1 || kv_heads < 1)
-        return la::fail(LA_EINVAL, "la_step_attention_batch: need W,G >= 0, N >= 2, heads,kv_heads >= 1 "
-                                   "(got W=%d N=%d G=%d heads=%d kv_heads=%d)", W, N, G, heads, kv_heads);
-    if (head_dim != 64 && head_dim != 128)
-        return la::fail(LA_EUNSUPPORTED, "la_step_attention_batch: head_dim %d is not 64 or 128", head_dim);
-    if (heads % kv_heads != 0)
-        return la::fail(LA_EUNSUPPORTED, "la_step_attention_batch: heads %d not a multiple of kv_heads %d", heads,
-                        kv_heads);
-    if (1 + (long long)(W + G) * (N - 1) > (1 << 20))
-        return la::fail(LA_EINVAL, "la_step_attention_batch: step too large");
+    const char* name = "la_step_attention_batch";
+    la_status st = batch_common_checks(name, seqs, n_seqs, W, N, G, heads, kv_heads, head_dim);
+    if (st != LA_OK) return st;
+    la::BatchSeq b[1024];
     for (int i = 0; i < n_seqs; ++i) {
         const la_step_desc& d = seqs[i];
         if (d.P < 0 || (long long)d.P > (1ll << 30) || d.reserved != 0)
-            return la::fail(LA_EINVAL, "la_step_attention_batch: descriptor %d: bad P or reserved field", i);
+            return la::fail(LA_EINVAL, "%s: descriptor %d: bad P or reserved field", name, i);
         if (!d.q || !d.step_k || !d.step_v || !d.out || (d.P > 0 && (!d.k_cache || !d.v_cache)))
-            return la::fail(LA_EINVAL, "la_step_attention_batch: descriptor %d: null pointer", i);
+            return la::fail(LA_EINVAL, "%s: descriptor %d: null pointer", name, i);
         const uintptr_t bits = (uintptr_t)d.q | (uintptr_t)d.k_cache | (uintptr_t)d.v_cache | (uintptr_t)d.step_k |
                                (uintptr_t)d.step_v | (uintptr_t)d.out;
-        if (bits & 15)
-            return la::fail(LA_EINVAL, "la_step_attention_batch: descriptor %d: buffers must be 16-byte aligned", i);
+        if (bits & 15) return la::fail(LA_EINVAL, "%s: descriptor %d: buffers must be 16-byte aligned", name, i);
+        b[i] = la::BatchSeq{d.q, d.k_cache, d.v_cache, nullptr, d.step_k, d.step_v, d.out, d.P};
     }
-    return la::launch_step_attention_batch(seqs, n_seqs, W, N, G, heads, kv_heads, head_dim, (hipStream_t)stream);
+    return la::launch_step_attention_batch(b, n_seqs, 0, 0, W, N, G, heads, kv_heads, head_dim, (hipStream_t)stream);
+}
+
+la_status la_step_attention_batch_paged(const la_step_desc_paged* seqs, int n_seqs, const void* k_pages,
+                                        const void* v_pages, int page_size, int n_pages, int W, int N, int G,
+                                        int heads, int kv_heads, int head_dim, void* stream)
+{
+    const char* name = "la_step_attention_batch_paged";
+    la_status st = batch_common_checks(name, seqs, n_seqs, W, N, G, heads, kv_heads, head_dim);
+    if (st != LA_OK) return st;
+    st = check_pages(name, nullptr, page_size, n_pages, 0);
+    if (st != LA_OK) return st;
+    if (!k_pages || !v_pages || (((uintptr_t)k_pages | (uintptr_t)v_pages) & 15))
+        return la::fail(LA_EINVAL, "%s: page pools are null or not 16-byte aligned", name);
+    la::BatchSeq b[1024];
+    for (int i = 0; i < n_seqs; ++i) {
+        const la_step_desc_paged& d = seqs[i];
+        if (d.P < 0 || (long long)d.P > (1ll << 30) || d.reserved != 0)
+            return la::fail(LA_EINVAL, "%s: descriptor %d: bad P or reserved field", name, i);
+        if (!d.q || !d.step_k || !d.step_v || !d.out || (d.P > 0 && !d.block_table))
+            return la::fail(LA_EINVAL, "%s: descriptor %d: null pointer", name, i);
+        const uintptr_t bits = (uintptr_t)d.q | (uintptr_t)d.step_k | (uintptr_t)d.step_v | (uintptr_t)d.out;
+        if ((bits & 15) || ((uintptr_t)d.block_table & 3))
+            return la::fail(LA_EINVAL, "%s: descriptor %d: misaligned buffer", name, i);
+        b[i] = la::BatchSeq{d.q, k_pages, v_pages, d.block_table, d.step_k, d.step_v, d.out, d.P};
+    }
+    return la::launch_step_attention_batch(b, n_seqs, page_size, n_pages, W, N, G, heads, kv_heads, head_dim,
+                                           (hipStream_t)stream);
 }
 
 la_status la_step_attention_rows(const void* q, const void* k_cache, const void* v_cache, const void* step_k,
@@ -343,6 +382,6 @@ void la_shutdown(void) { la::free_workspaces(); }
 
 const char* la_last_error(void) { return la::g_error; }
 
-int la_version(void) { return 1006; }
+int la_version(void) { return 1007; }
 
 }  // extern "C"

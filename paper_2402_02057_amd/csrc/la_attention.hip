@@ -1094,7 +1094,7 @@ struct BatchParams {
     int n;
 };
 
-template <int D, int RT, int KS, int KC, int NSTAGE>
+template <int D, int RT, int KS, int KC, int NSTAGE, bool PAGED = false>
 __global__ __launch_bounds__(RT* KS * 64) void step_attention_batch_kernel(const BatchParams bp)
 {
     const int slot = (int)(blockIdx.x >> 3);
@@ -1102,7 +1102,7 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_batch_kernel(const
 #pragma unroll
     for (int k = 1; k < kMaxBatch; ++k)
         if (k < bp.n && slot >= bp.slot0[k]) i = k;
-    step_attention_body<D, RT, KS, KC, NSTAGE>(bp.seq[i], (int)(blockIdx.x & 7), slot - bp.slot0[i]);
+    step_attention_body<D, RT, KS, KC, NSTAGE, PAGED>(bp.seq[i], (int)(blockIdx.x & 7), slot - bp.slot0[i]);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1377,11 +1377,11 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
 
 namespace {
 
-template <int D, int RT, int KS, int NSTAGE>
+template <int D, int RT, int KS, int NSTAGE, bool PAGED = false>
 la_status launch_batch_cfg(const BatchParams& bp, unsigned grid, hipStream_t stream)
 {
     using C = Cfg<D, RT, KS, 64, NSTAGE>;
-    auto kern = step_attention_batch_kernel<D, RT, KS, 64, NSTAGE>;
+    auto kern = step_attention_batch_kernel<D, RT, KS, 64, NSTAGE, PAGED>;
     static bool attr_set[16] = {false};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return fail(LA_EHIP, "hipGetDevice failed");
@@ -1401,9 +1401,10 @@ la_status launch_batch_cfg(const BatchParams& bp, unsigned grid, hipStream_t str
 
 static_assert(sizeof(BatchParams) <= 4000, "the batch travels as a kernel argument");
 
-la_status launch_step_attention_batch(const la_step_desc* seqs, int n_seqs, int W, int N, int G, int heads,
-                                      int kv_heads, int head_dim, hipStream_t stream)
+la_status launch_step_attention_batch(const BatchSeq* seqs, int n_seqs, int page_size, int n_pages, int W, int N,
+                                      int G, int heads, int kv_heads, int head_dim, hipStream_t stream)
 {
+    const bool paged = page_size > 0;
     const int T = 1 + (W + G) * (N - 1);
     const int group = heads / kv_heads;
     if ((long long)T * group >= (1 << 21) || (long long)T * heads * head_dim * 2 >= (1ll << 31) ||
@@ -1420,10 +1421,10 @@ la_status launch_step_attention_batch(const la_step_desc* seqs, int n_seqs, int 
     for (int first = 0; first < n_seqs; first += kMaxBatch) {
         const int n = n_seqs - first < kMaxBatch ? n_seqs - first : kMaxBatch;
         if (n == 1) {  // nothing to share a launch with: the one-step path and its own decomposition
-            const la_step_desc& d = seqs[order[first]];
-            const la_status st = launch_step_attention(d.q, d.k_cache, d.v_cache, d.P, nullptr, 0, 0, nullptr, 0,
-                                                       d.step_k, d.step_v, d.P, W, N, G, heads, kv_heads, head_dim,
-                                                       d.out, stream);
+            const BatchSeq& d = seqs[order[first]];
+            const la_status st = launch_step_attention(d.q, d.k_cache, d.v_cache, d.P, d.P > 0 ? d.block_table : nullptr,
+                                                       page_size, n_pages, nullptr, 0, d.step_k, d.step_v, d.P, W, N, G,
+                                                       heads, kv_heads, head_dim, d.out, stream);
             if (st != LA_OK) return st;
             continue;
         }
@@ -1463,7 +1464,7 @@ la_status launch_step_attention_batch(const la_step_desc* seqs, int n_seqs, int 
         size_t partial_bytes = 0, ticket_count = 0;
         int slot = 0;
         for (int i = 0; i < n; ++i) {
-            const la_step_desc& d = seqs[order[first + i]];
+            const BatchSeq& d = seqs[order[first + i]];
             Plan& q = pl[i];
             q.RT = RT; q.KS = KS; q.NS = 4; q.KC = 64; q.PRE = 0;
             q.n_row_blocks = n_row_blocks;
@@ -1472,7 +1473,8 @@ la_status launch_step_attention_batch(const la_step_desc* seqs, int n_seqs, int 
             if (xs > q.n_chunks / 2) xs = q.n_chunks / 2;
             if (xs > 64) xs = 64;
             q.XS = xs < 1 ? 1 : xs;
-            const la_status st = build_params(bp.seq[i], q, d.q, d.k_cache, d.v_cache, d.P, nullptr, 0, 0, nullptr, T,
+            const la_status st = build_params(bp.seq[i], q, d.q, d.k_cache, d.v_cache, d.P,
+                                              d.P > 0 ? d.block_table : nullptr, page_size, n_pages, nullptr, T,
                                               d.step_k, d.step_v, d.P, W, N, G, heads, kv_heads, head_dim, d.out);
             if (st != LA_OK) return st;
             bp.slot0[i] = slot;
@@ -1497,7 +1499,11 @@ la_status launch_step_attention_batch(const la_step_desc* seqs, int n_seqs, int 
         }
         const unsigned grid = (unsigned)slot * 8u;
         la_status st;
-        if (head_dim == 128 && RT == 4) st = launch_batch_cfg<128, 4, 2, 4>(bp, grid, stream);
+        if (paged) {
+            if (head_dim == 128 && RT == 4) st = launch_batch_cfg<128, 4, 2, 4, true>(bp, grid, stream);
+            else if (head_dim == 128) st = launch_batch_cfg<128, 2, 4, 4, true>(bp, grid, stream);
+            else st = launch_batch_cfg<64, 2, 2, 4, true>(bp, grid, stream);
+        } else if (head_dim == 128 && RT == 4) st = launch_batch_cfg<128, 4, 2, 4>(bp, grid, stream);
         else if (head_dim == 128) st = launch_batch_cfg<128, 2, 4, 4>(bp, grid, stream);
         else st = launch_batch_cfg<64, 2, 2, 4>(bp, grid, stream);
         if (st != LA_OK) return st;

@@ -37,8 +37,20 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
                                 const int* row_ids, int n_rows, const void* step_k, const void* step_v, int P,
                                 int W, int N, int G, int heads, int kv_heads, int head_dim, void* out,
                                 hipStream_t stream);
-la_status launch_step_attention_batch(const la_step_desc* seqs, int n_seqs, int W, int N, int G, int heads,
-                                      int kv_heads, int head_dim, hipStream_t stream);
+// One step of a batched launch.  Packed caches: k_cache / v_cache per step, block_table null.  Paged
+// (page_size > 0): k_cache / v_cache are the shared page pools, block_table the step's own table.
+struct BatchSeq {
+    const void* q;
+    const void* k_cache;
+    const void* v_cache;
+    const int* block_table;
+    const void* step_k;
+    const void* step_v;
+    void* out;
+    int P;
+};
+la_status launch_step_attention_batch(const BatchSeq* seqs, int n_seqs, int page_size, int n_pages, int W, int N,
+                                      int G, int heads, int kv_heads, int head_dim, hipStream_t stream);
 la_status launch_kv_commit(void* k_cache, void* v_cache, long long capacity, const int* block_table,
                            int page_size, int n_pages, const void* step_k, const void* step_v, int P, int W,
                            int N, int G, int kv_heads, int head_dim, const int* best, const int* n_out,

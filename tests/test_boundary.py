@@ -107,6 +107,20 @@ def test_batch_reports_argument_errors_without_a_gpu(lib):
     assert rc == -1 and b"descriptor 0" in lib.la_last_error()
 
 
+def test_paged_batch_reports_argument_errors_without_a_gpu(lib):
+    import ctypes
+    A = 4096
+    d = (binding.StepDescPaged * 1)()
+    d[0].q = d[0].step_k = d[0].step_v = d[0].out = d[0].block_table = A
+    d[0].P, d[0].reserved = 10, 0
+    ptr = ctypes.cast(d, ctypes.c_void_p)
+    assert lib.la_step_attention_batch_paged(ptr, 1, A, A, 96, 4, 1, 3, 1, 4, 4, 128, None) == -2     # page size
+    assert lib.la_step_attention_batch_paged(ptr, 1, None, A, 64, 4, 1, 3, 1, 4, 4, 128, None) == -1  # no pool
+    d[0].block_table = None
+    rc = lib.la_step_attention_batch_paged(ptr, 1, A, A, 64, 4, 1, 3, 1, 4, 4, 128, None)
+    assert rc == -1 and b"descriptor 0" in lib.la_last_error()
+
+
 def test_workspace_query(lib):
     assert binding.la_step_attention_workspace_bytes(1024, 15, 5, 15, 32, 32, 128) > 0
     assert binding.la_step_attention_workspace_bytes(0, 0, 2, 0, 1, 1, 128) == 0

@@ -82,3 +82,50 @@ def test_both_batch_decompositions(monkeypatch, plan):
     monkeypatch.setenv("LA_BATCH_PLAN", plan)
     run_batch([1024, 900, 64, 3000], 15, 5, 15, 32, 32, 128, seed=3, check_oracle={2, 3})
     run_batch([500, 2000], 4, 5, 4, 32, 8, 128, seed=4, check_oracle={0})
+
+
+@pytest.mark.parametrize("prefixes,page_size,W,N,G,H,KV,d", [
+    ([1024] * 8, 64, 15, 5, 15, 32, 32, 128),
+    ([2492, 13246, 1253, 7849], 256, 5, 5, 5, 32, 8, 128),
+    ([0, 64, 1, 65, 700], 64, 4, 3, 2, 4, 2, 64),
+    ([900, 10], 128, 10, 5, 10, 16, 16, 128),
+])
+def test_paged_batch(prefixes, page_size, W, N, G, H, KV, d):
+    """All sequences in one pool of pages, each with its own block table: per sequence the oracle's
+    step over the packed cache its table stands for, and the bits of the packed batch."""
+    print("case", dict(prefixes=prefixes, page=page_size, W=W, N=N, G=G, H=H, KV=KV, d=d), flush=True)
+    rng = np.random.default_rng(sum(prefixes) + page_size)
+    T = 1 + (W + G) * (N - 1)
+    seqs = [make_seq(rng, P, T, H, KV, d) for P in prefixes]
+    used = [(P + page_size - 1) // page_size for P in prefixes]
+    n_pages = sum(used) + 3
+    perm = rng.permutation(n_pages).astype(np.int32)
+    kp = np.full((n_pages, KV, page_size, d), 0x7FC0, dtype=np.uint16)       # NaN wherever nothing was put
+    vp = kp.copy()
+    tables, at = [], 0
+    for (x, _), P, n in zip(seqs, prefixes, used):
+        table = perm[at:at + n]
+        at += n
+        for i in range(n):
+            lo, hi = i * page_size, min(P, (i + 1) * page_size)
+            kp[table[i], :, :hi - lo] = x["k_cache"][:, lo:hi]
+            vp[table[i], :, :hi - lo] = x["v_cache"][:, lo:hi]
+        np.testing.assert_array_equal(orc.gather_pages(kp, table, P, page_size), x["k_cache"])
+        tables.append(torch.from_numpy(np.ascontiguousarray(table)).cuda() if n else None)
+    packed_out = []
+    binding.la_step_attention_batch([dev for _, dev in seqs], W, N, G, H, KV, d)
+    torch.cuda.synchronize()
+    for _, dev in seqs:
+        packed_out.append(dev["out"].clone())
+        dev["out"].fill_(float("nan"))
+    descs = [dict(q=dev["q"], block_table=t, step_k=dev["step_k"], step_v=dev["step_v"], out=dev["out"], P=dev["P"])
+             for (_, dev), t in zip(seqs, tables)]
+    binding.la_step_attention_batch_paged(descs, binding.bf16_tensor(kp), binding.bf16_tensor(vp), W, N, G, H, KV, d)
+    torch.cuda.synchronize()
+    order = np.argsort(prefixes)
+    for i, (x, dev) in enumerate(seqs):
+        assert torch.equal(dev["out"].view(torch.int16), packed_out[i].view(torch.int16)), i
+        if i in (int(order[0]), int(order[-1])):
+            want = orc.step_attention(x["q"], x["k_cache"], x["v_cache"], x["step_k"], x["step_v"], dev["P"], W, N, G,
+                                      H, KV, d)
+            assert np.abs(dev["out"].float().cpu().numpy() - want).max() <= TOL, i
