@@ -69,3 +69,15 @@ def test_a_subset_that_is_not_closed_changes_the_result():
                                   P, W, N, G, H, KV, d)
     assert np.abs(got[2] - full[5]).max() > 1e-3
     np.testing.assert_allclose(got[0], full[0], atol=1e-12)
+
+
+@pytest.mark.parametrize("W,N,G,parts", [(4, 3, 2, 2), (15, 5, 15, 4), (7, 5, 7, 8), (6, 4, 0, 3), (0, 3, 5, 2), (30, 5, 30, 16)])
+def test_the_products_share_helper(W, N, G, parts):
+    """paper_2402_02057_amd.lookahead.lp_share (host logic, no GPU): the shares written out above."""
+    from paper_2402_02057_amd import lookahead
+    mask = orc.step_mask(W, N, G)
+    T = 1 + (W + G) * (N - 1)
+    for part in range(parts):
+        ids = lookahead.lp_share(W, N, G, parts, part)
+        assert ids == share(W, N, G, parts, part)
+        assert not mask[ids][:, np.setdiff1d(np.arange(T), ids)].any()
