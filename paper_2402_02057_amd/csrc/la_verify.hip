@@ -535,13 +535,18 @@ __global__ __launch_bounds__(kThreads) void verify_sample_kernel(
                 }
                 // should rounding leave the target between the threads' intervals and the tile's
                 // total, the answer is the tile's last token with positive weight
+                // (one LDS atomic per wave: a thousand of them on one word take microseconds)
+                int last_here = -1;
                 if (mine > 0.0f) {
                     int lp = 0;
 #pragma unroll
                     for (int k = 0; k < 4; ++k)
                         if (ee[k] > 0.0f) lp = k;
-                    atomicMax(&sh_last, st + (jstar * kThreads + tid) * 4 + lp);
+                    last_here = st + (jstar * kThreads + tid) * 4 + lp;
                 }
+#pragma unroll
+                for (int sft = 32; sft >= 1; sft >>= 1) last_here = max(last_here, __shfl_xor(last_here, sft, 64));
+                if ((tid & 63) == 0 && last_here >= 0) atomicMax(&sh_last, last_here);
             }
         }
     } else {
