@@ -12,7 +12,10 @@
 // not depend on the order in which workgroups finish.  Each candidate has a ticket counter;
 // the workgroup that finishes last among a candidate's (N-1) x segments workgroups turns that
 // candidate's keys into `accepted` and `accept_len` and zeroes keys and ticket again, so the
-// workspace is clean for the next call without a memset.  Keys and tickets are touched only
+// workspace is clean for the next call without a memset.  (Where one workgroup covers a whole
+// row and N-1 <= 16, the keys are not needed at all: each row hands its match bit to the
+// candidate's counter together with its arrival, one atomic in place of three dependent ones.)
+// Keys and tickets are touched only
 // by device-scope atomics that return their old value (the ticket is taken after the key
 // update has come back), so no cache write-back or invalidate is needed: those cost tens of
 // microseconds on this part, more than the whole scan.
@@ -110,12 +113,35 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(
     const int v1 = min(V, v0 + seg_len);
     const float* p = logits + (size_t)row * V;
     const int tid = threadIdx.x;
+    const int want = cand_tokens[row];  // requested before the scan, used after it
 
     const unsigned long long key = scan_segment<kVec>(p, v0, v1, tid);
     __shared__ unsigned long long wave_key[kWaves];
     __shared__ unsigned last_flag;
     if ((tid & 63) == 0) wave_key[tid >> 6] = key;
     __syncthreads();
+    if (nseg == 1 && n1 <= 16) {
+        // One workgroup per row: its winner is final.  The row writes its own `accepted` entry
+        // and hands the candidate's counter its arrival (upper half) and its match bit (lower
+        // half) in ONE returning atomic; whoever completes the count has every match bit of the
+        // candidate in the returned word and needs nothing else from memory.
+        if (tid == 0) {
+            unsigned long long k = wave_key[0];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) k = wave_key[w] > k ? wave_key[w] : k;
+            const int tok = (int)(0xFFFFFFFFu - (unsigned)k);
+            const int g = row / n1, pos = row - g * n1;
+            accepted[row] = tok;
+            const unsigned mine = tok == want ? 1u << pos : 0u;
+            const unsigned old = atomicAdd(&tickets[g], 0x10000u | mine);
+            if ((old >> 16) == (unsigned)n1 - 1u) {
+                const unsigned miss = ~(old | mine) & ((1u << n1) - 1u);
+                accept_len[g] = miss ? (int)__builtin_ctz(miss) : n1;
+                atomicExch(&tickets[g], 0u);  // clean for the next call
+            }
+        }
+        return;
+    }
     if (tid == 0) {
         unsigned long long k = wave_key[0];
 #pragma unroll

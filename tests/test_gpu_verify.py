@@ -113,3 +113,27 @@ def test_many_rows():
             cand[g, cut[g]] = (cand[g, cut[g]] + 1) % V
     alen = check(logits, cand, G, N, V)
     np.testing.assert_array_equal(alen, np.minimum(cut, N - 1))
+
+
+@pytest.mark.parametrize("N", [2, 16, 17, 18, 25])
+@pytest.mark.parametrize("V", [500, 40000])
+def test_long_ngrams_every_cut(N, V):
+    """Every accept length 0 .. N-1, with matches again AFTER the first mismatch (they must not
+    count), for n-gram lengths on both sides of 16 rows per candidate and for one and two
+    workgroups per row."""
+    n1 = N - 1
+    G = n1 + 1
+    rng = np.random.default_rng(100 * N + V % 7)
+    logits = rng.standard_normal(size=(G, n1, V)).astype(np.float32)
+    cand = np.argmax(logits, axis=-1).astype(np.int32)
+    for g in range(G):
+        if g < n1:
+            cand[g, g] = (cand[g, g] + 1) % V          # first mismatch at position g
+        if g + 2 < n1:
+            cand[g, g + 2] = (cand[g, g + 2] + 3) % V  # and another one further on
+    alen = check(logits, cand, G, N, V)
+    assert alen.tolist() == list(range(n1)) + [n1]
+    # the other code path right after, on the same workspace
+    t = wl.TINY
+    logits, cand, _ = wl.verify_inputs(t)
+    check(logits, cand, t.G, t.N, t.V)
