@@ -226,6 +226,38 @@ def main():
         kc_ms.append(e[0].elapsed_time(e[1]) / kc_calls)
     kv_commit_us = float(np.median(kc_ms)) * 1e3
 
+    # the same append for every layer in ONE launch (la_kv_commit_batch): a step has as many appends
+    # as layers, all following the same best / n_out.  Layer 0's cache holds the prefix, so that it
+    # can be compared with the oracle's as a whole; the others only receive rows.
+    commits = []
+    for li, x in enumerate(layers):
+        kc_l = torch.zeros((KV, cap, d), dtype=torch.bfloat16, device="cuda") if li == 0 else \
+            torch.empty((KV, cap, d), dtype=torch.bfloat16, device="cuda")
+        vc_l = torch.zeros_like(kc_l) if li == 0 else torch.empty_like(kc_l)
+        if li == 0:
+            kc_l[:, :P], vc_l[:, :P] = x["k_cache"], x["v_cache"]
+        commits.append(dict(k_cache=kc_l, v_cache=vc_l, step_k=x["step_k"], step_v=x["step_v"], best=vs_out[2],
+                            n_out=vs_out[1], P=P))
+
+    def kv_commit_batch():
+        binding.la_kv_commit_batch(commits, s.W, s.N, s.G, KV, d)
+    kv_commit_batch()
+    run_kb, kb_calls = kv_commit_batch, 1
+    if use_graph:
+        gkb = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gkb):
+            for _ in range(8):
+                kv_commit_batch()
+        run_kb, kb_calls = gkb.replay, 8
+    kb_ms = []
+    for _ in range(reps):
+        e[0].record()
+        run_kb()
+        e[1].record()
+        torch.cuda.synchronize()
+        kb_ms.append(e[0].elapsed_time(e[1]) / kb_calls)
+    kv_commit_batch_us = float(np.median(kb_ms)) * 1e3
+
     # several independent steps in one launch (la_step_attention_batch), timed on its own: the first
     # eight layers' inputs stand for eight sequences.  Not part of `value` (one sequence per step).
     nb = min(8, L)
@@ -296,6 +328,14 @@ def main():
     ok_h[:, :P], ov_h[:, :P] = host0["k_cache"], host0["v_cache"]
     orc.kv_commit(ok_h, ov_h, host0["step_k"], host0["step_v"], P, s.W, s.N, s.G, w_best, len(w_out))
     exact_commit = bool(np.array_equal(binding.bf16_bits(kc_cap), ok_h) and np.array_equal(binding.bf16_bits(vc_cap), ov_h))
+    exact_commit_batch = bool(np.array_equal(binding.bf16_bits(commits[0]["k_cache"]), ok_h) and
+                              np.array_equal(binding.bf16_bits(commits[0]["v_cache"]), ov_h))
+    for c in commits[1:]:   # the other layers: the appended rows equal layer 0's choice of step rows
+        rows = [0] + [1 + s.W * (s.N - 1) + w_best * (s.N - 1) + i for i in range(len(w_out) - 1)]
+        src_k = c["step_k"][rows].transpose(0, 1)
+        src_v = c["step_v"][rows].transpose(0, 1)
+        exact_commit_batch = exact_commit_batch and bool(torch.equal(c["k_cache"][:, P:P + len(rows)], src_k)) \
+            and bool(torch.equal(c["v_cache"][:, P:P + len(rows)], src_v))
 
     w_tokens = orc.verify_sample(*sm_h[:4], float(sm_h[4][0]), 1.0, s.N, s.G, s.V)
     n = int(sm_out[1].item())
@@ -340,16 +380,19 @@ def main():
                           "gbs": verify_sample_bytes / (verify_sample_us * 1e-6) / 1e9,
                           "frac_of_hbm_peak": verify_sample_bytes / (verify_sample_us * 1e-6) / 1e9 / HBM_PEAK_GBS},
         "kv_commit": {"us": kv_commit_us, "rows": n_commit, "algorithmic_bytes": kv_commit_bytes},
+        "kv_commit_batch": {"layers_per_launch": L, "us_per_launch": kv_commit_batch_us,
+                            "us_per_layer": kv_commit_batch_us / L},
         "batch": {"steps_per_launch": nb, "us_per_launch": batch_us, "us_per_step": batch_us / nb,
                   "frac_of_roofline": max(t_hbm, t_mfma) * nb / (batch_us * 1e-6)},
         "attention_tflops": aflops / (attn_us * 1e-6) / 1e12,
         "attention_gbs": abytes / (attn_us * 1e-6) / 1e9,
         "parity": {"attention_max_abs_err_layer0": err, "verify_bit_exact": exact,
                    "verify_step_bit_exact": exact_step, "verify_sample_equals_oracle": sample_equal,
-                   "kv_commit_bit_exact": exact_commit, "batch_matches_single_calls": batch_equal},
+                   "kv_commit_bit_exact": exact_commit, "kv_commit_batch_bit_exact": exact_commit_batch,
+                   "batch_matches_single_calls": batch_equal},
     }
     print(json.dumps(line))
-    if err > 2e-2 or not exact or not exact_step or not exact_commit or not batch_equal:
+    if err > 2e-2 or not exact or not exact_step or not exact_commit or not exact_commit_batch or not batch_equal:
         print("bench.py: PARITY FAILURE", file=sys.stderr)
         sys.exit(1)
 

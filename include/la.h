@@ -131,6 +131,33 @@ la_status la_kv_commit_paged(void* k_pages, void* v_pages, const int* block_tabl
                              int head_dim, const int* best, const int* n_out, void* stream);
 
 /*
+ * Several appends in ONE launch: the layers of a model after a step (every layer's step keys
+ * and values go to that layer's cache, all following the same best / n_out), or several
+ * sequences, or both.  The same result as n_descs calls of la_kv_commit / la_kv_commit_paged,
+ * one per descriptor; a call costs a launch, and a step has as many appends as layers.
+ *
+ *   descs      HOST array of n_descs descriptors (read before the call returns), 1..1024
+ *   page_size, n_pages   of the page pools of the descriptors that name a block table (ignored
+ *                        if none does)
+ * Destination rows of different descriptors must not overlap.
+ */
+typedef struct la_commit_desc {
+    void* k_cache;           /* block_table NULL: bf16 [kv_heads][capacity][head_dim], P + N <= capacity; */
+    void* v_cache;           /* else the page pool, bf16 [n_pages][kv_heads][page_size][head_dim]         */
+    const int* block_table;  /* NULL, or int32 [ceil((P + N) / page_size)] on the device                  */
+    const void* step_k;      /* bf16 [T][kv_heads][head_dim] of the step just verified                    */
+    const void* step_v;
+    const int* best;         /* int32 [1] each on the device, as la_verify_step wrote them;               */
+    const int* n_out;        /* descriptors may share them                                                */
+    long long capacity;      /* rows per KV head of a packed cache (not used with a block table)          */
+    int P;                   /* keys the cache holds before the append                                    */
+    int reserved;            /* must be 0 */
+} la_commit_desc;
+
+la_status la_kv_commit_batch(const la_commit_desc* descs, int n_descs, int page_size, int n_pages, int W, int N,
+                             int G, int kv_heads, int head_dim, void* stream);
+
+/*
  * The step over a SUBSET of its rows: one device's share under lookahead parallelism
  * (Sec. 3.4), which keeps the current token and the oldest window level everywhere and deals
  * the columns of the newer levels and the candidates out to the devices; such a share needs no

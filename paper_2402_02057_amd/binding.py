@@ -29,6 +29,14 @@ class StepDescPaged(ctypes.Structure):
                 ("step_v", ctypes.c_void_p), ("out", ctypes.c_void_p), ("P", ctypes.c_int), ("reserved", ctypes.c_int)]
 
 
+class CommitDesc(ctypes.Structure):
+    """la_commit_desc of include/la.h."""
+    _fields_ = [("k_cache", ctypes.c_void_p), ("v_cache", ctypes.c_void_p), ("block_table", ctypes.c_void_p),
+                ("step_k", ctypes.c_void_p), ("step_v", ctypes.c_void_p), ("best", ctypes.c_void_p),
+                ("n_out", ctypes.c_void_p), ("capacity", ctypes.c_longlong), ("P", ctypes.c_int),
+                ("reserved", ctypes.c_int)]
+
+
 class LaError(RuntimeError):
     def __init__(self, code, message):
         super().__init__("la error %d: %s" % (code, message))
@@ -51,6 +59,8 @@ def load():
     lib.la_step_attention_cap.restype = i
     lib.la_kv_commit.argtypes = [p, p, ll, p, p, i, i, i, i, i, i, p, p, p]
     lib.la_kv_commit.restype = i
+    lib.la_kv_commit_batch.argtypes = [p, i, i, i, i, i, i, i, i, p]
+    lib.la_kv_commit_batch.restype = i
     lib.la_step_attention_batch.argtypes = [p, i, i, i, i, i, i, i, p]
     lib.la_step_attention_batch.restype = i
     lib.la_step_attention_batch_paged.argtypes = [p, i, p, p, i, i, i, i, i, i, i, i, p]
@@ -79,7 +89,7 @@ def load():
     return lib
 
 
-EXPORTS = ("la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown",
+EXPORTS = ("la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_kv_commit_batch", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown",
            "la_last_error", "la_version")
 
 
@@ -271,6 +281,37 @@ def la_kv_commit_paged(k_pages, v_pages, block_table, step_k, step_v, P, W, N, G
         P, W, N, G, kv_heads, head_dim,
         _ptr(best, torch.int32, (1,), "best"), _ptr(n_out, torch.int32, (1,), "n_out"), _stream(stream))
     _check(rc)
+
+
+def la_kv_commit_batch(appends, W, N, G, kv_heads, head_dim, stream=None):
+    """Several appends in one launch.  `appends`: dicts with k_cache, v_cache, step_k, step_v, best,
+    n_out, P and, for a paged cache, block_table (then k_cache / v_cache are the page pools
+    [n_pages, kv_heads, page_size, head_dim], the same geometry in all of them); asynchronous."""
+    T = 1 + (W + G) * (N - 1)
+    bf = torch.bfloat16
+    descs = (CommitDesc * len(appends))()
+    page_size = n_pages = 0
+    for d, x in zip(descs, appends):
+        P = int(x["P"])
+        bt = x.get("block_table")
+        if bt is not None:
+            kp, vp, btp, ps, npg = _pages(x["k_cache"], x["v_cache"], bt, kv_heads, head_dim, P + N)
+            if page_size and (ps, npg) != (page_size, n_pages):
+                raise ValueError("all page pools of a launch must have the same geometry")
+            page_size, n_pages = ps, npg
+            d.k_cache, d.v_cache, d.block_table, d.capacity = kp, vp, btp, 0
+        else:
+            cap = int(x["k_cache"].shape[1])
+            d.k_cache = _ptr(x["k_cache"], bf, (kv_heads, cap, head_dim), "k_cache")
+            d.v_cache = _ptr(x["v_cache"], bf, (kv_heads, cap, head_dim), "v_cache")
+            d.block_table, d.capacity = None, cap
+        d.step_k = _ptr(x["step_k"], bf, (T, kv_heads, head_dim), "step_k")
+        d.step_v = _ptr(x["step_v"], bf, (T, kv_heads, head_dim), "step_v")
+        d.best = _ptr(x["best"], torch.int32, (1,), "best")
+        d.n_out = _ptr(x["n_out"], torch.int32, (1,), "n_out")
+        d.P, d.reserved = P, 0
+    _check(load().la_kv_commit_batch(ctypes.cast(descs, ctypes.c_void_p), len(appends), page_size, n_pages, W, N, G,
+                                     kv_heads, head_dim, _stream(stream)))
 
 
 def la_verify(logits, cand_tokens, G, N, V, accept_len, accepted, stream=None):

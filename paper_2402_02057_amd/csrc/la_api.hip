@@ -317,6 +317,47 @@ la_status la_kv_commit(void* k_cache, void* v_cache, long long capacity, const v
                                 head_dim, best, n_out, (hipStream_t)stream);
 }
 
+la_status la_kv_commit_batch(const la_commit_desc* descs, int n_descs, int page_size, int n_pages, int W, int N,
+                             int G, int kv_heads, int head_dim, void* stream)
+{
+    const char* name = "la_kv_commit_batch";
+    if (n_descs < 1 || n_descs > 1024 || !descs)
+        return la::fail(LA_EINVAL, "%s: need 1..1024 descriptors (got %d)", name, n_descs);
+    if (W < 0 || G < 0 || N < 2 || kv_heads < 1)
+        return la::fail(LA_EINVAL, "%s: need W,G >= 0, N >= 2, kv_heads >= 1 (got W=%d N=%d G=%d kv_heads=%d)",
+                        name, W, N, G, kv_heads);
+    if (head_dim < 8 || head_dim % 8 != 0 || head_dim > 1024)
+        return la::fail(LA_EUNSUPPORTED, "%s: head_dim %d is not a multiple of 8 in 8..1024", name, head_dim);
+    if (1 + (long long)(W + G) * (N - 1) > (1 << 20) || N > 65535)
+        return la::fail(LA_EINVAL, "%s: step too large", name);
+    bool any_paged = false;
+    for (int i = 0; i < n_descs; ++i) any_paged = any_paged || descs[i].block_table != nullptr;
+    if (any_paged) {
+        const la_status st = check_pages(name, nullptr, page_size, n_pages, 0);
+        if (st != LA_OK) return st;
+    }
+    la::CommitSeq c[1024];
+    for (int i = 0; i < n_descs; ++i) {
+        const la_commit_desc& d = descs[i];
+        if (d.P < 0 || (long long)d.P > (1ll << 30) || d.reserved != 0)
+            return la::fail(LA_EINVAL, "%s: descriptor %d: bad P or reserved field", name, i);
+        if (!d.k_cache || !d.v_cache || !d.step_k || !d.step_v || !d.best || !d.n_out)
+            return la::fail(LA_EINVAL, "%s: descriptor %d: null pointer", name, i);
+        if (((uintptr_t)d.k_cache | (uintptr_t)d.v_cache | (uintptr_t)d.step_k | (uintptr_t)d.step_v) & 15)
+            return la::fail(LA_EINVAL, "%s: descriptor %d: caches and step tensors must be 16-byte aligned", name, i);
+        if (((uintptr_t)d.best | (uintptr_t)d.n_out | (uintptr_t)d.block_table) & 3)
+            return la::fail(LA_EINVAL, "%s: descriptor %d: best, n_out and block_table must be 4-byte aligned", name, i);
+        // up to N rows are appended; the count is only known on the device
+        if (!d.block_table && (d.capacity > (1ll << 40) || (long long)d.P + N > d.capacity))
+            return la::fail(LA_EINVAL, "%s: descriptor %d: capacity %lld cannot take N = %d more rows after P = %d",
+                            name, i, d.capacity, N, d.P);
+        c[i] = la::CommitSeq{d.k_cache, d.v_cache, d.block_table, d.step_k, d.step_v, d.best, d.n_out,
+                             d.block_table ? 0 : d.capacity, d.P};
+    }
+    return la::launch_kv_commit_batch(c, n_descs, any_paged ? page_size : 0, any_paged ? n_pages : 0, W, N, G,
+                                      kv_heads, head_dim, (hipStream_t)stream);
+}
+
 la_status la_verify(const float* logits, const int* cand_tokens, int G, int N, int V,
                     int* accept_len, int* accepted, void* stream)
 {
@@ -382,6 +423,6 @@ void la_shutdown(void) { la::free_workspaces(); }
 
 const char* la_last_error(void) { return la::g_error; }
 
-int la_version(void) { return 1007; }
+int la_version(void) { return 1008; }
 
 }  // extern "C"

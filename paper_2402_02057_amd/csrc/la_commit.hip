@@ -23,9 +23,9 @@ struct CommitParams {
     int row_bytes;        // head_dim * 2
 };
 
-__global__ __launch_bounds__(256) void kv_commit_kernel(CommitParams p)
+__device__ __forceinline__ void commit_row(const CommitParams& p, int i)
 {
-    const int i = blockIdx.x;               // i-th appended row: cache row P + i
+    // i-th appended row: cache row P + i
     int n = *p.n_out;
     n = n < 1 ? 1 : (n > p.N ? p.N : n);    // (a valid result is 1..N; never index past the step)
     if (i >= n) return;
@@ -55,6 +55,47 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(CommitParams p)
     }
 }
 
+__global__ __launch_bounds__(256) void kv_commit_kernel(CommitParams p) { commit_row(p, blockIdx.x); }
+
+// Several appends in one launch (the layers of a model after a step, or several sequences):
+// blockIdx.y names the append, blockIdx.x its row.  What differs between appends travels as a
+// kernel argument, kCommitBatch of them at a time.
+constexpr int kCommitBatch = 32;
+struct CommitOne {
+    unsigned char* k_cache;
+    unsigned char* v_cache;
+    const unsigned char* step_k;
+    const unsigned char* step_v;
+    const int* best;
+    const int* n_out;
+    const int* block_table;
+    long long capacity;
+    int P;
+};
+struct CommitBatchParams {
+    CommitOne one[kCommitBatch];
+    int page_size, n_pages, W, N, G, kv_heads, row_bytes;
+};
+
+__global__ __launch_bounds__(256) void kv_commit_batch_kernel(CommitBatchParams b)
+{
+    const CommitOne& o = b.one[blockIdx.y];
+    CommitParams p;
+    p.k_cache = o.k_cache;
+    p.v_cache = o.v_cache;
+    p.step_k = o.step_k;
+    p.step_v = o.step_v;
+    p.best = o.best;
+    p.n_out = o.n_out;
+    p.capacity = o.capacity;
+    p.block_table = o.block_table;
+    p.page_size = b.page_size;
+    p.n_pages = b.n_pages;
+    p.P = o.P; p.W = b.W; p.N = b.N; p.G = b.G; p.kv_heads = b.kv_heads;
+    p.row_bytes = b.row_bytes;
+    commit_row(p, blockIdx.x);
+}
+
 }  // namespace
 
 la_status launch_kv_commit(void* k_cache, void* v_cache, long long capacity, const int* block_table,
@@ -78,6 +119,36 @@ la_status launch_kv_commit(void* k_cache, void* v_cache, long long capacity, con
     hipLaunchKernelGGL(kv_commit_kernel, dim3((unsigned)N), dim3(256), 0, stream, p);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(LA_EHIP, "la_kv_commit launch: %s", hipGetErrorString(e));
+    return LA_OK;
+}
+
+la_status launch_kv_commit_batch(const CommitSeq* seqs, int n_seqs, int page_size, int n_pages, int W, int N,
+                                 int G, int kv_heads, int head_dim, hipStream_t stream)
+{
+    for (int i0 = 0; i0 < n_seqs; i0 += kCommitBatch) {
+        const int n = n_seqs - i0 < kCommitBatch ? n_seqs - i0 : kCommitBatch;
+        CommitBatchParams b;
+        for (int i = 0; i < n; ++i) {
+            const CommitSeq& s = seqs[i0 + i];
+            CommitOne& o = b.one[i];
+            o.k_cache = (unsigned char*)s.k_cache;
+            o.v_cache = (unsigned char*)s.v_cache;
+            o.step_k = (const unsigned char*)s.step_k;
+            o.step_v = (const unsigned char*)s.step_v;
+            o.best = s.best;
+            o.n_out = s.n_out;
+            o.block_table = s.block_table;
+            o.capacity = s.capacity;
+            o.P = s.P;
+        }
+        for (int i = n; i < kCommitBatch; ++i) b.one[i] = b.one[0];  // never indexed: the grid has n layers
+        b.page_size = page_size; b.n_pages = n_pages;
+        b.W = W; b.N = N; b.G = G; b.kv_heads = kv_heads;
+        b.row_bytes = head_dim * 2;
+        hipLaunchKernelGGL(kv_commit_batch_kernel, dim3((unsigned)N, (unsigned)n), dim3(256), 0, stream, b);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(LA_EHIP, "la_kv_commit_batch launch: %s", hipGetErrorString(e));
+    }
     return LA_OK;
 }
 

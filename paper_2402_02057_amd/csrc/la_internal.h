@@ -55,6 +55,21 @@ la_status launch_kv_commit(void* k_cache, void* v_cache, long long capacity, con
                            int page_size, int n_pages, const void* step_k, const void* step_v, int P, int W,
                            int N, int G, int kv_heads, int head_dim, const int* best, const int* n_out,
                            hipStream_t stream);
+// One append of a batched launch: block_table null = packed cache with `capacity` rows per head,
+// else the caches are page pools (page_size, n_pages common to the launch).
+struct CommitSeq {
+    void* k_cache;
+    void* v_cache;
+    const int* block_table;
+    const void* step_k;
+    const void* step_v;
+    const int* best;
+    const int* n_out;
+    long long capacity;
+    int P;
+};
+la_status launch_kv_commit_batch(const CommitSeq* seqs, int n_seqs, int page_size, int n_pages, int W, int N,
+                                 int G, int kv_heads, int head_dim, hipStream_t stream);
 size_t step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int kv_heads,
                                       int head_dim);
 

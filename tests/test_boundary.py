@@ -121,6 +121,38 @@ def test_paged_batch_reports_argument_errors_without_a_gpu(lib):
     assert rc == -1 and b"descriptor 0" in lib.la_last_error()
 
 
+def test_commit_batch_reports_argument_errors_without_a_gpu(lib):
+    import ctypes
+    A = 4096
+    d = (binding.CommitDesc * 2)()
+    for x in d:
+        x.k_cache = x.v_cache = x.step_k = x.step_v = x.best = x.n_out = A
+        x.block_table = None
+        x.capacity, x.P, x.reserved = 64, 10, 0
+    ptr = ctypes.cast(d, ctypes.c_void_p)
+    assert lib.la_kv_commit_batch(ptr, 0, 0, 0, 1, 3, 1, 4, 128, None) == -1
+    assert lib.la_kv_commit_batch(None, 2, 0, 0, 1, 3, 1, 4, 128, None) == -1
+    assert lib.la_kv_commit_batch(ptr, 2, 0, 0, 1, 1, 1, 4, 128, None) == -1            # N < 2
+    assert lib.la_kv_commit_batch(ptr, 2, 0, 0, 1, 3, 1, 4, 100, None) == -2            # head_dim % 8
+    d[1].capacity = 12
+    rc = lib.la_kv_commit_batch(ptr, 2, 0, 0, 1, 3, 1, 4, 128, None)
+    assert rc == -1 and b"descriptor 1" in lib.la_last_error() and b"capacity" in lib.la_last_error()
+    d[1].capacity = 64
+    d[0].n_out = None
+    rc = lib.la_kv_commit_batch(ptr, 2, 0, 0, 1, 3, 1, 4, 128, None)
+    assert rc == -1 and b"descriptor 0" in lib.la_last_error()
+    d[0].n_out = A
+    d[1].v_cache = A + 8
+    rc = lib.la_kv_commit_batch(ptr, 2, 0, 0, 1, 3, 1, 4, 128, None)
+    assert rc == -1 and b"aligned" in lib.la_last_error()
+    d[1].v_cache = A
+    d[1].block_table = A                     # a paged descriptor needs the launch's page geometry
+    rc = lib.la_kv_commit_batch(ptr, 2, 48, 4, 1, 3, 1, 4, 128, None)
+    assert rc == -2 and b"page_size" in lib.la_last_error()
+    rc = lib.la_kv_commit_batch(ptr, 2, 64, 0, 1, 3, 1, 4, 128, None)
+    assert rc == -1 and b"n_pages" in lib.la_last_error()
+
+
 def test_workspace_query(lib):
     assert binding.la_step_attention_workspace_bytes(1024, 15, 5, 15, 32, 32, 128) > 0
     assert binding.la_step_attention_workspace_bytes(0, 0, 2, 0, 1, 1, 128) == 0
