@@ -31,9 +31,9 @@ LAYERS = {"llama2-7b": 32, "llama2-13b": 40, "llama2-70b-gqa": 80}
 # by the same counter's reading for a 64 MiB copy): see profiles/attention_verify_<workload>.md.
 # (FETCH_SIZE reads half the bytes of a plain copy on this part, WRITE_SIZE all of them.)
 MEASURED_TRAFFIC_BYTES = {
-    "llama2-7b": int((11726.0 * 65536.0 / 32782.9 + 5328.4) * 1024),
-    "llama2-13b": int((23493.9 * 65536.0 / 32783.0 + 3879.1) * 1024),
-    "llama2-70b-gqa": int((10834.6 * 65536.0 / 32783.0 + 5000.5) * 1024),
+    "llama2-7b": int((11730.0 * 65536.0 / 32786.3 + 5328.4) * 1024),
+    "llama2-13b": int((23493.6 * 65536.0 / 32782.9 + 3879.1) * 1024),
+    "llama2-70b-gqa": int((10835.0 * 65536.0 / 32786.5 + 5000.5) * 1024),
 }
 
 
