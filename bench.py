@@ -226,6 +226,38 @@ def main():
         kc_ms.append(e[0].elapsed_time(e[1]) / kc_calls)
     kv_commit_us = float(np.median(kc_ms)) * 1e3
 
+    # the ends of eight sequences' steps in ONE launch (la_verify_step_batch), timed on its own:
+    # sequence 0 is the step above, the others are further seeded draws of the same shape
+    vsb_h = [vs_h] + [wl.verify_step_inputs(s, extra) for extra in range(1, 8)]
+    vsb = []
+    for h in vsb_h:
+        t4 = [torch.from_numpy(x).cuda() for x in h[:4]]
+        vsb.append(dict(logits_cur=t4[0], logits_look=t4[1], logits_cand=t4[2], cand_tokens=t4[3],
+                        out_tokens=torch.empty((s.N,), dtype=torch.int32, device="cuda"),
+                        n_out=torch.empty((1,), dtype=torch.int32, device="cuda"),
+                        best=torch.empty((1,), dtype=torch.int32, device="cuda"),
+                        new_window=torch.empty((s.W,), dtype=torch.int32, device="cuda"),
+                        accept_len=torch.empty((s.G,), dtype=torch.int32, device="cuda")))
+
+    def verify_step_batch():
+        binding.la_verify_step_batch(vsb, s.W, s.N, s.G, s.V)
+    verify_step_batch()
+    run_vb, vb_calls = verify_step_batch, 1
+    if use_graph:
+        gvb = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gvb):
+            for _ in range(8):
+                verify_step_batch()
+        run_vb, vb_calls = gvb.replay, 8
+    vb_ms = []
+    for _ in range(reps):
+        e[0].record()
+        run_vb()
+        e[1].record()
+        torch.cuda.synchronize()
+        vb_ms.append(e[0].elapsed_time(e[1]) / vb_calls)
+    verify_step_batch_us = float(np.median(vb_ms)) * 1e3
+
     # the same append for every layer in ONE launch (la_kv_commit_batch): a step has as many appends
     # as layers, all following the same best / n_out.  Layer 0's cache holds the prefix, so that it
     # can be compared with the oracle's as a whole; the others only receive rows.
@@ -323,6 +355,14 @@ def main():
                       np.array_equal(vs_out[3].cpu().numpy(), w_window) and
                       np.array_equal(vs_out[4].cpu().numpy(), w_len))
 
+    exact_step_batch = True
+    for h, x in zip(vsb_h[:3], vsb[:3]):      # (three of the eight: the oracle takes a while per sequence)
+        b_out, b_best, b_window, b_len = orc.verify_step(*h[:4], s.W, s.N, s.G, s.V)
+        nb_out = int(x["n_out"].item())
+        exact_step_batch = exact_step_batch and bool(
+            x["out_tokens"].cpu().numpy()[:nb_out].tolist() == b_out and int(x["best"].item()) == b_best and
+            np.array_equal(x["new_window"].cpu().numpy(), b_window) and
+            np.array_equal(x["accept_len"].cpu().numpy(), b_len))
     ok_h = np.zeros((KV, cap, d), np.uint16)
     ov_h = np.zeros((KV, cap, d), np.uint16)
     ok_h[:, :P], ov_h[:, :P] = host0["k_cache"], host0["v_cache"]
@@ -379,6 +419,10 @@ def main():
         "verify_sample": {"us": verify_sample_us, "algorithmic_bytes": verify_sample_bytes,
                           "gbs": verify_sample_bytes / (verify_sample_us * 1e-6) / 1e9,
                           "frac_of_hbm_peak": verify_sample_bytes / (verify_sample_us * 1e-6) / 1e9 / HBM_PEAK_GBS},
+        "verify_step_batch": {"sequences_per_launch": len(vsb), "us_per_launch": verify_step_batch_us,
+                              "gbs": len(vsb) * verify_step_bytes / (verify_step_batch_us * 1e-6) / 1e9,
+                              "frac_of_hbm_peak": len(vsb) * verify_step_bytes / (verify_step_batch_us * 1e-6) / 1e9
+                              / HBM_PEAK_GBS},
         "kv_commit": {"us": kv_commit_us, "rows": n_commit, "algorithmic_bytes": kv_commit_bytes},
         "kv_commit_batch": {"layers_per_launch": L, "us_per_launch": kv_commit_batch_us,
                             "us_per_layer": kv_commit_batch_us / L},
@@ -387,12 +431,13 @@ def main():
         "attention_tflops": aflops / (attn_us * 1e-6) / 1e12,
         "attention_gbs": abytes / (attn_us * 1e-6) / 1e9,
         "parity": {"attention_max_abs_err_layer0": err, "verify_bit_exact": exact,
-                   "verify_step_bit_exact": exact_step, "verify_sample_equals_oracle": sample_equal,
+                   "verify_step_bit_exact": exact_step, "verify_step_batch_bit_exact": exact_step_batch,
+                   "verify_sample_equals_oracle": sample_equal,
                    "kv_commit_bit_exact": exact_commit, "kv_commit_batch_bit_exact": exact_commit_batch,
                    "batch_matches_single_calls": batch_equal},
     }
     print(json.dumps(line))
-    if err > 2e-2 or not exact or not exact_step or not exact_commit or not exact_commit_batch or not batch_equal:
+    if err > 2e-2 or not exact or not exact_step or not exact_step_batch or not exact_commit or not exact_commit_batch or not batch_equal:
         print("bench.py: PARITY FAILURE", file=sys.stderr)
         sys.exit(1)
 

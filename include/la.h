@@ -264,6 +264,30 @@ la_status la_verify_step(const float* logits_cur, const float* logits_look, cons
                          int* best, int* new_window, int* accept_len, void* stream);
 
 /*
+ * The ends of several sequences' steps (same W, N, G, V) in ONE launch: the same result as
+ * n_descs calls of la_verify_step, one per descriptor.  With la_step_attention_batch and
+ * la_kv_commit_batch this keeps a step of a batch of sequences at one launch per operation.
+ *
+ *   descs    HOST array of n_descs descriptors (read before the call returns), 1..1024; the
+ *            pointers in them are device pointers with the shapes la_verify_step asks for
+ * Outputs of different descriptors must not overlap.
+ */
+typedef struct la_verify_desc {
+    const float* logits_cur;   /* fp32 [V] */
+    const float* logits_look;  /* fp32 [W][V]; may be NULL iff W == 0 */
+    const float* logits_cand;  /* fp32 [G][N-1][V]; may be NULL iff G == 0 */
+    const int* cand_tokens;    /* int32 [G][N-1] */
+    int* out_tokens;           /* int32 [N] */
+    int* n_out;                /* int32 [1] */
+    int* best;                 /* int32 [1] */
+    int* new_window;           /* int32 [W] */
+    int* accept_len;           /* int32 [G]; may be NULL */
+} la_verify_desc;
+
+la_status la_verify_step_batch(const la_verify_desc* descs, int n_descs, int W, int N, int G, int V,
+                               void* stream);
+
+/*
  * Sampling verification in one launch (Algorithm 4; App. B shows that every token it emits
  * follows the model's own distribution).  Distributions are softmax(logits / temperature).
  * Position by position the surviving candidates are examined in order: candidate token s is

@@ -37,6 +37,12 @@ class CommitDesc(ctypes.Structure):
                 ("reserved", ctypes.c_int)]
 
 
+class VerifyDesc(ctypes.Structure):
+    """la_verify_desc of include/la.h."""
+    _fields_ = [(n, ctypes.c_void_p) for n in ("logits_cur", "logits_look", "logits_cand", "cand_tokens",
+                                                "out_tokens", "n_out", "best", "new_window", "accept_len")]
+
+
 class LaError(RuntimeError):
     def __init__(self, code, message):
         super().__init__("la error %d: %s" % (code, message))
@@ -59,6 +65,8 @@ def load():
     lib.la_step_attention_cap.restype = i
     lib.la_kv_commit.argtypes = [p, p, ll, p, p, i, i, i, i, i, i, p, p, p]
     lib.la_kv_commit.restype = i
+    lib.la_verify_step_batch.argtypes = [p, i, i, i, i, i, p]
+    lib.la_verify_step_batch.restype = i
     lib.la_kv_commit_batch.argtypes = [p, i, i, i, i, i, i, i, i, p]
     lib.la_kv_commit_batch.restype = i
     lib.la_step_attention_batch.argtypes = [p, i, i, i, i, i, i, i, p]
@@ -89,7 +97,7 @@ def load():
     return lib
 
 
-EXPORTS = ("la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_kv_commit_batch", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown",
+EXPORTS = ("la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_kv_commit_batch", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_step_batch", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown",
            "la_last_error", "la_version")
 
 
@@ -341,6 +349,25 @@ def la_verify_step(logits_cur, logits_look, logits_cand, cand_tokens, W, N, G, V
         _ptr(accept_len, torch.int32, (G,), "accept_len", allow_empty_null=True), _stream(stream))
     _check(rc)
     return out_tokens, n_out, best, new_window, accept_len
+
+
+def la_verify_step_batch(seqs, W, N, G, V, stream=None):
+    """The ends of several sequences' steps in one launch.  `seqs`: dicts with logits_cur, logits_look,
+    logits_cand, cand_tokens, out_tokens, n_out, best, new_window and optionally accept_len (tensors
+    as for la_verify_step); asynchronous."""
+    descs = (VerifyDesc * len(seqs))()
+    f, i32 = torch.float32, torch.int32
+    for d, x in zip(descs, seqs):
+        d.logits_cur = _ptr(x["logits_cur"], f, (V,), "logits_cur")
+        d.logits_look = _ptr(x.get("logits_look"), f, (W, V), "logits_look", allow_empty_null=True)
+        d.logits_cand = _ptr(x.get("logits_cand"), f, (G, N - 1, V), "logits_cand", allow_empty_null=True)
+        d.cand_tokens = _ptr(x.get("cand_tokens"), i32, (G, N - 1), "cand_tokens", allow_empty_null=True)
+        d.out_tokens = _ptr(x["out_tokens"], i32, (N,), "out_tokens")
+        d.n_out = _ptr(x["n_out"], i32, (1,), "n_out")
+        d.best = _ptr(x["best"], i32, (1,), "best")
+        d.new_window = _ptr(x.get("new_window"), i32, (W,), "new_window", allow_empty_null=True)
+        d.accept_len = _ptr(x.get("accept_len"), i32, (G,), "accept_len", allow_empty_null=True)
+    _check(load().la_verify_step_batch(ctypes.cast(descs, ctypes.c_void_p), len(seqs), W, N, G, V, _stream(stream)))
 
 
 def la_verify_sample(logits_cur, logits_cand, cand_tokens, u_test, u_final, temperature, N, G, V, out_tokens,

@@ -392,6 +392,30 @@ la_status la_verify_step(const float* logits_cur, const float* logits_look, cons
                                   n_out, best, new_window, accept_len, (hipStream_t)stream);
 }
 
+la_status la_verify_step_batch(const la_verify_desc* descs, int n_descs, int W, int N, int G, int V, void* stream)
+{
+    const char* name = "la_verify_step_batch";
+    if (n_descs < 1 || n_descs > 1024 || !descs)
+        return la::fail(LA_EINVAL, "%s: need 1..1024 descriptors (got %d)", name, n_descs);
+    if (W < 0 || G < 0 || N < 2 || V < 1)
+        return la::fail(LA_EINVAL, "%s: need W >= 0, G >= 0, N >= 2, V >= 1 (got W=%d G=%d N=%d V=%d)", name, W, G,
+                        N, V);
+    la::VerifySeq v[1024];
+    for (int i = 0; i < n_descs; ++i) {
+        const la_verify_desc& d = descs[i];
+        if (!d.logits_cur || !d.out_tokens || !d.n_out || !d.best || (W > 0 && (!d.logits_look || !d.new_window)) ||
+            (G > 0 && (!d.logits_cand || !d.cand_tokens)))
+            return la::fail(LA_EINVAL, "%s: descriptor %d: null pointer", name, i);
+        if (((uintptr_t)d.logits_cur | (uintptr_t)d.logits_look | (uintptr_t)d.logits_cand |
+             (uintptr_t)d.cand_tokens | (uintptr_t)d.out_tokens | (uintptr_t)d.n_out | (uintptr_t)d.best |
+             (uintptr_t)d.new_window | (uintptr_t)d.accept_len) & 3)
+            return la::fail(LA_EINVAL, "%s: descriptor %d: buffers must be 4-byte aligned", name, i);
+        v[i] = la::VerifySeq{d.logits_cur, d.logits_look, d.logits_cand, d.cand_tokens, d.out_tokens,
+                             d.n_out,      d.best,        d.new_window,  d.accept_len};
+    }
+    return la::launch_verify_step_batch(v, n_descs, W, N, G, V, (hipStream_t)stream);
+}
+
 la_status la_verify_sample(const float* logits_cur, const float* logits_cand, const int* cand_tokens,
                            const float* u_test, const float* u_final, float temperature, int N, int G, int V,
                            int* out_tokens, int* n_out, void* stream)
@@ -423,6 +447,6 @@ void la_shutdown(void) { la::free_workspaces(); }
 
 const char* la_last_error(void) { return la::g_error; }
 
-int la_version(void) { return 1008; }
+int la_version(void) { return 1009; }
 
 }  // extern "C"

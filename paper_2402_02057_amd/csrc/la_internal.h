@@ -25,6 +25,20 @@ la_status launch_verify(const float* logits, const int* cand_tokens, int G, int 
 la_status launch_verify_step(const float* logits_cur, const float* logits_look, const float* logits_cand,
                              const int* cand_tokens, int W, int N, int G, int V, int* out_tokens, int* n_out,
                              int* best, int* new_window, int* accept_len, hipStream_t stream);
+// One sequence of a batched la_verify_step (pointers as for launch_verify_step).
+struct VerifySeq {
+    const float* logits_cur;
+    const float* logits_look;
+    const float* logits_cand;
+    const int* cand_tokens;
+    int* out_tokens;
+    int* n_out;
+    int* best;
+    int* new_window;
+    int* accept_len;
+};
+la_status launch_verify_step_batch(const VerifySeq* seqs, int n_seqs, int W, int N, int G, int V,
+                                   hipStream_t stream);
 la_status launch_verify_sample(const float* logits_cur, const float* logits_cand, const int* cand_tokens,
                                const float* u_test, const float* u_final, float temperature, int N, int G,
                                int V, int* out_tokens, int* n_out, hipStream_t stream);

@@ -192,14 +192,13 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(
 // tokens, 1 + W + g*n1 + k = output at candidate g's token k.  blockIdx.x = r * nseg + segment.
 // keys: one per row; l1: one counter per `fan` workgroups; l2: one counter.
 template <bool kVec>
-__global__ __launch_bounds__(kThreads) void verify_step_kernel(
+__device__ __forceinline__ void verify_step_body(
     const float* __restrict__ logits_cur, const float* __restrict__ logits_look,
     const float* __restrict__ logits_cand, const int* __restrict__ cand_tokens, int W, int n1, int G, int V,
     int seg_len, int nseg, int rows, unsigned fan, unsigned long long* keys, unsigned* l1, unsigned* l2,
     int* __restrict__ out_tokens, int* __restrict__ n_out, int* __restrict__ best_out,
-    int* __restrict__ new_window, int* __restrict__ accept_len)
+    int* __restrict__ new_window, int* __restrict__ accept_len, int* tok)
 {
-    extern __shared__ int tok[];  // rows greedy tokens, then one packed result per wave
     const int row = blockIdx.x / nseg;
     const int seg = blockIdx.x - row * nseg;
     const int v0 = seg * seg_len;
@@ -281,6 +280,55 @@ __global__ __launch_bounds__(kThreads) void verify_step_kernel(
         *best_out = best;
         if (gridDim.x > fan) atomicExch(l2, 0u);
     }
+}
+
+template <bool kVec>
+__global__ __launch_bounds__(kThreads) void verify_step_kernel(
+    const float* __restrict__ logits_cur, const float* __restrict__ logits_look,
+    const float* __restrict__ logits_cand, const int* __restrict__ cand_tokens, int W, int n1, int G, int V,
+    int seg_len, int nseg, int rows, unsigned fan, unsigned long long* keys, unsigned* l1, unsigned* l2,
+    int* __restrict__ out_tokens, int* __restrict__ n_out, int* __restrict__ best_out,
+    int* __restrict__ new_window, int* __restrict__ accept_len)
+{
+    extern __shared__ int tok[];  // rows greedy tokens
+    verify_step_body<kVec>(logits_cur, logits_look, logits_cand, cand_tokens, W, n1, G, V, seg_len, nseg, rows, fan,
+                           keys, l1, l2, out_tokens, n_out, best_out, new_window, accept_len, tok);
+}
+
+// The ends of several sequences' steps in one launch: blockIdx.y names the sequence, blockIdx.x
+// the row segment as above; every sequence has its own keys and counters in the workspace
+// (ws_stride bytes apart) and its own last workgroup.  What differs between sequences travels
+// as a kernel argument, kVerifyBatch of them at a time.
+constexpr int kVerifyBatch = 32;
+struct VerifyOne {
+    const float* logits_cur;
+    const float* logits_look;
+    const float* logits_cand;
+    const int* cand_tokens;
+    int* out_tokens;
+    int* n_out;
+    int* best;
+    int* new_window;
+    int* accept_len;
+};
+struct VerifyBatchParams {
+    VerifyOne one[kVerifyBatch];
+    unsigned char* ws;
+    size_t ws_stride, l1_offset, l2_offset;
+    int W, n1, G, V, seg_len, nseg, rows;
+    unsigned fan;
+};
+
+template <bool kVec>
+__global__ __launch_bounds__(kThreads) void verify_step_batch_kernel(VerifyBatchParams b)
+{
+    extern __shared__ int tok[];
+    const VerifyOne& o = b.one[blockIdx.y];
+    unsigned char* ws = b.ws + (size_t)blockIdx.y * b.ws_stride;
+    verify_step_body<kVec>(o.logits_cur, o.logits_look, o.logits_cand, o.cand_tokens, b.W, b.n1, b.G, b.V, b.seg_len,
+                           b.nseg, b.rows, b.fan, (unsigned long long*)ws, (unsigned*)(ws + b.l1_offset),
+                           (unsigned*)(ws + b.l2_offset), o.out_tokens, o.n_out, o.best, o.new_window, o.accept_len,
+                           tok);
 }
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -695,6 +743,50 @@ la_status launch_verify_step(const float* logits_cur, const float* logits_look, 
                            (int)rows, fan, keys, l1, l2, out_tokens, n_out, best, new_window, accept_len);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(LA_EHIP, "la_verify_step launch: %s", hipGetErrorString(e));
+    return LA_OK;
+}
+
+la_status launch_verify_step_batch(const VerifySeq* seqs, int n_seqs, int W, int N, int G, int V,
+                                   hipStream_t stream)
+{
+    const int n1 = N - 1;
+    const long long rows = 1ll + W + (long long)G * n1;
+    int nseg = (V + kMaxSeg - 1) / kMaxSeg;
+    int seg_len = (V + nseg - 1) / nseg;
+    seg_len = (seg_len + 3) & ~3;
+    nseg = (V + seg_len - 1) / seg_len;
+    const long long blocks = rows * nseg;
+    if (rows > 12 * 1024 || blocks > 0x7fffffffll)
+        return fail(LA_EUNSUPPORTED, "la_verify_step_batch: %lld rows is too many", rows);
+    const unsigned fan = blocks <= 128 ? (unsigned)blocks : 8u;
+    const size_t n_groups = (size_t)((blocks + fan - 1) / fan);
+    // per sequence: one 64-bit key per row, one counter per `fan` workgroups, one more counter
+    const size_t l1_offset = (size_t)rows * 8, l2_offset = l1_offset + n_groups * 4;
+    const size_t ws_stride = (l2_offset + 4 + 7) & ~(size_t)7;
+    for (int i0 = 0; i0 < n_seqs; i0 += kVerifyBatch) {
+        const int n = n_seqs - i0 < kVerifyBatch ? n_seqs - i0 : kVerifyBatch;
+        VerifyBatchParams b;
+        bool vec = V % 4 == 0;
+        for (int i = 0; i < n; ++i) {
+            const VerifySeq& q = seqs[i0 + i];
+            b.one[i] = VerifyOne{q.logits_cur, q.logits_look, q.logits_cand, q.cand_tokens, q.out_tokens,
+                                 q.n_out,      q.best,        q.new_window,  q.accept_len};
+            vec = vec && ((((uintptr_t)q.logits_cur | (uintptr_t)q.logits_look | (uintptr_t)q.logits_cand) & 15) == 0);
+        }
+        for (int i = n; i < kVerifyBatch; ++i) b.one[i] = b.one[0];  // never indexed: the grid has n layers
+        // (launches on one stream run in order, so they can share the workspace)
+        b.ws = (unsigned char*)zeroed_workspace(ws_stride * (size_t)n, stream);
+        if (!b.ws) return LA_ENOMEM;
+        b.ws_stride = ws_stride; b.l1_offset = l1_offset; b.l2_offset = l2_offset;
+        b.W = W; b.n1 = n1; b.G = G; b.V = V; b.seg_len = seg_len; b.nseg = nseg; b.rows = (int)rows;
+        b.fan = fan;
+        const size_t lds = (size_t)rows * sizeof(int);
+        const dim3 grid((unsigned)blocks, (unsigned)n);
+        if (vec) hipLaunchKernelGGL(verify_step_batch_kernel<true>, grid, dim3(kThreads), lds, stream, b);
+        else hipLaunchKernelGGL(verify_step_batch_kernel<false>, grid, dim3(kThreads), lds, stream, b);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(LA_EHIP, "la_verify_step_batch launch: %s", hipGetErrorString(e));
+    }
     return LA_OK;
 }
 

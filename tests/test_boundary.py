@@ -153,6 +153,28 @@ def test_commit_batch_reports_argument_errors_without_a_gpu(lib):
     assert rc == -1 and b"n_pages" in lib.la_last_error()
 
 
+def test_verify_step_batch_reports_argument_errors_without_a_gpu(lib):
+    import ctypes
+    A = 4096
+    d = (binding.VerifyDesc * 2)()
+    for x in d:
+        for name, _ in binding.VerifyDesc._fields_:
+            setattr(x, name, A)
+    ptr = ctypes.cast(d, ctypes.c_void_p)
+    assert lib.la_verify_step_batch(ptr, 0, 1, 3, 1, 10, None) == -1
+    assert lib.la_verify_step_batch(None, 2, 1, 3, 1, 10, None) == -1
+    assert lib.la_verify_step_batch(ptr, 2, 1, 1, 1, 10, None) == -1 and b"N >= 2" in lib.la_last_error()
+    d[1].best = None
+    rc = lib.la_verify_step_batch(ptr, 2, 1, 3, 1, 10, None)
+    assert rc == -1 and b"descriptor 1" in lib.la_last_error() and b"null" in lib.la_last_error()
+    d[1].best = A
+    d[0].logits_cand = A + 2
+    rc = lib.la_verify_step_batch(ptr, 2, 1, 3, 1, 10, None)
+    assert rc == -1 and b"descriptor 0" in lib.la_last_error() and b"aligned" in lib.la_last_error()
+    d[0].logits_cand = None                  # allowed without candidates only
+    assert lib.la_verify_step_batch(ptr, 2, 1, 3, 1, 10, None) == -1
+
+
 def test_workspace_query(lib):
     assert binding.la_step_attention_workspace_bytes(1024, 15, 5, 15, 32, 32, 128) > 0
     assert binding.la_step_attention_workspace_bytes(0, 0, 2, 0, 1, 1, 128) == 0
