@@ -111,3 +111,40 @@ def test_sampling_loop_at_vanishing_temperature_is_greedy():
     dec = lookahead.LookaheadDecoder(lookahead.ToyAttentionLM(seed), prompt, 6, 4, 6, seed=seed, temperature=0.02)
     assert dec.generate(300) == ref.greedy_decode(ref.ToyModel(seed), prompt, 300)
     assert 300 / dec.steps > 1.5
+
+
+@pytest.mark.parametrize("W,N,G", [(5, 4, 5), (0, 3, 3), (3, 3, 0), (15, 5, 15)])
+def test_batched_loop_moves_every_sequence_as_it_would_alone(W, N, G):
+    """Several sequences through the batched entry points (one launch per operation and step):
+    each one's trace equals the oracle loop's for that sequence alone, step by step - the padding
+    of the candidate lists to a common count changes nothing."""
+    print("case", dict(W=W, N=N, G=G), flush=True)
+    seed, n_seq, n_tokens = 5, 5, 80
+    prompts = [[0, 3 + i, 7, 3 + i] for i in range(n_seq)]
+    prompts[2] = [0]                                      # a sequence that starts with an empty cache
+    seeds = [10 + i for i in range(n_seq)]
+    cpu = ref.ToyModel(seed)
+    want = [ref.lookahead_decode(cpu, p, W, N, G, n_tokens, seed=sd) for p, sd in zip(prompts, seeds)]
+    dec = lookahead.BatchedLookaheadDecoder(lookahead.ToyBatchLM(seed, n_seq, max_len=1024), prompts, W, N, G,
+                                            seeds=seeds)
+    got = [[] for _ in range(n_seq)]
+    for step in range(max(w[1] for w in want)):
+        for i, (accepted, tokens, best, new) in enumerate(dec.step()):
+            trace = want[i][2]
+            if step < len(trace):                         # (a sequence that is done keeps stepping with the others)
+                rec = trace[step]
+                assert (tokens, accepted, best, new) == (rec["tokens"], rec["accepted"], rec["best"], rec["window"]), \
+                    (i, step)
+            got[i].extend(accepted)
+    for i in range(n_seq):
+        assert got[i][:n_tokens] == want[i][0] == ref.greedy_decode(cpu, prompts[i], n_tokens)
+
+
+def test_batched_long_run_is_lossless():
+    seed, n_seq = 6, 8
+    prompts = [[0, 5 + i, 9] for i in range(n_seq)]
+    dec = lookahead.BatchedLookaheadDecoder(lookahead.ToyBatchLM(seed, n_seq, max_len=2048), prompts, 7, 5, 7)
+    got = dec.generate(600)                               # prefixes grow across many pages
+    cpu = ref.ToyModel(seed)
+    for i in range(n_seq):
+        assert got[i] == ref.greedy_decode(cpu, prompts[i], 600)
