@@ -1078,9 +1078,37 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
     }
 }
 
-template <int D, int RT, int KS, int KC, int NSTAGE, bool PAGED = false, bool ROWSET = false>
-__global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnParams p)
+// Kernel arguments are read through the scalar cache, which every launch finds empty; the compiler
+// loads a field shortly before its first use, so the way to the first request to memory led
+// through several such misses one after the other.  Here every 64-byte line of the arguments is
+// touched at once - one miss - and the pointer the kernel then reads its arguments through is an
+// output of that statement, so that no such read can be moved ahead of it.  Plain scalar loads,
+// waited for on the spot.  `offset`: where in the argument segment the T sits (the kernel's own
+// parameter only gives the segment its layout).
+template <class T>
+__device__ __forceinline__ const T& warmed_arguments(unsigned offset = 0)
 {
+    typedef const char __attribute__((address_space(4))) * kernarg_ptr;
+    kernarg_ptr k = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr() + offset;
+    constexpr unsigned bytes = (unsigned)sizeof(T);
+    static_assert(bytes <= 256, "four lines per statement");
+    unsigned d0, d1, d2, d3;
+    asm volatile(
+        "s_load_dword %0, %4, 0x0\n\t"
+        "s_load_dword %1, %4, %5\n\t"
+        "s_load_dword %2, %4, %6\n\t"
+        "s_load_dword %3, %4, %7\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&s"(d0), "=&s"(d1), "=&s"(d2), "=&s"(d3), "+s"(k)
+        : "s"(bytes > 64 ? 64u : 0u), "s"(bytes > 128 ? 128u : 0u), "s"(bytes > 192 ? 192u : bytes - 4u)
+        : "memory");
+    return *(const T*)k;
+}
+
+template <int D, int RT, int KS, int KC, int NSTAGE, bool PAGED = false, bool ROWSET = false>
+__global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnParams)
+{
+    const AttnParams& p = warmed_arguments<AttnParams>();
     step_attention_body<D, RT, KS, KC, NSTAGE, PAGED, ROWSET>(p, (int)(blockIdx.x & 7), (int)(blockIdx.x >> 3));
 }
 
@@ -1088,21 +1116,27 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnP
 // slot0[i] .. slot0[i+1]-1.  Workgroups are handed out in id order, so the steps start in the
 // order given (longest first) and the tail of one overlaps the head of the next.
 constexpr int kMaxBatch = 16;
-struct BatchParams {
-    AttnParams seq[kMaxBatch];
+struct BatchSlots {
     int slot0[kMaxBatch + 1];
     int n;
 };
+struct BatchParams {
+    AttnParams seq[kMaxBatch];
+    BatchSlots slots;
+};
 
 template <int D, int RT, int KS, int KC, int NSTAGE, bool PAGED = false>
-__global__ __launch_bounds__(RT* KS * 64) void step_attention_batch_kernel(const BatchParams bp)
+__global__ __launch_bounds__(RT* KS * 64) void step_attention_batch_kernel(const BatchParams)
 {
+    // two misses of the scalar cache: the slot table, then the arguments of this workgroup's step
+    const BatchSlots& sl = warmed_arguments<BatchSlots>((unsigned)offsetof(BatchParams, slots));
     const int slot = (int)(blockIdx.x >> 3);
     int i = 0;
 #pragma unroll
     for (int k = 1; k < kMaxBatch; ++k)
-        if (k < bp.n && slot >= bp.slot0[k]) i = k;
-    step_attention_body<D, RT, KS, KC, NSTAGE, PAGED>(bp.seq[i], (int)(blockIdx.x & 7), slot - bp.slot0[i]);
+        if (k < sl.n && slot >= sl.slot0[k]) i = k;
+    const AttnParams& p = warmed_arguments<AttnParams>((unsigned)i * (unsigned)sizeof(AttnParams));
+    step_attention_body<D, RT, KS, KC, NSTAGE, PAGED>(p, (int)(blockIdx.x & 7), slot - sl.slot0[i]);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1460,7 +1494,7 @@ la_status launch_step_attention_batch(const BatchSeq* seqs, int n_seqs, int page
         long long target = (work + wgs - 1) / wgs;   // chunks per workgroup
         if (target < 4) target = 4;
         BatchParams bp;
-        bp.n = n;
+        bp.slots.n = n;
         size_t partial_bytes = 0, ticket_count = 0;
         int slot = 0;
         for (int i = 0; i < n; ++i) {
@@ -1477,14 +1511,14 @@ la_status launch_step_attention_batch(const BatchSeq* seqs, int n_seqs, int page
                                               d.P > 0 ? d.block_table : nullptr, page_size, n_pages, nullptr, T,
                                               d.step_k, d.step_v, d.P, W, N, G, heads, kv_heads, head_dim, d.out);
             if (st != LA_OK) return st;
-            bp.slot0[i] = slot;
+            bp.slots.slot0[i] = slot;
             slot += bp.seq[i].wg_per_xcd;
             if (q.XS > 1) {
                 partial_bytes += (size_t)bp.seq[i].total_wg * q.partial_bytes_per_wg;
                 ticket_count += (size_t)kv_heads * n_row_blocks;
             }
         }
-        for (int i = n; i <= kMaxBatch; ++i) bp.slot0[i] = slot;
+        for (int i = n; i <= kMaxBatch; ++i) bp.slots.slot0[i] = slot;
         if (partial_bytes) {
             unsigned* tickets = (unsigned*)zeroed_workspace(ticket_count * sizeof(unsigned), stream);
             unsigned char* partials = (unsigned char*)scratch_workspace(partial_bytes);
