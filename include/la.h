@@ -42,7 +42,9 @@
  * different streams of the same device must not overlap in time.  The calls may
  * be recorded into a HIP graph once a call of the same (or a larger) shape has
  * run outside the capture: that one sizes and clears the workspace, the kernels
- * leave it cleared.
+ * leave it cleared.  A workspace block that a later, larger call replaces stays
+ * allocated until la_shutdown, so graphs recorded before remain valid (do not
+ * call la_shutdown while such a graph may still be launched).
  *
  * Errors are returned, never thrown; on error nothing has been launched.
  */

@@ -5,6 +5,7 @@
 #include <stdio.h>
 
 #include <mutex>
+#include <vector>
 
 #include "la_internal.h"
 
@@ -28,6 +29,9 @@ struct Pool {
     size_t zeroed_bytes = 0;
     void* scratch = nullptr;
     size_t scratch_bytes = 0;
+    // Blocks that a growth replaced.  They are kept until la_shutdown: work already issued, and
+    // HIP graphs recorded earlier, still name them (and no call has to wait for the device).
+    std::vector<void*> retired;
 };
 Pool g_pools[kMaxDevices];
 std::mutex g_mutex;
@@ -49,9 +53,8 @@ void* zeroed_workspace(size_t bytes, hipStream_t stream)
     Pool* p = current_pool();
     if (!p) return nullptr;
     if (bytes <= p->zeroed_bytes) return p->zeroed;
-    // Growing: earlier work that still uses the old block has been issued to a stream; wait
-    // for the device to drain before freeing it.  This happens only when a larger shape
-    // than any before is seen.
+    // Growing (only when a larger shape than any before is seen): a fresh block, cleared on
+    // this stream ahead of the kernel that will use it; the old one is retired, not freed.
     size_t want = bytes < (1u << 16) ? (1u << 16) : bytes;
     void* fresh = nullptr;
     if (hipMalloc(&fresh, want) != hipSuccess) {
@@ -63,10 +66,7 @@ void* zeroed_workspace(size_t bytes, hipStream_t stream)
         fail(LA_EHIP, "hipMemsetAsync on the ticket workspace failed");
         return nullptr;
     }
-    if (p->zeroed) {
-        (void)hipDeviceSynchronize();
-        (void)hipFree(p->zeroed);
-    }
+    if (p->zeroed) p->retired.push_back(p->zeroed);
     p->zeroed = fresh;
     p->zeroed_bytes = want;
     return fresh;
@@ -84,10 +84,7 @@ void* scratch_workspace(size_t bytes)
         fail(LA_ENOMEM, "hipMalloc of %zu bytes of partial-result workspace failed", want);
         return nullptr;
     }
-    if (p->scratch) {
-        (void)hipDeviceSynchronize();
-        (void)hipFree(p->scratch);
-    }
+    if (p->scratch) p->retired.push_back(p->scratch);
     p->scratch = fresh;
     p->scratch_bytes = want;
     return fresh;
@@ -100,11 +97,12 @@ void free_workspaces()
     (void)hipGetDevice(&saved);
     for (int d = 0; d < kMaxDevices; ++d) {
         Pool& p = g_pools[d];
-        if (!p.zeroed && !p.scratch) continue;
+        if (!p.zeroed && !p.scratch && p.retired.empty()) continue;
         if (hipSetDevice(d) != hipSuccess) continue;
         (void)hipDeviceSynchronize();
         if (p.zeroed) (void)hipFree(p.zeroed);
         if (p.scratch) (void)hipFree(p.scratch);
+        for (void* block : p.retired) (void)hipFree(block);
         p = Pool();
     }
     (void)hipSetDevice(saved);

@@ -90,3 +90,69 @@ def test_replays_equal_eager_calls():
         assert torch.equal(kcap.view(torch.int16), want_cache.view(torch.int16)), replay
         assert int(eager["n_out"].item()) >= 2
         del scratch
+
+
+def test_a_recorded_graph_survives_the_growth_of_the_workspace():
+    """A graph names the workspace blocks of the time it was recorded.  Larger calls afterwards
+    make the library allocate bigger blocks; the old ones must stay valid (and clean) for the
+    graph's replays."""
+    torch.cuda.synchronize()
+    binding.la_shutdown()                       # start from an empty workspace
+    s = wl.LLAMA2_7B
+    W, N, G, V, H, KV, d, P, T = s.W, s.N, s.G, s.V, s.heads, s.kv_heads, s.head_dim, s.P, s.T
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(11)
+
+    def rb(*shape):
+        return torch.randn(shape, device="cuda", generator=gen).bfloat16()
+    q, kc, vc, sk, sv = rb(T, H, d), rb(KV, P, d), rb(KV, P, d), rb(T, KV, d), rb(T, KV, d)
+    logits = [torch.randn(shape, device="cuda", generator=gen) for shape in ((V,), (W, V), (G, N - 1, V))]
+    cand = torch.randint(0, V, (G, N - 1), device="cuda", generator=gen, dtype=torch.int32)
+    i32 = dict(dtype=torch.int32, device="cuda")
+
+    def outputs():
+        return [torch.empty((T, H, d), dtype=torch.bfloat16, device="cuda"), torch.empty(N, **i32), torch.empty(1, **i32),
+                torch.empty(1, **i32), torch.empty(W, **i32), torch.empty(G, **i32)]
+
+    def calls(o):
+        binding.la_step_attention(q, kc, vc, sk, sv, P, W, N, G, H, KV, d, o[0])
+        binding.la_verify_step(*logits, cand, W, N, G, V, *o[1:])
+
+    eager = outputs()
+    calls(eager)
+    torch.cuda.synchronize()
+    captured = outputs()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        calls(captured)
+    before = binding.la_step_attention_workspace_bytes(P, W, N, G, H, KV, d)
+
+    # partial results of a much longer step, and the keys of 32 wide verification steps at once
+    P2, W2 = 16000, 30
+    T2 = 1 + 2 * W2 * (N - 1)
+    assert binding.la_step_attention_workspace_bytes(P2, W2, N, W2, 64, 8, d) > max(before, 8 << 20)
+    big = torch.empty((T2, 64, d), dtype=torch.bfloat16, device="cuda")
+    binding.la_step_attention(rb(T2, 64, d), rb(8, P2, d), rb(8, P2, d), rb(T2, 8, d), rb(T2, 8, d), P2, W2, N, W2, 64, 8,
+                              d, big)
+    Wv, Gv, Vv = 1500, 1500, 16
+    seqs = [dict(logits_cur=torch.randn(Vv, device="cuda", generator=gen),
+                 logits_look=torch.randn(Wv, Vv, device="cuda", generator=gen),
+                 logits_cand=torch.randn(Gv, N - 1, Vv, device="cuda", generator=gen),
+                 cand_tokens=torch.randint(0, Vv, (Gv, N - 1), device="cuda", generator=gen, dtype=torch.int32),
+                 out_tokens=torch.empty(N, **i32), n_out=torch.empty(1, **i32), best=torch.empty(1, **i32),
+                 new_window=torch.empty(Wv, **i32)) for _ in range(32)]
+    binding.la_verify_step_batch(seqs, Wv, N, Gv, Vv)          # 32 x 7501 keys: beyond the first block
+    torch.cuda.synchronize()
+
+    for replay in range(3):
+        for t in (q, sk, sv):
+            t.copy_(torch.randn(t.shape, device="cuda", generator=gen).bfloat16())
+        logits[0].copy_(torch.randn(V, device="cuda", generator=gen))
+        calls(eager)                                           # (uses the new blocks)
+        graph.replay()                                         # (uses the old ones)
+        torch.cuda.synchronize()
+        assert torch.equal(eager[0].view(torch.int16), captured[0].view(torch.int16)), replay
+        n = int(eager[2].item())
+        assert int(captured[2].item()) == n and torch.equal(eager[1][:n], captured[1][:n]), replay
+        for a, b in zip(eager[3:], captured[3:]):
+            assert torch.equal(a, b), replay
