@@ -8,6 +8,9 @@ cache after any run of lookahead steps equals the cache of plain autoregressive 
 parallelism), dense numpy with the explicit mask, pinned by equality with the full step on closed
 subsets.  `gather_pages` / `kv_commit_paged` define what a paged cache stands for (pinned as the inverse of
 a scatter written in the test, and against the packed append).
+`step_rope` rotates the step's queries and keys by the positions of Fig. 2(b) (rotary position
+embedding written out pair by pair in fp64); pins: the printed digits, norms, the dependence of a
+score on the distance only, a quarter turn, and complex multiplication.
 """
 import ctypes
 
@@ -272,3 +275,38 @@ def step_attention_rows(q, k_cache, v_cache, step_k, step_v, row_ids, P, W, N, G
 
 def bf16_to_f64(bits):
     return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def step_rope(q, step_k, cos, sin, P, W, N, G, interleaved=False):
+    """Rotary position embedding of a step's queries and keys at the positions the step's tokens
+    hold: row r sits at P + position(r), the relative positions being the digits printed on the
+    tokens of Fig. 2(b) (current token 0, lookahead token of level l and column j at 1 + l + j,
+    candidate token k at 1 + k; Sec. 3.1 and 3.3).  The rotation itself is the published one: the
+    head dimension is cut into d/2 pairs, pair i of a vector at position t turns by the angle whose
+    cosine and sine are cos[t, i], sin[t, i]:
+        (a, b) -> (a cos - b sin, b cos + a sin).
+    Pair i is (x[i], x[i + d/2]), or (x[2i], x[2i + 1]) with `interleaved`.
+
+    q [T, heads, d], step_k [T, kv_heads, d]: float arrays (any float dtype); cos, sin
+    [max_pos, d/2].  Returns the rotated (q, step_k) in float64; nothing is rounded here.
+    """
+    T = num_rows(W, N, G)
+    out = []
+    for x in (q, step_k):
+        x = np.asarray(x, dtype=np.float64)
+        assert x.shape[0] == T and x.shape[2] % 2 == 0
+        half = x.shape[2] // 2
+        y = np.empty_like(x)
+        for r in range(T):
+            t = P + position(r, W, N, G)
+            c, s_ = np.asarray(cos[t], dtype=np.float64), np.asarray(sin[t], dtype=np.float64)
+            assert c.shape == (half,)
+            for h in range(x.shape[1]):
+                for i in range(half):
+                    ia, ib = (2 * i, 2 * i + 1) if interleaved else (i, i + half)
+                    a, b = x[r, h, ia], x[r, h, ib]
+                    y[r, h, ia] = a * c[i] - b * s_[i]
+                    y[r, h, ib] = b * c[i] + a * s_[i]
+        out.append(y)
+    return out[0], out[1]
+

@@ -271,3 +271,12 @@ def uniform_draw(seed, step, index):
     h = (h * 0xD6E8FEB86659FD93) % (1 << 64)
     h ^= h >> 32
     return np.float32((h >> 40) / float(1 << 24))
+
+
+def rope_tables(max_pos, head_dim, base=10000.0):
+    """cos, sin fp32 [max_pos, head_dim / 2] of rotary position embedding: entry [t, i] belongs to
+    the angle t * base^(-2 i / head_dim).  Inputs like weights: a model brings its own tables."""
+    i = np.arange(head_dim // 2, dtype=np.float64)
+    angle = np.arange(max_pos, dtype=np.float64)[:, None] * base ** (-2.0 * i / head_dim)[None, :]
+    return np.cos(angle).astype(np.float32), np.sin(angle).astype(np.float32)
+
