@@ -226,6 +226,30 @@ def main():
         kc_ms.append(e[0].elapsed_time(e[1]) / kc_calls)
     kv_commit_us = float(np.median(kc_ms)) * 1e3
 
+    # rotary position embedding of the step's q and keys at the step's positions (la_step_rope), on
+    # copies, timed on its own (its parity with the oracle is a GPU test: tests/test_gpu_rope.py)
+    rope_q, rope_k = layers[0]["q"].clone(), layers[0]["step_k"].clone()
+    rope_cos, rope_sin = [torch.from_numpy(x).cuda() for x in wl.rope_tables(P + s.W + s.N, d)]
+
+    def rope():
+        binding.la_step_rope(rope_q, rope_k, rope_cos, rope_sin, P, s.W, s.N, s.G, H, KV, d)
+    rope()
+    run_r, r_calls = rope, 1
+    if use_graph:
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            for _ in range(32):
+                rope()
+        run_r, r_calls = gr.replay, 32
+    r_ms = []
+    for _ in range(reps):
+        e[0].record()
+        run_r()
+        e[1].record()
+        torch.cuda.synchronize()
+        r_ms.append(e[0].elapsed_time(e[1]) / r_calls)
+    rope_us = float(np.median(r_ms)) * 1e3
+
     # the ends of eight sequences' steps in ONE launch (la_verify_step_batch), timed on its own:
     # sequence 0 is the step above, the others are further seeded draws of the same shape
     vsb_h = [vs_h] + [wl.verify_step_inputs(s, extra) for extra in range(1, 8)]
@@ -423,6 +447,7 @@ def main():
                               "gbs": len(vsb) * verify_step_bytes / (verify_step_batch_us * 1e-6) / 1e9,
                               "frac_of_hbm_peak": len(vsb) * verify_step_bytes / (verify_step_batch_us * 1e-6) / 1e9
                               / HBM_PEAK_GBS},
+        "rope": {"us": rope_us, "algorithmic_bytes": 2 * (T * H * d + T * KV * d) * 2},
         "kv_commit": {"us": kv_commit_us, "rows": n_commit, "algorithmic_bytes": kv_commit_bytes},
         "kv_commit_batch": {"layers_per_launch": L, "us_per_launch": kv_commit_batch_us,
                             "us_per_layer": kv_commit_batch_us / L},

@@ -82,6 +82,27 @@ la_status la_step_attention(const void* q, const void* k_cache, const void* v_ca
                             int heads, int kv_heads, int head_dim, void* out, void* stream);
 
 /*
+ * Rotary position embedding of a step's queries and keys, in place, at the positions the
+ * step's tokens hold: row r of the layout above sits at P + (its relative position, the
+ * digit printed on the token in Fig. 2(b)).  Run it on the projected q and step_k before
+ * la_step_attention*; the keys la_kv_commit* appends afterwards are then the rotated ones,
+ * as the cache needs them (an accepted token keeps the position it was evaluated at,
+ * Sec. 3.3).  Pair i of a head turns by the angle whose cosine and sine are cos[t][i],
+ * sin[t][i], t the row's position: (a, b) -> (a cos - b sin, b cos + a sin), computed in fp32
+ * and rounded to bf16 once.
+ *
+ *   q            bf16 [T][heads][head_dim], in/out;  step_k  bf16 [T][kv_heads][head_dim], in/out
+ *   cos, sin     fp32 [max_pos][head_dim/2] on the device (the model's tables)
+ *   max_pos      positions the tables hold; the step reaches P + max(W + N - 2, N - 1)
+ *   interleaved  0: pair i is (x[i], x[i + head_dim/2]);  nonzero: (x[2i], x[2i + 1])
+ *   head_dim: a multiple of 16 up to 1024.  All four pointers 16-byte aligned.
+ * A separate pass rather than part of the attention kernel: there every row block and every
+ * head of a group would rotate the same keys again.
+ */
+la_status la_step_rope(void* q, void* step_k, const float* cos, const float* sin, int max_pos, int P, int W, int N,
+                       int G, int heads, int kv_heads, int head_dim, int interleaved, void* stream);
+
+/*
  * The same step over a cache allocated for more keys than it holds, as a decoding loop keeps
  * it (rows are appended in place, see la_kv_commit):
  *   k_cache, v_cache  bf16 [kv_heads][capacity][head_dim]; rows 0..P-1 of every head are the

@@ -65,6 +65,8 @@ def load():
     lib.la_step_attention_cap.restype = i
     lib.la_kv_commit.argtypes = [p, p, ll, p, p, i, i, i, i, i, i, p, p, p]
     lib.la_kv_commit.restype = i
+    lib.la_step_rope.argtypes = [p, p, p, p, i, i, i, i, i, i, i, i, i, p]
+    lib.la_step_rope.restype = i
     lib.la_verify_step_batch.argtypes = [p, i, i, i, i, i, p]
     lib.la_verify_step_batch.restype = i
     lib.la_kv_commit_batch.argtypes = [p, i, i, i, i, i, i, i, i, p]
@@ -97,7 +99,7 @@ def load():
     return lib
 
 
-EXPORTS = ("la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_kv_commit_batch", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_step_batch", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown",
+EXPORTS = ("la_step_rope", "la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_kv_commit_batch", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_step_batch", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown",
            "la_last_error", "la_version")
 
 
@@ -167,6 +169,20 @@ def la_step_attention_cap(q, k_cache, v_cache, step_k, step_v, P, W, N, G, heads
         _ptr(out, bf, (T, heads, head_dim), "out"), _stream(stream))
     _check(rc)
     return out
+
+
+def la_step_rope(q, step_k, cos, sin, P, W, N, G, heads, kv_heads, head_dim, interleaved=False, stream=None):
+    """Rotate q [T, heads, d] and step_k [T, kv_heads, d] (bf16, in place) by the step's positions with
+    the fp32 tables cos, sin [max_pos, d/2]; asynchronous."""
+    T = 1 + (W + G) * (N - 1)
+    max_pos = int(cos.shape[0])
+    rc = load().la_step_rope(
+        _ptr(q, torch.bfloat16, (T, heads, head_dim), "q"),
+        _ptr(step_k, torch.bfloat16, (T, kv_heads, head_dim), "step_k"),
+        _ptr(cos, torch.float32, (max_pos, head_dim // 2), "cos"),
+        _ptr(sin, torch.float32, (max_pos, head_dim // 2), "sin"),
+        max_pos, P, W, N, G, heads, kv_heads, head_dim, 1 if interleaved else 0, _stream(stream))
+    _check(rc)
 
 
 def la_kv_commit(k_cache, v_cache, step_k, step_v, P, W, N, G, kv_heads, head_dim, best, n_out, stream=None):

@@ -356,6 +356,29 @@ la_status la_kv_commit_batch(const la_commit_desc* descs, int n_descs, int page_
                                       kv_heads, head_dim, (hipStream_t)stream);
 }
 
+la_status la_step_rope(void* q, void* step_k, const float* cos, const float* sin, int max_pos, int P, int W, int N,
+                       int G, int heads, int kv_heads, int head_dim, int interleaved, void* stream)
+{
+    if (P < 0 || W < 0 || G < 0 || N < 2 || heads < 1 || kv_heads < 1)
+        return la::fail(LA_EINVAL, "la_step_rope: need P,W,G >= 0, N >= 2, heads,kv_heads >= 1 "
+                                   "(got P=%d W=%d N=%d G=%d heads=%d kv_heads=%d)", P, W, N, G, heads, kv_heads);
+    if (head_dim < 16 || head_dim % 16 != 0 || head_dim > 1024)
+        return la::fail(LA_EUNSUPPORTED, "la_step_rope: head_dim %d is not a multiple of 16 in 16..1024", head_dim);
+    const long long T = 1 + (long long)(W + G) * (N - 1);
+    if (T > (1 << 20) || (long long)heads + kv_heads > (1 << 16) || (long long)P > (1ll << 30))
+        return la::fail(LA_EINVAL, "la_step_rope: step, heads or prefix too large");
+    // the furthest position of the step: the newest window level's last column, or a candidate's last token
+    const long long furthest = (long long)P + (W > 0 && W + N - 2 > N - 1 ? W + N - 2 : (W > 0 || G > 0 ? N - 1 : 0));
+    if (max_pos < 1 || furthest >= max_pos)
+        return la::fail(LA_EINVAL, "la_step_rope: the tables hold %d positions, the step reaches position %lld",
+                        max_pos, furthest);
+    if (!q || !step_k || !cos || !sin) return la::fail(LA_EINVAL, "la_step_rope: null pointer");
+    if (((uintptr_t)q | (uintptr_t)step_k | (uintptr_t)cos | (uintptr_t)sin) & 15)
+        return la::fail(LA_EINVAL, "la_step_rope: q, step_k and the tables must be 16-byte aligned");
+    return la::launch_step_rope(q, step_k, cos, sin, P, W, N, G, heads, kv_heads, head_dim, interleaved != 0,
+                                (hipStream_t)stream);
+}
+
 la_status la_verify(const float* logits, const int* cand_tokens, int G, int N, int V,
                     int* accept_len, int* accepted, void* stream)
 {
@@ -445,6 +468,6 @@ void la_shutdown(void) { la::free_workspaces(); }
 
 const char* la_last_error(void) { return la::g_error; }
 
-int la_version(void) { return 1009; }
+int la_version(void) { return 1010; }
 
 }  // extern "C"

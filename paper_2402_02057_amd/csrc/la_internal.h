@@ -84,6 +84,8 @@ struct CommitSeq {
 };
 la_status launch_kv_commit_batch(const CommitSeq* seqs, int n_seqs, int page_size, int n_pages, int W, int N,
                                  int G, int kv_heads, int head_dim, hipStream_t stream);
+la_status launch_step_rope(void* q, void* step_k, const float* cos, const float* sin, int P, int W, int N, int G,
+                           int heads, int kv_heads, int head_dim, int interleaved, hipStream_t stream);
 size_t step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int kv_heads,
                                       int head_dim);
 

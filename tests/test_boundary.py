@@ -175,6 +175,16 @@ def test_verify_step_batch_reports_argument_errors_without_a_gpu(lib):
     assert lib.la_verify_step_batch(ptr, 2, 1, 3, 1, 10, None) == -1
 
 
+def test_rope_reports_argument_errors_without_a_gpu(lib):
+    A = 4096
+    assert lib.la_step_rope(A, A, A, A, 64, 10, 1, 1, 1, 4, 4, 128, 0, None) == -1      # N < 2
+    assert lib.la_step_rope(A, A, A, A, 64, 10, 1, 3, 1, 4, 4, 72, 0, None) == -2       # head_dim % 16
+    rc = lib.la_step_rope(A, A, A, A, 12, 10, 3, 3, 1, 4, 4, 128, 0, None)              # reaches 10 + 4
+    assert rc == -1 and b"positions" in lib.la_last_error()
+    assert lib.la_step_rope(A, None, A, A, 64, 10, 1, 3, 1, 4, 4, 128, 0, None) == -1   # null
+    assert lib.la_step_rope(A, A, A + 4, A, 64, 10, 1, 3, 1, 4, 4, 128, 0, None) == -1  # misaligned table
+
+
 def test_workspace_query(lib):
     assert binding.la_step_attention_workspace_bytes(1024, 15, 5, 15, 32, 32, 128) > 0
     assert binding.la_step_attention_workspace_bytes(0, 0, 2, 0, 1, 1, 128) == 0
