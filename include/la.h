@@ -39,7 +39,8 @@
  * workspace per device (split partials, tickets), grown on demand with
  * hipMalloc - so the first call at a new size may allocate - and shared by
  * all calls on that device: calls issued to one stream are ordered; calls on
- * different streams of the same device must not overlap in time.  The calls may
+ * different streams of the same device must not overlap in time unless they use
+ * different workspace sets (la_select_workspace).  The calls may
  * be recorded into a HIP graph once a call of the same (or a larger) shape has
  * run outside the capture: that one sizes and clears the workspace, the kernels
  * leave it cleared.  A workspace block that a later, larger call replaces stays
@@ -345,6 +346,14 @@ long long la_step_attention_workspace_bytes(int P, int W, int N, int G, int head
 
 /* Free the per-device workspaces.  No call may be in flight.  Optional at exit. */
 void la_shutdown(void);
+
+/*
+ * Which of the library's 16 workspace sets (per device) the calling thread's next calls use;
+ * 0 until told otherwise.  Calls that may overlap in time on one device - issued to different
+ * streams - must use different sets; a HIP graph keeps the set that was selected when it was
+ * recorded.  A set costs memory only once it has been used.  LA_EINVAL outside 0..15.
+ */
+la_status la_select_workspace(int set);
 
 /* Host string describing the most recent error on this thread ("" if none). */
 const char* la_last_error(void);

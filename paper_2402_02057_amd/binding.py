@@ -93,13 +93,15 @@ def load():
     lib.la_shutdown.restype = None
     lib.la_last_error.argtypes = []
     lib.la_last_error.restype = ctypes.c_char_p
+    lib.la_select_workspace.argtypes = [i]
+    lib.la_select_workspace.restype = i
     lib.la_version.argtypes = []
     lib.la_version.restype = i
     _lib = lib
     return lib
 
 
-EXPORTS = ("la_step_rope", "la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_kv_commit_batch", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_step_batch", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown",
+EXPORTS = ("la_step_rope", "la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_kv_commit_batch", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_step_batch", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown", "la_select_workspace",
            "la_last_error", "la_version")
 
 
@@ -407,6 +409,12 @@ def la_step_attention_workspace_bytes(P, W, N, G, heads, kv_heads, head_dim):
 
 def la_shutdown():
     load().la_shutdown()
+
+
+def la_select_workspace(index):
+    """The calling thread's next calls use workspace set `index` (0..15): calls on different streams
+    that may overlap need different sets."""
+    _check(load().la_select_workspace(int(index)))
 
 
 def la_version():

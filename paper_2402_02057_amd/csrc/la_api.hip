@@ -33,7 +33,12 @@ struct Pool {
     // HIP graphs recorded earlier, still name them (and no call has to wait for the device).
     std::vector<void*> retired;
 };
-Pool g_pools[kMaxDevices];
+// Per device, a few independent sets of blocks.  A thread's calls use the set it selected
+// (la_select_workspace, set 0 unless told otherwise): calls that may overlap in time - on different
+// streams - must use different sets, calls on one stream run in order and share one.
+constexpr int kWorkspaceSets = 16;
+Pool g_pools[kMaxDevices][kWorkspaceSets];
+thread_local int g_set = 0;
 std::mutex g_mutex;
 
 Pool* current_pool()
@@ -43,9 +48,17 @@ Pool* current_pool()
         fail(LA_EHIP, "hipGetDevice failed or device index out of range");
         return nullptr;
     }
-    return &g_pools[dev];
+    return &g_pools[dev][g_set];
 }
 }  // namespace
+
+la_status select_workspace(int set)
+{
+    if (set < 0 || set >= kWorkspaceSets)
+        return fail(LA_EINVAL, "la_select_workspace: set %d is not in 0..%d", set, kWorkspaceSets - 1);
+    g_set = set;
+    return LA_OK;
+}
 
 void* zeroed_workspace(size_t bytes, hipStream_t stream)
 {
@@ -96,14 +109,17 @@ void free_workspaces()
     int saved = 0;
     (void)hipGetDevice(&saved);
     for (int d = 0; d < kMaxDevices; ++d) {
-        Pool& p = g_pools[d];
-        if (!p.zeroed && !p.scratch && p.retired.empty()) continue;
+        bool any = false;
+        for (const Pool& p : g_pools[d]) any = any || p.zeroed || p.scratch || !p.retired.empty();
+        if (!any) continue;
         if (hipSetDevice(d) != hipSuccess) continue;
         (void)hipDeviceSynchronize();
-        if (p.zeroed) (void)hipFree(p.zeroed);
-        if (p.scratch) (void)hipFree(p.scratch);
-        for (void* block : p.retired) (void)hipFree(block);
-        p = Pool();
+        for (Pool& p : g_pools[d]) {
+            if (p.zeroed) (void)hipFree(p.zeroed);
+            if (p.scratch) (void)hipFree(p.scratch);
+            for (void* block : p.retired) (void)hipFree(block);
+            p = Pool();
+        }
     }
     (void)hipSetDevice(saved);
 }
@@ -466,8 +482,10 @@ long long la_step_attention_workspace_bytes(int P, int W, int N, int G, int head
 
 void la_shutdown(void) { la::free_workspaces(); }
 
+la_status la_select_workspace(int set) { return la::select_workspace(set); }
+
 const char* la_last_error(void) { return la::g_error; }
 
-int la_version(void) { return 1010; }
+int la_version(void) { return 1011; }
 
 }  // extern "C"

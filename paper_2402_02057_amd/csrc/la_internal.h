@@ -18,6 +18,7 @@ la_status fail(la_status code, const char* fmt, ...);
 void* zeroed_workspace(size_t bytes, hipStream_t stream);
 void* scratch_workspace(size_t bytes);
 void free_workspaces();
+la_status select_workspace(int set);
 
 // Launchers (defined next to their kernels).
 la_status launch_verify(const float* logits, const int* cand_tokens, int G, int N, int V,

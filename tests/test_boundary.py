@@ -185,6 +185,13 @@ def test_rope_reports_argument_errors_without_a_gpu(lib):
     assert lib.la_step_rope(A, A, A + 4, A, 64, 10, 1, 3, 1, 4, 4, 128, 0, None) == -1  # misaligned table
 
 
+def test_workspace_sets_are_range_checked(lib):
+    assert lib.la_select_workspace(-1) == -1 and b"0..15" in lib.la_last_error()
+    assert lib.la_select_workspace(16) == -1
+    assert lib.la_select_workspace(15) == 0
+    assert lib.la_select_workspace(0) == 0
+
+
 def test_workspace_query(lib):
     assert binding.la_step_attention_workspace_bytes(1024, 15, 5, 15, 32, 32, 128) > 0
     assert binding.la_step_attention_workspace_bytes(0, 0, 2, 0, 1, 1, 128) == 0
