@@ -340,6 +340,27 @@ la_status la_verify_sample(const float* logits_cur, const float* logits_cand, co
                            const float* u_test, const float* u_final, float temperature, int N, int G, int V,
                            int* out_tokens, int* n_out, void* stream);
 
+/*
+ * Sampling verification for several sequences (same N, G, V) in ONE launch: the same result as
+ * n_descs calls of la_verify_sample, one per descriptor, each with its own draws and
+ * temperature.
+ *   descs    HOST array of n_descs descriptors (read before the call returns), 1..1024; device
+ *            pointers with the shapes la_verify_sample asks for
+ */
+typedef struct la_sample_desc {
+    const float* logits_cur;   /* fp32 [V] */
+    const float* logits_cand;  /* fp32 [G][N-1][V]; may be NULL iff G == 0 */
+    const int* cand_tokens;    /* int32 [G][N-1] */
+    const float* u_test;       /* fp32 [N-1][G] */
+    const float* u_final;      /* fp32 [1] */
+    int* out_tokens;           /* int32 [N] */
+    int* n_out;                /* int32 [1] */
+    float temperature;         /* > 0 */
+    int reserved;              /* must be 0 */
+} la_sample_desc;
+
+la_status la_verify_sample_batch(const la_sample_desc* descs, int n_descs, int N, int G, int V, void* stream);
+
 /* Bytes of device workspace la_step_attention needs for this shape (0 if none). */
 long long la_step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int kv_heads,
                                             int head_dim);

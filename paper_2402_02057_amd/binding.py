@@ -43,6 +43,13 @@ class VerifyDesc(ctypes.Structure):
                                                 "out_tokens", "n_out", "best", "new_window", "accept_len")]
 
 
+class SampleDesc(ctypes.Structure):
+    """la_sample_desc of include/la.h."""
+    _fields_ = [(n, ctypes.c_void_p) for n in ("logits_cur", "logits_cand", "cand_tokens", "u_test", "u_final",
+                                                "out_tokens", "n_out")] + \
+               [("temperature", ctypes.c_float), ("reserved", ctypes.c_int)]
+
+
 class LaError(RuntimeError):
     def __init__(self, code, message):
         super().__init__("la error %d: %s" % (code, message))
@@ -65,6 +72,8 @@ def load():
     lib.la_step_attention_cap.restype = i
     lib.la_kv_commit.argtypes = [p, p, ll, p, p, i, i, i, i, i, i, p, p, p]
     lib.la_kv_commit.restype = i
+    lib.la_verify_sample_batch.argtypes = [p, i, i, i, i, p]
+    lib.la_verify_sample_batch.restype = i
     lib.la_step_rope.argtypes = [p, p, p, p, i, i, i, i, i, i, i, i, i, p]
     lib.la_step_rope.restype = i
     lib.la_verify_step_batch.argtypes = [p, i, i, i, i, i, p]
@@ -101,7 +110,7 @@ def load():
     return lib
 
 
-EXPORTS = ("la_step_rope", "la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_kv_commit_batch", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_step_batch", "la_verify_sample", "la_step_attention_workspace_bytes", "la_shutdown", "la_select_workspace",
+EXPORTS = ("la_step_rope", "la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_kv_commit_batch", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_step_batch", "la_verify_sample", "la_verify_sample_batch", "la_step_attention_workspace_bytes", "la_shutdown", "la_select_workspace",
            "la_last_error", "la_version")
 
 
@@ -401,6 +410,24 @@ def la_verify_sample(logits_cur, logits_cand, cand_tokens, u_test, u_final, temp
         _stream(stream))
     _check(rc)
     return out_tokens, n_out
+
+
+def la_verify_sample_batch(seqs, N, G, V, stream=None):
+    """Sampling verification of several sequences in one launch.  `seqs`: dicts with logits_cur,
+    logits_cand, cand_tokens, u_test, u_final, temperature, out_tokens, n_out (tensors as for
+    la_verify_sample); asynchronous."""
+    descs = (SampleDesc * len(seqs))()
+    f, i32 = torch.float32, torch.int32
+    for d, x in zip(descs, seqs):
+        d.logits_cur = _ptr(x["logits_cur"], f, (V,), "logits_cur")
+        d.logits_cand = _ptr(x.get("logits_cand"), f, (G, N - 1, V), "logits_cand", allow_empty_null=True)
+        d.cand_tokens = _ptr(x.get("cand_tokens"), i32, (G, N - 1), "cand_tokens", allow_empty_null=True)
+        d.u_test = _ptr(x.get("u_test"), f, (N - 1, G), "u_test", allow_empty_null=True)
+        d.u_final = _ptr(x["u_final"], f, (1,), "u_final")
+        d.out_tokens = _ptr(x["out_tokens"], i32, (N,), "out_tokens")
+        d.n_out = _ptr(x["n_out"], i32, (1,), "n_out")
+        d.temperature, d.reserved = float(x["temperature"]), 0
+    _check(load().la_verify_sample_batch(ctypes.cast(descs, ctypes.c_void_p), len(seqs), N, G, V, _stream(stream)))
 
 
 def la_step_attention_workspace_bytes(P, W, N, G, heads, kv_heads, head_dim):

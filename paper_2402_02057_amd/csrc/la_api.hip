@@ -471,6 +471,31 @@ la_status la_verify_sample(const float* logits_cur, const float* logits_cand, co
                                     out_tokens, n_out, (hipStream_t)stream);
 }
 
+la_status la_verify_sample_batch(const la_sample_desc* descs, int n_descs, int N, int G, int V, void* stream)
+{
+    const char* name = "la_verify_sample_batch";
+    if (n_descs < 1 || n_descs > 1024 || !descs)
+        return la::fail(LA_EINVAL, "%s: need 1..1024 descriptors (got %d)", name, n_descs);
+    if (G < 0 || N < 2 || V < 1)
+        return la::fail(LA_EINVAL, "%s: need G >= 0, N >= 2, V >= 1 (got G=%d N=%d V=%d)", name, G, N, V);
+    if (G > 1024) return la::fail(LA_EUNSUPPORTED, "%s: at most 1024 candidates (got %d)", name, G);
+    la::SampleSeq v[1024];
+    for (int i = 0; i < n_descs; ++i) {
+        const la_sample_desc& d = descs[i];
+        if (!(d.temperature > 0.0f) || d.reserved != 0)
+            return la::fail(LA_EINVAL, "%s: descriptor %d: temperature must be positive, reserved 0", name, i);
+        if (!d.logits_cur || !d.u_final || !d.out_tokens || !d.n_out ||
+            (G > 0 && (!d.logits_cand || !d.cand_tokens || !d.u_test)))
+            return la::fail(LA_EINVAL, "%s: descriptor %d: null pointer", name, i);
+        if (((uintptr_t)d.logits_cur | (uintptr_t)d.logits_cand | (uintptr_t)d.cand_tokens | (uintptr_t)d.u_test |
+             (uintptr_t)d.u_final | (uintptr_t)d.out_tokens | (uintptr_t)d.n_out) & 3)
+            return la::fail(LA_EINVAL, "%s: descriptor %d: buffers must be 4-byte aligned", name, i);
+        v[i] = la::SampleSeq{d.logits_cur, d.logits_cand, d.cand_tokens, d.u_test,
+                             d.u_final,    d.out_tokens,  d.n_out,       d.temperature};
+    }
+    return la::launch_verify_sample_batch(v, n_descs, N, G, V, (hipStream_t)stream);
+}
+
 long long la_step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int kv_heads,
                                             int head_dim)
 {
@@ -486,6 +511,6 @@ la_status la_select_workspace(int set) { return la::select_workspace(set); }
 
 const char* la_last_error(void) { return la::g_error; }
 
-int la_version(void) { return 1011; }
+int la_version(void) { return 1012; }
 
 }  // extern "C"

@@ -70,6 +70,18 @@ la_status launch_kv_commit(void* k_cache, void* v_cache, long long capacity, con
                            int page_size, int n_pages, const void* step_k, const void* step_v, int P, int W,
                            int N, int G, int kv_heads, int head_dim, const int* best, const int* n_out,
                            hipStream_t stream);
+// One sequence of a batched la_verify_sample (pointers as for launch_verify_sample).
+struct SampleSeq {
+    const float* logits_cur;
+    const float* logits_cand;
+    const int* cand_tokens;
+    const float* u_test;
+    const float* u_final;
+    int* out_tokens;
+    int* n_out;
+    float temperature;
+};
+la_status launch_verify_sample_batch(const SampleSeq* seqs, int n_seqs, int N, int G, int V, hipStream_t stream);
 // One append of a batched launch: block_table null = packed cache with `capacity` rows per head,
 // else the caches are page pools (page_size, n_pages common to the launch).
 struct CommitSeq {

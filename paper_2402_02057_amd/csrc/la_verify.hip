@@ -350,13 +350,13 @@ __device__ __forceinline__ float expw(float logit, float inv_t, float m)
 // Row r: 0 = output at the current token, 1 + g*n1 + k = output at candidate g's token k.
 // blockIdx.x = r * nseg + segment.  stats: one packed (max, sum) per workgroup.
 template <bool kVec>
-__global__ __launch_bounds__(kThreads) void verify_sample_kernel(
+__device__ __forceinline__ void verify_sample_body(
     const float* __restrict__ logits_cur, const float* __restrict__ logits_cand,
     const int* __restrict__ cand_tokens, const float* __restrict__ u_test, const float* __restrict__ u_final,
     float inv_t, int n1, int G, int V, int seg_len, int nseg, int rows, unsigned fan, int lds_copy,
-    unsigned long long* stats, unsigned* l1, unsigned* l2, int* __restrict__ out_tokens, int* __restrict__ n_out)
+    unsigned long long* stats, unsigned* l1, unsigned* l2, int* __restrict__ out_tokens, int* __restrict__ n_out,
+    float* dyn)  // dynamic LDS; last workgroup: row max [rows], row sum [rows], tokens [G], survivors [G]
 {
-    extern __shared__ float dyn[];  // last workgroup: row max [rows], row sum [rows], tokens [G], survivors [G]
     __shared__ float wave_m[kWaves], wave_z[kWaves], wave_tot[kWaves];
     __shared__ unsigned last_flag;
     __shared__ int sh_len, sh_jrow, sh_n_rej, sh_found, sh_last;
@@ -670,6 +670,50 @@ __global__ __launch_bounds__(kThreads) void verify_sample_kernel(
     }
 }
 
+template <bool kVec>
+__global__ __launch_bounds__(kThreads) void verify_sample_kernel(
+    const float* __restrict__ logits_cur, const float* __restrict__ logits_cand,
+    const int* __restrict__ cand_tokens, const float* __restrict__ u_test, const float* __restrict__ u_final,
+    float inv_t, int n1, int G, int V, int seg_len, int nseg, int rows, unsigned fan, int lds_copy,
+    unsigned long long* stats, unsigned* l1, unsigned* l2, int* __restrict__ out_tokens, int* __restrict__ n_out)
+{
+    extern __shared__ float dyn[];
+    verify_sample_body<kVec>(logits_cur, logits_cand, cand_tokens, u_test, u_final, inv_t, n1, G, V, seg_len, nseg,
+                             rows, fan, lds_copy, stats, l1, l2, out_tokens, n_out, dyn);
+}
+
+// Sampling verification for several sequences in one launch: blockIdx.y names the sequence; each
+// has its own statistics and counters in the workspace (ws_stride bytes apart), its own draws
+// and temperature, and its own last workgroup.
+struct SampleOne {
+    const float* logits_cur;
+    const float* logits_cand;
+    const int* cand_tokens;
+    const float* u_test;
+    const float* u_final;
+    int* out_tokens;
+    int* n_out;
+    float inv_t;
+};
+struct SampleBatchParams {
+    SampleOne one[kVerifyBatch];
+    unsigned char* ws;
+    size_t ws_stride, l1_offset, l2_offset;
+    int n1, G, V, seg_len, nseg, rows, lds_copy;
+    unsigned fan;
+};
+
+template <bool kVec>
+__global__ __launch_bounds__(kThreads) void verify_sample_batch_kernel(SampleBatchParams b)
+{
+    extern __shared__ float dyn[];
+    const SampleOne& o = b.one[blockIdx.y];
+    unsigned char* ws = b.ws + (size_t)blockIdx.y * b.ws_stride;
+    verify_sample_body<kVec>(o.logits_cur, o.logits_cand, o.cand_tokens, o.u_test, o.u_final, o.inv_t, b.n1, b.G, b.V,
+                             b.seg_len, b.nseg, b.rows, b.fan, b.lds_copy, (unsigned long long*)ws,
+                             (unsigned*)(ws + b.l1_offset), (unsigned*)(ws + b.l2_offset), o.out_tokens, o.n_out, dyn);
+}
+
 }  // namespace
 
 la_status launch_verify(const float* logits, const int* cand_tokens, int G, int N, int V,
@@ -830,6 +874,49 @@ la_status launch_verify_sample(const float* logits_cur, const float* logits_cand
                            nseg, (int)rows, fan, lds_copy, stats, l1, l2, out_tokens, n_out);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(LA_EHIP, "la_verify_sample launch: %s", hipGetErrorString(e));
+    return LA_OK;
+}
+
+la_status launch_verify_sample_batch(const SampleSeq* seqs, int n_seqs, int N, int G, int V, hipStream_t stream)
+{
+    const int n1 = N - 1;
+    const long long rows = 1ll + (long long)G * n1;
+    int nseg = (V + kMaxSeg - 1) / kMaxSeg;
+    int seg_len = (V + nseg - 1) / nseg;
+    seg_len = (seg_len + 3) & ~3;
+    nseg = (V + seg_len - 1) / seg_len;
+    const long long blocks = rows * nseg;
+    size_t lds = ((size_t)rows * 2 + (size_t)(G > 0 ? G : 1) * 2) * sizeof(float);
+    if (lds > 48 * 1024 || blocks > 0x7fffffffll)
+        return fail(LA_EUNSUPPORTED, "la_verify_sample_batch: %lld rows is too many", rows);
+    const int lds_copy = lds + (size_t)G * n1 * 8 <= 48 * 1024 ? 1 : 0;
+    if (lds_copy) lds += (size_t)G * n1 * 8;
+    const unsigned fan = blocks <= 128 ? (unsigned)blocks : 8u;
+    const size_t n_groups = (size_t)((blocks + fan - 1) / fan);
+    const size_t l1_offset = (size_t)blocks * 8, l2_offset = l1_offset + n_groups * 4;
+    const size_t ws_stride = (l2_offset + 4 + 7) & ~(size_t)7;
+    for (int i0 = 0; i0 < n_seqs; i0 += kVerifyBatch) {
+        const int n = n_seqs - i0 < kVerifyBatch ? n_seqs - i0 : kVerifyBatch;
+        SampleBatchParams b;
+        bool vec = V % 4 == 0;
+        for (int i = 0; i < n; ++i) {
+            const SampleSeq& q = seqs[i0 + i];
+            b.one[i] = SampleOne{q.logits_cur, q.logits_cand, q.cand_tokens, q.u_test,
+                                 q.u_final,    q.out_tokens,  q.n_out,       1.0f / q.temperature};
+            vec = vec && ((((uintptr_t)q.logits_cur | (uintptr_t)q.logits_cand) & 15) == 0);
+        }
+        for (int i = n; i < kVerifyBatch; ++i) b.one[i] = b.one[0];  // never indexed: the grid has n layers
+        b.ws = (unsigned char*)zeroed_workspace(ws_stride * (size_t)n, stream);
+        if (!b.ws) return LA_ENOMEM;
+        b.ws_stride = ws_stride; b.l1_offset = l1_offset; b.l2_offset = l2_offset;
+        b.n1 = n1; b.G = G; b.V = V; b.seg_len = seg_len; b.nseg = nseg; b.rows = (int)rows; b.lds_copy = lds_copy;
+        b.fan = fan;
+        const dim3 grid((unsigned)blocks, (unsigned)n);
+        if (vec) hipLaunchKernelGGL(verify_sample_batch_kernel<true>, grid, dim3(kThreads), lds, stream, b);
+        else hipLaunchKernelGGL(verify_sample_batch_kernel<false>, grid, dim3(kThreads), lds, stream, b);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(LA_EHIP, "la_verify_sample_batch launch: %s", hipGetErrorString(e));
+    }
     return LA_OK;
 }
 

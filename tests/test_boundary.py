@@ -185,6 +185,28 @@ def test_rope_reports_argument_errors_without_a_gpu(lib):
     assert lib.la_step_rope(A, A, A + 4, A, 64, 10, 1, 3, 1, 4, 4, 128, 0, None) == -1  # misaligned table
 
 
+def test_verify_sample_batch_reports_argument_errors_without_a_gpu(lib):
+    import ctypes
+    A = 4096
+    d = (binding.SampleDesc * 2)()
+    for x in d:
+        for name in ("logits_cur", "logits_cand", "cand_tokens", "u_test", "u_final", "out_tokens", "n_out"):
+            setattr(x, name, A)
+        x.temperature, x.reserved = 1.0, 0
+    ptr = ctypes.cast(d, ctypes.c_void_p)
+    assert lib.la_verify_sample_batch(ptr, 0, 3, 1, 10, None) == -1
+    assert lib.la_verify_sample_batch(None, 2, 3, 1, 10, None) == -1
+    assert lib.la_verify_sample_batch(ptr, 2, 1, 1, 10, None) == -1 and b"N >= 2" in lib.la_last_error()
+    assert lib.la_verify_sample_batch(ptr, 2, 3, 2000, 10, None) == -2
+    d[1].temperature = -1.0
+    rc = lib.la_verify_sample_batch(ptr, 2, 3, 1, 10, None)
+    assert rc == -1 and b"descriptor 1" in lib.la_last_error() and b"temperature" in lib.la_last_error()
+    d[1].temperature = 1.0
+    d[0].u_test = None
+    rc = lib.la_verify_sample_batch(ptr, 2, 3, 1, 10, None)
+    assert rc == -1 and b"descriptor 0" in lib.la_last_error() and b"null" in lib.la_last_error()
+
+
 def test_workspace_sets_are_range_checked(lib):
     assert lib.la_select_workspace(-1) == -1 and b"0..15" in lib.la_last_error()
     assert lib.la_select_workspace(16) == -1
