@@ -361,6 +361,25 @@ typedef struct la_sample_desc {
 
 la_status la_verify_sample_batch(const la_sample_desc* descs, int n_descs, int N, int G, int V, void* stream);
 
+/*
+ * la_step_attention for callers that cannot allocate device memory: code under HIP graph
+ * capture with no warm-up call, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels, same result as la_step_attention; the difference is where the
+ * scratch memory (tickets and split partials) comes from: a fixed block of 4 KiB + 12 MiB
+ * inside the library's own image, present once on every device the library runs on until the
+ * process ends.  The call never calls hipMalloc, hipFree or any allocating routine.
+ *
+ * Limits: a step whose decomposition needs more than 1024 split groups or more than 12 MiB of
+ * partials is refused with LA_EUNSUPPORTED (la_last_error says how much it needs); the
+ * benchmark shapes need at most 8.3 MiB.  Every call on a device shares that device's block:
+ * the tickets are cleared by a small kernel in front of the step (no memset node, so the call
+ * can be captured), the partials are overwritten; two such calls that overlap in time on one
+ * device (different streams) race and give wrong results.  la_select_workspace does not apply.
+ */
+la_status la_step_attention_noalloc(const void* q, const void* k_cache, const void* v_cache,
+                                    const void* step_k, const void* step_v, int P, int W, int N, int G,
+                                    int heads, int kv_heads, int head_dim, void* out, void* stream);
+
 /* Bytes of device workspace la_step_attention needs for this shape (0 if none). */
 long long la_step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int kv_heads,
                                             int head_dim);

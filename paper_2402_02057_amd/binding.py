@@ -13,6 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libla_hip.so")
 
 LA_OK = 0
+LA_EINVAL, LA_EUNSUPPORTED, LA_ENOMEM, LA_EHIP = -1, -2, -3, -4
 _lib = None
 
 
@@ -67,6 +68,8 @@ def load():
     i, p = ctypes.c_int, ctypes.c_void_p
     lib.la_step_attention.argtypes = [p, p, p, p, p, i, i, i, i, i, i, i, p, p]
     lib.la_step_attention.restype = i
+    lib.la_step_attention_noalloc.argtypes = [p, p, p, p, p, i, i, i, i, i, i, i, p, p]
+    lib.la_step_attention_noalloc.restype = i
     ll = ctypes.c_longlong
     lib.la_step_attention_cap.argtypes = [p, p, p, ll, p, p, i, i, i, i, i, i, i, p, p]
     lib.la_step_attention_cap.restype = i
@@ -110,7 +113,7 @@ def load():
     return lib
 
 
-EXPORTS = ("la_step_rope", "la_step_attention", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_kv_commit_batch", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_step_batch", "la_verify_sample", "la_verify_sample_batch", "la_step_attention_workspace_bytes", "la_shutdown", "la_select_workspace",
+EXPORTS = ("la_step_rope", "la_step_attention", "la_step_attention_noalloc", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_kv_commit_batch", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_step_batch", "la_verify_sample", "la_verify_sample_batch", "la_step_attention_workspace_bytes", "la_shutdown", "la_select_workspace",
            "la_last_error", "la_version")
 
 
@@ -152,6 +155,23 @@ def la_step_attention(q, k_cache, v_cache, step_k, step_v, P, W, N, G, heads, kv
     T = 1 + (W + G) * (N - 1)
     bf = torch.bfloat16
     rc = load().la_step_attention(
+        _ptr(q, bf, (T, heads, head_dim), "q"),
+        _ptr(k_cache, bf, (kv_heads, P, head_dim), "k_cache", allow_empty_null=True),
+        _ptr(v_cache, bf, (kv_heads, P, head_dim), "v_cache", allow_empty_null=True),
+        _ptr(step_k, bf, (T, kv_heads, head_dim), "step_k"),
+        _ptr(step_v, bf, (T, kv_heads, head_dim), "step_v"),
+        P, W, N, G, heads, kv_heads, head_dim,
+        _ptr(out, bf, (T, heads, head_dim), "out"), _stream(stream))
+    _check(rc)
+    return out
+
+
+def la_step_attention_noalloc(q, k_cache, v_cache, step_k, step_v, P, W, N, G, heads, kv_heads, head_dim,
+                              out, stream=None):
+    """la_step_attention through the entry point that allocates nothing (fixed scratch block)."""
+    T = 1 + (W + G) * (N - 1)
+    bf = torch.bfloat16
+    rc = load().la_step_attention_noalloc(
         _ptr(q, bf, (T, heads, head_dim), "q"),
         _ptr(k_cache, bf, (kv_heads, P, head_dim), "k_cache", allow_empty_null=True),
         _ptr(v_cache, bf, (kv_heads, P, head_dim), "v_cache", allow_empty_null=True),

@@ -40,6 +40,8 @@
 // so no memset is needed between calls.
 #include <stdlib.h>
 
+#include <mutex>
+
 #include "la_internal.h"
 
 namespace la {
@@ -1139,6 +1141,21 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_batch_kernel(const
     step_attention_body<D, RT, KS, KC, NSTAGE, PAGED>(p, (int)(blockIdx.x & 7), slot - sl.slot0[i]);
 }
 
+// Scratch memory of the entry point that allocates nothing (la_step_attention_noalloc): the
+// tickets and the split partials of one step, in the library's own image.  Every device the
+// library runs on holds one copy until the process ends.  In host code the name below is only a
+// handle: its device address is looked up once per device (fixed_workspace) and only that
+// pointer is handed to kernels.
+constexpr size_t kFixedTicketBytes = 4096;                      // 1024 split groups
+constexpr size_t kFixedPartialBytes = (size_t)12 << 20;         // 12 MiB of partials
+static __device__ __align__(256) unsigned char scratch[kFixedTicketBytes + kFixedPartialBytes];
+
+__global__ void clear_words_kernel(unsigned* words, int n)
+{
+    const int i = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (i < n) words[i] = 0u;
+}
+
 // ---------------------------------------------------------------------------------------
 // host side
 
@@ -1339,7 +1356,7 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
                                 long long capacity, const int* block_table, int page_size, int n_pages,
                                 const int* row_ids, int n_rows, const void* step_k, const void* step_v, int P,
                                 int W, int N, int G, int heads, int kv_heads, int head_dim, void* out,
-                                hipStream_t stream)
+                                hipStream_t stream, const FixedWorkspace* fixed)
 {
     const int T = row_ids ? n_rows : 1 + (W + G) * (N - 1);
     const int group = heads / kv_heads;
@@ -1355,11 +1372,28 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
 
     if (pl.XS > 1) {
         const size_t ticket_bytes = (size_t)kv_heads * pl.n_row_blocks * sizeof(unsigned);
-        prm.tickets = (unsigned*)zeroed_workspace(ticket_bytes, stream);
-        if (!prm.tickets) return LA_ENOMEM;
         const size_t bytes = (size_t)total * pl.partial_bytes_per_wg;
-        prm.partials = scratch_workspace(bytes);
-        if (!prm.partials) return LA_ENOMEM;
+        if (fixed) {
+            // a caller that cannot allocate: the blocks are given and cannot grow
+            if (ticket_bytes > fixed->ticket_bytes || bytes > fixed->partial_bytes)
+                return fail(LA_EUNSUPPORTED,
+                            "la_step_attention_noalloc: the step needs %zu + %zu bytes of scratch memory, the fixed "
+                            "block holds %zu + %zu", ticket_bytes, bytes, fixed->ticket_bytes, fixed->partial_bytes);
+            prm.tickets = (unsigned*)fixed->tickets;
+            prm.partials = fixed->partials;
+            // the block is shared by every call on this device and keeps what the last one left:
+            // the tickets must start at zero (a fill kernel, not a memset, so that the call can
+            // be recorded into a graph)
+            const int n_words = (int)(ticket_bytes / sizeof(unsigned));
+            hipLaunchKernelGGL(clear_words_kernel, dim3((n_words + 255) / 256), dim3(256), 0, stream, prm.tickets, n_words);
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return fail(LA_EHIP, "la_step_attention_noalloc: clearing the tickets: %s", hipGetErrorString(e));
+        } else {
+            prm.tickets = (unsigned*)zeroed_workspace(ticket_bytes, stream);
+            if (!prm.tickets) return LA_ENOMEM;
+            prm.partials = scratch_workspace(bytes);
+            if (!prm.partials) return LA_ENOMEM;
+        }
     }
 
     if (row_ids) {
@@ -1542,6 +1576,30 @@ la_status launch_step_attention_batch(const BatchSeq* seqs, int n_seqs, int page
         else st = launch_batch_cfg<64, 2, 2, 4>(bp, grid, stream);
         if (st != LA_OK) return st;
     }
+    return LA_OK;
+}
+
+// ---- the fixed scratch block of la_step_attention_noalloc
+
+la_status fixed_workspace(FixedWorkspace* ws)
+{
+    static std::mutex mutex;
+    static unsigned char* base[16] = {nullptr};  // device address of `scratch`, per device
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return fail(LA_EHIP, "hipGetDevice failed");
+    std::lock_guard<std::mutex> lock(mutex);
+    if (!base[dev]) {
+        // each device has its own copy of the array at its own address; `dev` is current here
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return fail(LA_EHIP, "la_step_attention_noalloc: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        base[dev] = (unsigned char*)ptr;
+    }
+    ws->tickets = base[dev];
+    ws->ticket_bytes = kFixedTicketBytes;
+    ws->partials = base[dev] + kFixedTicketBytes;
+    ws->partial_bytes = kFixedPartialBytes;
     return LA_OK;
 }
 

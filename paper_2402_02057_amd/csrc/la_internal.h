@@ -43,6 +43,16 @@ la_status launch_verify_step_batch(const VerifySeq* seqs, int n_seqs, int W, int
 la_status launch_verify_sample(const float* logits_cur, const float* logits_cand, const int* cand_tokens,
                                const float* u_test, const float* u_final, float temperature, int N, int G,
                                int V, int* out_tokens, int* n_out, hipStream_t stream);
+// Scratch memory that the caller of launch_step_attention provides instead of the per-device
+// pools (which grow with hipMalloc): tickets (cleared by the launcher) and room for partials.
+struct FixedWorkspace {
+    void* tickets;
+    size_t ticket_bytes;
+    void* partials;
+    size_t partial_bytes;
+};
+// The library's own fixed block on the current device (a file-scope device array; no allocation).
+la_status fixed_workspace(FixedWorkspace* ws);
 // `capacity`: rows between the caches of consecutive KV heads (P for a packed cache).
 // `block_table` != nullptr: the caches are pages [n_pages][kv_heads][page_size][head_dim]
 // (page_size a multiple of 64) and `capacity` is not used.  `row_ids` != nullptr: the step holds
@@ -51,7 +61,7 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
                                 long long capacity, const int* block_table, int page_size, int n_pages,
                                 const int* row_ids, int n_rows, const void* step_k, const void* step_v, int P,
                                 int W, int N, int G, int heads, int kv_heads, int head_dim, void* out,
-                                hipStream_t stream);
+                                hipStream_t stream, const FixedWorkspace* fixed = nullptr);
 // One step of a batched launch.  Packed caches: k_cache / v_cache per step, block_table null.  Paged
 // (page_size > 0): k_cache / v_cache are the shared page pools, block_table the step's own table.
 struct BatchSeq {
