@@ -365,13 +365,13 @@ la_status la_verify_sample_batch(const la_sample_desc* descs, int n_descs, int N
  * la_step_attention for callers that cannot allocate device memory: code under HIP graph
  * capture with no warm-up call, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments, same kernels, same result as la_step_attention; the difference is where the
- * scratch memory (tickets and split partials) comes from: a fixed block of 4 KiB + 12 MiB
+ * scratch memory (tickets and split partials) comes from: a fixed block of 128 KiB + 12 MiB
  * inside the library's own image, present once on every device the library runs on until the
  * process ends.  The call never calls hipMalloc, hipFree or any allocating routine.
  *
- * Limits: a step whose decomposition needs more than 1024 split groups or more than 12 MiB of
- * partials is refused with LA_EUNSUPPORTED (la_last_error says how much it needs); the
- * benchmark shapes need at most 8.3 MiB.  Every call on a device shares that device's block:
+ * Limits: a step whose decomposition needs more than 128 KiB of tickets (128 split groups) or
+ * more than 12 MiB of partials is refused with LA_EUNSUPPORTED (la_last_error says how much it
+ * needs); the library's own decomposition needs at most 5 MiB.  Every call on a device shares that device's block:
  * the tickets are cleared by a small kernel in front of the step (no memset node, so the call
  * can be captured), the partials are overwritten; two such calls that overlap in time on one
  * device (different streams) race and give wrong results.  la_select_workspace does not apply.

@@ -45,8 +45,18 @@
 #include "la_internal.h"
 #include "la_attention_common.h"
 
+#ifdef LA_DEV_HOOKS
+#include LA_DEV_HOOKS  // developer builds only: timing stamps, never part of the product build
+#else
+#define LA_STAMP(k) do { } while (0)
+#endif
+
 namespace la {
 namespace {
+
+// Tickets of different waves sit in different 128-byte lines: atomics on one line are served one
+// after the other by the L2 (eight counters side by side cost a microsecond at the 7B shape).
+constexpr int kTicketStride = 32;  // in 4-byte words
 
 struct AttnParams {
     const __bf16* q;
@@ -55,8 +65,8 @@ struct AttnParams {
     const __bf16* step_k;
     const __bf16* step_v;
     __bf16* out;
-    void* partials;     // XS > 1: per workgroup, fragment-layout bf16 accumulators and fp32 (m, l)
-    unsigned* tickets;  // XS > 1: one counter per (KV head, row block), zero between calls
+    void* partials;     // XS > 1: per workgroup and wave, fragment-layout bf16 slices and fp32 (m, l)
+    unsigned* tickets;  // XS > 1: one counter (kTicketStride words apart) per (KV head, row block, wave), zero between calls
     int P, W, N, G, T;
     long long cache_rows;  // rows between the caches of consecutive KV heads (>= P; paged: the page size)
     // Paged cache (block_table != nullptr): k_cache / v_cache are [n_pages][kv_heads][page][head_dim]
@@ -84,10 +94,6 @@ struct AttnParams {
     int chunks_lo, chunks_rem;  // n_chunks = XS * chunks_lo + chunks_rem
     int pre;              // chunks requested before the loop starts (1 .. stages)
     int force_recompute;  // testing: treat every group as spread over several XCDs
-#ifdef LA_DEV_KNOBS
-    int dev_mode;         // timing experiments only (results are wrong): see LA_DEV_MODE
-    long long* dev_trace; // 8 wall-clock stamps per workgroup
-#endif
 };
 
 // Row-subset variant: a row of the full layout as (branch, coordinates), and the pairwise rule
@@ -144,11 +150,11 @@ struct Cfg {
     static constexpr int SPW = KS > 1 ? DB / KS : DB;
     static constexpr int FRAG_FLOATS = DB * 16 * 64;      // one tile's accumulators
     static constexpr int TILE_FLOATS = FRAG_FLOATS + 128; // + m and l per lane
-    // a split's partial in global memory: per tile the accumulators as bf16 in fragment order
-    // ([8 values][lane], 16 bytes per lane and access) followed by (m, l) per lane in fp32
-    static constexpr int PART_ACC_BYTES = DB * 16 * 64 * 2;
-    static constexpr int PART_TILE_BYTES = PART_ACC_BYTES + 64 * 8;
-    static constexpr int PART_WG_BYTES = TILES * PART_TILE_BYTES;
+    // a split's partial in global memory, per wave: its SPW slices as bf16 in fragment order
+    // ([8 values][lane], 16 bytes per lane and access) followed by (m, l) of its rows per lane in fp32
+    static constexpr int PART_ACC_BYTES = SPW * 16 * 64 * 2;
+    static constexpr int PART_WAVE_BYTES = PART_ACC_BYTES + 64 * 8;
+    static constexpr int PART_WG_BYTES = NW * PART_WAVE_BYTES;
     static constexpr int Q_BYTES = ROWS * RBYTES;         // the workgroup's query rows
     static constexpr int Q_OFFSET = NSTAGE * STAGE_BYTES; // they sit behind the stage ring
     static constexpr int QLPW = Q_BYTES / 1024 / NW;      // Q loads per wave
@@ -169,19 +175,6 @@ struct Cfg {
     static_assert(LDS_BYTES <= 160 * 1024, "LDS of a compute unit");
 };
 
-#ifdef LA_DEV_KNOBS
-#define LA_STAMP(k) do { if (p.dev_trace && (threadIdx.x & 63) == 0) p.dev_trace[((size_t)blockIdx.x * 8 + (threadIdx.x >> 6)) * 24 + (k)] = wall_clock64(); } while (0)
-#define LA_CYCW(k) do { if (p.dev_trace && (threadIdx.x & 63) == 0) p.dev_trace[((size_t)blockIdx.x * 8 + (threadIdx.x >> 6)) * 24 + (k)] = __builtin_readcyclecounter(); } while (0)
-#ifdef LA_NO_CYC
-#define LA_CYC(k) do { } while (0)
-#else
-#define LA_CYC(k) do { if (p.dev_trace && (threadIdx.x & 63) == 0 && it == 1) p.dev_trace[((size_t)(4096 + blockIdx.x) * 8 + (threadIdx.x >> 6)) * 24 + (k)] = __builtin_readcyclecounter(); } while (0)
-#endif
-#else
-#define LA_STAMP(k) do { } while (0)
-#define LA_CYCW(k) do { } while (0)
-#define LA_CYC(k) do { } while (0)
-#endif
 
 // Write one finished (tile, 32-column) slice: lane (l32, hi) holds, for query row tile*32 + l32 of
 // the workgroup, columns db*32 + i4*8 + hi*4 .. +3 in vals[i4*4 .. +3].  The two half-waves of a
@@ -290,12 +283,7 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
     // Consecutive workgroup ids go round-robin over the 8 XCDs (each with its own L2); put
     // the workgroups that stream the same KV head on one XCD.
     LA_STAMP(0);
-    LA_CYCW(22);
     int logical = xcd * p.wg_per_xcd + slot;
-#ifdef LA_DEV_KNOBS
-    if (p.dev_mode & 16) logical = (int)blockIdx.x;  // experiment: no XCD grouping (wrong combine!)
-    if ((p.dev_mode & 64) && blockIdx.x >= 8) return;  // experiment: one workgroup per XCD only
-#endif
     if (logical >= p.total_wg) return;
     // (the float arithmetic runs on the vector unit: tell the compiler the results are uniform,
     // or every loop and branch that depends on them is compiled as divergent control flow)
@@ -491,11 +479,7 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
         }
         issued = upfront;
     };
-#ifdef LA_DEV_KNOBS
-    issue_first(!(p.dev_mode & 32));
-#else
     issue_first(true);
-#endif
     LA_STAMP(1);
 
     // which step keys this lane's row may see
@@ -514,9 +498,12 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
     // that a last iteration with fewer chunks than CPI leaves one busy wave on every SIMD
     // instead of two on half of them.
     const int cw = KS > C::KB ? (ks / C::KB + rt) % C::CPI : 0;
-    // after the ticket: 0 not last, 1 last and co-located, 2 recompute (a word of LDS, addressed as such)
+    // which waves ask for the recompute pass (a word of LDS, addressed as such)
     typedef __attribute__((address_space(3))) unsigned lds_u32;
-    lds_u32* const s_role = (lds_u32*)(lds + C::ROLE_OFFSET);
+    volatile lds_u32* const s_recompute = (volatile lds_u32*)(lds + C::ROLE_OFFSET);
+    unsigned store_mask = ~0u;  // recompute pass: which waves write their slices
+    // the wave's counter of this split group
+    unsigned* const my_ticket = p.XS > 1 ? p.tickets + ((size_t)unit * C::NW + wave) * kTicketStride : nullptr;
 
     // LDS read offsets of this lane relative to the start of a stage; the loop adds only the stage.
     //   K operand: key row kb*32 + l32, pieces k16*2 + hi (swizzled).
@@ -562,18 +549,10 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
         // Iteration `it` consumes chunks done .. done+CPI-1 of this pass (done = it*CPI).
         int cons_c = c_begin + cw;                     // the chunk this wave takes next
         unsigned cons_stage = (unsigned)cw * C::STAGE_BYTES;  // and the LDS offset of its stage
-#ifdef LA_DEV_KNOBS
-        // timing experiment: run the loop many times over the chunks already in LDS (needs n_my <= pre)
-        for (int rep = 0, reps = (p.dev_mode & 128) ? 200 : 1; rep < reps; ++rep) {
-        cons_c = c_begin + cw;
-        cons_stage = (unsigned)cw * C::STAGE_BYTES;
-#endif
         for (int it = 0, done = 0; done < n_my; ++it, done += C::CPI) {
             // Wait for this wave's loads of the chunks needed now; younger ones stay in flight.
             wait_young<C::LPW, NSTAGE - C::CPI>(issued - min(n_my, done + C::CPI));
-            LA_CYC(7);
             __syncthreads();  // these chunks are complete in LDS; everyone is done with the last ones
-            LA_CYC(6);
             if (it < 4) LA_STAMP(8 + 2 * it);
             if (it == 0 && pass == 0) {
                 // Q has landed with the first chunks: move this wave's rows to registers
@@ -602,10 +581,6 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
                 --slots_left;
             };
             bool compute = done + cw < n_my && wave_active;
-#ifdef LA_DEV_KNOBS
-            if ((p.dev_mode & 15) == 2) compute = false;  // loads only
-            if (rep > 0) slots_left = 0;
-#endif
             if (compute) {
             const bool is_step = cons_c >= n_prefix_chunks;
             const int chunk_key0 = (cons_c - (is_step ? n_prefix_chunks : 0)) * KC;
@@ -667,9 +642,7 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
                         vf[kk][db] = u.v;
                     }
                 };
-                LA_CYC(0);
                 read_v(0);
-                LA_CYC(1);
 
                 // ---- S^T block: 32 keys x 32 rows
                 f32x16 s;
@@ -678,7 +651,6 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
 #pragma unroll
                 for (int k16 = 0; k16 < D / 16; ++k16)
                     s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[k16], qreg[k16], s, 0, 0, 0);
-                LA_CYC(2);
                 if (slots_left > 0) issue_slot();
                 read_v(1);  // in flight during the softmax arithmetic
 
@@ -690,11 +662,11 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
                         if (!((word >> bit) & 1u)) s[i] = kNegInf;
                     }
                 }
+                if (full) settle_mfma_result(s);  // (the mask above is compiler-visible arithmetic on s)
                 float mx = max3(s[0], s[1], s[2]);
 #pragma unroll
                 for (int i = 3; i < 15; i += 2) mx = max3(mx, s[i], s[i + 1]);
                 mx = max_across_halves(max2(mx, s[15]));
-                LA_CYC(3);
                 // Scores stay unscaled; exp(x/sqrt(d)) = exp2(x * scale_log2).  The reference
                 // m_run only moves when the block maximum exceeds it by more than 2^8 in the
                 // exponent (or no key was seen yet): softmax is invariant to the reference, and
@@ -730,7 +702,6 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
                     }
                     l_run += psum0 + psum1;
                 }
-                LA_CYC(4);
 
                 // ---- O^T += V^T P^T
 #pragma unroll
@@ -747,25 +718,17 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
             cons_c += C::CPI;
             cons_stage += C::CPI * C::STAGE_BYTES;
             if (cons_stage >= (unsigned)(NSTAGE * C::STAGE_BYTES)) cons_stage -= NSTAGE * C::STAGE_BYTES;
-            LA_CYC(5);
             if (it < 4) LA_STAMP(9 + 2 * it);
         }
-#ifdef LA_DEV_KNOBS
-        }
-#endif
 
         LA_STAMP(3);
-#ifdef LA_DEV_KNOBS
-        if ((p.dev_mode & 15) == 1 || (p.dev_mode & 15) == 2) {  // stop after the main loop
-            if (l_run == 123.456f) p.out[tid] = (__bf16)o[0][0];
-            return;
-        }
-#endif
         // the two half-waves of a row hold the sums over their own keys
         l_run += __shfl_xor(l_run, 32, 64);
 
         __syncthreads();  // all stages consumed: LDS is reused below
         LA_STAMP(16);
+        if (tid == 0) *s_recompute = 0u;
+        if (KS == 1) __syncthreads();  // (with key-split waves the merge's barrier does this)
 
         // ---- merge the KS waves of a row tile; the key index is uniform in a wave, and branching
         //      on it keeps every register index a compile-time constant
@@ -780,141 +743,123 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
         LA_STAMP(4);
         if (direct) break;
 
-        // ---- split combine: store this split's partial, then take a ticket
-        unsigned char* group_base = reinterpret_cast<unsigned char*>(p.partials) +
-                                    (size_t)((kvh * p.n_row_blocks + rb) * p.XS) * C::PART_WG_BYTES;
+        // ---- split combine, wave by wave (no workgroup barrier): a wave stores its slices with its
+        //      rows' (m, l), waits for the L2 of this XCD to acknowledge the stores and takes a ticket
+        //      of its own; the wave that arrives last in its group merges the XS partials of these
+        //      slices in index order (so results do not depend on arrival order)
         if (wave_active) {
-            unsigned char* dst = group_base + (size_t)xs * C::PART_WG_BYTES + (size_t)rt * C::PART_TILE_BYTES;
+            unsigned char* const group_base = reinterpret_cast<unsigned char*>(p.partials) +
+                                              (size_t)unit * p.XS * C::PART_WG_BYTES + (size_t)wave * C::PART_WAVE_BYTES;
+            {
+                unsigned char* dst = group_base + (size_t)xs * C::PART_WG_BYTES;
 #pragma unroll
-            for (int u = 0; u < C::SPW; ++u)
+                for (int u = 0; u < C::SPW; ++u)
 #pragma unroll
-                for (int i8 = 0; i8 < 2; ++i8) {
-                    bf16x8 v;
+                    for (int i8 = 0; i8 < 2; ++i8) {
+                        bf16x8 v;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) v[e] = (__bf16)o[u][i8 * 8 + e];
-                    *reinterpret_cast<bf16x8*>(dst + (((db0 + u) * 2 + i8) * 64 + lane) * 16) = v;
-                }
-            if (db0 == 0) *reinterpret_cast<f32x2*>(dst + C::PART_ACC_BYTES + lane * 8) = f32x2{m_run, l_run};
-        }
-        // Stores are acknowledged by the L2 of this XCD: wait for them, then publish.
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
-        LA_STAMP(5);
-        if (tid == 0) {
-            // One atomic carries the arrival count and, to tell whether every member of the group
-            // ran on the same XCD (and so shares one L2), the sum and the sum of squares of the
-            // members' XCD ids: XS * sum(x^2) == (sum x)^2 holds iff all ids are equal.
-            const unsigned x = xcc_id();
-            const unsigned mine = 1u | (x << 8) | ((x * x) << 18);
-            unsigned* ticket = p.tickets + (kvh * p.n_row_blocks + rb);
-            const unsigned total = atomicAdd(ticket, mine) + mine;
-            const unsigned cnt = total & 0xffu, sum = (total >> 8) & 0x3ffu, sq = total >> 18;
-            unsigned role = 0;
-            if (cnt == (unsigned)p.XS) {
-                *ticket = 0u;  // everyone has arrived; clean for the next call
-                role = (sq * (unsigned)p.XS == sum * sum && !p.force_recompute) ? 1u : 2u;
+                        for (int e = 0; e < 8; ++e) v[e] = (__bf16)o[u][i8 * 8 + e];
+                        *reinterpret_cast<bf16x8*>(dst + ((u * 2 + i8) * 64 + lane) * 16) = v;
+                    }
+                *reinterpret_cast<f32x2*>(dst + C::PART_ACC_BYTES + lane * 8) = f32x2{m_run, l_run};
             }
-            *s_role = role;
-        }
-        __syncthreads();
-        const unsigned role = __builtin_amdgcn_readfirstlane(*s_role);  // same in every lane
-        LA_STAMP(6);
-        if (role == 0) return;
-#ifdef LA_DEV_KNOBS
-        if (p.dev_mode == 4) return;  // everything but the final merge
-#endif
-        if (role == 1) {
-            // ---- last to arrive, all partials sit in the L2 this XCD shares: merge them in
-            //      index order.  Work unit: one (tile, 32-column) slice; a wave requests all the
-            //      partials of its units before merging any, so that the usual case (at most 4
-            //      splits) costs one trip to the L2.
-            constexpr int NSUB = C::TILES * C::DB;
-            constexpr int NU = NSUB > C::NW ? 2 : 1;  // units in flight per wave
-            constexpr int MB = 4;                     // splits requested at a time
-            LA_STAMP(17);
-            for (int st0 = wave; st0 < NSUB; st0 += NU * C::NW) {
-                float m_acc[NU], l_acc[NU];
-                float acc[NU][16];
+            __builtin_amdgcn_s_waitcnt(0);
+            LA_STAMP(5);
+            unsigned role = 0;  // 0 not last, 1 last and co-located, 2 last but spread over several XCDs
+            if (lane == 0) {
+                // One atomic carries the arrival count and, to tell whether every member of the group
+                // ran on the same XCD (and so shares one L2), the sum and the sum of squares of the
+                // members' XCD ids: XS * sum(x^2) == (sum x)^2 holds iff all ids are equal.
+                const unsigned x = xcc_id();
+                const unsigned mine = 1u | (x << 8) | ((x * x) << 18);
+                const unsigned total = atomicAdd(my_ticket, mine) + mine;
+                const unsigned cnt = total & 0xffu, sum = (total >> 8) & 0x3ffu, sq = total >> 18;
+                if (cnt == (unsigned)p.XS) {
+                    *my_ticket = 0u;  // everyone has arrived; clean for the next call
+                    role = (sq * (unsigned)p.XS == sum * sum && !p.force_recompute) ? 1u : 2u;
+                }
+            }
+            role = __builtin_amdgcn_readfirstlane(role);
+            LA_STAMP(6);
+            if (role == 1) {
+                // ---- all partials sit in the L2 this XCD shares: four splits per trip to the L2
+                constexpr int MB = 4;
+                float m_acc = kNegInf, l_acc = 0.0f;
+                float acc[C::SPW][16];
 #pragma unroll
-                for (int u = 0; u < NU; ++u) {
-                    m_acc[u] = kNegInf;
-                    l_acc[u] = 0.0f;
+                for (int u = 0; u < C::SPW; ++u)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) acc[u][i] = 0.0f;
-                }
                 for (int s0 = 0; s0 < p.XS; s0 += MB) {
-                    // request everything of this batch, then merge: one trip to the L2
-                    f32x2 ml[NU][MB];
-                    bf16x8 v[NU][MB][2];
+                    f32x2 ml[MB];
+                    bf16x8 v[MB][C::SPW][2];
 #pragma unroll
-                    for (int u = 0; u < NU; ++u) {
-                        const int st = min(st0 + u * C::NW, NSUB - 1);
-                        const int tile = st / C::DB, db = st - tile * C::DB;
-                        const unsigned char* src0 = group_base + (size_t)tile * C::PART_TILE_BYTES;
+                    for (int w = 0; w < MB; ++w) {
+                        const int s2 = min(s0 + w, p.XS - 1);
+                        const unsigned char* src = group_base + (size_t)s2 * C::PART_WG_BYTES;
+                        ml[w] = *reinterpret_cast<const f32x2*>(src + C::PART_ACC_BYTES + lane * 8);
 #pragma unroll
-                        for (int w = 0; w < MB; ++w) {
-                            const int s2 = min(s0 + w, p.XS - 1);
-                            const unsigned char* src = src0 + (size_t)s2 * C::PART_WG_BYTES;
-                            ml[u][w] = *reinterpret_cast<const f32x2*>(src + C::PART_ACC_BYTES + lane * 8);
+                        for (int u = 0; u < C::SPW; ++u)
 #pragma unroll
                             for (int i8 = 0; i8 < 2; ++i8)
-                                v[u][w][i8] = *reinterpret_cast<const bf16x8*>(src + ((db * 2 + i8) * 64 + lane) * 16);
-                        }
+                                v[w][u][i8] = *reinterpret_cast<const bf16x8*>(src + ((u * 2 + i8) * 64 + lane) * 16);
                     }
                     LA_STAMP(18);
+                    // batch maximum, then one weight per split: acc = acc * a0 + sum_w v_w * a_w
+                    float mb = m_acc;
 #pragma unroll
-                    for (int u = 0; u < NU; ++u) {
-                        // batch maximum, then one weight per split: acc = acc * a0 + sum_w v_w * a_w
-                        float mb = m_acc[u];
+                    for (int w = 0; w < MB; ++w)
+                        if (s0 + w < p.XS) mb = fmaxf(mb, ml[w][0]);
+                    const float m_use = (mb == kNegInf) ? 0.0f : mb;
+                    const float a0 = fast_exp2((m_acc - m_use) * p.scale_log2);
+                    l_acc *= a0;
+                    if (s0 > 0) {
 #pragma unroll
-                        for (int w = 0; w < MB; ++w)
-                            if (s0 + w < p.XS) mb = fmaxf(mb, ml[u][w][0]);
-                        const float m_use = (mb == kNegInf) ? 0.0f : mb;
-                        const float a0 = fast_exp2((m_acc[u] - m_use) * p.scale_log2);
-                        l_acc[u] *= a0;
-                        if (s0 > 0) {
+                        for (int u = 0; u < C::SPW; ++u)
 #pragma unroll
                             for (int i = 0; i < 16; ++i) acc[u][i] *= a0;
-                        }
-                        m_acc[u] = mb;
+                    }
+                    m_acc = mb;
 #pragma unroll
-                        for (int w = 0; w < MB; ++w) {
-                            const float aw = s0 + w < p.XS ? fast_exp2((ml[u][w][0] - m_use) * p.scale_log2) : 0.0f;
-                            l_acc[u] = __builtin_fmaf(ml[u][w][1], aw, l_acc[u]);
+                    for (int w = 0; w < MB; ++w) {
+                        const float aw = s0 + w < p.XS ? fast_exp2((ml[w][0] - m_use) * p.scale_log2) : 0.0f;
+                        l_acc = __builtin_fmaf(ml[w][1], aw, l_acc);
+#pragma unroll
+                        for (int u = 0; u < C::SPW; ++u)
 #pragma unroll
                             for (int i8 = 0; i8 < 2; ++i8)
 #pragma unroll
                                 for (int e = 0; e < 8; ++e)
-                                    acc[u][i8 * 8 + e] = __builtin_fmaf((float)v[u][w][i8][e], aw, acc[u][i8 * 8 + e]);
-                        }
+                                    acc[u][i8 * 8 + e] = __builtin_fmaf((float)v[w][u][i8][e], aw, acc[u][i8 * 8 + e]);
                     }
                 }
+                const float inv = 1.0f / l_acc;
 #pragma unroll
-                for (int u = 0; u < NU; ++u) {
-                    const int st = st0 + u * C::NW;
-                    if (st >= NSUB) break;
-                    const int tile = st / C::DB, db = st - tile * C::DB;
+                for (int u = 0; u < C::SPW; ++u) {
                     f32x16 vals;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) vals[i] = acc[u][i];
-                    store_slice<C>(p, rb, kvh, tile, db, l32, hi, vals, 1.0f / l_acc[u]);
+                    store_slice<C>(p, rb, kvh, rt, db0 + u, l32, hi, vals, inv);
                 }
+                LA_STAMP(7);
             }
-            LA_STAMP(20);
-            LA_STAMP(7);
-            LA_CYCW(23);
-            return;
+            // ---- a wave that arrived last in a group spread over several XCDs, whose L2s are not
+            //      coherent with each other inside a kernel, cannot trust the partials: the whole
+            //      workgroup then recomputes its rows over every chunk from the read-only inputs (which
+            //      are always coherent), and the waves that asked for it write their slices directly
+            if (role == 2 && lane == 0) atomicOr((unsigned*)(lds + C::ROLE_OFFSET), 1u << wave);
         }
-        // ---- role 2: the group was spread over several XCDs, whose L2s are not coherent with
-        //      each other inside a kernel.  Inputs are read-only and always coherent, so the last
-        //      workgroup simply recomputes its rows over every chunk and writes them directly.
+        __syncthreads();
+        store_mask = (unsigned)__builtin_amdgcn_readfirstlane((int)*s_recompute);
+        if (store_mask == 0u) return;
+        __syncthreads();  // everyone has read the mask before the next pass clears it
         c_begin = 0;
         c_end = p.n_chunks;
         direct = true;
     }
 
     // ---- normalise and write this wave's slices (>= 1 visible key per row, so l > 0)
-    if (wave_active) {
+    if (wave_active && ((store_mask >> wave) & 1u)) {
         const float inv = 1.0f / l_run;
 #pragma unroll
         for (int u = 0; u < C::SPW; ++u) store_slice<C>(p, rb, kvh, rt, db0 + u, l32, hi, o[u], inv);
@@ -960,7 +905,7 @@ __global__ __launch_bounds__(RT* KS * 64) void step_attention_batch_kernel(const
 // library runs on holds one copy until the process ends.  In host code the name below is only a
 // handle: its device address is looked up once per device (fixed_workspace) and only that
 // pointer is handed to kernels.
-constexpr size_t kFixedTicketBytes = 4096;                      // 1024 split groups
+constexpr size_t kFixedTicketBytes = (size_t)128 << 10;          // 128 split groups x 8 waves, 128 bytes apart
 constexpr size_t kFixedPartialBytes = (size_t)12 << 20;         // 12 MiB of partials
 static __device__ __align__(256) unsigned char scratch[kFixedTicketBytes + kFixedPartialBytes];
 
@@ -981,6 +926,13 @@ struct Plan {
     int n_prefix_chunks, n_chunks;
     size_t partial_bytes_per_wg;
 };
+
+// Bytes of one workgroup's partial (Cfg::PART_WG_BYTES): per wave its slices as bf16 and (m, l).
+size_t partial_wg_bytes(int D, int RT, int KS)
+{
+    const int DB = D / 32, SPW = KS > 1 ? DB / KS : DB;
+    return (size_t)RT * KS * ((size_t)SPW * 16 * 64 * 2 + 64 * 8);
+}
 
 // Most LDS stages that fit beside the workgroup's Q rows.
 int max_stages(int D, int RT)
@@ -1059,7 +1011,7 @@ Plan make_plan(int P, int T, int group, int kv_heads, int D, bool paged = false,
     }
     if (pl.XS > pl.n_chunks) pl.XS = pl.n_chunks;
     if (pl.XS > 64) pl.XS = 64;
-    pl.partial_bytes_per_wg = (size_t)pl.RT * ((size_t)(D / 32) * 16 * 64 * 2 + 64 * 8);
+    pl.partial_bytes_per_wg = partial_wg_bytes(D, pl.RT, pl.KS);
     return pl;
 }
 
@@ -1155,12 +1107,6 @@ la_status build_params(AttnParams& prm, const Plan& pl, const void* q, const voi
     // testing hook: exercise the path taken when a split group is not on one XCD
     const char* fr = getenv("LA_FORCE_RECOMPUTE");
     prm.force_recompute = (fr && fr[0] == '1') ? 1 : 0;
-#ifdef LA_DEV_KNOBS
-    const char* dm = getenv("LA_DEV_MODE");
-    prm.dev_mode = dm ? atoi(dm) : 0;
-    const char* tp = getenv("LA_DEV_TRACE_PTR");
-    prm.dev_trace = tp ? (long long*)strtoull(tp, nullptr, 16) : nullptr;
-#endif
     return LA_OK;
 }
 
@@ -1185,7 +1131,7 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
     const long long total = prm.total_wg;
 
     if (pl.XS > 1) {
-        const size_t ticket_bytes = (size_t)kv_heads * pl.n_row_blocks * sizeof(unsigned);
+        const size_t ticket_bytes = (size_t)kv_heads * pl.n_row_blocks * pl.RT * pl.KS * sizeof(unsigned) * kTicketStride;
         const size_t bytes = (size_t)total * pl.partial_bytes_per_wg;
         if (fixed) {
             // a caller that cannot allocate: the blocks are given and cannot grow
@@ -1350,7 +1296,7 @@ la_status launch_step_attention_batch(const BatchSeq* seqs, int n_seqs, int page
             Plan& q = pl[i];
             q.RT = RT; q.KS = KS; q.NS = 4; q.KC = 64; q.PRE = 0;
             q.n_row_blocks = n_row_blocks;
-            q.partial_bytes_per_wg = (size_t)RT * ((size_t)(head_dim / 32) * 16 * 64 * 2 + 64 * 8);
+            q.partial_bytes_per_wg = partial_wg_bytes(head_dim, RT, KS);
             int xs = (int)((q.n_chunks + target - 1) / target);
             if (xs > q.n_chunks / 2) xs = q.n_chunks / 2;
             if (xs > 64) xs = 64;
@@ -1363,7 +1309,7 @@ la_status launch_step_attention_batch(const BatchSeq* seqs, int n_seqs, int page
             slot += bp.seq[i].wg_per_xcd;
             if (q.XS > 1) {
                 partial_bytes += (size_t)bp.seq[i].total_wg * q.partial_bytes_per_wg;
-                ticket_count += (size_t)kv_heads * n_row_blocks;
+                ticket_count += (size_t)kv_heads * n_row_blocks * RT * KS * kTicketStride;
             }
         }
         for (int i = n; i <= kMaxBatch; ++i) bp.slots.slot0[i] = slot;
@@ -1375,7 +1321,7 @@ la_status launch_step_attention_batch(const BatchSeq* seqs, int n_seqs, int page
                 if (pl[i].XS <= 1) continue;
                 bp.seq[i].tickets = tickets;
                 bp.seq[i].partials = partials;
-                tickets += (size_t)kv_heads * n_row_blocks;
+                tickets += (size_t)kv_heads * n_row_blocks * RT * KS * kTicketStride;
                 partials += (size_t)bp.seq[i].total_wg * pl[i].partial_bytes_per_wg;
             }
         }

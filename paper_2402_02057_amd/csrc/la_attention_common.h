@@ -75,6 +75,18 @@ __device__ __forceinline__ float max3(float a, float b, float c)
     return r;
 }
 
+// The maxima above and below are written as assembly, which the compiler's hazard bookkeeping does
+// not look into: a vector instruction must not read the result registers of a matrix instruction
+// for up to 19 cycles after it was issued (it would see the accumulator before the last pass; seen
+// here as a reference maximum that changed from run to run).  Where such a maximum may directly
+// follow the MFMA that produces its operands, these idle cycles stand in for the wait the compiler
+// would have inserted.
+template <class V>
+__device__ __forceinline__ void settle_mfma_result(V& acc)
+{
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 2" : "+v"(acc));
+}
+
 __device__ __forceinline__ float max2(float a, float b)
 {
     float r;

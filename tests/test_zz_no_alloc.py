@@ -75,7 +75,7 @@ def test_two_calls_second_smaller():
 
 def test_refuses_what_does_not_fit(monkeypatch):
     """A decomposition whose partials exceed the fixed block is refused before anything is launched
-    (the library's own choice never needs more than 8.3 MiB; a 64-way split forced by hand does).
+    (the library's own choice never needs more than 5 MiB; a 64-way split forced by hand does).
     The buffers are real and of the right size all the same."""
     torch.cuda.set_device(0)
     monkeypatch.setenv("LA_ATTN_PLAN", "2,4,64,4,64")
