@@ -325,7 +325,9 @@ la_status la_verify_step_batch(const la_verify_desc* descs, int n_descs, int W, 
  *                                  candidate)
  *   logits_cand  fp32 [G][N-1][V]  row (g,k): output at candidate g's token k (its distribution
  *                                  k+2); NULL iff G == 0
- *   cand_tokens  int32 [G][N-1]
+ *   cand_tokens  int32 [G][N-1]    a token outside 0 .. V-1 (a padding id) is examined like any
+ *                                  other - its draw is spent - and has probability zero: never
+ *                                  accepted, nothing ruled out, no logit read
  *   u_test       fp32 [N-1][G]     uniform draws in [0,1): u_test[i][j] serves the j-th candidate
  *                                  examined at position i; NULL iff G == 0
  *   u_final      fp32 [1]          the draw for the last token (inverse CDF in index order)
@@ -379,6 +381,35 @@ la_status la_verify_sample_batch(const la_sample_desc* descs, int n_descs, int N
 la_status la_step_attention_noalloc(const void* q, const void* k_cache, const void* v_cache,
                                     const void* step_k, const void* step_v, int P, int W, int N, int G,
                                     int heads, int kv_heads, int head_dim, void* out, void* stream);
+
+/*
+ * Testing hooks (host strings; not for production use).  They take their first values from the
+ * environment variables named below, read once at the first attention call, and apply to the
+ * whole process from then on:
+ *   "attn_plan"        (LA_ATTN_PLAN)        "RT,KS,XS,NS,KC[,PRE]": the decomposition of the one-step
+ *                                            entry points forced by hand (ignored where no such
+ *                                            kernel is compiled); NULL or "" = the library's choice
+ *   "batch_plan"       (LA_BATCH_PLAN)       "2" or "4": 32-row tiles per workgroup of a batched launch
+ *   "force_recompute"  (LA_FORCE_RECOMPUTE)  "1": treat every split group as spread over several
+ *                                            XCDs, so that the recompute path runs
+ * Returns LA_EINVAL for an unknown key or a malformed plan.
+ */
+la_status la_debug_override(const char* key, const char* value);
+
+/*
+ * Measurement aids (not part of the method; Sec. 1 and Sec. 4.2 argue from the gap between what
+ * decoding moves and what the device can compute, so a benchmark quotes both): what this device
+ * reaches at best.  Time them with events on `stream`.
+ *   la_probe_stream_read  reads `bytes` (a multiple of 16, 16-byte aligned) of device memory once;
+ *                         `sink` (4 bytes of device memory) is never written in practice
+ *   la_probe_mfma         `iters` x 8 bf16 MFMAs (32x32x16) per wave on register operands, 32 waves
+ *                         per compute unit; returns the floating-point operations of the launch
+ *                         (-1 on error).  `sink`: 24 bytes of device memory, 8-byte aligned; the
+ *                         first wave leaves its elapsed shader-clock cycles in sink[0] and its
+ *                         elapsed 100 MHz ticks in sink[1] (uint64 each): the clock it ran at
+ */
+la_status la_probe_stream_read(const void* src, long long bytes, void* sink, void* stream);
+long long la_probe_mfma(int iters, void* sink, void* stream);
 
 /* Bytes of device workspace la_step_attention needs for this shape (0 if none). */
 long long la_step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int kv_heads,

@@ -127,6 +127,16 @@ int la_oracle_threads(void)
 #endif
 }
 
+/* How many threads the loops over heads may use from now on (timing the oracle on one core). */
+void la_oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 /*
  * out = softmax(mask(q k^T / sqrt(head_dim))) v, per head (Sec. 2, "Causal
  * Attention in Decoder Models", with the mask of Sec. 3.3).  Keys of a row are
@@ -333,7 +343,8 @@ int la_oracle_verify_step(const float *logits_cur, const float *logits_look, con
  * Readings: the test "r <= P(s)" is taken as r < P(s) for r in [0,1) (same probability; a
  * token of probability zero is never accepted); sampling is by inverse CDF in index order:
  * the first v whose cumulative probability exceeds u.  G == 0: one token sampled from the
- * current token's distribution.
+ * current token's distribution.  A candidate token outside 0 .. V-1 (a padding id) is examined
+ * like any other - its draw is spent - and has probability zero.
  */
 static void softmax_row(const float *row, int V, double inv_t, double *P)
 {
@@ -381,6 +392,9 @@ int la_oracle_verify_sample(const float *logits_cur, const float *logits_cand, c
         for (int j = 0; j < n_alive; ++j) {
             const int s = cand_tokens[alive[j] * n1 + i];
             const double r = (double)u_test[i * G + j];
+            /* a token outside the vocabulary has probability zero under every distribution over
+             * it: the draw is spent, the token is not accepted and there is nothing to rule out */
+            if (s < 0 || s >= V) continue;
             if (r < P[s]) {
                 out_tokens[len++] = s;
                 accepted = 1;

@@ -61,6 +61,11 @@ def threads():
     return _load().la_oracle_threads()
 
 
+def set_threads(n):
+    """Let the oracle's loops over heads use `n` threads from now on (for timing on one core)."""
+    _load().la_oracle_set_threads(int(n))
+
+
 def step_mask(W, N, G):
     """bool [T, T]: may step row r attend to step key c (Sec. 3.3)."""
     T = num_rows(W, N, G)
@@ -153,6 +158,57 @@ def verify_sample(logits_cur, logits_cand, cand_tokens, u_test, u_final, tempera
     if rc != 0:
         raise ValueError("la_oracle_verify_sample: bad arguments (rc=%d)" % rc)
     return [int(t) for t in out[:int(n_out[0])]]
+
+
+def verify_sample_margin(logits_cur, logits_cand, cand_tokens, u_test, u_final, temperature, N, G, V):
+    """Algorithm 4 once more, in NumPy fp64, returning (tokens, margin): margin is the smallest
+    distance between a uniform draw and the value it was compared with (an accept test against
+    P(s), or a step of the cumulative distribution of the last draw).  An fp32 implementation may
+    decide a comparison whose margin is within its rounding (about 1e-6) the other way; callers
+    that check one against the oracle demand equality unless the margin is that small."""
+    n1 = N - 1
+    cur = np.asarray(logits_cur, dtype=np.float64)
+    cnd = np.asarray(logits_cand, dtype=np.float64).reshape(G, n1, V)
+    cand = np.asarray(cand_tokens).reshape(G, n1)
+    ut = np.asarray(u_test, dtype=np.float64).reshape(n1, G)
+    margin = [1.0]
+
+    def dist(row):
+        z = row / float(temperature)
+        e = np.exp(z - z.max())
+        return e / e.sum()
+
+    def draw(P, u):
+        cdf = np.cumsum(P)
+        v = min(int(np.searchsorted(cdf, u, side="right")), V - 1)
+        while P[v] == 0.0 and v > 0:
+            v -= 1
+        margin[0] = min(margin[0], abs(cdf[v] - u))
+        if v > 0:
+            margin[0] = min(margin[0], abs(cdf[v - 1] - u))
+        return v
+    alive, out = list(range(G)), []
+    for i in range(n1):
+        if not alive:
+            break
+        P = dist(cur if i == 0 else cnd[alive[0], i - 1])
+        accepted = False
+        for j, g in enumerate(alive):
+            s = int(cand[g, i])
+            if not 0 <= s < V:
+                continue
+            margin[0] = min(margin[0], abs(ut[i, j] - P[s]))
+            if ut[i, j] < P[s]:
+                out.append(s)
+                alive = [k for k in alive[j:] if cand[k, i] == s]
+                accepted = True
+                break
+            P[s] = 0.0
+            P = P / P.sum()
+        if not accepted:
+            return out + [draw(P, float(u_final))], margin[0]
+    P = dist(cur if not out else cnd[alive[0], len(out) - 1])
+    return out + [draw(P, float(u_final))], margin[0]
 
 
 def greedy_verification(candidates, dist_argmax):

@@ -105,6 +105,12 @@ def load():
     lib.la_shutdown.restype = None
     lib.la_last_error.argtypes = []
     lib.la_last_error.restype = ctypes.c_char_p
+    lib.la_probe_stream_read.argtypes = [p, ll, p, p]
+    lib.la_probe_stream_read.restype = i
+    lib.la_probe_mfma.argtypes = [i, p, p]
+    lib.la_probe_mfma.restype = ll
+    lib.la_debug_override.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
+    lib.la_debug_override.restype = i
     lib.la_select_workspace.argtypes = [i]
     lib.la_select_workspace.restype = i
     lib.la_version.argtypes = []
@@ -113,7 +119,7 @@ def load():
     return lib
 
 
-EXPORTS = ("la_step_rope", "la_step_attention", "la_step_attention_noalloc", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_kv_commit_batch", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_step_batch", "la_verify_sample", "la_verify_sample_batch", "la_step_attention_workspace_bytes", "la_shutdown", "la_select_workspace",
+EXPORTS = ("la_step_rope", "la_step_attention", "la_step_attention_noalloc", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_kv_commit_batch", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_step_batch", "la_verify_sample", "la_verify_sample_batch", "la_step_attention_workspace_bytes", "la_shutdown", "la_select_workspace", "la_debug_override", "la_probe_stream_read", "la_probe_mfma",
            "la_last_error", "la_version")
 
 
@@ -479,3 +485,22 @@ def bf16_bits(t):
     """bf16 tensor -> numpy uint16 bit patterns on the host."""
     import numpy as np
     return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def la_debug_override(key, value):
+    """Testing hook: force a decomposition ("attn_plan", "batch_plan") or the recompute path
+    ("force_recompute"); value None clears it."""
+    _check(load().la_debug_override(key.encode(), None if value is None else str(value).encode()))
+
+
+def la_probe_stream_read(buf, sink, stream=None):
+    """Measurement aid: read every byte of the uint8 tensor `buf` once (asynchronous)."""
+    _check(load().la_probe_stream_read(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(), _stream(stream)))
+
+
+def la_probe_mfma(iters, sink, stream=None):
+    """Measurement aid: a register-resident bf16 MFMA loop; returns the flops of the launch."""
+    flops = load().la_probe_mfma(int(iters), sink.data_ptr(), _stream(stream))
+    if flops < 0:
+        raise LaError(LA_EHIP, load().la_last_error().decode())
+    return int(flops)

@@ -12,6 +12,7 @@
 namespace la {
 
 static thread_local char g_error[512] = "";
+static thread_local la_status g_last_code = LA_OK;
 
 la_status fail(la_status code, const char* fmt, ...)
 {
@@ -19,8 +20,11 @@ la_status fail(la_status code, const char* fmt, ...)
     va_start(ap, fmt);
     vsnprintf(g_error, sizeof g_error, fmt, ap);
     va_end(ap);
+    g_last_code = code;
     return code;
 }
+
+la_status last_failure() { return g_last_code; }
 
 namespace {
 constexpr int kMaxDevices = 16;
@@ -60,12 +64,29 @@ la_status select_workspace(int set)
     return LA_OK;
 }
 
+namespace {
+// Growing a block means hipMalloc (and a clear on the stream): neither may happen while the
+// stream is being captured into a graph - the allocation would invalidate the capture, the
+// clear would be recorded as a node of it.
+bool growth_allowed(hipStream_t stream)
+{
+    hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &status) == hipSuccess && status != hipStreamCaptureStatusNone) {
+        fail(LA_EUNSUPPORTED, "the device workspace must grow for this shape, which cannot happen while the stream is "
+                              "being captured: run a call of this (or a larger) shape outside the capture first");
+        return false;
+    }
+    return true;
+}
+}  // namespace
+
 void* zeroed_workspace(size_t bytes, hipStream_t stream)
 {
     std::lock_guard<std::mutex> lock(g_mutex);
     Pool* p = current_pool();
     if (!p) return nullptr;
     if (bytes <= p->zeroed_bytes) return p->zeroed;
+    if (!growth_allowed(stream)) return nullptr;
     // Growing (only when a larger shape than any before is seen): a fresh block, cleared on
     // this stream ahead of the kernel that will use it; the old one is retired, not freed.
     size_t want = bytes < (1u << 16) ? (1u << 16) : bytes;
@@ -85,12 +106,13 @@ void* zeroed_workspace(size_t bytes, hipStream_t stream)
     return fresh;
 }
 
-void* scratch_workspace(size_t bytes)
+void* scratch_workspace(size_t bytes, hipStream_t stream)
 {
     std::lock_guard<std::mutex> lock(g_mutex);
     Pool* p = current_pool();
     if (!p) return nullptr;
     if (bytes <= p->scratch_bytes) return p->scratch;
+    if (!growth_allowed(stream)) return nullptr;
     size_t want = bytes < (size_t(8) << 20) ? (size_t(8) << 20) : bytes + bytes / 4;
     void* fresh = nullptr;
     if (hipMalloc(&fresh, want) != hipSuccess) {
@@ -516,9 +538,27 @@ long long la_step_attention_workspace_bytes(int P, int W, int N, int G, int head
     return (long long)la::step_attention_workspace_bytes(P, W, N, G, heads, kv_heads, head_dim);
 }
 
+la_status la_probe_stream_read(const void* src, long long bytes, void* sink, void* stream)
+{
+    if (!src || !sink || bytes < 16 || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)sink & 3))
+        return la::fail(LA_EINVAL, "la_probe_stream_read: need a 16-byte aligned buffer of a multiple of 16 bytes and a sink");
+    return la::launch_probe_stream_read(src, bytes, sink, (hipStream_t)stream);
+}
+
+long long la_probe_mfma(int iters, void* sink, void* stream)
+{
+    if (iters < 1 || iters > (1 << 24) || !sink || ((uintptr_t)sink & 7)) {
+        la::fail(LA_EINVAL, "la_probe_mfma: need 1 <= iters <= 2^24 and an 8-byte aligned sink of 24 bytes");
+        return -1;
+    }
+    return la::launch_probe_mfma(iters, sink, (hipStream_t)stream);
+}
+
 void la_shutdown(void) { la::free_workspaces(); }
 
 la_status la_select_workspace(int set) { return la::select_workspace(set); }
+
+la_status la_debug_override(const char* key, const char* value) { return la::set_override(key, value); }
 
 const char* la_last_error(void) { return la::g_error; }
 

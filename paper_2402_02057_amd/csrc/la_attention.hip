@@ -41,6 +41,7 @@
 #include <stdlib.h>
 
 #include <mutex>
+#include <string>
 
 #include "la_internal.h"
 #include "la_attention_common.h"
@@ -918,6 +919,58 @@ __global__ void clear_words_kernel(unsigned* words, int n)
 // ---------------------------------------------------------------------------------------
 // host side
 
+// Testing hooks (la_debug_override; the environment gives their values at the first call): a
+// decomposition forced by hand, and the recompute path of a split group forced on.
+struct Overrides {
+    bool has_plan = false;
+    int plan[6] = {0, 0, 0, 0, 0, 0};  // RT, KS, XS, NS, KC, PRE (XS = 0, PRE = 0: heuristic)
+    int batch_rows = 0;                // 2 or 4: 32-row tiles per workgroup of a batched launch
+    bool force_recompute = false;
+};
+std::mutex g_config_mutex;  // the overrides, and the once-per-device kernel attributes
+Overrides g_overrides;
+bool g_overrides_from_env = false;
+
+bool parse_plan(const char* text, Overrides& o)
+{
+    int v[6] = {0, 0, 0, 0, 0, 0};
+    o.has_plan = text && sscanf(text, "%d,%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4], &v[5]) >= 5;
+    for (int i = 0; i < 6; ++i) o.plan[i] = o.has_plan ? v[i] : 0;
+    return o.has_plan;
+}
+
+void overrides_from_env_locked()
+{
+    if (g_overrides_from_env) return;
+    g_overrides_from_env = true;
+    parse_plan(getenv("LA_ATTN_PLAN"), g_overrides);
+    const char* b = getenv("LA_BATCH_PLAN");
+    g_overrides.batch_rows = (b && (b[0] == '2' || b[0] == '4')) ? b[0] - '0' : 0;
+    const char* f = getenv("LA_FORCE_RECOMPUTE");
+    g_overrides.force_recompute = f && f[0] == '1';
+}
+
+Overrides current_overrides()
+{
+    std::lock_guard<std::mutex> lock(g_config_mutex);
+    overrides_from_env_locked();
+    return g_overrides;
+}
+
+// hipFuncSetAttribute once per kernel and device (`done` is that kernel's own table)
+la_status set_lds_attribute_once(const void* kern, int lds_bytes, bool (&done)[16])
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return fail(LA_EHIP, "hipGetDevice failed");
+    std::lock_guard<std::mutex> lock(g_config_mutex);
+    if (!done[dev]) {
+        const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return fail(LA_EHIP, "hipFuncSetAttribute(%d bytes LDS): %s", lds_bytes, hipGetErrorString(e));
+        done[dev] = true;
+    }
+    return LA_OK;
+}
+
 struct Plan {
     int RT, KS, XS, NS;       // NS = LDS stages
     int PRE;                  // chunks requested before the loop (0 = all stages)
@@ -968,7 +1021,7 @@ bool rowset_plan_supported(int D, int RT, int KS, int NS, int KC)
     return paged_plan_supported(D, RT, KS, NS, KC) && RT != 4;
 }
 
-Plan make_plan(int P, int T, int group, int kv_heads, int D, bool paged = false, bool rowset = false)
+Plan make_plan(const Overrides& ov, int P, int T, int group, int kv_heads, int D, bool paged = false, bool rowset = false)
 {
     Plan pl;
     const int R = T * group;
@@ -986,11 +1039,10 @@ Plan make_plan(int P, int T, int group, int kv_heads, int D, bool paged = false,
     pl.XS = 0;
     pl.NS = 0;
     pl.PRE = 0;
-    // developer override: LA_ATTN_PLAN="RT,KS,XS,NS,KC[,PRE]" (XS = 0, PRE = 0: heuristic)
-    if (const char* env = getenv("LA_ATTN_PLAN")) {
-        int b = 0, c = 0, d = 0, e = 0, f = 0, g = 0;
-        if (sscanf(env, "%d,%d,%d,%d,%d,%d", &b, &c, &d, &e, &f, &g) >= 5 &&
-            plan_supported(D, b, c, e, f) && (!paged || paged_plan_supported(D, b, c, e, f)) &&
+    // testing hook: a decomposition forced by hand, "RT,KS,XS,NS,KC[,PRE]" (XS = 0, PRE = 0: heuristic)
+    if (ov.has_plan) {
+        const int b = ov.plan[0], c = ov.plan[1], d = ov.plan[2], e = ov.plan[3], f = ov.plan[4], g = ov.plan[5];
+        if (plan_supported(D, b, c, e, f) && (!paged || paged_plan_supported(D, b, c, e, f)) &&
             (!rowset || rowset_plan_supported(D, b, c, e, f))) {
             pl.RT = b; pl.KS = c; pl.XS = d; pl.NS = e; pl.KC = f;
             pl.PRE = g;
@@ -1023,14 +1075,8 @@ la_status launch_cfg(const AttnParams& prm, hipStream_t stream)
     static_assert(kLds <= 160 * 1024, "LDS of a compute unit");
     auto kern = step_attention_kernel<D, RT, KS, KC, NSTAGE, PAGED, ROWSET>;
     static bool attr_set[16] = {false};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return fail(LA_EHIP, "hipGetDevice failed");
-    if (!attr_set[dev]) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-        if (e != hipSuccess) return fail(LA_EHIP, "hipFuncSetAttribute(%d bytes LDS): %s", kLds, hipGetErrorString(e));
-        attr_set[dev] = true;
-    }
+    const la_status st = set_lds_attribute_once(reinterpret_cast<const void*>(kern), kLds, attr_set);
+    if (st != LA_OK) return st;
     const unsigned grid = (unsigned)prm.wg_per_xcd * 8u;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), kLds, stream, prm);
     const hipError_t e = hipGetLastError();
@@ -1043,7 +1089,7 @@ la_status launch_cfg(const AttnParams& prm, hipStream_t stream)
 size_t step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int kv_heads, int head_dim)
 {
     const int T = 1 + (W + G) * (N - 1);
-    const Plan pl = make_plan(P, T, heads / kv_heads, kv_heads, head_dim);
+    const Plan pl = make_plan(current_overrides(), P, T, heads / kv_heads, kv_heads, head_dim);
     if (pl.XS <= 1) return 0;
     return (size_t)kv_heads * pl.n_row_blocks * pl.XS * pl.partial_bytes_per_wg;
 }
@@ -1051,7 +1097,7 @@ size_t step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int
 namespace {
 
 // Everything of a launch's parameters that follows from the arguments and the plan (no workspace).
-la_status build_params(AttnParams& prm, const Plan& pl, const void* q, const void* k_cache, const void* v_cache,
+la_status build_params(AttnParams& prm, const Overrides& ov, const Plan& pl, const void* q, const void* k_cache, const void* v_cache,
                        long long capacity, const int* block_table, int page_size, int n_pages, const int* row_ids,
                        int T, const void* step_k, const void* step_v, int P, int W, int N, int G, int heads,
                        int kv_heads, int head_dim, void* out)
@@ -1105,8 +1151,7 @@ la_status build_params(AttnParams& prm, const Plan& pl, const void* q, const voi
     // per workgroup, a loss at 8).
     if (pl.PRE == 0 && cpi == 1 && prm.chunks_lo >= 16) prm.pre = pl.NS;
     // testing hook: exercise the path taken when a split group is not on one XCD
-    const char* fr = getenv("LA_FORCE_RECOMPUTE");
-    prm.force_recompute = (fr && fr[0] == '1') ? 1 : 0;
+    prm.force_recompute = ov.force_recompute ? 1 : 0;
     return LA_OK;
 }
 
@@ -1123,9 +1168,10 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
     if ((long long)T * group >= (1 << 21) || (long long)T * heads * head_dim * 2 >= (1ll << 31) ||
         (long long)kv_heads * head_dim * 2 >= (1 << 24))
         return fail(LA_EUNSUPPORTED, "la_step_attention: step too large (T=%d, heads=%d)", T, heads);
-    const Plan pl = make_plan(P, T, group, kv_heads, head_dim, block_table != nullptr, row_ids != nullptr);
+    const Overrides ov = current_overrides();
+    const Plan pl = make_plan(ov, P, T, group, kv_heads, head_dim, block_table != nullptr, row_ids != nullptr);
     AttnParams prm;
-    const la_status st = build_params(prm, pl, q, k_cache, v_cache, capacity, block_table, page_size, n_pages, row_ids,
+    const la_status st = build_params(prm, ov, pl, q, k_cache, v_cache, capacity, block_table, page_size, n_pages, row_ids,
                                       T, step_k, step_v, P, W, N, G, heads, kv_heads, head_dim, out);
     if (st != LA_OK) return st;
     const long long total = prm.total_wg;
@@ -1150,9 +1196,9 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
             if (e != hipSuccess) return fail(LA_EHIP, "la_step_attention_noalloc: clearing the tickets: %s", hipGetErrorString(e));
         } else {
             prm.tickets = (unsigned*)zeroed_workspace(ticket_bytes, stream);
-            if (!prm.tickets) return LA_ENOMEM;
-            prm.partials = scratch_workspace(bytes);
-            if (!prm.partials) return LA_ENOMEM;
+            if (!prm.tickets) return last_failure();
+            prm.partials = scratch_workspace(bytes, stream);
+            if (!prm.partials) return last_failure();
         }
     }
 
@@ -1211,14 +1257,8 @@ la_status launch_batch_cfg(const BatchParams& bp, unsigned grid, hipStream_t str
     using C = Cfg<D, RT, KS, 64, NSTAGE>;
     auto kern = step_attention_batch_kernel<D, RT, KS, 64, NSTAGE, PAGED>;
     static bool attr_set[16] = {false};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return fail(LA_EHIP, "hipGetDevice failed");
-    if (!attr_set[dev]) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-        if (e != hipSuccess) return fail(LA_EHIP, "hipFuncSetAttribute(%d bytes LDS): %s", C::LDS_BYTES, hipGetErrorString(e));
-        attr_set[dev] = true;
-    }
+    const la_status st = set_lds_attribute_once(reinterpret_cast<const void*>(kern), C::LDS_BYTES, attr_set);
+    if (st != LA_OK) return st;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), C::LDS_BYTES, stream, bp);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(LA_EHIP, "la_step_attention_batch launch: %s", hipGetErrorString(e));
@@ -1238,6 +1278,7 @@ la_status launch_step_attention_batch(const BatchSeq* seqs, int n_seqs, int page
     if ((long long)T * group >= (1 << 21) || (long long)T * heads * head_dim * 2 >= (1ll << 31) ||
         (long long)kv_heads * head_dim * 2 >= (1 << 24))
         return fail(LA_EUNSUPPORTED, "la_step_attention_batch: step too large (T=%d, heads=%d)", T, heads);
+    const Overrides ov = current_overrides();
     // longest first: workgroups are handed out in id order
     int order[1024];
     if (n_seqs > 1024) return fail(LA_EUNSUPPORTED, "la_step_attention_batch: at most 1024 steps per call");
@@ -1260,7 +1301,7 @@ la_status launch_step_attention_batch(const BatchSeq* seqs, int n_seqs, int page
         // cut so that every workgroup gets about the same number of chunks, with enough
         // workgroups for two rounds over the 256 compute units.
         Plan pl[kMaxBatch];
-        for (int i = 0; i < n; ++i) pl[i] = make_plan(seqs[order[first + i]].P, T, group, kv_heads, head_dim);
+        for (int i = 0; i < n; ++i) pl[i] = make_plan(Overrides(), seqs[order[first + i]].P, T, group, kv_heads, head_dim);
         long long work = 0;
         // 128-row workgroups (a chunk of K/V staged once for four row tiles: half the traffic into
         // LDS per flop) as soon as the batch fills three quarters of the GPU with them; otherwise
@@ -1273,10 +1314,8 @@ la_status launch_step_attention_batch(const BatchSeq* seqs, int n_seqs, int page
         } else {
             KS = 2;
         }
-        if (const char* bp_env = getenv("LA_BATCH_PLAN")) {   // experiments
-            if (head_dim == 128 && bp_env[0] == '4') { RT = 4; KS = 2; }
-            if (head_dim == 128 && bp_env[0] == '2') { RT = 2; KS = 4; }
-        }
+        if (head_dim == 128 && ov.batch_rows == 4) { RT = 4; KS = 2; }  // testing hook
+        if (head_dim == 128 && ov.batch_rows == 2) { RT = 2; KS = 4; }
         const int rows_wg = RT * 32;
         const int n_row_blocks = (T * group + rows_wg - 1) / rows_wg;
         for (int i = 0; i < n; ++i) work += (long long)kv_heads * n_row_blocks * pl[i].n_chunks;
@@ -1301,7 +1340,7 @@ la_status launch_step_attention_batch(const BatchSeq* seqs, int n_seqs, int page
             if (xs > q.n_chunks / 2) xs = q.n_chunks / 2;
             if (xs > 64) xs = 64;
             q.XS = xs < 1 ? 1 : xs;
-            const la_status st = build_params(bp.seq[i], q, d.q, d.k_cache, d.v_cache, d.P,
+            const la_status st = build_params(bp.seq[i], ov, q, d.q, d.k_cache, d.v_cache, d.P,
                                               d.P > 0 ? d.block_table : nullptr, page_size, n_pages, nullptr, T,
                                               d.step_k, d.step_v, d.P, W, N, G, heads, kv_heads, head_dim, d.out);
             if (st != LA_OK) return st;
@@ -1315,8 +1354,8 @@ la_status launch_step_attention_batch(const BatchSeq* seqs, int n_seqs, int page
         for (int i = n; i <= kMaxBatch; ++i) bp.slots.slot0[i] = slot;
         if (partial_bytes) {
             unsigned* tickets = (unsigned*)zeroed_workspace(ticket_count * sizeof(unsigned), stream);
-            unsigned char* partials = (unsigned char*)scratch_workspace(partial_bytes);
-            if (!tickets || !partials) return LA_ENOMEM;
+            unsigned char* partials = (unsigned char*)scratch_workspace(partial_bytes, stream);
+            if (!tickets || !partials) return last_failure();
             for (int i = 0; i < n; ++i) {
                 if (pl[i].XS <= 1) continue;
                 bp.seq[i].tickets = tickets;
@@ -1335,6 +1374,27 @@ la_status launch_step_attention_batch(const BatchSeq* seqs, int n_seqs, int page
         else if (head_dim == 128) st = launch_batch_cfg<128, 2, 4, 4>(bp, grid, stream);
         else st = launch_batch_cfg<64, 2, 2, 4>(bp, grid, stream);
         if (st != LA_OK) return st;
+    }
+    return LA_OK;
+}
+
+// ---- testing hooks
+
+la_status set_override(const char* key, const char* value)
+{
+    if (!key) return fail(LA_EINVAL, "la_debug_override: null key");
+    const std::string k = key;
+    std::lock_guard<std::mutex> lock(g_config_mutex);
+    overrides_from_env_locked();
+    if (k == "attn_plan") {
+        if (!parse_plan(value, g_overrides) && value && value[0])
+            return fail(LA_EINVAL, "la_debug_override: attn_plan wants \"RT,KS,XS,NS,KC[,PRE]\", got \"%s\"", value);
+    } else if (k == "batch_plan") {
+        g_overrides.batch_rows = (value && (value[0] == '2' || value[0] == '4')) ? value[0] - '0' : 0;
+    } else if (k == "force_recompute") {
+        g_overrides.force_recompute = value && value[0] == '1';
+    } else {
+        return fail(LA_EINVAL, "la_debug_override: unknown key \"%s\"", key);
     }
     return LA_OK;
 }

@@ -11,14 +11,20 @@ namespace la {
 
 // Record a message for la_last_error() and hand back `code`.
 la_status fail(la_status code, const char* fmt, ...);
+// The code of this thread's last fail(): what a caller returns when a helper that reports through
+// a null pointer (the workspaces) has failed.
+la_status last_failure();
 
 // Per-device scratch memory.  `bytes` of zero-initialised device memory that every kernel
 // leaves zeroed again (tickets, packed argmax keys), and `bytes` of uninitialised memory
-// (split partials).  Grown on demand; returns nullptr (and records the error) on failure.
+// (split partials).  Grown on demand - never while `stream` is being captured; returns nullptr
+// (and records the error) on failure.
 void* zeroed_workspace(size_t bytes, hipStream_t stream);
-void* scratch_workspace(size_t bytes);
+void* scratch_workspace(size_t bytes, hipStream_t stream);
 void free_workspaces();
 la_status select_workspace(int set);
+// Testing hooks of the attention launchers (la_debug_override).
+la_status set_override(const char* key, const char* value);
 
 // Launchers (defined next to their kernels).
 la_status launch_verify(const float* logits, const int* cand_tokens, int G, int N, int V,
@@ -111,5 +117,9 @@ la_status launch_step_rope(void* q, void* step_k, const float* cos, const float*
                            int heads, int kv_heads, int head_dim, int interleaved, hipStream_t stream);
 size_t step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int kv_heads,
                                       int head_dim);
+
+// Measurement aids (la_probe.hip).
+la_status launch_probe_stream_read(const void* src, long long bytes, void* sink, hipStream_t stream);
+long long launch_probe_mfma(int iters, void* sink, hipStream_t stream);  // flops of the launch, -1 on error
 
 }  // namespace la

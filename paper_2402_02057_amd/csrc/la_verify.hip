@@ -462,7 +462,10 @@ __device__ __forceinline__ void verify_sample_body(
                 const int j = base + lane;
                 const bool valid = j < n_alive;
                 const int t = valid ? ct[alive[j] * n1 + i] : -1;
-                const float e = valid ? expw(prow[t], inv_t, mrow) : 0.0f;
+                // a candidate token outside the vocabulary (a padding id, say) has probability zero: it
+                // is never accepted, rules nothing out, and its logit is never read
+                const bool in_vocab = valid && (unsigned)t < (unsigned)V;
+                const float e = in_vocab ? expw(prow[t], inv_t, mrow) : 0.0f;
                 const float u = valid ? ut[i * G + j] : 2.0f;
                 if (valid) tok[j] = t;
                 __builtin_amdgcn_wave_barrier();
@@ -732,7 +735,7 @@ la_status launch_verify(const float* logits, const int* cand_tokens, int G, int 
     // workspace: one 64-bit key per row, then one ticket per candidate
     const size_t bytes = (size_t)rows * 8 + (size_t)G * 4;
     char* ws = (char*)zeroed_workspace(bytes, stream);
-    if (!ws) return LA_ENOMEM;
+    if (!ws) return last_failure();
     unsigned long long* keys = (unsigned long long*)ws;
     unsigned* ticket = (unsigned*)(ws + (size_t)rows * 8);
 
@@ -770,7 +773,7 @@ la_status launch_verify_step(const float* logits_cur, const float* logits_look, 
     const size_t n_groups = (size_t)((blocks + fan - 1) / fan);
     const size_t bytes = (size_t)rows * 8 + n_groups * 4 + 4;
     char* ws = (char*)zeroed_workspace(bytes, stream);
-    if (!ws) return LA_ENOMEM;
+    if (!ws) return last_failure();
     unsigned long long* keys = (unsigned long long*)ws;
     unsigned* l1 = (unsigned*)(ws + (size_t)rows * 8);
     unsigned* l2 = l1 + n_groups;
@@ -820,7 +823,7 @@ la_status launch_verify_step_batch(const VerifySeq* seqs, int n_seqs, int W, int
         for (int i = n; i < kVerifyBatch; ++i) b.one[i] = b.one[0];  // never indexed: the grid has n layers
         // (launches on one stream run in order, so they can share the workspace)
         b.ws = (unsigned char*)zeroed_workspace(ws_stride * (size_t)n, stream);
-        if (!b.ws) return LA_ENOMEM;
+        if (!b.ws) return last_failure();
         b.ws_stride = ws_stride; b.l1_offset = l1_offset; b.l2_offset = l2_offset;
         b.W = W; b.n1 = n1; b.G = G; b.V = V; b.seg_len = seg_len; b.nseg = nseg; b.rows = (int)rows;
         b.fan = fan;
@@ -857,7 +860,7 @@ la_status launch_verify_sample(const float* logits_cur, const float* logits_cand
     const size_t n_groups = (size_t)((blocks + fan - 1) / fan);
     const size_t bytes = (size_t)blocks * 8 + n_groups * 4 + 4;
     char* ws = (char*)zeroed_workspace(bytes, stream);
-    if (!ws) return LA_ENOMEM;
+    if (!ws) return last_failure();
     unsigned long long* stats = (unsigned long long*)ws;
     unsigned* l1 = (unsigned*)(ws + (size_t)blocks * 8);
     unsigned* l2 = l1 + n_groups;
@@ -907,7 +910,7 @@ la_status launch_verify_sample_batch(const SampleSeq* seqs, int n_seqs, int N, i
         }
         for (int i = n; i < kVerifyBatch; ++i) b.one[i] = b.one[0];  // never indexed: the grid has n layers
         b.ws = (unsigned char*)zeroed_workspace(ws_stride * (size_t)n, stream);
-        if (!b.ws) return LA_ENOMEM;
+        if (!b.ws) return last_failure();
         b.ws_stride = ws_stride; b.l1_offset = l1_offset; b.l2_offset = l2_offset;
         b.n1 = n1; b.G = G; b.V = V; b.seg_len = seg_len; b.nseg = nseg; b.rows = (int)rows; b.lds_copy = lds_copy;
         b.fan = fan;

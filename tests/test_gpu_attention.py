@@ -167,10 +167,10 @@ def test_ragged_long_context(seq, W):
           s.name)
 
 
-def test_recompute_path_for_groups_not_on_one_xcd(monkeypatch):
+def test_recompute_path_for_groups_not_on_one_xcd(override):
     """Force the path the last workgroup takes when its split group is spread over several
     XCDs (it recomputes from the inputs instead of reading the other workgroups' partials)."""
-    monkeypatch.setenv("LA_FORCE_RECOMPUTE", "1")
+    override("force_recompute", "1")
     for s in (wl.LLAMA2_7B, wl.LLAMA2_70B, wl.TINY):
         check(wl.attention_inputs(s), s.P, s.W, s.N, s.G, s.heads, s.kv_heads, s.head_dim,
               s.name + "-recompute")
@@ -189,9 +189,9 @@ PLANS_D64 = ["1,2,3,2,64", "1,2,1,4,64", "2,2,4,4,64", "2,2,1,2,64", "4,1,2,4,64
 
 
 @pytest.mark.parametrize("plan", PLANS_D128)
-def test_every_kernel_variant(monkeypatch, plan):
+def test_every_kernel_variant(override, plan):
     """Each compiled decomposition (row tiles, key-split waves, splits, stages, up-front depth)."""
-    monkeypatch.setenv("LA_ATTN_PLAN", plan)
+    override("attn_plan", plan)
     x = rand_inputs(123, 777, 9, 5, 9, 8, 2, 128)      # R = 292 rows per KV head
     check(x, 777, 9, 5, 9, 8, 2, 128, "plan " + plan)
     x = rand_inputs(124, 130, 2, 3, 1, 2, 2, 128)      # R = 7
@@ -199,8 +199,8 @@ def test_every_kernel_variant(monkeypatch, plan):
 
 
 @pytest.mark.parametrize("plan", PLANS_D64)
-def test_every_kernel_variant_head_dim_64(monkeypatch, plan):
-    monkeypatch.setenv("LA_ATTN_PLAN", plan)
+def test_every_kernel_variant_head_dim_64(override, plan):
+    override("attn_plan", plan)
     x = rand_inputs(125, 700, 7, 5, 7, 6, 2, 64)       # R = 171 rows per KV head
     check(x, 700, 7, 5, 7, 6, 2, 64, "plan " + plan)
     x = rand_inputs(126, 65, 2, 3, 1, 2, 2, 64)        # R = 7

@@ -61,8 +61,8 @@ def test_batch_matches_the_oracle_and_the_single_calls(prefixes, W, N, G, H, KV,
     run_batch(list(prefixes), W, N, G, H, KV, d, seed=len(prefixes) + W, check_oracle={int(order[0]), int(order[-1])})
 
 
-def test_batch_recompute_path(monkeypatch):
-    monkeypatch.setenv("LA_FORCE_RECOMPUTE", "1")
+def test_batch_recompute_path(override):
+    override("force_recompute", "1")
     run_batch([2492, 13246, 1253], 5, 5, 5, 32, 8, 128, seed=1, check_oracle={2})
 
 
@@ -77,9 +77,9 @@ def test_argument_errors():
 
 
 @pytest.mark.parametrize("plan", ["2", "4"])
-def test_both_batch_decompositions(monkeypatch, plan):
-    """64-row and 128-row workgroups (LA_BATCH_PLAN overrides the choice the library makes)."""
-    monkeypatch.setenv("LA_BATCH_PLAN", plan)
+def test_both_batch_decompositions(override, plan):
+    """64-row and 128-row workgroups (the batch_plan hook overrides the choice the library makes)."""
+    override("batch_plan", plan)
     run_batch([1024, 900, 64, 3000], 15, 5, 15, 32, 32, 128, seed=3, check_oracle={2, 3})
     run_batch([500, 2000], 4, 5, 4, 32, 8, 128, seed=4, check_oracle={0})
 

@@ -156,3 +156,41 @@ def test_a_recorded_graph_survives_the_growth_of_the_workspace():
         assert int(captured[2].item()) == n and torch.equal(eager[1][:n], captured[1][:n]), replay
         for a, b in zip(eager[3:], captured[3:]):
             assert torch.equal(a, b), replay
+
+
+def test_a_capture_that_would_have_to_grow_the_workspace_is_refused():
+    """Growing the workspace allocates (and clears on the stream), which must not happen while the
+    stream is being captured: such a call returns LA_EUNSUPPORTED, launches nothing and leaves the
+    capture usable; after one call of the shape outside a capture, recording works."""
+    torch.cuda.synchronize()
+    binding.la_shutdown()                       # an empty workspace: any split step has to grow it
+    s = wl.LLAMA2_7B
+    W, N, G, H, KV, d, P, T = s.W, s.N, s.G, s.heads, s.kv_heads, s.head_dim, s.P, s.T
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(13)
+
+    def rb(*shape):
+        return torch.randn(shape, device="cuda", generator=gen).bfloat16()
+    q, kc, vc, sk, sv = rb(T, H, d), rb(KV, P, d), rb(KV, P, d), rb(T, KV, d), rb(T, KV, d)
+    out = torch.zeros((T, H, d), dtype=torch.bfloat16, device="cuda")
+    tiny_q, tiny_kv, tiny_out = rb(1, 1, 64), rb(1, 1, 64), torch.zeros((1, 1, 64), dtype=torch.bfloat16, device="cuda")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        with pytest.raises(binding.LaError) as e:
+            binding.la_step_attention(q, kc, vc, sk, sv, P, W, N, G, H, KV, d, out)
+        # a step that needs no workspace can still be recorded after the refusal
+        binding.la_step_attention(tiny_q, None, None, tiny_kv, tiny_kv, 0, 0, 2, 0, 1, 1, 64, tiny_out)
+    assert e.value.code == binding.LA_EUNSUPPORTED and "captured" in str(e.value)
+    graph.replay()
+    torch.cuda.synchronize()
+    assert not out.any().item()                 # nothing of the refused call ran
+    assert torch.equal(tiny_out, tiny_kv)       # one row that sees only itself: out = v
+    eager = torch.empty_like(out)
+    binding.la_step_attention(q, kc, vc, sk, sv, P, W, N, G, H, KV, d, eager)   # sizes the workspace
+    torch.cuda.synchronize()
+    graph2 = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph2):
+        binding.la_step_attention(q, kc, vc, sk, sv, P, W, N, G, H, KV, d, out)
+    graph2.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out, eager)

@@ -143,7 +143,7 @@ def test_every_paged_plan():
     want = orc.step_attention(x["q"], x["k_cache"], x["v_cache"], x["step_k"], x["step_v"], P, W, N, G, H, KV, d)
     for plan in ("2,2,2,9,32,9", "2,4,1,4,64,4", "4,2,2,4,64,4", "1,2,3,4,64"):
         print("case plan", plan, flush=True)
-        os.environ["LA_ATTN_PLAN"] = plan
+        binding.la_debug_override("attn_plan", plan)
         try:
             out = torch.full((T, H, d), float("nan"), dtype=torch.bfloat16, device="cuda")
             binding.la_step_attention_paged(binding.bf16_tensor(x["q"]), binding.bf16_tensor(kp), binding.bf16_tensor(vp),
@@ -151,14 +151,14 @@ def test_every_paged_plan():
                                             binding.bf16_tensor(x["step_v"]), P, W, N, G, H, KV, d, out)
             torch.cuda.synchronize()
         finally:
-            del os.environ["LA_ATTN_PLAN"]
+            binding.la_debug_override("attn_plan", None)
         got = out.float().cpu().numpy().astype(np.float64)
         assert np.isfinite(got).all() and np.abs(got - want).max() <= TOL, plan
 
 
-def test_paged_recompute_path(monkeypatch):
+def test_paged_recompute_path(override):
     """The fallback of a split group that is not on one XCD (the last workgroup walks every chunk
     again, through the block table) with a paged cache."""
-    monkeypatch.setenv("LA_FORCE_RECOMPUTE", "1")
+    override("force_recompute", "1")
     test_paged_attention_matches_the_oracle(1000, 128, 10, 5, 10, 8, 8, 128)
     test_paged_attention_matches_the_oracle(1024, 64, 15, 5, 15, 32, 32, 128)

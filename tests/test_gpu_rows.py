@@ -96,8 +96,8 @@ def test_argument_errors():
         binding.la_step_attention_rows(z, None, None, z, z, ids, 0, 1, 2, 1, 2, 2, 64, z.clone())
 
 
-def test_rows_recompute_path(monkeypatch):
+def test_rows_recompute_path(override):
     """The same with the fallback of a split group that is not on one XCD forced."""
-    monkeypatch.setenv("LA_FORCE_RECOMPUTE", "1")
+    override("force_recompute", "1")
     test_every_share_equals_the_full_step_on_its_rows(1024, 15, 5, 15, 32, 32, 128, 4)
     test_every_share_equals_the_full_step_on_its_rows(300, 30, 5, 30, 8, 2, 128, 4)

@@ -55,6 +55,8 @@ def walk_with_margin(cur, cnd, cand, u_test, u_final, temperature, N, G, V):
         accepted = False
         for j, g in enumerate(alive):
             s = int(cand[g, i])
+            if not 0 <= s < V:     # outside the vocabulary: probability zero, nothing ruled out
+                continue
             margin = min(margin, abs(float(u_test[i, j]) - P[s]))
             if u_test[i, j] < P[s]:
                 out.append(s)
@@ -130,6 +132,29 @@ def test_shapes_and_degenerate_cases(N, G):
         u_final = rng.random(1, dtype=np.float32)
         exact += check(cur, cnd, cand, u_test, u_final, 1.3, N, G, V)
     assert exact >= 4
+
+
+@pytest.mark.parametrize("bad", [-1, 501, 2**31 - 1, -2**31])
+def test_tokens_outside_the_vocabulary_are_never_accepted_and_never_read(bad):
+    """Padding ids among the candidate tokens: probability zero, no logit read (the logits sit at
+    the very end of their allocation here, and in front of it)."""
+    rng = np.random.default_rng(5)
+    N, G, V = 4, 6, 501
+    cur = (rng.standard_normal(V) * 4).astype(np.float32)
+    cnd = (rng.standard_normal((G, N - 1, V)) * 4).astype(np.float32)
+    cand = rng.integers(0, V, size=(G, N - 1)).astype(np.int32)
+    cand[:, 0] = np.argsort(cur)[::-1][rng.integers(0, 2, size=G)]
+    cand[0, :] = bad              # a whole candidate of padding
+    cand[2, 1] = bad              # padding after a real first token
+    cand[4, 0] = bad
+    exact = 0
+    for t in range(6):
+        u_test = rng.random((N - 1, G), dtype=np.float32) * 0.5   # low draws: accept often
+        u_final = rng.random(1, dtype=np.float32)
+        exact += check(cur, cnd, cand, u_test, u_final, 1.0, N, G, V, "bad token %d" % bad)
+        got = run_hip(cur, cnd, cand, u_test, u_final, 1.0, N, G, V)
+        assert all(0 <= t < V for t in got)
+    assert exact >= 5
 
 
 def test_draw_extremes_and_sharp_distributions():

@@ -193,3 +193,31 @@ def test_a_rejected_token_is_never_accepted_later():
     assert got[0] == 1            # third candidate: residual P(1) = 0.6 > 0.59
     got = orc.verify_sample(cur, cnd, cand, np.array([[0.6, 0.0, 0.61]], np.float32), 0.5, 1.0, N, G, V)
     assert got == [2]             # all rejected; residual is (0, 0, 1)
+
+
+def test_a_token_outside_the_vocabulary_has_probability_zero():
+    """A candidate token outside 0 .. V-1 (a padding id) spends its draw, is never accepted and
+    rules nothing out: the walk equals the one over the other candidates with the draws they saw."""
+    rng = np.random.default_rng(11)
+    V, N = 7, 3
+    cur = (rng.standard_normal(V) * 2).astype(np.float32)
+    for bad in (-1, V, V + 5, -2**31, 2**31 - 1):
+        for trial in range(40):
+            tok = rng.integers(0, V, size=(1, N - 1)).astype(np.int32)
+            cnd1 = (rng.standard_normal((1, N - 1, V)) * 2).astype(np.float32)
+            u = rng.random((N - 1, 2), dtype=np.float32)
+            u_final = float(rng.random())
+            # the bad candidate first: it uses up draw [0][0]; the good one is examined second
+            cand2 = np.concatenate([np.full((1, N - 1), bad, np.int32), tok])
+            cnd2 = np.concatenate([np.zeros_like(cnd1), cnd1])
+            got = orc.verify_sample(cur, cnd2, cand2, u, u_final, 0.8, N, 2, V)
+            # position 0 examines both (draws u[0][0], u[0][1]); from position 1 on only the good one
+            # is alive if it was accepted, and it is examined first there (draw u[1][0])
+            want = orc.verify_sample(cur, cnd1, tok, np.array([[u[0, 1]], [u[1, 0]]], np.float32), u_final, 0.8, N, 1, V)
+            assert got == want
+        # alone, it is the same as no candidate at all
+        u = rng.random((N - 1, 1), dtype=np.float32)
+        got = orc.verify_sample(cur, np.zeros((1, N - 1, V), np.float32), np.full((1, N - 1), bad, np.int32), u, 0.3, 0.8, N, 1, V)
+        want = orc.verify_sample(cur, np.zeros((0, N - 1, V), np.float32), np.zeros((0, N - 1), np.int32),
+                                 np.zeros((N - 1, 0), np.float32), 0.3, 0.8, N, 0, V)
+        assert got == want

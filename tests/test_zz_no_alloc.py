@@ -73,12 +73,12 @@ def test_two_calls_second_smaller():
     assert np.array_equal(fixed, pooled)
 
 
-def test_refuses_what_does_not_fit(monkeypatch):
+def test_refuses_what_does_not_fit(override):
     """A decomposition whose partials exceed the fixed block is refused before anything is launched
     (the library's own choice never needs more than 5 MiB; a 64-way split forced by hand does).
     The buffers are real and of the right size all the same."""
     torch.cuda.set_device(0)
-    monkeypatch.setenv("LA_ATTN_PLAN", "2,4,64,4,64")
+    override("attn_plan", "2,4,64,4,64")
     shape = (4096, 15, 5, 15, 32, 32, 128)
     P, W, N, G, H, KV, d = shape
     T = 1 + (W + G) * (N - 1)
