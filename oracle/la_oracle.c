@@ -118,6 +118,27 @@ static double bf16_bits_to_double(uint16_t b)
     return (double)f;
 }
 
+/*
+ * The 8-bit float of a quantised KV cache: the OCP "E4M3" format in its finite-only form (one sign
+ * bit, four exponent bits with bias 7, three mantissa bits).  Exponent field 0 holds the subnormals
+ * m/8 * 2^-6; there are no infinities, and S.1111.111 is the only NaN, so the largest value is
+ * 1.75 * 2^8 = 448.  (An extension of the step to a quantised cache: the paper computes in 16 bits.)
+ */
+static double fp8_e4m3_to_double(uint8_t c)
+{
+    const int sign = c >> 7, e = (c >> 3) & 15, m = c & 7;
+    double v;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0) v = ldexp((double)m / 8.0, -6);
+    else v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
+void la_oracle_fp8_e4m3_decode(const uint8_t *codes, size_t n, double *out)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = fp8_e4m3_to_double(codes[i]);
+}
+
 int la_oracle_threads(void)
 {
 #ifdef _OPENMP
@@ -150,9 +171,18 @@ void la_oracle_set_threads(int n)
  *   out     [T][heads][head_dim]      fp64
  * Returns 0, or -1 for an impossible shape.
  */
-int la_oracle_step_attention(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache,
-                             const uint16_t *step_k, const uint16_t *step_v, int P, int W, int N,
-                             int G, int heads, int kv_heads, int head_dim, double *out)
+/* One key or value element as fp64: a bf16 bit pattern, or (quantised cache) an 8-bit float times
+ * the scale of its KV head. */
+static double kv_element(const void *base, size_t index, int fp8, double scale)
+{
+    if (fp8) return fp8_e4m3_to_double(((const uint8_t *)base)[index]) * scale;
+    return bf16_bits_to_double(((const uint16_t *)base)[index]);
+}
+
+static int step_attention_dense(const uint16_t *q, const void *k_cache, const void *v_cache,
+                                const void *step_k, const void *step_v, int fp8, const float *k_scale,
+                                const float *v_scale, int P, int W, int N, int G, int heads,
+                                int kv_heads, int head_dim, double *out)
 {
     if (P < 0 || W < 0 || G < 0 || N < 2 || heads < 1 || kv_heads < 1 || head_dim < 1) return -1;
     if (heads % kv_heads != 0) return -1;
@@ -185,17 +215,18 @@ int la_oracle_step_attention(const uint16_t *q, const uint16_t *k_cache, const u
             continue;
         }
         /* keys and values of this head, prefix then step tokens, as fp64 */
+        const double ksc = fp8 ? (double)k_scale[kvh] : 1.0, vsc = fp8 ? (double)v_scale[kvh] : 1.0;
         for (int p = 0; p < P; ++p)
             for (int e = 0; e < d; ++e) {
                 size_t src = ((size_t)kvh * P + p) * d + e;
-                K[(size_t)p * d + e] = bf16_bits_to_double(k_cache[src]);
-                V[(size_t)p * d + e] = bf16_bits_to_double(v_cache[src]);
+                K[(size_t)p * d + e] = kv_element(k_cache, src, fp8, ksc);
+                V[(size_t)p * d + e] = kv_element(v_cache, src, fp8, vsc);
             }
         for (int c = 0; c < T; ++c)
             for (int e = 0; e < d; ++e) {
                 size_t src = ((size_t)c * kv_heads + kvh) * d + e;
-                K[((size_t)P + c) * d + e] = bf16_bits_to_double(step_k[src]);
-                V[((size_t)P + c) * d + e] = bf16_bits_to_double(step_v[src]);
+                K[((size_t)P + c) * d + e] = kv_element(step_k, src, fp8, ksc);
+                V[((size_t)P + c) * d + e] = kv_element(step_v, src, fp8, vsc);
             }
         /* dense scores */
         for (int r = 0; r < T; ++r) {
@@ -231,6 +262,32 @@ int la_oracle_step_attention(const uint16_t *q, const uint16_t *k_cache, const u
     }
     free(mask);
     return failed ? -1 : 0;
+}
+
+int la_oracle_step_attention(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache,
+                             const uint16_t *step_k, const uint16_t *step_v, int P, int W, int N,
+                             int G, int heads, int kv_heads, int head_dim, double *out)
+{
+    return step_attention_dense(q, k_cache, v_cache, step_k, step_v, 0, NULL, NULL, P, W, N, G, heads,
+                                kv_heads, head_dim, out);
+}
+
+/*
+ * The same step over a quantised KV cache: k_cache, v_cache, step_k and step_v hold 8-bit floats
+ * (E4M3, see fp8_e4m3_to_double) in the layouts above, and an element of KV head h stands for its
+ * decoded value times k_scale[h] (keys) or v_scale[h] (values).  The step's own keys and values are
+ * quantised like the cache, so that a token committed later is read back exactly as its step saw it.
+ * q stays bf16; everything is decoded to fp64 and goes through the dense definition unchanged.
+ * Returns 0, or -1 for an impossible shape or a missing scale array.
+ */
+int la_oracle_step_attention_fp8kv(const uint16_t *q, const uint8_t *k_cache, const uint8_t *v_cache,
+                                   const uint8_t *step_k, const uint8_t *step_v, const float *k_scale,
+                                   const float *v_scale, int P, int W, int N, int G, int heads,
+                                   int kv_heads, int head_dim, double *out)
+{
+    if (!k_scale || !v_scale) return -1;
+    return step_attention_dense(q, k_cache, v_cache, step_k, step_v, 1, k_scale, v_scale, P, W, N, G,
+                                heads, kv_heads, head_dim, out);
 }
 
 /*

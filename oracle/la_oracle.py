@@ -8,6 +8,10 @@ cache after any run of lookahead steps equals the cache of plain autoregressive 
 parallelism), dense numpy with the explicit mask, pinned by equality with the full step on closed
 subsets.  `gather_pages` / `kv_commit_paged` define what a paged cache stands for (pinned as the inverse of
 a scatter written in the test, and against the packed append).
+`step_attention_fp8kv` is the step over a KV cache quantised to 8-bit floats with one scale per KV head
+(decode, scale, then the same dense definition); pins: every code point against a library's cast,
+equality with the 16-bit step on inputs both formats hold exactly, linearity in the value scale, the
+one-token decode against a library attention, and a hand-indexed read-out of one value row.
 `step_rope` rotates the step's queries and keys by the positions of Fig. 2(b) (rotary position
 embedding written out pair by pair in fp64); pins: the printed digits, norms, the dependence of a
 score on the distance only, a quarter turn, and complex multiplication.
@@ -38,6 +42,10 @@ def _load():
         lib.la_oracle_threads.restype = i
         lib.la_oracle_step_attention.argtypes = [p, p, p, p, p, i, i, i, i, i, i, i, p]
         lib.la_oracle_step_attention.restype = i
+        lib.la_oracle_step_attention_fp8kv.argtypes = [p, p, p, p, p, p, p, i, i, i, i, i, i, i, p]
+        lib.la_oracle_step_attention_fp8kv.restype = i
+        lib.la_oracle_fp8_e4m3_decode.argtypes = [p, ctypes.c_size_t, p]
+        lib.la_oracle_fp8_e4m3_decode.restype = None
         lib.la_oracle_verify.argtypes = [p, p, i, i, i, p, p]
         lib.la_oracle_verify.restype = i
         lib.la_oracle_verify_step.argtypes = [p, p, p, p, i, i, i, i, p, p, p, p, p]
@@ -95,6 +103,45 @@ def step_attention(q, k_cache, v_cache, step_k, step_v, P, W, N, G, heads, kv_he
                                           heads, kv_heads, head_dim, out.ctypes.data)
     if rc != 0:
         raise ValueError("la_oracle_step_attention: bad shape (rc=%d)" % rc)
+    return out
+
+
+def _u8(a, shape):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint8 and a.shape == tuple(shape), (a.dtype, a.shape, shape)
+    return a
+
+
+def fp8_e4m3_decode(codes):
+    """fp64 values of 8-bit float codes (E4M3, finite-only: exponent bias 7, no infinities, 0x7f / 0xff NaN)."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    out = np.empty(codes.shape, dtype=np.float64)
+    _load().la_oracle_fp8_e4m3_decode(codes.ctypes.data, ctypes.c_size_t(codes.size), out.ctypes.data)
+    return out
+
+
+def step_attention_fp8kv(q, k_cache, v_cache, step_k, step_v, k_scale, v_scale, P, W, N, G, heads, kv_heads,
+                         head_dim):
+    """The step over a quantised KV cache: fp64 [T, heads, head_dim] from a bf16 q (uint16 bit patterns),
+    8-bit float keys and values (uint8 codes, cache and step rows alike) and one fp32 scale per KV head
+    for the keys and one for the values."""
+    T = num_rows(W, N, G)
+    q = _u16(q, (T, heads, head_dim))
+    k_cache = _u8(k_cache, (kv_heads, P, head_dim))
+    v_cache = _u8(v_cache, (kv_heads, P, head_dim))
+    step_k = _u8(step_k, (T, kv_heads, head_dim))
+    step_v = _u8(step_v, (T, kv_heads, head_dim))
+    k_scale = np.ascontiguousarray(k_scale)
+    v_scale = np.ascontiguousarray(v_scale)
+    assert k_scale.dtype == np.float32 and k_scale.shape == (kv_heads,)
+    assert v_scale.dtype == np.float32 and v_scale.shape == (kv_heads,)
+    out = np.empty((T, heads, head_dim), dtype=np.float64)
+    rc = _load().la_oracle_step_attention_fp8kv(q.ctypes.data, k_cache.ctypes.data, v_cache.ctypes.data,
+                                                step_k.ctypes.data, step_v.ctypes.data, k_scale.ctypes.data,
+                                                v_scale.ctypes.data, P, W, N, G, heads, kv_heads, head_dim,
+                                                out.ctypes.data)
+    if rc != 0:
+        raise ValueError("la_oracle_step_attention_fp8kv: bad shape (rc=%d)" % rc)
     return out
 
 

@@ -280,3 +280,38 @@ def rope_tables(max_pos, head_dim, base=10000.0):
     angle = np.arange(max_pos, dtype=np.float64)[:, None] * base ** (-2.0 * i / head_dim)[None, :]
     return np.cos(angle).astype(np.float32), np.sin(angle).astype(np.float32)
 
+
+
+FP8_MAX = 448.0   # largest finite value of the 8-bit float (E4M3, finite-only) a quantised cache stores
+
+
+def quantize_fp8(x, scale):
+    """8-bit float codes (uint8) of x / scale, by the library's round-to-nearest cast (torch, CPU).
+
+    Input preparation only: what a code stands for is defined by the consumer of the bytes."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(x / scale, dtype=np.float32))
+    return t.to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+
+
+def attention_inputs_fp8(s: StepShape, extra=0):
+    """The draws of attention_inputs with keys and values (cache and step rows) quantised to 8-bit
+    floats: per KV head one scale for the keys and one for the values, the head's largest magnitude
+    over FP8_MAX, as an offline calibration of a quantised cache would choose them.
+
+    dict: q (bf16 bits), k_cache / v_cache / step_k / step_v (uint8 codes), k_scale / v_scale (fp32 [kv_heads]).
+    """
+    x = {k: bf16_bits_to_f32(v) for k, v in attention_inputs(s, extra).items()}
+    k_amax = np.maximum(np.abs(x["k_cache"]).max(axis=(1, 2), initial=0.0), np.abs(x["step_k"]).max(axis=(0, 2)))
+    v_amax = np.maximum(np.abs(x["v_cache"]).max(axis=(1, 2), initial=0.0), np.abs(x["step_v"]).max(axis=(0, 2)))
+    k_scale = (k_amax / FP8_MAX).astype(np.float32)
+    v_scale = (v_amax / FP8_MAX).astype(np.float32)
+    return {
+        "q": f32_to_bf16_bits(x["q"]),
+        "k_cache": quantize_fp8(x["k_cache"], k_scale[:, None, None]),
+        "v_cache": quantize_fp8(x["v_cache"], v_scale[:, None, None]),
+        "step_k": quantize_fp8(x["step_k"], k_scale[None, :, None]),
+        "step_v": quantize_fp8(x["step_v"], v_scale[None, :, None]),
+        "k_scale": k_scale,
+        "v_scale": v_scale,
+    }

@@ -42,6 +42,7 @@ def run_batch(prefixes, W, N, G, H, KV, d, seed, check_oracle):
             want = orc.step_attention(x["q"], x["k_cache"], x["v_cache"], x["step_k"], x["step_v"], dev["P"], W, N, G,
                                       H, KV, d)
             assert np.abs(got - want).max() <= TOL, i
+            print("  sequence %d (P=%d): oracle agrees" % (i, dev["P"]), flush=True)
 
 
 @pytest.mark.parametrize("prefixes,W,N,G,H,KV,d", [
@@ -59,6 +60,16 @@ def test_batch_matches_the_oracle_and_the_single_calls(prefixes, W, N, G, H, KV,
     # the oracle on the shortest and the longest sequence (it is slow on long prefixes)
     order = np.argsort(prefixes)
     run_batch(list(prefixes), W, N, G, H, KV, d, seed=len(prefixes) + W, check_oracle={int(order[0]), int(order[-1])})
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("W", [5, 30])
+def test_ragged_sweep_every_sequence_against_the_oracle(W):
+    """The narrowest and the widest window of the ragged sweep, one launch over all eight sequences, the
+    oracle on each of them (the other widths are covered on the shortest and the longest sequence)."""
+    prefixes = list(wl.ragged_prefix_lengths())
+    print("case", dict(prefixes=prefixes, W=W), flush=True)
+    run_batch(prefixes, W, 5, W, 32, 8, 128, seed=40 + W, check_oracle=set(range(len(prefixes))))
 
 
 def test_batch_recompute_path(override):
