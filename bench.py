@@ -541,6 +541,29 @@ def main():
                                   H, KV, d, outs[0])
     cache_hot_us = None if args.no_cache_hot else time_calls(torch, np, cache_hot, L, reps, use_graph)
 
+    # the same layers over a KV cache of 8-bit floats (la_step_attention_fp8kv): the seeded draws
+    # quantised per KV head, timed on their own.  Not part of `value`.
+    f8_layers, f8_host0 = [], None
+    for layer in range(L):
+        x8 = wl.attention_inputs_fp8(s, extra=layer)
+        if layer == 0:
+            f8_host0 = x8
+        dev8 = {k: torch.from_numpy(v).cuda() for k, v in x8.items() if k != "q"}
+        dev8["q"] = layers[layer]["q"]
+        f8_layers.append(dev8)
+    f8_outs = [torch.empty((T, H, d), dtype=torch.bfloat16, device="cuda") for _ in range(L)]
+    f8_it = iter(range(1 << 30))
+
+    def fp8_layer():
+        i = next(f8_it) % L
+        x8 = f8_layers[i]
+        binding.la_step_attention_fp8kv(x8["q"], x8["k_cache"], x8["v_cache"], x8["step_k"], x8["step_v"],
+                                        x8["k_scale"], x8["v_scale"], P, s.W, s.N, s.G, H, KV, d, f8_outs[i])
+    for _ in range(L):
+        fp8_layer()
+    fp8_us = time_calls(torch, np, fp8_layer, L, reps, use_graph)
+    fp8_bytes = 2 * P * KV * d + 2 * T * KV * d + 2 * T * H * d * 2
+
     if args.copy_calibration:
         # a copy kernel of known size: 64 MiB read + 64 MiB written per launch
         src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda").random_()
@@ -554,6 +577,10 @@ def main():
     want = orc.step_attention(host0["q"], host0["k_cache"], host0["v_cache"], host0["step_k"],
                               host0["step_v"], P, s.W, s.N, s.G, H, KV, d)
     err = float(np.abs(outs[0].float().cpu().numpy().astype(np.float64) - want).max())
+    want8 = orc.step_attention_fp8kv(f8_host0["q"], f8_host0["k_cache"], f8_host0["v_cache"], f8_host0["step_k"],
+                                     f8_host0["step_v"], f8_host0["k_scale"], f8_host0["v_scale"], P, s.W, s.N, s.G,
+                                     H, KV, d)
+    err8 = float(np.abs(f8_outs[0].float().cpu().numpy().astype(np.float64) - want8).max())
     want_len, want_acc = orc.verify(logits_h, cand_h, s.G, s.N, s.V)
     exact = bool(np.array_equal(alen.cpu().numpy(), want_len) and np.array_equal(acc.cpu().numpy(), want_acc))
     w_out, w_best, w_window, w_len = orc.verify_step(*vs_h[:4], s.W, s.N, s.G, s.V)
@@ -654,16 +681,21 @@ def main():
                   "frac_of_roofline": max(t_hbm, t_mfma) * nb / (batch_us * 1e-6)},
         "attention_tflops": aflops / (attn_us * 1e-6) / 1e12,
         "attention_gbs": abytes / (attn_us * 1e-6) / 1e9,
+        "attention_fp8kv": {"us_per_launch": fp8_us, "algorithmic_bytes": fp8_bytes,
+                            "gbs": fp8_bytes / (fp8_us * 1e-6) / 1e9,
+                            "frac_of_roofline": max(fp8_bytes / (HBM_PEAK_GBS * 1e9), t_mfma) / (fp8_us * 1e-6),
+                            "speedup_over_bf16_cache": attn_us / fp8_us,
+                            "note": "keys and values as 8-bit floats with one scale per KV head; q and out bf16"},
         "attention_cache_hot": {"us_per_launch": cache_hot_us,
                                 "note": "all launches on one layer's buffers (served by the caches, not HBM)"},
         "parity": {"attention_max_abs_err_layer0": err, "verify_bit_exact": exact,
                    "verify_step_bit_exact": exact_step, "verify_step_batch_bit_exact": exact_step_batch,
                    "verify_sample_equals_oracle": sample_equal,
                    "kv_commit_bit_exact": exact_commit, "kv_commit_batch_bit_exact": exact_commit_batch,
-                   "batch_matches_single_calls": batch_equal},
+                   "batch_matches_single_calls": batch_equal, "attention_fp8kv_max_abs_err_layer0": err8},
     }
     print(json.dumps(line))
-    if err > 2e-2 or not exact or not exact_step or not exact_step_batch or not exact_commit or not exact_commit_batch \
+    if err > 2e-2 or err8 > 2e-2 or not exact or not exact_step or not exact_step_batch or not exact_commit or not exact_commit_batch \
             or not batch_equal or not sample_ok:
         print("bench.py: PARITY FAILURE", file=sys.stderr)
         sys.exit(1)

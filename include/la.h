@@ -104,6 +104,30 @@ la_status la_step_rope(void* q, void* step_k, const float* cos, const float* sin
                        int G, int heads, int kv_heads, int head_dim, int interleaved, void* stream);
 
 /*
+ * The same step (Sec. 3.3 mask, Sec. 2 attention) over a KV cache quantised to 8-bit floats: an
+ * extension for memory-bound decoding, the regime the method targets (Sec. 1, Sec. 4.2); the
+ * paper itself computes in 16 bits.  A key or value element of KV head h is a code of the OCP
+ * E4M3 format in its finite-only form (exponent bias 7, no infinities, largest value 448) and
+ * stands for the code's value times k_scale[h] (keys) or v_scale[h] (values).  The step's own
+ * keys and values arrive quantised the same way, so that a token committed to the cache later
+ * is read back exactly as its step saw it.
+ *
+ *   q                 bf16 [T][heads][head_dim]
+ *   k_cache, v_cache  8-bit [kv_heads][P][head_dim]
+ *   step_k, step_v    8-bit [T][kv_heads][head_dim]
+ *   k_scale, v_scale  fp32 [kv_heads], device memory, 4-byte aligned, finite and > 0
+ *   out               bf16 [T][heads][head_dim]
+ * Codes are converted exactly (every E4M3 value is a bf16 number), the products run on the
+ * bf16 MFMA pipes with fp32 accumulation, the key scale multiplies the scores and the value
+ * scale the finished rows.  The two NaN codes (0x7f, 0xff) give NaN outputs in the rows that
+ * see them.  Everything else (row order, head mapping, alignment, errors, workspace) as
+ * la_step_attention.  Packed caches and whole steps only.
+ */
+la_status la_step_attention_fp8kv(const void* q, const void* k_cache, const void* v_cache, const void* step_k,
+                                  const void* step_v, const float* k_scale, const float* v_scale, int P, int W,
+                                  int N, int G, int heads, int kv_heads, int head_dim, void* out, void* stream);
+
+/*
  * The same step over a cache allocated for more keys than it holds, as a decoding loop keeps
  * it (rows are appended in place, see la_kv_commit):
  *   k_cache, v_cache  bf16 [kv_heads][capacity][head_dim]; rows 0..P-1 of every head are the

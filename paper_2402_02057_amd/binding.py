@@ -70,6 +70,8 @@ def load():
     lib.la_step_attention.restype = i
     lib.la_step_attention_noalloc.argtypes = [p, p, p, p, p, i, i, i, i, i, i, i, p, p]
     lib.la_step_attention_noalloc.restype = i
+    lib.la_step_attention_fp8kv.argtypes = [p, p, p, p, p, p, p, i, i, i, i, i, i, i, p, p]
+    lib.la_step_attention_fp8kv.restype = i
     ll = ctypes.c_longlong
     lib.la_step_attention_cap.argtypes = [p, p, p, ll, p, p, i, i, i, i, i, i, i, p, p]
     lib.la_step_attention_cap.restype = i
@@ -119,7 +121,7 @@ def load():
     return lib
 
 
-EXPORTS = ("la_step_rope", "la_step_attention", "la_step_attention_noalloc", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_kv_commit_batch", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_step_batch", "la_verify_sample", "la_verify_sample_batch", "la_step_attention_workspace_bytes", "la_shutdown", "la_select_workspace", "la_debug_override", "la_probe_stream_read", "la_probe_mfma",
+EXPORTS = ("la_step_rope", "la_step_attention", "la_step_attention_noalloc", "la_step_attention_fp8kv", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_kv_commit_batch", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_step_batch", "la_verify_sample", "la_verify_sample_batch", "la_step_attention_workspace_bytes", "la_shutdown", "la_select_workspace", "la_debug_override", "la_probe_stream_read", "la_probe_mfma",
            "la_last_error", "la_version")
 
 
@@ -183,6 +185,26 @@ def la_step_attention_noalloc(q, k_cache, v_cache, step_k, step_v, P, W, N, G, h
         _ptr(v_cache, bf, (kv_heads, P, head_dim), "v_cache", allow_empty_null=True),
         _ptr(step_k, bf, (T, kv_heads, head_dim), "step_k"),
         _ptr(step_v, bf, (T, kv_heads, head_dim), "step_v"),
+        P, W, N, G, heads, kv_heads, head_dim,
+        _ptr(out, bf, (T, heads, head_dim), "out"), _stream(stream))
+    _check(rc)
+    return out
+
+
+def la_step_attention_fp8kv(q, k_cache, v_cache, step_k, step_v, k_scale, v_scale, P, W, N, G, heads, kv_heads,
+                            head_dim, out, stream=None):
+    """The step over a cache of 8-bit floats (uint8 codes, cache and step rows) with one fp32 scale per
+    KV head for the keys and one for the values; q and out are bf16.  Asynchronous."""
+    T = 1 + (W + G) * (N - 1)
+    bf, u8 = torch.bfloat16, torch.uint8
+    rc = load().la_step_attention_fp8kv(
+        _ptr(q, bf, (T, heads, head_dim), "q"),
+        _ptr(k_cache, u8, (kv_heads, P, head_dim), "k_cache", allow_empty_null=True),
+        _ptr(v_cache, u8, (kv_heads, P, head_dim), "v_cache", allow_empty_null=True),
+        _ptr(step_k, u8, (T, kv_heads, head_dim), "step_k"),
+        _ptr(step_v, u8, (T, kv_heads, head_dim), "step_v"),
+        _ptr(k_scale, torch.float32, (kv_heads,), "k_scale"),
+        _ptr(v_scale, torch.float32, (kv_heads,), "v_scale"),
         P, W, N, G, heads, kv_heads, head_dim,
         _ptr(out, bf, (T, heads, head_dim), "out"), _stream(stream))
     _check(rc)

@@ -157,7 +157,8 @@ la_status step_attention_checked(const char* name, const void* q, const void* k_
                                  long long capacity, const int* block_table, int page_size, int n_pages,
                                  const void* step_k, const void* step_v, int P, int W, int N, int G, int heads,
                                  int kv_heads, int head_dim, void* out, void* stream, const int* row_ids = nullptr,
-                                 int n_rows = 0, const la::FixedWorkspace* fixed = nullptr)
+                                 int n_rows = 0, const la::FixedWorkspace* fixed = nullptr,
+                                 const float* k_scale = nullptr, const float* v_scale = nullptr)
 {
     if (P < 0 || W < 0 || G < 0 || N < 2 || heads < 1 || kv_heads < 1)
         return la::fail(LA_EINVAL, "%s: need P,W,G >= 0, N >= 2, heads,kv_heads >= 1 "
@@ -180,7 +181,7 @@ la_status step_attention_checked(const char* name, const void* q, const void* k_
     if (bits & 15) return la::fail(LA_EINVAL, "%s: buffers must be 16-byte aligned", name);
     return la::launch_step_attention(q, k_cache, v_cache, capacity, block_table, page_size, n_pages, row_ids,
                                      n_rows, step_k, step_v, P, W, N, G, heads, kv_heads, head_dim, out,
-                                     (hipStream_t)stream, fixed);
+                                     (hipStream_t)stream, fixed, k_scale, v_scale);
 }
 
 // page geometry shared by the paged entry points
@@ -212,6 +213,17 @@ la_status la_step_attention_noalloc(const void* q, const void* k_cache, const vo
     if (st != LA_OK) return st;
     return step_attention_checked("la_step_attention_noalloc", q, k_cache, v_cache, P, nullptr, 0, 0, step_k, step_v,
                                   P, W, N, G, heads, kv_heads, head_dim, out, stream, nullptr, 0, &ws);
+}
+
+la_status la_step_attention_fp8kv(const void* q, const void* k_cache, const void* v_cache, const void* step_k,
+                                  const void* step_v, const float* k_scale, const float* v_scale, int P, int W,
+                                  int N, int G, int heads, int kv_heads, int head_dim, void* out, void* stream)
+{
+    if (!k_scale || !v_scale || (((uintptr_t)k_scale | (uintptr_t)v_scale) & 3))
+        return la::fail(LA_EINVAL, "la_step_attention_fp8kv: k_scale / v_scale must be 4-byte aligned device arrays");
+    return step_attention_checked("la_step_attention_fp8kv", q, k_cache, v_cache, P, nullptr, 0, 0, step_k, step_v,
+                                  P, W, N, G, heads, kv_heads, head_dim, out, stream, nullptr, 0, nullptr, k_scale,
+                                  v_scale);
 }
 
 la_status la_step_attention_cap(const void* q, const void* k_cache, const void* v_cache, long long capacity,

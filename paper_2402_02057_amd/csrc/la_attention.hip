@@ -66,6 +66,9 @@ struct AttnParams {
     const __bf16* step_k;
     const __bf16* step_v;
     __bf16* out;
+    // Quantised cache (8-bit keys and values): one fp32 scale per KV head each; else nullptr.
+    const float* k_scale;
+    const float* v_scale;
     void* partials;     // XS > 1: per workgroup and wave, fragment-layout bf16 slices and fp32 (m, l)
     unsigned* tickets;  // XS > 1: one counter (kTicketStride words apart) per (KV head, row block, wave), zero between calls
     int P, W, N, G, T;
@@ -129,12 +132,16 @@ __device__ __forceinline__ bool visible_pair(const RowPos& q, int tk, int W, int
     return q.cls == 2 && k.a == q.a && k.b <= q.b;
 }
 
-template <int D, int RT, int KS, int KC, int NSTAGE>
+// KVB: bytes per key / value element (2: bf16; 1: 8-bit float, quantised cache).  Q rows are bf16 always.
+template <int D, int RT, int KS, int KC, int NSTAGE, int KVB = 2>
 struct Cfg {
+    static constexpr int HEAD_DIM = D;
     static constexpr int NW = RT * KS;
     static constexpr int NT = NW * 64;
-    static constexpr int RBYTES = D * 2;
-    static constexpr int NCH = D / 8;                     // 16-byte pieces per row
+    static constexpr int RBYTES = D * KVB;                // a key or value row
+    static constexpr int QRBYTES = D * 2;                 // a query row
+    static constexpr int NCH = RBYTES / 16;               // 16-byte pieces per key / value row
+    static constexpr int QNCH = QRBYTES / 16;             // per query row
     static constexpr int KB = KC / 32;                    // 32-key blocks per chunk
     // Key-split waves of a row tile: up to KB of them share a chunk (one or more blocks each);
     // beyond that, groups of KB waves take consecutive chunks of the same iteration.
@@ -156,7 +163,7 @@ struct Cfg {
     static constexpr int PART_ACC_BYTES = SPW * 16 * 64 * 2;
     static constexpr int PART_WAVE_BYTES = PART_ACC_BYTES + 64 * 8;
     static constexpr int PART_WG_BYTES = NW * PART_WAVE_BYTES;
-    static constexpr int Q_BYTES = ROWS * RBYTES;         // the workgroup's query rows
+    static constexpr int Q_BYTES = ROWS * QRBYTES;        // the workgroup's query rows
     static constexpr int Q_OFFSET = NSTAGE * STAGE_BYTES; // they sit behind the stage ring
     static constexpr int QLPW = Q_BYTES / 1024 / NW;      // Q loads per wave
     static constexpr int LDS_MAIN = NSTAGE * STAGE_BYTES + Q_BYTES;
@@ -180,7 +187,7 @@ struct Cfg {
 // Write one finished (tile, 32-column) slice: lane (l32, hi) holds, for query row tile*32 + l32 of
 // the workgroup, columns db*32 + i4*8 + hi*4 .. +3 in vals[i4*4 .. +3].  The two half-waves of a
 // row fill 16 contiguous bytes per i4, 64 per slice.
-template <class C, int D = C::RBYTES / 2>
+template <class C, int D = C::HEAD_DIM>
 __device__ __forceinline__ void store_slice(const AttnParams& p, int rb, int kvh, int tile, int db, int l32,
                                             int hi, const f32x16& vals, float inv)
 {
@@ -275,10 +282,11 @@ __device__ __forceinline__ void merge_key_splits(const AttnParams& p, unsigned c
 // lookahead parallelism, Sec. 3.4); row ids come from p.row_ids and the mask is evaluated pair by pair.
 // The body is shared by the one-step kernel and the batched one: `xcd` is the XCD this workgroup
 // runs on (its id modulo 8) and `slot` its index among the step's workgroups on that XCD.
-template <int D, int RT, int KS, int KC, int NSTAGE, bool PAGED = false, bool ROWSET = false>
+template <int D, int RT, int KS, int KC, int NSTAGE, bool PAGED = false, bool ROWSET = false, int KVB = 2>
 __device__ __forceinline__ void step_attention_body(const AttnParams& p, const int xcd, const int slot)
 {
-    using C = Cfg<D, RT, KS, KC, NSTAGE>;
+    using C = Cfg<D, RT, KS, KC, NSTAGE, KVB>;
+    static_assert(KVB == 2 || (KVB == 1 && !PAGED && !ROWSET), "the quantised cache is packed and takes whole steps");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
     // Consecutive workgroup ids go round-robin over the 8 XCDs (each with its own L2); put
@@ -322,7 +330,7 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
 #pragma unroll
     for (int j = 0; j < C::LPW / 2; ++j) {
         ld_row[j] = (wave + j * C::NW) * (64 / C::NCH) + lane_row;
-        ld_piece[j] = (unsigned)((lane_pc ^ swizzle<D>(ld_row[j])) << 4);
+        ld_piece[j] = (unsigned)((lane_pc ^ row_swizzle<C::RBYTES>(ld_row[j])) << 4);
     }
 
     // This KV head's part of the four key/value tensors (wave-uniform).
@@ -443,8 +451,8 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
 #pragma unroll
         for (int i = 0; i < C::QLPW; ++i) {
             const int wl = wave + i * C::NW;
-            const int row = wl * (64 / C::NCH) + lane_row;
-            const int lc = lane_pc ^ swizzle<D>(row);
+            const int row = wl * (64 / C::QNCH) + lane / C::QNCH;
+            const int lc = (lane % C::QNCH) ^ swizzle<D>(row);
             const int rr = min(rb * C::ROWS + row, p.R - 1);
             const int t = div_small(rr, p.inv_group), hh = rr - t * p.group;
             // (the host checks that q spans less than 2^31 bytes)
@@ -461,6 +469,17 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
             }
         }
     };
+
+    // Quantised cache: a key stands for its code times the head's key scale, which goes into the
+    // factor the scores are multiplied with anyway; the value scale is applied to the finished rows.
+    // (Read as constants, so that they come through the scalar cache and their wait is not a wait
+    // for the loads requested below.)
+    float sl2 = p.scale_log2, out_scale = 1.0f;
+    if constexpr (KVB == 1) {
+        typedef const float __attribute__((address_space(4)))* const_f32;
+        sl2 *= ((const_f32)(unsigned long long)p.k_scale)[kvh];
+        out_scale = ((const_f32)(unsigned long long)p.v_scale)[kvh];
+    }
 
     // Requests first: the stream from HBM is the critical path.  The chunks of the first
     // iteration, then Q (needed with them), then the rest of the `pre` chunks.
@@ -512,24 +531,42 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
     //   (the layout S^T leaves P in).  A 16-lane block reads 4 keys x 16 columns; the transposing
     //   read hands lane n column n.  The swizzle of those rows does not depend on kb or kk.
     const int kb_first = KS >= C::KB ? ks % C::KB : ks;  // this wave's (first) block of a chunk
-    unsigned k_off[D / 16], v_off[2][C::DB];
+    // (quantised cache: a 16-byte piece of K feeds two MFMA steps and one transposing read of V
+    // covers 8 keys, so half the offsets are in use)
+    constexpr int NKOFF = KVB == 2 ? D / 16 : D / 32;
+    unsigned k_off[NKOFF], v_off[2][C::DB];
     {
         const int krow = kb_first * 32 + l32;
-        const int ksw = swizzle<D>(krow);
+        const int ksw = row_swizzle<C::RBYTES>(krow);
 #pragma unroll
-        for (int k16 = 0; k16 < D / 16; ++k16)
-            k_off[k16] = (unsigned)(krow * C::RBYTES + (((k16 * 2 + hi) ^ ksw) << 4));
+        for (int j = 0; j < NKOFF; ++j)
+            k_off[j] = (unsigned)(krow * C::RBYTES + (((j * 2 + hi) ^ ksw) << 4));
         const int b16 = lane >> 4, i16 = lane & 15;
-        const int jj = i16 >> 2, q4 = i16 & 3;
+        if constexpr (KVB == 2) {
+            const int jj = i16 >> 2, q4 = i16 & 3;
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            const int vrow = kb_first * 32 + hi * 4 + jj + r * 8;  // e = 0..3 (r = 0), 4..7 (r = 1); kk = 0
-            const int sw = swizzle<D>(vrow);
+            for (int r = 0; r < 2; ++r) {
+                const int vrow = kb_first * 32 + hi * 4 + jj + r * 8;  // e = 0..3 (r = 0), 4..7 (r = 1); kk = 0
+                const int sw = swizzle<D>(vrow);
+#pragma unroll
+                for (int db = 0; db < C::DB; ++db) {
+                    const int col = db * 32 + (b16 & 1) * 16 + q4 * 4;
+                    const int lc = col >> 3, within = (col & 7) * 2;
+                    v_off[r][db] = (unsigned)(C::KV_BYTES + vrow * C::RBYTES + ((lc ^ sw) << 4) + within);
+                }
+            }
+        } else {
+            // The 8-bit transposing read takes, from the 16 lanes of a block, 8 rows of 16 bytes (lane
+            // 2b + h supplies bytes h*8 .. +7 of row b) and hands lane n the 8 bytes of column n.
+            // Row b is the key of k-slot b: (b/4)*8 + hi*4 + b%4.
+            const int b = i16 >> 1, h = i16 & 1;
+            const int vrow = kb_first * 32 + (b >> 2) * 8 + hi * 4 + (b & 3);  // kk = 0
+            const int sw = row_swizzle<C::RBYTES>(vrow);
 #pragma unroll
             for (int db = 0; db < C::DB; ++db) {
-                const int col = db * 32 + (b16 & 1) * 16 + q4 * 4;
-                const int lc = col >> 3, within = (col & 7) * 2;
-                v_off[r][db] = (unsigned)(C::KV_BYTES + vrow * C::RBYTES + ((lc ^ sw) << 4) + within);
+                const int lc = db * 2 + (b16 & 1);  // 16 columns = one piece
+                v_off[0][db] = (unsigned)(C::KV_BYTES + vrow * C::RBYTES + ((lc ^ sw) << 4) + h * 8);
+                v_off[1][db] = 0u;
             }
         }
     }
@@ -558,11 +595,15 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
             if (it == 0 && pass == 0) {
                 // Q has landed with the first chunks: move this wave's rows to registers
                 const int qrow = rt * 32 + l32;
-                const unsigned char* qr = lds + C::Q_OFFSET + qrow * C::RBYTES;
+                const unsigned char* qr = lds + C::Q_OFFSET + qrow * C::QRBYTES;
                 const int qsw = swizzle<D>(qrow);
 #pragma unroll
-                for (int k16 = 0; k16 < D / 16; ++k16)
-                    qreg[k16] = *reinterpret_cast<const bf16x8*>(qr + (((k16 * 2 + hi) ^ qsw) << 4));
+                for (int k16 = 0; k16 < D / 16; ++k16) {
+                    // the 8 columns of MFMA step k16 in this half-wave: k16*16 + hi*8 .. +7, or, where a
+                    // 16-byte piece of 8-bit keys spans two steps, (k16/2)*32 + hi*16 + (k16%2)*8 .. +7
+                    const int piece = KVB == 2 ? k16 * 2 + hi : (k16 >> 1) * 4 + hi * 2 + (k16 & 1);
+                    qreg[k16] = *reinterpret_cast<const bf16x8*>(qr + ((piece ^ qsw) << 4));
+                }
                 if constexpr (ROWSET) {
                     const int t_full = 1 + (p.W + p.G) * (p.N - 1);
                     const int tq = *reinterpret_cast<const int*>(lds + C::ROWIDS_OFFSET + t_lane * 4);
@@ -625,22 +666,34 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
                 // ---- operands: all K pieces of the block, and the V pieces of its first 16 keys,
                 //      are requested from LDS before the first MFMA (LDS answers in order)
                 const unsigned char* blk = lds + (cons_stage + (unsigned)(kbw * KS * 32 * C::RBYTES));
-                bf16x8 kf[D / 16];
+                bf16x8 kf[KVB == 2 ? D / 16 : 1];
+                u32x4 kraw[KVB == 2 ? 1 : D / 32];   // quantised: 16 codes per read, converted at the MFMA
+                if constexpr (KVB == 2) {
 #pragma unroll
-                for (int k16 = 0; k16 < D / 16; ++k16)
-                    kf[k16] = *reinterpret_cast<const bf16x8*>(blk + k_off[k16]);
-                bf16x8 vf[2][C::DB];
+                    for (int k16 = 0; k16 < D / 16; ++k16)
+                        kf[k16] = *reinterpret_cast<const bf16x8*>(blk + k_off[k16]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < D / 32; ++j) kraw[j] = *reinterpret_cast<const u32x4*>(blk + k_off[j]);
+                }
+                bf16x8 vf[2][KVB == 2 ? C::DB : 1];
+                i32x2 vraw[2][KVB == 2 ? 1 : C::DB];
                 auto read_v = [&](int kk) {
 #pragma unroll
                     for (int db = 0; db < C::DB; ++db) {
                         const unsigned char* a0 = blk + v_off[0][db] + kk * 16 * C::RBYTES;
-                        const unsigned char* a1 = blk + v_off[1][db] + kk * 16 * C::RBYTES;
-                        union { struct { short4v a, b; } s; bf16x8 v; } u;
-                        u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (short4v __attribute__((address_space(3)))*)a0);
-                        u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (short4v __attribute__((address_space(3)))*)a1);
-                        vf[kk][db] = u.v;
+                        if constexpr (KVB == 2) {
+                            const unsigned char* a1 = blk + v_off[1][db] + kk * 16 * C::RBYTES;
+                            union { struct { short4v a, b; } s; bf16x8 v; } u;
+                            u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                                (short4v __attribute__((address_space(3)))*)a0);
+                            u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                                (short4v __attribute__((address_space(3)))*)a1);
+                            vf[kk][db] = u.v;
+                        } else {
+                            vraw[kk][db] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+                                (i32x2 __attribute__((address_space(3)))*)a0);
+                        }
                     }
                 };
                 read_v(0);
@@ -650,8 +703,12 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
 #pragma unroll
                 for (int i = 0; i < 16; ++i) s[i] = 0.0f;
 #pragma unroll
-                for (int k16 = 0; k16 < D / 16; ++k16)
-                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[k16], qreg[k16], s, 0, 0, 0);
+                for (int k16 = 0; k16 < D / 16; ++k16) {
+                    bf16x8 a;
+                    if constexpr (KVB == 2) a = kf[k16];
+                    else a = fp8x8_to_bf16(kraw[k16 >> 1][(k16 & 1) * 2], kraw[k16 >> 1][(k16 & 1) * 2 + 1]);
+                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[k16], s, 0, 0, 0);
+                }
                 if (slots_left > 0) issue_slot();
                 read_v(1);  // in flight during the softmax arithmetic
 
@@ -672,12 +729,12 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
                 // m_run only moves when the block maximum exceeds it by more than 2^8 in the
                 // exponent (or no key was seen yet): softmax is invariant to the reference, and
                 // skipping small moves saves rescaling the accumulators nearly every time.
-                const bool move = (mx - m_run) * p.scale_log2 > 8.0f || m_run == kNegInf;
+                const bool move = (mx - m_run) * sl2 > 8.0f || m_run == kNegInf;
                 const float m_new = move ? mx : m_run;
                 const float m_use = (m_new == kNegInf) ? 0.0f : m_new;  // the row has seen no key at all
-                const float neg_mc = -m_use * p.scale_log2;
+                const float neg_mc = -m_use * sl2;
                 if (__builtin_amdgcn_ballot_w64(move) != 0ull) {
-                    const float alpha = fast_exp2(__builtin_fmaf(m_run, p.scale_log2, neg_mc));
+                    const float alpha = fast_exp2(__builtin_fmaf(m_run, sl2, neg_mc));
                     l_run *= alpha;
 #pragma unroll
                     for (int db = 0; db < C::DB; ++db)
@@ -690,7 +747,7 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
                 bf16x8 pf[2];
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
-                    pf[i >> 3][i & 7] = (__bf16)fast_exp2(__builtin_fmaf(s[i], p.scale_log2, neg_mc));
+                    pf[i >> 3][i & 7] = (__bf16)fast_exp2(__builtin_fmaf(s[i], sl2, neg_mc));
                 {
                     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
                     float psum0 = 0.0f, psum1 = 0.0f;
@@ -708,8 +765,12 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
 #pragma unroll
                 for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-                    for (int db = 0; db < C::DB; ++db)
-                        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kk][db], pf[kk], o[db], 0, 0, 0);
+                    for (int db = 0; db < C::DB; ++db) {
+                        bf16x8 a;
+                        if constexpr (KVB == 2) a = vf[kk][db];
+                        else a = fp8x8_to_bf16((unsigned)vraw[kk][db][0], (unsigned)vraw[kk][db][1]);
+                        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kk], o[db], 0, 0, 0);
+                    }
             }
             }
 #pragma unroll
@@ -734,7 +795,7 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
         // ---- merge the KS waves of a row tile; the key index is uniform in a wave, and branching
         //      on it keeps every register index a compile-time constant
         if (KS > 1) {
-            const float sc = p.scale_log2;
+            const float sc = sl2;
             if (ks == 0) merge_key_splits<C, KS, 0>(p, lds, rt, lane, wave_active, o, m_run, l_run, sc);
             if (KS > 1 && ks == 1) merge_key_splits<C, KS, (KS > 1 ? 1 : 0)>(p, lds, rt, lane, wave_active, o, m_run, l_run, sc);
             if (KS > 2 && ks == 2) merge_key_splits<C, KS, (KS > 2 ? 2 : 0)>(p, lds, rt, lane, wave_active, o, m_run, l_run, sc);
@@ -812,7 +873,7 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
                     for (int w = 0; w < MB; ++w)
                         if (s0 + w < p.XS) mb = fmaxf(mb, ml[w][0]);
                     const float m_use = (mb == kNegInf) ? 0.0f : mb;
-                    const float a0 = fast_exp2((m_acc - m_use) * p.scale_log2);
+                    const float a0 = fast_exp2((m_acc - m_use) * sl2);
                     l_acc *= a0;
                     if (s0 > 0) {
 #pragma unroll
@@ -823,7 +884,7 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
                     m_acc = mb;
 #pragma unroll
                     for (int w = 0; w < MB; ++w) {
-                        const float aw = s0 + w < p.XS ? fast_exp2((ml[w][0] - m_use) * p.scale_log2) : 0.0f;
+                        const float aw = s0 + w < p.XS ? fast_exp2((ml[w][0] - m_use) * sl2) : 0.0f;
                         l_acc = __builtin_fmaf(ml[w][1], aw, l_acc);
 #pragma unroll
                         for (int u = 0; u < C::SPW; ++u)
@@ -834,7 +895,7 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
                                     acc[u][i8 * 8 + e] = __builtin_fmaf((float)v[w][u][i8][e], aw, acc[u][i8 * 8 + e]);
                     }
                 }
-                const float inv = 1.0f / l_acc;
+                const float inv = out_scale / l_acc;
 #pragma unroll
                 for (int u = 0; u < C::SPW; ++u) {
                     f32x16 vals;
@@ -861,17 +922,17 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
 
     // ---- normalise and write this wave's slices (>= 1 visible key per row, so l > 0)
     if (wave_active && ((store_mask >> wave) & 1u)) {
-        const float inv = 1.0f / l_run;
+        const float inv = out_scale / l_run;
 #pragma unroll
         for (int u = 0; u < C::SPW; ++u) store_slice<C>(p, rb, kvh, rt, db0 + u, l32, hi, o[u], inv);
     }
 }
 
-template <int D, int RT, int KS, int KC, int NSTAGE, bool PAGED = false, bool ROWSET = false>
+template <int D, int RT, int KS, int KC, int NSTAGE, bool PAGED = false, bool ROWSET = false, int KVB = 2>
 __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnParams)
 {
     const AttnParams& p = warmed_arguments<AttnParams>();
-    step_attention_body<D, RT, KS, KC, NSTAGE, PAGED, ROWSET>(p, (int)(blockIdx.x & 7), (int)(blockIdx.x >> 3));
+    step_attention_body<D, RT, KS, KC, NSTAGE, PAGED, ROWSET, KVB>(p, (int)(blockIdx.x & 7), (int)(blockIdx.x >> 3));
 }
 
 // Several independent steps (sequences) in one launch: on every XCD, step i owns the slots
@@ -1067,13 +1128,13 @@ Plan make_plan(const Overrides& ov, int P, int T, int group, int kv_heads, int D
     return pl;
 }
 
-template <int D, int RT, int KS, int NSTAGE, int KC = 64, bool PAGED = false, bool ROWSET = false>
+template <int D, int RT, int KS, int NSTAGE, int KC = 64, bool PAGED = false, bool ROWSET = false, int KVB = 2>
 la_status launch_cfg(const AttnParams& prm, hipStream_t stream)
 {
-    using C = Cfg<D, RT, KS, KC, NSTAGE>;
+    using C = Cfg<D, RT, KS, KC, NSTAGE, KVB>;
     constexpr int kLds = C::LDS_BYTES + (ROWSET ? C::ROWIDS_BYTES : 0);
     static_assert(kLds <= 160 * 1024, "LDS of a compute unit");
-    auto kern = step_attention_kernel<D, RT, KS, KC, NSTAGE, PAGED, ROWSET>;
+    auto kern = step_attention_kernel<D, RT, KS, KC, NSTAGE, PAGED, ROWSET, KVB>;
     static bool attr_set[16] = {false};
     const la_status st = set_lds_attribute_once(reinterpret_cast<const void*>(kern), kLds, attr_set);
     if (st != LA_OK) return st;
@@ -1109,6 +1170,8 @@ la_status build_params(AttnParams& prm, const Overrides& ov, const Plan& pl, con
     prm.step_k = (const __bf16*)step_k;
     prm.step_v = (const __bf16*)step_v;
     prm.out = (__bf16*)out;
+    prm.k_scale = nullptr;
+    prm.v_scale = nullptr;
     prm.partials = nullptr;
     prm.tickets = nullptr;
     prm.P = P; prm.W = W; prm.N = N; prm.G = G; prm.T = T;
@@ -1161,7 +1224,8 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
                                 long long capacity, const int* block_table, int page_size, int n_pages,
                                 const int* row_ids, int n_rows, const void* step_k, const void* step_v, int P,
                                 int W, int N, int G, int heads, int kv_heads, int head_dim, void* out,
-                                hipStream_t stream, const FixedWorkspace* fixed)
+                                hipStream_t stream, const FixedWorkspace* fixed, const float* k_scale,
+                                const float* v_scale)
 {
     const int T = row_ids ? n_rows : 1 + (W + G) * (N - 1);
     const int group = heads / kv_heads;
@@ -1175,6 +1239,19 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
                                       T, step_k, step_v, P, W, N, G, heads, kv_heads, head_dim, out);
     if (st != LA_OK) return st;
     const long long total = prm.total_wg;
+    const bool quantised = k_scale != nullptr;
+    if (quantised) {
+        // 8-bit keys and values: rows of head_dim bytes (cache_rows counts rows, so it stands)
+        prm.k_scale = k_scale;
+        prm.v_scale = v_scale;
+        const bool compiled = pl.KC == 64 && pl.NS == 4 &&
+                              (head_dim == 128 ? ((pl.RT == 2 && pl.KS == 4) || (pl.RT == 4 && pl.KS == 2) ||
+                                                  (pl.RT == 1 && pl.KS == 2) || (pl.RT == 2 && pl.KS == 2))
+                                               : ((pl.RT == 1 && pl.KS == 2) || (pl.RT == 2 && pl.KS == 2)));
+        if (block_table || row_ids || !compiled)
+            return fail(LA_EUNSUPPORTED, "la_step_attention_fp8kv: no kernel for head_dim=%d plan (%d,%d,%d,%d)",
+                        head_dim, pl.RT, pl.KS, pl.NS, pl.KC);
+    }
 
     if (pl.XS > 1) {
         const size_t ticket_bytes = (size_t)kv_heads * pl.n_row_blocks * pl.RT * pl.KS * sizeof(unsigned) * kTicketStride;
@@ -1226,6 +1303,16 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
         }
         if (pl.RT == 1) return launch_cfg<64, 1, 2, 4, 64, true>(prm, stream);
         return launch_cfg<64, 2, 2, 4, 64, true>(prm, stream);
+    }
+    if (quantised) {
+        if (head_dim == 128) {
+            if (pl.KS == 4) return launch_cfg<128, 2, 4, 4, 64, false, false, 1>(prm, stream);
+            if (pl.RT == 4) return launch_cfg<128, 4, 2, 4, 64, false, false, 1>(prm, stream);
+            if (pl.RT == 1) return launch_cfg<128, 1, 2, 4, 64, false, false, 1>(prm, stream);
+            return launch_cfg<128, 2, 2, 4, 64, false, false, 1>(prm, stream);
+        }
+        if (pl.RT == 1) return launch_cfg<64, 1, 2, 4, 64, false, false, 1>(prm, stream);
+        return launch_cfg<64, 2, 2, 4, 64, false, false, 1>(prm, stream);
     }
     if (pl.KC == 32) return launch_cfg<128, 2, 2, 9, 32>(prm, stream);
     if (pl.KS == 4) return launch_cfg<128, 2, 4, 4>(prm, stream);

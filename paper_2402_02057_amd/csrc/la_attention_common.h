@@ -15,6 +15,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float kNegInf = -__builtin_huge_valf();
 
@@ -163,12 +165,34 @@ __device__ __forceinline__ unsigned lds_address(const void* p)
     return (unsigned)(size_t)(const __attribute__((address_space(3))) void*)p;
 }
 
-// 16-byte piece `lc` of row `row` lives at piece position lc ^ swizzle(row) of that row.
+// 16-byte piece `lc` of row `row` lives at piece position lc ^ row_swizzle(row) of that row, for
+// rows of RB bytes (256: 16 pieces, 128: 8 pieces, 64: 4 pieces).  Chosen so that the lanes of a
+// 16-byte read down a column of pieces (16 consecutive rows), and of a transposing read (rows
+// h*4 .. h*4+3 and 8 + h*4 .. +3), hit distinct banks.
+template <int RB>
+__device__ __forceinline__ int row_swizzle(int row)
+{
+    static_assert(RB == 256 || RB == 128 || RB == 64, "row sizes in use");
+    if (RB == 256) return ((row & 3) << 2) | ((row >> 2) & 3);
+    if (RB == 128) return (row >> 1) & 7;
+    return (row >> 2) & 3;
+}
+// (rows of D bf16 elements)
 template <int D>
 __device__ __forceinline__ int swizzle(int row)
 {
-    if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
-    return (row >> 1) & 7;
+    return row_swizzle<D * 2>(row);
+}
+
+// Eight 8-bit floats (E4M3, finite-only; `lo` holds the first four, lowest byte first) as bf16:
+// every such value is a bf16 number, so the conversion (scale 1) is exact.
+__device__ __forceinline__ bf16x8 fp8x8_to_bf16(unsigned lo, unsigned hi)
+{
+    const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, false);
+    const bf16x2 b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, true);
+    const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, false);
+    const bf16x2 d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, true);
+    return bf16x8{a[0], a[1], b[0], b[1], c[0], c[1], d[0], d[1]};
 }
 
 // Id of the XCD (accelerator die, with its own L2) this wave runs on.

@@ -62,12 +62,14 @@ la_status fixed_workspace(FixedWorkspace* ws);
 // `capacity`: rows between the caches of consecutive KV heads (P for a packed cache).
 // `block_table` != nullptr: the caches are pages [n_pages][kv_heads][page_size][head_dim]
 // (page_size a multiple of 64) and `capacity` is not used.  `row_ids` != nullptr: the step holds
-// n_rows rows of the (W, N, G) layout (packed cache only).
+// n_rows rows of the (W, N, G) layout (packed cache only).  `k_scale` != nullptr: keys and values
+// (cache and step rows) are 8-bit floats with one scale per KV head each (packed cache, whole steps).
 la_status launch_step_attention(const void* q, const void* k_cache, const void* v_cache,
                                 long long capacity, const int* block_table, int page_size, int n_pages,
                                 const int* row_ids, int n_rows, const void* step_k, const void* step_v, int P,
                                 int W, int N, int G, int heads, int kv_heads, int head_dim, void* out,
-                                hipStream_t stream, const FixedWorkspace* fixed = nullptr);
+                                hipStream_t stream, const FixedWorkspace* fixed = nullptr,
+                                const float* k_scale = nullptr, const float* v_scale = nullptr);
 // One step of a batched launch.  Packed caches: k_cache / v_cache per step, block_table null.  Paged
 // (page_size > 0): k_cache / v_cache are the shared page pools, block_table the step's own table.
 struct BatchSeq {

@@ -19,7 +19,7 @@ def lib():
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "la.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(la_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(la_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_functions_are_exported(lib):
