@@ -434,6 +434,20 @@ def main():
         torch.cuda.synchronize()
         r_ms.append(e[0].elapsed_time(e[1]) / r_calls)
     rope_us = float(np.median(r_ms)) * 1e3
+    # the alternative: the keys alone in a pass of their own, the queries rotated inside the attention
+    # kernel (la_step_attention_rope; its parity is tests/test_gpu_attention_rope.py).  Per layer a
+    # model pays attention + rope either way: both sums are reported.
+    rope_keys_us = time_calls(torch, np, lambda: binding.la_step_rope(None, rope_k, rope_cos, rope_sin, P, s.W, s.N,
+                                                                      s.G, H, KV, d), 32, reps, use_graph)
+    rot_it = iter(range(1 << 30))
+
+    def attention_rope_layer():
+        i = next(rot_it) % L
+        x = layers[i]
+        binding.la_step_attention_rope(x["q"], x["k_cache"], x["v_cache"], x["step_k"], x["step_v"], rope_cos,
+                                       rope_sin, P, s.W, s.N, s.G, H, KV, d, outs_rot[i])
+    outs_rot = [torch.empty((T, H, d), dtype=torch.bfloat16, device="cuda") for _ in range(L)]
+    attention_rope_us = time_calls(torch, np, attention_rope_layer, L, reps, use_graph)
 
     # the ends of eight sequences' steps in ONE launch (la_verify_step_batch), timed on its own:
     # sequence 0 is the step above, the others are further seeded draws of the same shape
@@ -673,7 +687,10 @@ def main():
                               "gbs": len(vsb) * verify_step_bytes / (verify_step_batch_us * 1e-6) / 1e9,
                               "frac_of_hbm_peak": len(vsb) * verify_step_bytes / (verify_step_batch_us * 1e-6) / 1e9
                               / HBM_PEAK_GBS},
-        "rope": {"us": rope_us, "algorithmic_bytes": 2 * (T * H * d + T * KV * d) * 2},
+        "rope": {"us": rope_us, "algorithmic_bytes": 2 * (T * H * d + T * KV * d) * 2,
+                 "keys_only_us": rope_keys_us, "attention_with_q_rotation_us": attention_rope_us,
+                 "per_layer_two_passes_us": attn_us + rope_us,
+                 "per_layer_q_in_attention_us": attention_rope_us + rope_keys_us},
         "kv_commit": {"us": kv_commit_us, "rows": n_commit, "algorithmic_bytes": kv_commit_bytes},
         "kv_commit_batch": {"layers_per_launch": L, "us_per_launch": kv_commit_batch_us,
                             "us_per_layer": kv_commit_batch_us / L},

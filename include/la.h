@@ -92,7 +92,8 @@ la_status la_step_attention(const void* q, const void* k_cache, const void* v_ca
  * sin[t][i], t the row's position: (a, b) -> (a cos - b sin, b cos + a sin), computed in fp32
  * and rounded to bf16 once.
  *
- *   q            bf16 [T][heads][head_dim], in/out;  step_k  bf16 [T][kv_heads][head_dim], in/out
+ *   q            bf16 [T][heads][head_dim], in/out, or NULL: then only the keys are rotated
+ *   step_k       bf16 [T][kv_heads][head_dim], in/out
  *   cos, sin     fp32 [max_pos][head_dim/2] on the device (the model's tables)
  *   max_pos      positions the tables hold; the step reaches P + max(W + N - 2, N - 1)
  *   interleaved  0: pair i is (x[i], x[i + head_dim/2]);  nonzero: (x[2i], x[2i + 1])
@@ -126,6 +127,28 @@ la_status la_step_rope(void* q, void* step_k, const float* cos, const float* sin
 la_status la_step_attention_fp8kv(const void* q, const void* k_cache, const void* v_cache, const void* step_k,
                                   const void* step_v, const float* k_scale, const float* v_scale, int P, int W,
                                   int N, int G, int heads, int kv_heads, int head_dim, void* out, void* stream);
+
+/*
+ * la_step_attention with the rotary position embedding of the QUERY rows done inside the
+ * kernel: q arrives as the projection left it and is not modified; the kernel stages its rows
+ * in on-chip memory, turns them by the positions of Fig. 2(b) (row r sits at P + its digit)
+ * with the arithmetic of la_step_rope, and goes on as la_step_attention does.  The result has
+ * the bits of la_step_rope on q followed by la_step_attention.  The step's keys must already
+ * be rotated (la_step_rope with q == NULL rotates step_k alone; the cache needs the rotated
+ * keys anyway, see la_kv_commit).
+ *
+ *   cos, sin     fp32 [max_pos][head_dim/2] on the device, 16-byte aligned
+ *   max_pos      positions the tables hold; the step reaches P + max(W + N - 2, N - 1)
+ *   interleaved  0: pair i is (x[i], x[i + head_dim/2]);  nonzero: (x[2i], x[2i + 1])
+ * Everything else as la_step_attention.  Limit: the table rows of the step's positions are
+ * staged beside the key/value ring; with head_dim 128 there is room for 32 positions
+ * (W + N - 2 <= 31) in the common decomposition.  A step that needs more is refused with
+ * LA_EUNSUPPORTED: rotate q with la_step_rope then.
+ */
+la_status la_step_attention_rope(const void* q, const void* k_cache, const void* v_cache, const void* step_k,
+                                 const void* step_v, const float* cos, const float* sin, int max_pos, int interleaved,
+                                 int P, int W, int N, int G, int heads, int kv_heads, int head_dim, void* out,
+                                 void* stream);
 
 /*
  * The same step over a cache allocated for more keys than it holds, as a decoding loop keeps

@@ -158,7 +158,8 @@ la_status step_attention_checked(const char* name, const void* q, const void* k_
                                  const void* step_k, const void* step_v, int P, int W, int N, int G, int heads,
                                  int kv_heads, int head_dim, void* out, void* stream, const int* row_ids = nullptr,
                                  int n_rows = 0, const la::FixedWorkspace* fixed = nullptr,
-                                 const float* k_scale = nullptr, const float* v_scale = nullptr)
+                                 const float* k_scale = nullptr, const float* v_scale = nullptr,
+                                 const la::RopeTables* rope = nullptr)
 {
     if (P < 0 || W < 0 || G < 0 || N < 2 || heads < 1 || kv_heads < 1)
         return la::fail(LA_EINVAL, "%s: need P,W,G >= 0, N >= 2, heads,kv_heads >= 1 "
@@ -181,7 +182,7 @@ la_status step_attention_checked(const char* name, const void* q, const void* k_
     if (bits & 15) return la::fail(LA_EINVAL, "%s: buffers must be 16-byte aligned", name);
     return la::launch_step_attention(q, k_cache, v_cache, capacity, block_table, page_size, n_pages, row_ids,
                                      n_rows, step_k, step_v, P, W, N, G, heads, kv_heads, head_dim, out,
-                                     (hipStream_t)stream, fixed, k_scale, v_scale);
+                                     (hipStream_t)stream, fixed, k_scale, v_scale, rope);
 }
 
 // page geometry shared by the paged entry points
@@ -224,6 +225,25 @@ la_status la_step_attention_fp8kv(const void* q, const void* k_cache, const void
     return step_attention_checked("la_step_attention_fp8kv", q, k_cache, v_cache, P, nullptr, 0, 0, step_k, step_v,
                                   P, W, N, G, heads, kv_heads, head_dim, out, stream, nullptr, 0, nullptr, k_scale,
                                   v_scale);
+}
+
+la_status la_step_attention_rope(const void* q, const void* k_cache, const void* v_cache, const void* step_k,
+                                 const void* step_v, const float* cos, const float* sin, int max_pos, int interleaved,
+                                 int P, int W, int N, int G, int heads, int kv_heads, int head_dim, void* out,
+                                 void* stream)
+{
+    if (P < 0 || W < 0 || G < 0 || N < 2)
+        return la::fail(LA_EINVAL, "la_step_attention_rope: need P,W,G >= 0, N >= 2 (got P=%d W=%d N=%d G=%d)", P, W, N, G);
+    if (!cos || !sin || (((uintptr_t)cos | (uintptr_t)sin) & 15))
+        return la::fail(LA_EINVAL, "la_step_attention_rope: cos / sin must be 16-byte aligned device arrays");
+    const long long furthest = (long long)P + (W > 0 && W + N - 2 > N - 1 ? W + N - 2 : (W > 0 || G > 0 ? N - 1 : 0));
+    if (max_pos < 1 || furthest >= max_pos)
+        return la::fail(LA_EINVAL, "la_step_attention_rope: the tables hold %d positions, the step reaches position %lld",
+                        max_pos, furthest);
+    const la::RopeTables rope = {cos, sin, interleaved != 0};
+    return step_attention_checked("la_step_attention_rope", q, k_cache, v_cache, P, nullptr, 0, 0, step_k, step_v,
+                                  P, W, N, G, heads, kv_heads, head_dim, out, stream, nullptr, 0, nullptr, nullptr,
+                                  nullptr, &rope);
 }
 
 la_status la_step_attention_cap(const void* q, const void* k_cache, const void* v_cache, long long capacity,
@@ -433,7 +453,7 @@ la_status la_step_rope(void* q, void* step_k, const float* cos, const float* sin
     if (max_pos < 1 || furthest >= max_pos)
         return la::fail(LA_EINVAL, "la_step_rope: the tables hold %d positions, the step reaches position %lld",
                         max_pos, furthest);
-    if (!q || !step_k || !cos || !sin) return la::fail(LA_EINVAL, "la_step_rope: null pointer");
+    if (!step_k || !cos || !sin) return la::fail(LA_EINVAL, "la_step_rope: null pointer");
     if (((uintptr_t)q | (uintptr_t)step_k | (uintptr_t)cos | (uintptr_t)sin) & 15)
         return la::fail(LA_EINVAL, "la_step_rope: q, step_k and the tables must be 16-byte aligned");
     return la::launch_step_rope(q, step_k, cos, sin, P, W, N, G, heads, kv_heads, head_dim, interleaved != 0,

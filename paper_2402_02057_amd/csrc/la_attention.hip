@@ -45,6 +45,7 @@
 
 #include "la_internal.h"
 #include "la_attention_common.h"
+#include "la_rope_common.h"
 
 #ifdef LA_DEV_HOOKS
 #include LA_DEV_HOOKS  // developer builds only: timing stamps, never part of the product build
@@ -66,17 +67,31 @@ struct AttnParams {
     const __bf16* step_k;
     const __bf16* step_v;
     __bf16* out;
-    // Quantised cache (8-bit keys and values): one fp32 scale per KV head each; else nullptr.
-    const float* k_scale;
-    const float* v_scale;
+    // Two pointers whose meaning depends on the kernel variant (the variants exclude each other, and
+    // the structure has to stay small: it travels as a kernel argument, sixteen at a time in a batch):
+    //   paged cache       block_table: k_cache / v_cache are [n_pages][kv_heads][page][head_dim] and
+    //                     prefix key t sits in page block_table[t / page] at slot t % page
+    //   row subset        row_ids: T ids of rows of the full (W, N, G) layout
+    //   quantised cache   k_scale, v_scale: one fp32 scale per KV head each (8-bit keys and values)
+    //   rotating          rope_cos, rope_sin: the rows of the model's tables from the prefix length
+    //                     on, [rope_rows][head_dim/2] fp32 each (query rows rotated on the way in)
+    union {
+        const int* block_table;
+        const float* k_scale;
+        const float* rope_cos;
+    };
+    union {
+        const int* row_ids;
+        const float* v_scale;
+        const float* rope_sin;
+    };
+    int rope_rows;         // positions P .. P + rope_rows - 1 are staged in LDS
+    int rope_block;        // LDS bytes reserved per table (rope_rows * head_dim * 2 rounded up to 1 KB)
+    int rope_interleaved;  // pairing of the rotation: 0 (x[i], x[i + d/2]), 1 (x[2i], x[2i + 1])
     void* partials;     // XS > 1: per workgroup and wave, fragment-layout bf16 slices and fp32 (m, l)
     unsigned* tickets;  // XS > 1: one counter (kTicketStride words apart) per (KV head, row block, wave), zero between calls
     int P, W, N, G, T;
     long long cache_rows;  // rows between the caches of consecutive KV heads (>= P; paged: the page size)
-    // Paged cache (block_table != nullptr): k_cache / v_cache are [n_pages][kv_heads][page][head_dim]
-    // and prefix key t sits in page block_table[t / page] at slot t % page.
-    const int* block_table;
-    const int* row_ids;    // row-subset variant: T ids of rows of the full (W, N, G) layout, else nullptr
     long long page_bytes;  // bytes of one page (all KV heads)
     int page_chunks;       // chunks per page
     int n_pages;           // table entries are clamped to 0 .. n_pages-1
@@ -176,6 +191,11 @@ struct Cfg {
     static_assert(WLOADS % NW == 0, "chunk loads must divide among the waves");
     static_assert((Q_BYTES / 1024) % NW == 0, "Q loads must divide among the waves");
     static_assert(NSTAGE <= 9, "wait_chunks covers up to 8 younger chunks");
+    // rotating variant: the cosine and sine rows of the step's positions, behind everything else
+    static constexpr int ROPE_OFFSET = LDS_BYTES;
+    static constexpr int ROPE_POS_BYTES = D * 2;           // one position of one table (D/2 fp32)
+    static constexpr int ROPE_MAX_BYTES = (160 * 1024 - LDS_BYTES) / 2048 * 2048 < 64 * 1024
+                                              ? (160 * 1024 - LDS_BYTES) / 2048 * 2048 : 64 * 1024;  // both tables
     // row-subset variant: the ids of up to ROWSET_MAX rows, staged behind everything else
     static constexpr int ROWSET_MAX = 1024;
     static constexpr int ROWIDS_OFFSET = LDS_BYTES;
@@ -282,11 +302,12 @@ __device__ __forceinline__ void merge_key_splits(const AttnParams& p, unsigned c
 // lookahead parallelism, Sec. 3.4); row ids come from p.row_ids and the mask is evaluated pair by pair.
 // The body is shared by the one-step kernel and the batched one: `xcd` is the XCD this workgroup
 // runs on (its id modulo 8) and `slot` its index among the step's workgroups on that XCD.
-template <int D, int RT, int KS, int KC, int NSTAGE, bool PAGED = false, bool ROWSET = false, int KVB = 2>
+template <int D, int RT, int KS, int KC, int NSTAGE, bool PAGED = false, bool ROWSET = false, int KVB = 2, bool ROPE = false>
 __device__ __forceinline__ void step_attention_body(const AttnParams& p, const int xcd, const int slot)
 {
     using C = Cfg<D, RT, KS, KC, NSTAGE, KVB>;
     static_assert(KVB == 2 || (KVB == 1 && !PAGED && !ROWSET), "the quantised cache is packed and takes whole steps");
+    static_assert(!ROPE || (!PAGED && !ROWSET && KVB == 2), "the rotating variant takes packed bf16 caches and whole steps");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
     // Consecutive workgroup ids go round-robin over the 8 XCDs (each with its own L2); put
@@ -448,6 +469,19 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
     // The workgroup's query rows go to LDS like a chunk (same swizzle as K); rows past the end
     // repeat the last row.
     auto issue_q = [&]() {
+        if constexpr (ROPE) {
+            // the table rows of the step's positions: two linear blocks, 1 KB per wave-load, lanes
+            // past the end repeat the last 16 bytes
+            const int per_table = p.rope_block >> 10;
+            const unsigned last = (unsigned)(p.rope_rows * C::ROPE_POS_BYTES - 16);
+            for (int i = wave; i < 2 * per_table; i += C::NW) {
+                const bool is_sin = i >= per_table;
+                const int j = is_sin ? i - per_table : i;
+                const unsigned off = min((unsigned)(j * 1024 + lane * 16), last);
+                dma16_base(is_sin ? p.rope_sin : p.rope_cos, off,
+                           lds_base + C::ROPE_OFFSET + (is_sin ? p.rope_block : 0) + j * 1024);
+            }
+        }
 #pragma unroll
         for (int i = 0; i < C::QLPW; ++i) {
             const int wl = wave + i * C::NW;
@@ -490,7 +524,9 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
         const int upfront = min(n_my, p.pre);
         // (paged cache: Q does not depend on the block table, so it goes first and the wait for
         // the table's first entries overlaps its issue)
-        const bool q_first = table != nullptr;
+        // (rotating variant: Q and the tables first as well: they are rotated in LDS while the first
+        // chunks are still on their way)
+        const bool q_first = table != nullptr || ROPE;
         if (q_first && with_q) issue_q();
 #pragma unroll
         for (int s = 0; s < NSTAGE; ++s) {
@@ -501,6 +537,38 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
     };
     issue_first(true);
     LA_STAMP(1);
+
+    if constexpr (ROPE) {
+        // Q and the table rows are older than every chunk requested so far: wait for them alone,
+        // then every thread turns eight pairs of the workgroup's query rows in place (the same
+        // arithmetic as the pass of its own).  The barrier of the first iteration orders these
+        // writes before the waves read their rows into registers.
+        // (a ring requested in full: the first chunk is waited for as well; the counter has 6 bits)
+        wait_young<C::LPW, NSTAGE - 1>(min(issued, NSTAGE - 1));
+        __syncthreads();
+        constexpr int UPR = D / 16;  // units of eight pairs per row
+        const bool inter = p.rope_interleaved != 0;
+        for (int u = tid; u < C::ROWS * UPR; u += C::NT) {
+            const int r = u / UPR, c = u - r * UPR;
+            const int rr = min(rb * C::ROWS + r, p.R - 1);
+            const int digit = min(step_row_digit(div_small(rr, p.inv_group), p.W, p.N, p.inv_W, p.inv_n1), p.rope_rows - 1);
+            unsigned char* qrow = lds + C::Q_OFFSET + r * C::QRBYTES;
+            const int sw = swizzle<D>(r);
+            bf16x8* va = reinterpret_cast<bf16x8*>(qrow + (((inter ? 2 * c : c) ^ sw) << 4));
+            bf16x8* vb = reinterpret_cast<bf16x8*>(qrow + (((inter ? 2 * c + 1 : c + UPR) ^ sw) << 4));
+            const float* cs = reinterpret_cast<const float*>(lds + C::ROPE_OFFSET + digit * C::ROPE_POS_BYTES) + c * 8;
+            const float* sn = reinterpret_cast<const float*>(lds + C::ROPE_OFFSET + p.rope_block + digit * C::ROPE_POS_BYTES) + c * 8;
+            const f32x4 c0 = *reinterpret_cast<const f32x4*>(cs), c1 = *reinterpret_cast<const f32x4*>(cs + 4);
+            const f32x4 s0 = *reinterpret_cast<const f32x4*>(sn), s1 = *reinterpret_cast<const f32x4*>(sn + 4);
+            const float co[8] = {c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
+            const float si[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
+            const bf16x8 xa = *va, xb = *vb;
+            bf16x8 ya, yb;
+            rope_eight_pairs(xa, xb, co, si, inter, ya, yb);
+            *va = ya;
+            *vb = yb;
+        }
+    }
 
     // which step keys this lane's row may see
     const int t_lane = div_small(min(row_base + l32, p.R - 1), p.inv_group);  // step row of this lane's query row
@@ -928,11 +996,11 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
     }
 }
 
-template <int D, int RT, int KS, int KC, int NSTAGE, bool PAGED = false, bool ROWSET = false, int KVB = 2>
+template <int D, int RT, int KS, int KC, int NSTAGE, bool PAGED = false, bool ROWSET = false, int KVB = 2, bool ROPE = false>
 __global__ __launch_bounds__(RT* KS * 64) void step_attention_kernel(const AttnParams)
 {
     const AttnParams& p = warmed_arguments<AttnParams>();
-    step_attention_body<D, RT, KS, KC, NSTAGE, PAGED, ROWSET, KVB>(p, (int)(blockIdx.x & 7), (int)(blockIdx.x >> 3));
+    step_attention_body<D, RT, KS, KC, NSTAGE, PAGED, ROWSET, KVB, ROPE>(p, (int)(blockIdx.x & 7), (int)(blockIdx.x >> 3));
 }
 
 // Several independent steps (sequences) in one launch: on every XCD, step i owns the slots
@@ -1082,7 +1150,8 @@ bool rowset_plan_supported(int D, int RT, int KS, int NS, int KC)
     return paged_plan_supported(D, RT, KS, NS, KC) && RT != 4;
 }
 
-Plan make_plan(const Overrides& ov, int P, int T, int group, int kv_heads, int D, bool paged = false, bool rowset = false)
+Plan make_plan(const Overrides& ov, int P, int T, int group, int kv_heads, int D, bool paged = false, bool rowset = false,
+               bool rope = false)
 {
     Plan pl;
     const int R = T * group;
@@ -1095,7 +1164,7 @@ Plan make_plan(const Overrides& ov, int P, int T, int group, int kv_heads, int D
     // chunk in LDS).  Head dimension 64 and single-tile problems keep four-wave workgroups.
     if (tiles <= 1) { pl.RT = 1; pl.KS = 2; }
     else if (D != 128) { pl.RT = 2; pl.KS = 2; }
-    else if (tiles >= 16 && (P + T) / pl.KC >= 64 && !rowset) { pl.RT = 4; pl.KS = 2; }
+    else if (tiles >= 16 && (P + T) / pl.KC >= 64 && !rowset && !rope) { pl.RT = 4; pl.KS = 2; }  // (no LDS left for tables)
     else { pl.RT = 2; pl.KS = 4; }
     pl.XS = 0;
     pl.NS = 0;
@@ -1128,13 +1197,17 @@ Plan make_plan(const Overrides& ov, int P, int T, int group, int kv_heads, int D
     return pl;
 }
 
-template <int D, int RT, int KS, int NSTAGE, int KC = 64, bool PAGED = false, bool ROWSET = false, int KVB = 2>
+template <int D, int RT, int KS, int NSTAGE, int KC = 64, bool PAGED = false, bool ROWSET = false, int KVB = 2, bool ROPE = false>
 la_status launch_cfg(const AttnParams& prm, hipStream_t stream)
 {
     using C = Cfg<D, RT, KS, KC, NSTAGE, KVB>;
-    constexpr int kLds = C::LDS_BYTES + (ROWSET ? C::ROWIDS_BYTES : 0);
+    constexpr int kLds = C::LDS_BYTES + (ROWSET ? C::ROWIDS_BYTES : 0) + (ROPE ? C::ROPE_MAX_BYTES : 0);
     static_assert(kLds <= 160 * 1024, "LDS of a compute unit");
-    auto kern = step_attention_kernel<D, RT, KS, KC, NSTAGE, PAGED, ROWSET, KVB>;
+    if (ROPE && 2 * prm.rope_block > C::ROPE_MAX_BYTES)
+        return fail(LA_EUNSUPPORTED, "la_step_attention_rope: %d positions of cosines and sines do not fit beside this "
+                                     "decomposition (%d bytes of LDS left): rotate q with la_step_rope instead",
+                    prm.rope_rows, C::ROPE_MAX_BYTES);
+    auto kern = step_attention_kernel<D, RT, KS, KC, NSTAGE, PAGED, ROWSET, KVB, ROPE>;
     static bool attr_set[16] = {false};
     const la_status st = set_lds_attribute_once(reinterpret_cast<const void*>(kern), kLds, attr_set);
     if (st != LA_OK) return st;
@@ -1170,8 +1243,7 @@ la_status build_params(AttnParams& prm, const Overrides& ov, const Plan& pl, con
     prm.step_k = (const __bf16*)step_k;
     prm.step_v = (const __bf16*)step_v;
     prm.out = (__bf16*)out;
-    prm.k_scale = nullptr;
-    prm.v_scale = nullptr;
+    prm.rope_rows = prm.rope_block = prm.rope_interleaved = 0;
     prm.partials = nullptr;
     prm.tickets = nullptr;
     prm.P = P; prm.W = W; prm.N = N; prm.G = G; prm.T = T;
@@ -1225,7 +1297,7 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
                                 const int* row_ids, int n_rows, const void* step_k, const void* step_v, int P,
                                 int W, int N, int G, int heads, int kv_heads, int head_dim, void* out,
                                 hipStream_t stream, const FixedWorkspace* fixed, const float* k_scale,
-                                const float* v_scale)
+                                const float* v_scale, const RopeTables* rope)
 {
     const int T = row_ids ? n_rows : 1 + (W + G) * (N - 1);
     const int group = heads / kv_heads;
@@ -1233,7 +1305,8 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
         (long long)kv_heads * head_dim * 2 >= (1 << 24))
         return fail(LA_EUNSUPPORTED, "la_step_attention: step too large (T=%d, heads=%d)", T, heads);
     const Overrides ov = current_overrides();
-    const Plan pl = make_plan(ov, P, T, group, kv_heads, head_dim, block_table != nullptr, row_ids != nullptr);
+    const Plan pl = make_plan(ov, P, T, group, kv_heads, head_dim, block_table != nullptr, row_ids != nullptr,
+                              rope != nullptr);
     AttnParams prm;
     const la_status st = build_params(prm, ov, pl, q, k_cache, v_cache, capacity, block_table, page_size, n_pages, row_ids,
                                       T, step_k, step_v, P, W, N, G, heads, kv_heads, head_dim, out);
@@ -1242,8 +1315,6 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
     const bool quantised = k_scale != nullptr;
     if (quantised) {
         // 8-bit keys and values: rows of head_dim bytes (cache_rows counts rows, so it stands)
-        prm.k_scale = k_scale;
-        prm.v_scale = v_scale;
         const bool compiled = pl.KC == 64 && pl.NS == 4 &&
                               (head_dim == 128 ? ((pl.RT == 2 && pl.KS == 4) || (pl.RT == 4 && pl.KS == 2) ||
                                                   (pl.RT == 1 && pl.KS == 2) || (pl.RT == 2 && pl.KS == 2))
@@ -1251,6 +1322,8 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
         if (block_table || row_ids || !compiled)
             return fail(LA_EUNSUPPORTED, "la_step_attention_fp8kv: no kernel for head_dim=%d plan (%d,%d,%d,%d)",
                         head_dim, pl.RT, pl.KS, pl.NS, pl.KC);
+        prm.k_scale = k_scale;  // (in place of the block table and the row ids, which this variant does not have)
+        prm.v_scale = v_scale;
     }
 
     if (pl.XS > 1) {
@@ -1303,6 +1376,29 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
         }
         if (pl.RT == 1) return launch_cfg<64, 1, 2, 4, 64, true>(prm, stream);
         return launch_cfg<64, 2, 2, 4, 64, true>(prm, stream);
+    }
+    if (rope) {
+        // the furthest position of the step: the newest window level's last column, or a candidate's last token
+        const int far = W > 0 ? (W + N - 2 > N - 1 ? W + N - 2 : N - 1) : (G > 0 ? N - 1 : 0);
+        prm.rope_rows = far + 1;
+        prm.rope_block = (prm.rope_rows * head_dim * 2 + 1023) / 1024 * 1024;
+        prm.rope_interleaved = rope->interleaved ? 1 : 0;
+        const bool compiled = pl.KC == 64 && pl.NS == 4 &&
+                              (head_dim == 128 ? ((pl.RT == 2 && pl.KS == 4) || (pl.RT == 1 && pl.KS == 2) ||
+                                                  (pl.RT == 2 && pl.KS == 2))
+                                               : ((pl.RT == 1 && pl.KS == 2) || (pl.RT == 2 && pl.KS == 2)));
+        if (block_table || row_ids || quantised || !compiled)
+            return fail(LA_EUNSUPPORTED, "la_step_attention_rope: no kernel for head_dim=%d plan (%d,%d,%d,%d)",
+                        head_dim, pl.RT, pl.KS, pl.NS, pl.KC);
+        prm.rope_cos = rope->cos + (size_t)P * (head_dim / 2);
+        prm.rope_sin = rope->sin + (size_t)P * (head_dim / 2);
+        if (head_dim == 128) {
+            if (pl.KS == 4) return launch_cfg<128, 2, 4, 4, 64, false, false, 2, true>(prm, stream);
+            if (pl.RT == 1) return launch_cfg<128, 1, 2, 4, 64, false, false, 2, true>(prm, stream);
+            return launch_cfg<128, 2, 2, 4, 64, false, false, 2, true>(prm, stream);
+        }
+        if (pl.RT == 1) return launch_cfg<64, 1, 2, 4, 64, false, false, 2, true>(prm, stream);
+        return launch_cfg<64, 2, 2, 4, 64, false, false, 2, true>(prm, stream);
     }
     if (quantised) {
         if (head_dim == 128) {

@@ -184,6 +184,17 @@ __device__ __forceinline__ int swizzle(int row)
     return row_swizzle<D * 2>(row);
 }
 
+// Position of step row t relative to the current token (the digit on the token in Fig. 2(b)):
+// 0 for the current token, 1 + level + column for a lookahead token, 1 + index for a candidate token.
+__device__ __forceinline__ int step_row_digit(int t, int W, int N, float inv_W, float inv_n1)
+{
+    if (t == 0) return 0;
+    const int n_look = W * (N - 1);
+    if (t <= n_look) return 1 + (t - 1) - div_small(t - 1, inv_W) * (W - 1);  // 1 + l + j with t - 1 = l*W + j
+    const int x = t - 1 - n_look;
+    return 1 + x - div_small(x, inv_n1) * (N - 1);
+}
+
 // Eight 8-bit floats (E4M3, finite-only; `lo` holds the first four, lowest byte first) as bf16:
 // every such value is a bf16 number, so the conversion (scale 1) is exact.
 __device__ __forceinline__ bf16x8 fp8x8_to_bf16(unsigned lo, unsigned hi)

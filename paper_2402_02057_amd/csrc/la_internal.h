@@ -57,6 +57,13 @@ struct FixedWorkspace {
     void* partials;
     size_t partial_bytes;
 };
+// Rotary position embedding applied to the query rows inside the attention kernel: the model's
+// tables, fp32 [max_pos][head_dim/2] on the device (the launcher takes the rows from P on).
+struct RopeTables {
+    const float* cos;
+    const float* sin;
+    bool interleaved;
+};
 // The library's own fixed block on the current device (a file-scope device array; no allocation).
 la_status fixed_workspace(FixedWorkspace* ws);
 // `capacity`: rows between the caches of consecutive KV heads (P for a packed cache).
@@ -69,7 +76,8 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
                                 const int* row_ids, int n_rows, const void* step_k, const void* step_v, int P,
                                 int W, int N, int G, int heads, int kv_heads, int head_dim, void* out,
                                 hipStream_t stream, const FixedWorkspace* fixed = nullptr,
-                                const float* k_scale = nullptr, const float* v_scale = nullptr);
+                                const float* k_scale = nullptr, const float* v_scale = nullptr,
+                                const RopeTables* rope = nullptr);
 // One step of a batched launch.  Packed caches: k_cache / v_cache per step, block_table null.  Paged
 // (page_size > 0): k_cache / v_cache are the shared page pools, block_table the step's own table.
 struct BatchSeq {

@@ -1,12 +1,14 @@
 // Rotary position embedding of a step's queries and keys at the positions the step's tokens hold
 // (the digits of Fig. 2(b): current token 0, lookahead token of level l and column j at 1 + l + j,
-// candidate token k at 1 + k; Sec. 3.1 and 3.3), in place and in one launch for both tensors.
+// candidate token k at 1 + k; Sec. 3.1 and 3.3), in place and in one launch for both tensors (or
+// for the keys alone).
 //
 // One workgroup per step row.  A work item is eight pairs of one head: two 16-byte vectors of the
 // row (pieces c and c + d/16 when pair i is (x[i], x[i + d/2]); pieces 2c and 2c + 1 when it is
 // (x[2i], x[2i + 1])) and eight cosines and sines of the row's position.  Arithmetic in fp32,
 // one rounding to bf16.  The pass is bound by its launch: 2 MB at the 7B shape.
 #include "la_internal.h"
+#include "la_rope_common.h"
 
 namespace la {
 namespace {
@@ -54,24 +56,7 @@ __global__ __launch_bounds__(256) void step_rope_kernel(RopeParams p)
         const float co[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
         const float si[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
         bf16x8 ya, yb;
-        if (p.interleaved) {
-            // the sixteen elements are pairs (0,1), (2,3), ...: pair e is element 2e, 2e + 1
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float a = e < 4 ? (float)xa[2 * e] : (float)xb[2 * e - 8];
-                const float b = e < 4 ? (float)xa[2 * e + 1] : (float)xb[2 * e - 7];
-                const float ra = a * co[e] - b * si[e], rb = b * co[e] + a * si[e];
-                if (e < 4) { ya[2 * e] = (__bf16)ra; ya[2 * e + 1] = (__bf16)rb; }
-                else { yb[2 * e - 8] = (__bf16)ra; yb[2 * e - 7] = (__bf16)rb; }
-            }
-        } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float a = (float)xa[e], b = (float)xb[e];
-                ya[e] = (__bf16)(a * co[e] - b * si[e]);
-                yb[e] = (__bf16)(b * co[e] + a * si[e]);
-            }
-        }
+        rope_eight_pairs(xa, xb, co, si, p.interleaved != 0, ya, yb);
         *va = ya;
         *vb = yb;
     }
@@ -88,7 +73,8 @@ la_status launch_step_rope(void* q, void* step_k, const float* cos, const float*
     p.cos = cos;
     p.sin = sin;
     p.P = P; p.W = W; p.n1 = N - 1; p.G = G;
-    p.heads = heads; p.kv_heads = kv_heads; p.head_dim = head_dim; p.interleaved = interleaved;
+    p.heads = q ? heads : 0;  // no q: the keys alone (the attention kernel can rotate its queries itself)
+    p.kv_heads = kv_heads; p.head_dim = head_dim; p.interleaved = interleaved;
     const int T = 1 + (W + G) * (N - 1);
     hipLaunchKernelGGL(step_rope_kernel, dim3((unsigned)T), dim3(256), 0, stream, p);
     const hipError_t e = hipGetLastError();

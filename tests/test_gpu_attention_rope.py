@@ -1,0 +1,129 @@
+"""GPU parity of la_step_attention_rope (query rows rotated inside the attention kernel) and of the
+keys-only mode of la_step_rope.
+
+Two bars: against the oracle (step_rope in fp64, rounded to bf16 as the tensors in memory are, then
+step_attention) within 2e-2; and against the library's own two-pass path (la_step_rope on q and
+step_k, then la_step_attention), whose output bits it must reproduce exactly, because both rotate
+with the same arithmetic."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import la_oracle as orc
+from paper_2402_02057_amd import binding, workloads as wl
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+def make(seed, P, W, N, G, H, KV, d):
+    rng = np.random.default_rng(seed)
+    T = 1 + (W + G) * (N - 1)
+    bf = lambda shape: wl.f32_to_bf16_bits(rng.standard_normal(size=shape, dtype=np.float32))
+    x = dict(q=bf((T, H, d)), k_cache=bf((KV, P, d)), v_cache=bf((KV, P, d)), step_k=bf((T, KV, d)), step_v=bf((T, KV, d)))
+    reach = P + max(W + N - 2 if W else 0, N - 1 if (W or G) else 0)
+    cos, sin = wl.rope_tables(reach + 5, d)
+    return x, cos, sin
+
+
+def run_case(seed, P, W, N, G, H, KV, d, interleaved, oracle=True):
+    print("case", dict(P=P, W=W, N=N, G=G, H=H, KV=KV, d=d, interleaved=interleaved), flush=True)
+    x, cos, sin = make(seed, P, W, N, G, H, KV, d)
+    T = 1 + (W + G) * (N - 1)
+    dev = {k: binding.bf16_tensor(v) for k, v in x.items()}
+    dcos, dsin = torch.from_numpy(cos).cuda(), torch.from_numpy(sin).cuda()
+
+    # two passes: rotate q and the keys in memory, then the plain step
+    q2, k2 = dev["q"].clone(), dev["step_k"].clone()
+    binding.la_step_rope(q2, k2, dcos, dsin, P, W, N, G, H, KV, d, interleaved)
+    two = torch.empty((T, H, d), dtype=torch.bfloat16, device="cuda")
+    binding.la_step_attention(q2, dev["k_cache"], dev["v_cache"], k2, dev["step_v"], P, W, N, G, H, KV, d, two)
+
+    # fused: the keys alone in memory, q rotated inside the attention kernel
+    k1 = dev["step_k"].clone()
+    binding.la_step_rope(None, k1, dcos, dsin, P, W, N, G, H, KV, d, interleaved)
+    q_before = dev["q"].clone()
+    one = torch.full((T, H, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    binding.la_step_attention_rope(dev["q"], dev["k_cache"], dev["v_cache"], k1, dev["step_v"], dcos, dsin, P, W, N, G,
+                                   H, KV, d, one, interleaved)
+    torch.cuda.synchronize()
+    assert torch.equal(k1.view(torch.int16), k2.view(torch.int16)), "keys-only rotation differs from the full pass"
+    assert torch.equal(dev["q"].view(torch.int16), q_before.view(torch.int16)), "q was modified"
+    assert torch.equal(one.view(torch.int16), two.view(torch.int16)), "fused and two-pass outputs differ"
+
+    if oracle:
+        rq, rk = orc.step_rope(orc.bf16_to_f64(x["q"]), orc.bf16_to_f64(x["step_k"]), cos, sin, P, W, N, G, interleaved)
+        want = orc.step_attention(wl.f32_to_bf16_bits(rq.astype(np.float32)), x["k_cache"], x["v_cache"],
+                                  wl.f32_to_bf16_bits(rk.astype(np.float32)), x["step_v"], P, W, N, G, H, KV, d)
+        got = one.float().cpu().numpy().astype(np.float64)
+        assert np.isfinite(got).all()
+        err = np.abs(got - want).max()
+        assert err <= TOL, "max abs err %g" % err
+
+
+@pytest.mark.parametrize("interleaved", [False, True])
+@pytest.mark.parametrize("P,W,N,G,H,KV,d", [
+    (64, 4, 3, 2, 4, 4, 64),          # the tiny shape
+    (0, 5, 4, 2, 2, 1, 64),           # the layout of Fig. 2(b), empty prefix
+    (17, 0, 3, 4, 4, 2, 128),         # no window
+    (17, 4, 2, 0, 3, 1, 128),         # no candidates, N = 2
+    (5, 0, 2, 0, 1, 1, 128),          # a plain decode token
+    (333, 15, 5, 15, 4, 4, 128),      # several row tiles, ragged last one
+    (517, 3, 7, 3, 16, 2, 128),       # group of 8 heads per KV head
+    (129, 20, 5, 20, 2, 2, 64),       # head_dim 64, 24 positions
+    (1000, 28, 5, 3, 8, 8, 128),      # 32 positions: the most that fit beside the ring at head_dim 128
+])
+def test_small_shapes(P, W, N, G, H, KV, d, interleaved):
+    run_case(P + W + d, P, W, N, G, H, KV, d, interleaved)
+
+
+@pytest.mark.parametrize("shape", [wl.LLAMA2_7B, wl.LLAMA2_13B, wl.LLAMA2_70B], ids=lambda s: s.name)
+def test_paper_configs_full_size(shape):
+    s = shape
+    run_case(7, s.P, s.W, s.N, s.G, s.heads, s.kv_heads, s.head_dim, False)
+
+
+def test_long_ragged_sequence_takes_the_64_row_workgroups():
+    """A shape whose plain step uses 128-row workgroups (no LDS left for the tables): the rotating entry
+    point falls back to 64-row ones, so the output bits may differ from the two-pass path; the oracle decides."""
+    s = wl.ragged_shape(7, 15)
+    x, cos, sin = make(3, s.P, s.W, s.N, s.G, s.heads, s.kv_heads, s.head_dim)
+    dev = {k: binding.bf16_tensor(v) for k, v in x.items()}
+    dcos, dsin = torch.from_numpy(cos).cuda(), torch.from_numpy(sin).cuda()
+    binding.la_step_rope(None, dev["step_k"], dcos, dsin, s.P, s.W, s.N, s.G, s.heads, s.kv_heads, s.head_dim)
+    out = torch.full((s.T, s.heads, s.head_dim), float("nan"), dtype=torch.bfloat16, device="cuda")
+    binding.la_step_attention_rope(dev["q"], dev["k_cache"], dev["v_cache"], dev["step_k"], dev["step_v"], dcos, dsin,
+                                   s.P, s.W, s.N, s.G, s.heads, s.kv_heads, s.head_dim, out)
+    torch.cuda.synchronize()
+    rq, rk = orc.step_rope(orc.bf16_to_f64(x["q"]), orc.bf16_to_f64(x["step_k"]), cos, sin, s.P, s.W, s.N, s.G)
+    want = orc.step_attention(wl.f32_to_bf16_bits(rq.astype(np.float32)), x["k_cache"], x["v_cache"],
+                              wl.f32_to_bf16_bits(rk.astype(np.float32)), x["step_v"], s.P, s.W, s.N, s.G, s.heads,
+                              s.kv_heads, s.head_dim)
+    assert np.abs(out.float().cpu().numpy().astype(np.float64) - want).max() <= TOL
+
+
+@pytest.mark.parametrize("plan", ["2,2,0,4,64", "1,2,0,4,64", "2,4,2,4,64"])
+def test_other_decompositions(override, plan):
+    override("attn_plan", plan)
+    run_case(31, 700, 10, 5, 10, 8, 4, 128, False)
+
+
+def test_recompute_path(override):
+    override("force_recompute", "1")
+    run_case(32, 900, 15, 5, 15, 8, 8, 128, False)
+
+
+def test_limits_and_argument_errors():
+    # 34 positions (W = 30, N = 5) do not fit beside the ring at head_dim 128
+    P, W, N, G, H, KV, d = 300, 30, 5, 30, 8, 2, 128
+    x, cos, sin = make(1, P, W, N, G, H, KV, d)
+    dev = {k: binding.bf16_tensor(v) for k, v in x.items()}
+    dcos, dsin = torch.from_numpy(cos).cuda(), torch.from_numpy(sin).cuda()
+    out = torch.empty((1 + (W + G) * (N - 1), H, d), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(binding.LaError, match="positions"):
+        binding.la_step_attention_rope(dev["q"], dev["k_cache"], dev["v_cache"], dev["step_k"], dev["step_v"], dcos,
+                                       dsin, P, W, N, G, H, KV, d, out)
+    # tables that end before the step's furthest position
+    with pytest.raises(binding.LaError, match="positions"):
+        binding.la_step_attention_rope(dev["q"], dev["k_cache"], dev["v_cache"], dev["step_k"], dev["step_v"],
+                                       dcos[:P + 10].contiguous(), dsin[:P + 10].contiguous(), P, W, N, G, H, KV, d, out)
