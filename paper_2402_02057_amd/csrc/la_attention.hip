@@ -171,8 +171,26 @@ struct Cfg {
     static constexpr int DB = D / 32;                     // 32-wide blocks of head_dim
     // After the key-split merge a wave owns SPW of its tile's DB (tile, 32-column) slices.
     static constexpr int SPW = KS > 1 ? DB / KS : DB;
-    static constexpr int FRAG_FLOATS = DB * 16 * 64;      // one tile's accumulators
-    static constexpr int TILE_FLOATS = FRAG_FLOATS + 128; // + m and l per lane
+    // Key-split merge through LDS: a wave leaves the DB - SPW slices it does not own as bf16 (16
+    // values x 64 lanes x 2 bytes each, fragment order) followed by (m, l) of its rows per lane in fp32.
+    static constexpr int MERGE_WAVE_BYTES = KS > 1 ? (DB - SPW) * 2048 + 512 : 0;
+    static constexpr int MERGE_BYTES = NW * MERGE_WAVE_BYTES;
+    // The merge area lies in ring stages that the last iteration of the loop does not read (that
+    // iteration reads stages F .. F + CPI - 1, F a multiple of CPI): the longer of the runs below
+    // and above them.  FREE_STAGES is the shortest such run over all F; where the area (and the
+    // flag word behind it) fits into it, no barrier is needed between the loop and the merge.
+    static constexpr int free_stages()
+    {
+        int least = NSTAGE;
+        for (int f = 0; f + CPI <= NSTAGE; f += CPI) {
+            const int below = f, above = NSTAGE - CPI - f;
+            const int best = below > above ? below : above;
+            if (best < least) least = best;
+        }
+        return least;
+    }
+    static constexpr int FREE_STAGES = free_stages();
+    static constexpr bool MERGE_EARLY = KS > 1 && MERGE_BYTES + 16 <= FREE_STAGES * STAGE_BYTES;
     // a split's partial in global memory, per wave: its SPW slices as bf16 in fragment order
     // ([8 values][lane], 16 bytes per lane and access) followed by (m, l) of its rows per lane in fp32
     static constexpr int PART_ACC_BYTES = SPW * 16 * 64 * 2;
@@ -182,9 +200,7 @@ struct Cfg {
     static constexpr int Q_OFFSET = NSTAGE * STAGE_BYTES; // they sit behind the stage ring
     static constexpr int QLPW = Q_BYTES / 1024 / NW;      // Q loads per wave
     static constexpr int LDS_MAIN = NSTAGE * STAGE_BYTES + Q_BYTES;
-    static constexpr int LDS_MERGE = KS > 1 ? NW * TILE_FLOATS * 4 : 0;
-    static constexpr int ROLE_OFFSET = LDS_MERGE;  // one flag word, used once the ring is dead
-    static constexpr int LDS_BYTES = LDS_MAIN > LDS_MERGE + 16 ? LDS_MAIN : LDS_MERGE + 16;
+    static constexpr int LDS_BYTES = LDS_MAIN > MERGE_BYTES + 16 ? LDS_MAIN : MERGE_BYTES + 16;
     static_assert(KS >= KB ? KS % KB == 0 : KB % KS == 0, "key-split waves and blocks must divide");
     static_assert(KS == 1 || DB % KS == 0, "key-split waves must divide the head_dim blocks");
     static_assert(NSTAGE >= CPI, "an iteration's chunks must fit the ring");
@@ -225,29 +241,34 @@ __device__ __forceinline__ void store_slice(const AttnParams& p, int rb, int kvh
 }
 
 // Merge the KS key-split waves of a row tile, for the wave whose key index is MYKS.  Every
-// wave leaves the slices it does not own in LDS (fragment layout: [4 regs][lane], 16 bytes per
-// lane and access) with its (max, sum); after one barrier each wave sums its own SPW slices
-// over the KS states, in key order.  On return o[0 .. SPW-1] hold the merged slices
-// MYKS*SPW .. MYKS*SPW+SPW-1 and (m_run, l_run) the merged softmax state of the row.
+// wave leaves the slices it does not own in `area` (bf16, fragment layout: [2 halves][lane], 16
+// bytes per lane and access) with its (max, sum); after one barrier each wave sums its own SPW
+// slices over the KS states, in key order (its own state stays in fp32).  On return
+// o[0 .. SPW-1] hold the merged slices MYKS*SPW .. MYKS*SPW+SPW-1 and (m_run, l_run) the merged
+// softmax state of the row.
 template <class C, int KS, int MYKS>
-__device__ __forceinline__ void merge_key_splits(const AttnParams& p, unsigned char* lds, int rt, int lane,
-                                                 bool wave_active, f32x16 (&o)[C::DB], float& m_run,
-                                                 float& l_run, float scale_log2)
+__device__ __forceinline__ void merge_key_splits(unsigned char* area, int rt, int lane, bool wave_active,
+                                                 f32x16 (&o)[C::DB], float& m_run, float& l_run, float scale_log2)
 {
     constexpr int DB0 = MYKS * C::SPW;
-    float* mg = reinterpret_cast<float*>(lds) + rt * KS * C::TILE_FLOATS;  // this tile's states
+    constexpr int ML_OFFSET = (C::DB - C::SPW) * 2048;
+    unsigned char* const tile = area + rt * KS * C::MERGE_WAVE_BYTES;  // this tile's states
     if (wave_active) {
-        float* dst = mg + MYKS * C::TILE_FLOATS;
+        unsigned char* dst = tile + MYKS * C::MERGE_WAVE_BYTES;
+        int slot = 0;
 #pragma unroll
         for (int db = 0; db < C::DB; ++db) {
             if (db >= DB0 && db < DB0 + C::SPW) continue;  // stays in registers
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                const f32x4 v = {o[db][i4 * 4], o[db][i4 * 4 + 1], o[db][i4 * 4 + 2], o[db][i4 * 4 + 3]};
-                *reinterpret_cast<f32x4*>(dst + ((db * 4 + i4) * 64 + lane) * 4) = v;
+            for (int i8 = 0; i8 < 2; ++i8) {
+                bf16x8 v;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = (__bf16)o[db][i8 * 8 + e];
+                *reinterpret_cast<bf16x8*>(dst + ((slot * 2 + i8) * 64 + lane) * 16) = v;
             }
+            ++slot;
         }
-        *reinterpret_cast<f32x2*>(dst + C::FRAG_FLOATS + lane * 2) = f32x2{m_run, l_run};
+        *reinterpret_cast<f32x2*>(dst + ML_OFFSET + lane * 8) = f32x2{m_run, l_run};
     }
     LA_STAMP(2);
     __syncthreads();
@@ -257,19 +278,20 @@ __device__ __forceinline__ void merge_key_splits(const AttnParams& p, unsigned c
 #pragma unroll
     for (int k = 0; k < KS; ++k)
         ml[k] = k == MYKS ? f32x2{m_run, l_run}
-                          : *reinterpret_cast<const f32x2*>(mg + k * C::TILE_FLOATS + C::FRAG_FLOATS + lane * 2);
-    f32x4 v[C::SPW][KS][4];
+                          : *reinterpret_cast<const f32x2*>(tile + k * C::MERGE_WAVE_BYTES + ML_OFFSET + lane * 8);
+    bf16x8 v[C::SPW][KS][2];
 #pragma unroll
     for (int u = 0; u < C::SPW; ++u)
 #pragma unroll
-        for (int k = 0; k < KS; ++k)
+        for (int k = 0; k < KS; ++k) {
+            if (k == MYKS) continue;
+            // wave k stored its slices in order, skipping its own k*SPW .. k*SPW+SPW-1
+            const int slot = DB0 + u < k * C::SPW ? DB0 + u : DB0 + u - C::SPW;
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4)
-                v[u][k][i4] = k == MYKS
-                                  ? f32x4{o[DB0 + u][i4 * 4], o[DB0 + u][i4 * 4 + 1], o[DB0 + u][i4 * 4 + 2],
-                                          o[DB0 + u][i4 * 4 + 3]}
-                                  : *reinterpret_cast<const f32x4*>(
-                                        mg + k * C::TILE_FLOATS + (((DB0 + u) * 4 + i4) * 64 + lane) * 4);
+            for (int i8 = 0; i8 < 2; ++i8)
+                v[u][k][i8] = *reinterpret_cast<const bf16x8*>(tile + k * C::MERGE_WAVE_BYTES +
+                                                               ((slot * 2 + i8) * 64 + lane) * 16);
+        }
     float m_all = ml[0][0];
 #pragma unroll
     for (int k = 1; k < KS; ++k) m_all = fmaxf(m_all, ml[k][0]);
@@ -286,14 +308,15 @@ __device__ __forceinline__ void merge_key_splits(const AttnParams& p, unsigned c
 #pragma unroll
     for (int u = 0; u < C::SPW; ++u)
 #pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4)
+        for (int i = 0; i < 16; ++i) {
+            float acc = 0.0f;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float acc = v[u][0][i4][e] * a[0];
-#pragma unroll
-                for (int k = 1; k < KS; ++k) acc = __builtin_fmaf(v[u][k][i4][e], a[k], acc);
-                o[u][i4 * 4 + e] = acc;
+            for (int k = 0; k < KS; ++k) {
+                const float x = k == MYKS ? o[DB0 + u][i] : (float)v[u][k][i >> 3][i & 7];
+                acc = k == 0 ? x * a[0] : __builtin_fmaf(x, a[k], acc);
             }
+            o[u][i] = acc;
+        }
 }
 
 // PAGED: the prefix cache is reached through a block table (a kernel of its own: the walk then
@@ -588,7 +611,7 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
     const int cw = KS > C::KB ? (ks / C::KB + rt) % C::CPI : 0;
     // which waves ask for the recompute pass (a word of LDS, addressed as such)
     typedef __attribute__((address_space(3))) unsigned lds_u32;
-    volatile lds_u32* const s_recompute = (volatile lds_u32*)(lds + C::ROLE_OFFSET);
+    volatile lds_u32* s_recompute = nullptr;  // (set once a pass knows where its merge area lies)
     unsigned store_mask = ~0u;  // recompute pass: which waves write their slices
     // the wave's counter of this split group
     unsigned* const my_ticket = p.XS > 1 ? p.tickets + ((size_t)unit * C::NW + wave) * kTicketStride : nullptr;
@@ -855,8 +878,20 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
         // the two half-waves of a row hold the sums over their own keys
         l_run += __shfl_xor(l_run, 32, 64);
 
-        __syncthreads();  // all stages consumed: LDS is reused below
+        // ---- where the merge leaves its data: ring stages that nobody reads any more.  The
+        //      waves are at most one iteration apart, so once a wave is past the loop the others
+        //      read the last iteration's stages at most: anywhere else may be written at once.
+        unsigned char* merge_area = lds;
+        if constexpr (C::MERGE_EARLY) {
+            const int iters = (n_my + C::CPI - 1) / C::CPI;
+            const int first = ((iters - 1) * C::CPI) % NSTAGE;       // stages first .. first + CPI - 1 are live
+            const int below = first, above = NSTAGE - C::CPI - first;
+            merge_area = lds + (above >= below ? (first + C::CPI) * C::STAGE_BYTES : 0);
+        } else {
+            __syncthreads();  // all stages consumed: LDS is reused below
+        }
         LA_STAMP(16);
+        s_recompute = (volatile lds_u32*)(merge_area + C::MERGE_BYTES);
         if (tid == 0) *s_recompute = 0u;
         if (KS == 1) __syncthreads();  // (with key-split waves the merge's barrier does this)
 
@@ -864,10 +899,10 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
         //      on it keeps every register index a compile-time constant
         if (KS > 1) {
             const float sc = sl2;
-            if (ks == 0) merge_key_splits<C, KS, 0>(p, lds, rt, lane, wave_active, o, m_run, l_run, sc);
-            if (KS > 1 && ks == 1) merge_key_splits<C, KS, (KS > 1 ? 1 : 0)>(p, lds, rt, lane, wave_active, o, m_run, l_run, sc);
-            if (KS > 2 && ks == 2) merge_key_splits<C, KS, (KS > 2 ? 2 : 0)>(p, lds, rt, lane, wave_active, o, m_run, l_run, sc);
-            if (KS > 3 && ks == 3) merge_key_splits<C, KS, (KS > 3 ? 3 : 0)>(p, lds, rt, lane, wave_active, o, m_run, l_run, sc);
+            if (ks == 0) merge_key_splits<C, KS, 0>(merge_area, rt, lane, wave_active, o, m_run, l_run, sc);
+            if (KS > 1 && ks == 1) merge_key_splits<C, KS, (KS > 1 ? 1 : 0)>(merge_area, rt, lane, wave_active, o, m_run, l_run, sc);
+            if (KS > 2 && ks == 2) merge_key_splits<C, KS, (KS > 2 ? 2 : 0)>(merge_area, rt, lane, wave_active, o, m_run, l_run, sc);
+            if (KS > 3 && ks == 3) merge_key_splits<C, KS, (KS > 3 ? 3 : 0)>(merge_area, rt, lane, wave_active, o, m_run, l_run, sc);
             static_assert(KS <= 4, "one branch per key index");
         }
         LA_STAMP(4);
@@ -889,7 +924,9 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
                         bf16x8 v;
 #pragma unroll
                         for (int e = 0; e < 8; ++e) v[e] = (__bf16)o[u][i8 * 8 + e];
-                        *reinterpret_cast<bf16x8*>(dst + ((u * 2 + i8) * 64 + lane) * 16) = v;
+                        // (streaming stores: the partials are read once, by one other wave, and measured
+                        // faster this way than with the default cache policy)
+                        __builtin_nontemporal_store(v, reinterpret_cast<bf16x8*>(dst + ((u * 2 + i8) * 64 + lane) * 16));
                     }
                 *reinterpret_cast<f32x2*>(dst + C::PART_ACC_BYTES + lane * 8) = f32x2{m_run, l_run};
             }
@@ -977,7 +1014,7 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
             //      coherent with each other inside a kernel, cannot trust the partials: the whole
             //      workgroup then recomputes its rows over every chunk from the read-only inputs (which
             //      are always coherent), and the waves that asked for it write their slices directly
-            if (role == 2 && lane == 0) atomicOr((unsigned*)(lds + C::ROLE_OFFSET), 1u << wave);
+            if (role == 2 && lane == 0) atomicOr(reinterpret_cast<unsigned*>(merge_area + C::MERGE_BYTES), 1u << wave);
         }
         __syncthreads();
         store_mask = (unsigned)__builtin_amdgcn_readfirstlane((int)*s_recompute);

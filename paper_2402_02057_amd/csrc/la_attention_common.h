@@ -148,6 +148,7 @@ __device__ __forceinline__ void dma16_base(const void* base, unsigned lane_off, 
                  : "memory");
 }
 
+
 // The same with 4 bytes per lane (256 bytes per wave).
 __device__ __forceinline__ void dma4_base(const void* base, unsigned lane_off, unsigned lds_base)
 {
