@@ -26,18 +26,26 @@
 // (Algorithm 2's conditioning sets read as index ranges), turned into one 32-bit word per
 // (row, key block) from integer ranges in registers; no mask tensor exists anywhere.
 //
-// Split combine, in the same launch.  With XS > 1 each workgroup stores its unnormalised fp32
-// accumulator and (max, sum) per row, waits for the stores to reach the L2, and takes a
-// ticket; the workgroup that arrives last merges all XS partials in index order (so results
-// do not depend on arrival order), normalises and writes bf16.  The L2 of one XCD is
+// Split combine, in the same launch, wave by wave.  With XS > 1 each wave stores the slice(s)
+// of the unnormalised accumulator it owns after the key-split merge, rounded to bf16, and
+// (max, sum) per row, waits for the stores to be acknowledged by the L2, and takes a ticket of
+// its own; the wave that arrives last in its group merges all XS partials in index order (so
+// results do not depend on arrival order), normalises and writes bf16.  The L2 of one XCD is
 // coherent for all its compute units, but the eight L2s are not coherent with each other
 // inside a kernel, and an agent-scope fence (L2 write-back + invalidate) costs tens of
 // microseconds here.  So the workgroups of a split group are laid out on one XCD (workgroup
 // ids go round-robin over XCDs) and the ticket also carries the XCD id each member read
 // from the hardware register: if all ids agree the partials are read straight from the shared
-// L2; if not, the last workgroup ignores the partials and recomputes its rows over all
-// chunks from the read-only inputs.  Either way the result is exact; tickets return to zero,
-// so no memset is needed between calls.
+// L2; if not, the last wave ignores the partials and its workgroup recomputes its rows over
+// all chunks from the read-only inputs and writes them directly.  The two paths agree to the
+// bf16 rounding of the partials, not bit for bit (the recomputed accumulator is never rounded),
+// so a result can differ in the last place with where the workgroups happened to run; both are
+// within the tolerance of the step.  Tickets return to zero, so no memset is needed between
+// calls.
+//
+// Variants of the same kernel (template parameters): a paged cache (block table), a subset of
+// the step's rows, keys and values as 8-bit floats with a scale per KV head (converted exactly
+// to bf16 in front of the MFMA), and query rows rotated on the way in (rotary embedding).
 #include <stdlib.h>
 
 #include <mutex>
