@@ -184,21 +184,30 @@ struct Cfg {
     static constexpr int MERGE_WAVE_BYTES = KS > 1 ? (DB - SPW) * 2048 + 512 : 0;
     static constexpr int MERGE_BYTES = NW * MERGE_WAVE_BYTES;
     // The merge area lies in ring stages that the last iteration of the loop does not read (that
-    // iteration reads stages F .. F + CPI - 1, F a multiple of CPI): the longer of the runs below
-    // and above them.  FREE_STAGES is the shortest such run over all F; where the area (and the
-    // flag word behind it) fits into it, no barrier is needed between the loop and the merge.
+    // iteration reads stages F .. F + CPI - 1 modulo NSTAGE): the longer of the runs below and
+    // above them, or the run between them when they wrap around.  FREE_STAGES is the shortest
+    // such run over all F; where the area (and the flag word behind it) fits into it, no barrier
+    // is needed between the loop and the merge.
     static constexpr int free_stages()
     {
         int least = NSTAGE;
-        for (int f = 0; f + CPI <= NSTAGE; f += CPI) {
-            const int below = f, above = NSTAGE - CPI - f;
-            const int best = below > above ? below : above;
+        for (int k = 0; k < NSTAGE; ++k) {
+            const int f = (k * CPI) % NSTAGE;  // the first live stage is a multiple of CPI modulo NSTAGE
+            int best = 0;
+            if (f + CPI <= NSTAGE) {
+                const int below = f, above = NSTAGE - CPI - f;
+                best = below > above ? below : above;
+            } else {
+                best = NSTAGE - CPI;  // the live stages wrap around: everything between them is free
+            }
             if (best < least) least = best;
         }
         return least;
     }
     static constexpr int FREE_STAGES = free_stages();
     static constexpr bool MERGE_EARLY = KS > 1 && MERGE_BYTES + 16 <= FREE_STAGES * STAGE_BYTES;
+    static_assert(!(D == 128 && RT == 2 && KS == 4 && NSTAGE == 4 && KVB == 2) || MERGE_EARLY,
+                  "the plan of the benchmark shapes merges without a barrier after the loop");
     // a split's partial in global memory, per wave: its SPW slices as bf16 in fragment order
     // ([8 values][lane], 16 bytes per lane and access) followed by (m, l) of its rows per lane in fp32
     static constexpr int PART_ACC_BYTES = SPW * 16 * 64 * 2;
@@ -481,7 +490,7 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
             iss_rows = n_T;
             iss_stride = step_stride;
             iss_page_left = kNoPage;
-        } else if (--iss_page_left == 0) {  // paged cache: the next chunk starts the next page
+        } else if (PAGED && --iss_page_left == 0) {  // paged cache: the next chunk starts the next page
             if (iss_q == 0) refill_entries();  // (only when more chunks are requested in a row than the queue holds)
             ++iss_page;
             const size_t page_off = page_offset(iss_ent0);
@@ -721,6 +730,11 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
                 }
                 --slots_left;
             };
+            // With two chunks per iteration the first refill goes out right here: at long prefixes an
+            // iteration waits for the data requested one iteration earlier, so every request that
+            // leaves sooner shortens it (70B shape -5 %, 13B -2.5 %); the second follows the first
+            // batch of MFMAs (both at once measured slower: the requests stall the wave).
+            if (slots_left > 1) issue_slot();
             bool compute = done + cw < n_my && wave_active;
             if (compute) {
             const bool is_step = cons_c >= n_prefix_chunks;
@@ -892,9 +906,13 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
         unsigned char* merge_area = lds;
         if constexpr (C::MERGE_EARLY) {
             const int iters = (n_my + C::CPI - 1) / C::CPI;
-            const int first = ((iters - 1) * C::CPI) % NSTAGE;       // stages first .. first + CPI - 1 are live
-            const int below = first, above = NSTAGE - C::CPI - first;
-            merge_area = lds + (above >= below ? (first + C::CPI) * C::STAGE_BYTES : 0);
+            const int first = ((iters - 1) * C::CPI) % NSTAGE;       // stages first .. first + CPI - 1 (mod NSTAGE) are live
+            if (first + C::CPI <= NSTAGE) {
+                const int below = first, above = NSTAGE - C::CPI - first;
+                merge_area = lds + (above >= below ? (first + C::CPI) * C::STAGE_BYTES : 0);
+            } else {
+                merge_area = lds + (first + C::CPI - NSTAGE) * C::STAGE_BYTES;
+            }
         } else {
             __syncthreads();  // all stages consumed: LDS is reused below
         }
