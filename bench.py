@@ -81,12 +81,14 @@ def time_calls(torch, np, fn, calls, reps, use_graph):
     run()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     ms = []
+    replays = 4 if use_graph else 1   # (one replay alone also carries the start-up of a graph launch)
     for _ in range(reps):
         e0.record()
-        run()
+        for _ in range(replays):
+            run()
         e1.record()
         torch.cuda.synchronize()
-        ms.append(e0.elapsed_time(e1) / calls)
+        ms.append(e0.elapsed_time(e1) / (calls * replays))
     return float(np.median(ms)) * 1e3
 
 
@@ -363,9 +365,13 @@ def main():
         run_vs = verify_step
         run_sm = verify_sample
         ver_calls = 1
+    # (several replays between the two events, as in the timed loop above: one replay alone also
+    # carries the start-up of a graph launch, 0.3 us per kernel at 32 kernels per graph)
+    attn_replays = 4 if use_graph else 1
     for _ in range(reps):
         e[0].record()
-        run_attn()
+        for _ in range(attn_replays):
+            run_attn()
         e[1].record()
         run_ver()
         e[2].record()
@@ -374,7 +380,7 @@ def main():
         run_sm()
         e[4].record()
         torch.cuda.synchronize()
-        attn_ms.append(e[0].elapsed_time(e[1]))
+        attn_ms.append(e[0].elapsed_time(e[1]) / attn_replays)
         ver_ms.append(e[1].elapsed_time(e[2]) / ver_calls)
         vs_ms.append(e[2].elapsed_time(e[3]) / ver_calls)
         sm_ms.append(e[3].elapsed_time(e[4]) / ver_calls)
