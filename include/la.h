@@ -177,6 +177,8 @@ la_status la_step_attention_cap(const void* q, const void* k_cache, const void* 
  *   best, n_out       int32 [1] each, as written by la_verify_step (values outside -1..G-1
  *                     and 1..N are clamped, never followed out of bounds)
  *   head_dim: any multiple of 8 up to 1024.
+ * Rows are moved as bytes (2 * head_dim of them) and never interpreted: for a cache of 8-bit
+ * elements (la_step_attention_fp8kv) pass head_dim / 2, so that a row is head_dim bytes.
  */
 la_status la_kv_commit(void* k_cache, void* v_cache, long long capacity, const void* step_k,
                        const void* step_v, int P, int W, int N, int G, int kv_heads, int head_dim,

@@ -179,3 +179,39 @@ def test_argument_errors():
                                      dev["v_scale"].data_ptr(), s.P, s.W, s.N, s.G, s.heads, s.kv_heads, 96,
                                      out.data_ptr(), None)
     assert rc == binding.LA_EUNSUPPORTED
+
+
+def test_committed_rows_are_read_back_as_the_step_saw_them():
+    """A step over a quantised cache, the append of its accepted rows (la_kv_commit moves bytes: rows of
+    head_dim bytes are head_dim / 2 sixteen-bit elements to it), and the next step over the longer
+    prefix: the appended cache equals the oracle's append bit for bit, and the next step equals the
+    oracle's over that cache."""
+    P, W, N, G, H, KV, d = 200, 4, 3, 2, 4, 2, 128
+    T = 1 + (W + G) * (N - 1)
+    x = rand_inputs(77, P, W, N, G, H, KV, d)
+    cap = P + N
+    best, n_out = 1, 3                      # candidate 1 accepted in full: rows 0, and its two tokens
+    kc = torch.zeros((KV, cap, d), dtype=torch.uint8, device="cuda")
+    vc = torch.zeros_like(kc)
+    kc[:, :P], vc[:, :P] = torch.from_numpy(x["k_cache"]).cuda(), torch.from_numpy(x["v_cache"]).cuda()
+    sk, sv = torch.from_numpy(x["step_k"]).cuda(), torch.from_numpy(x["step_v"]).cuda()
+    as16 = lambda t: t.view(torch.bfloat16)
+    binding.la_kv_commit(as16(kc), as16(vc), as16(sk), as16(sv), P, W, N, G, KV, d // 2,
+                         torch.tensor([best], dtype=torch.int32, device="cuda"),
+                         torch.tensor([n_out], dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    ok = np.zeros((KV, cap, d // 2), np.uint16)
+    ov = np.zeros_like(ok)
+    ok[:, :P], ov[:, :P] = x["k_cache"].view(np.uint16), x["v_cache"].view(np.uint16)
+    orc.kv_commit(ok, ov, x["step_k"].view(np.uint16), x["step_v"].view(np.uint16), P, W, N, G, best, n_out)
+    np.testing.assert_array_equal(kc.cpu().numpy().view(np.uint16), ok)
+    np.testing.assert_array_equal(vc.cpu().numpy().view(np.uint16), ov)
+    # the appended keys are step rows 0, 1 + W(N-1) + best(N-1), ... as codes, unchanged
+    rows = [0] + [1 + W * (N - 1) + best * (N - 1) + i for i in range(n_out - 1)]
+    np.testing.assert_array_equal(kc.cpu().numpy()[:, P:P + n_out], x["step_k"][rows].transpose(1, 0, 2))
+    # next step over the longer prefix (a fresh draw for its own rows, the same scales)
+    P2 = P + n_out
+    y = rand_inputs(78, P2, W, N, G, H, KV, d)
+    y["k_cache"], y["v_cache"] = kc.cpu().numpy()[:, :P2].copy(), vc.cpu().numpy()[:, :P2].copy()
+    y["k_scale"], y["v_scale"] = x["k_scale"], x["v_scale"]
+    check(y, P2, W, N, G, H, KV, d, "after the append")
