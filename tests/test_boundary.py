@@ -82,6 +82,38 @@ def test_cache_forms_report_argument_errors_without_a_gpu(lib):
     assert lib.la_kv_commit_paged(A, A, A, 48, 4, A, A, 0, 1, 3, 1, 4, 128, A, A, None) == -2
 
 
+def test_quantised_and_rotating_forms_report_argument_errors_without_a_gpu(lib):
+    A = 4096
+    # 8-bit cache: scales are required and must be aligned
+    rc = lib.la_step_attention_fp8kv(A, A, A, A, A, None, A, 10, 1, 3, 1, 4, 4, 128, A, None)
+    assert rc == -1 and b"k_scale" in lib.la_last_error()
+    rc = lib.la_step_attention_fp8kv(A, A, A, A, A, A, A + 2, 10, 1, 3, 1, 4, 4, 128, A, None)
+    assert rc == -1 and b"aligned" in lib.la_last_error()
+    rc = lib.la_step_attention_fp8kv(A, A, A, A, A, A, A, 10, 1, 1, 1, 4, 4, 128, A, None)
+    assert rc == -1 and b"N >= 2" in lib.la_last_error()
+    rc = lib.la_step_attention_fp8kv(A, A, A, A, A, A, A, 10, 1, 3, 1, 4, 4, 96, A, None)
+    assert rc == -2 and b"head_dim" in lib.la_last_error()
+    # rotation inside the kernel: tables present, aligned, and long enough for the step's furthest position
+    args = (10, 3, 4, 2, 4, 4, 128, A, None)            # P, W, N, G, heads, kv_heads, head_dim, out, stream
+    rc = lib.la_step_attention_rope(A, A, A, A, A, None, A, 64, 0, *args)
+    assert rc == -1 and b"cos" in lib.la_last_error()
+    rc = lib.la_step_attention_rope(A, A, A, A, A, A + 4, A, 64, 0, *args)
+    assert rc == -1 and b"aligned" in lib.la_last_error()
+    rc = lib.la_step_attention_rope(A, A, A, A, A, A, A, 15, 0, *args)       # reaches 10 + 3 + 4 - 2 = 15
+    assert rc == -1 and b"positions" in lib.la_last_error()
+    rc = lib.la_step_attention_rope(A, A, A, A, A, A, A, 16, 0, 10, 3, 1, 2, 4, 4, 128, A, None)
+    assert rc == -1 and b"N >= 2" in lib.la_last_error()
+    rc = lib.la_step_attention_rope(A, A, A, None, A, A, A, 16, 0, *args)
+    assert rc == -1 and b"null" in lib.la_last_error()
+    # the rope pass takes a null q (keys alone) but not null keys or tables
+    rc = lib.la_step_rope(None, None, A, A, 64, 10, 3, 4, 2, 4, 4, 128, 0, None)
+    assert rc == -1 and b"null" in lib.la_last_error()
+    # testing hooks: unknown keys and malformed plans are refused
+    assert lib.la_debug_override(b"no_such_key", b"1") == -1
+    assert lib.la_debug_override(b"attn_plan", b"2,4") == -1
+    assert lib.la_debug_override(b"attn_plan", None) == 0
+
+
 def test_batch_reports_argument_errors_without_a_gpu(lib):
     import ctypes
     A = 4096
