@@ -63,10 +63,10 @@ def test_batch_matches_the_oracle_and_the_single_calls(prefixes, W, N, G, H, KV,
 
 
 @pytest.mark.timeout(600)
-@pytest.mark.parametrize("W", [5, 30])
+@pytest.mark.parametrize("W", list(wl.RAGGED_W))
 def test_ragged_sweep_every_sequence_against_the_oracle(W):
-    """The narrowest and the widest window of the ragged sweep, one launch over all eight sequences, the
-    oracle on each of them (the other widths are covered on the shortest and the longest sequence)."""
+    """Every point of the ragged sweep (8 sequences x 5 window widths): one launch over all eight
+    sequences per width, the oracle on each of them."""
     prefixes = list(wl.ragged_prefix_lengths())
     print("case", dict(prefixes=prefixes, W=W), flush=True)
     run_batch(prefixes, W, 5, W, 32, 8, 128, seed=40 + W, check_oracle=set(range(len(prefixes))))
