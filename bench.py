@@ -454,6 +454,20 @@ def main():
                                        rope_sin, P, s.W, s.N, s.G, H, KV, d, outs_rot[i])
     outs_rot = [torch.empty((T, H, d), dtype=torch.bfloat16, device="cuda") for _ in range(L)]
     attention_rope_us = time_calls(torch, np, attention_rope_layer, L, reps, use_graph)
+    # and with nothing rotated in memory: the attention kernel turns the step keys it stages as well,
+    # the append turns the few key rows it copies (la_kv_commit_rope)
+    rot2_it = iter(range(1 << 30))
+
+    def attention_rope_all_layer():
+        i = next(rot2_it) % L
+        x = layers[i]
+        binding.la_step_attention_rope(x["q"], x["k_cache"], x["v_cache"], x["step_k"], x["step_v"], rope_cos,
+                                       rope_sin, P, s.W, s.N, s.G, H, KV, d, outs_rot[i], rotate_keys=True)
+    attention_rope_all_us = time_calls(torch, np, attention_rope_all_layer, L, reps, use_graph)
+    kc_rot, vc_rot = kc_cap.clone(), vc_cap.clone()     # (caches of its own: kc_cap is compared with the oracle)
+    kv_commit_rope_us = time_calls(torch, np, lambda: binding.la_kv_commit_rope(
+        kc_rot, vc_rot, layers[0]["step_k"], layers[0]["step_v"], rope_cos, rope_sin, P, s.W, s.N, s.G, KV, d,
+        vs_out[2], vs_out[1]), 32, reps, use_graph)
 
     # the ends of eight sequences' steps in ONE launch (la_verify_step_batch), timed on its own:
     # sequence 0 is the step above, the others are further seeded draws of the same shape
@@ -696,7 +710,10 @@ def main():
         "rope": {"us": rope_us, "algorithmic_bytes": 2 * (T * H * d + T * KV * d) * 2,
                  "keys_only_us": rope_keys_us, "attention_with_q_rotation_us": attention_rope_us,
                  "per_layer_two_passes_us": attn_us + rope_us,
-                 "per_layer_q_in_attention_us": attention_rope_us + rope_keys_us},
+                 "per_layer_q_in_attention_us": attention_rope_us + rope_keys_us,
+                 "attention_with_q_and_key_rotation_us": attention_rope_all_us,
+                 "per_layer_all_in_attention_us": attention_rope_all_us,
+                 "kv_commit_rope_us": kv_commit_rope_us},
         "kv_commit": {"us": kv_commit_us, "rows": n_commit, "algorithmic_bytes": kv_commit_bytes},
         "kv_commit_batch": {"layers_per_launch": L, "us_per_launch": kv_commit_batch_us,
                             "us_per_layer": kv_commit_batch_us / L},

@@ -129,13 +129,18 @@ la_status la_step_attention_fp8kv(const void* q, const void* k_cache, const void
                                   int N, int G, int heads, int kv_heads, int head_dim, void* out, void* stream);
 
 /*
- * la_step_attention with the rotary position embedding of the QUERY rows done inside the
- * kernel: q arrives as the projection left it and is not modified; the kernel stages its rows
- * in on-chip memory, turns them by the positions of Fig. 2(b) (row r sits at P + its digit)
- * with the arithmetic of la_step_rope, and goes on as la_step_attention does.  The result has
- * the bits of la_step_rope on q followed by la_step_attention.  The step's keys must already
- * be rotated (la_step_rope with q == NULL rotates step_k alone; the cache needs the rotated
- * keys anyway, see la_kv_commit).
+ * la_step_attention with the rotary position embedding done inside the kernel: q arrives as
+ * the projection left it and is not modified; the kernel stages its rows in on-chip memory,
+ * turns them by the positions of Fig. 2(b) (row r sits at P + its digit) with the arithmetic
+ * of la_step_rope, and goes on as la_step_attention does.
+ *
+ *   rotate_keys == 0: step_k is already rotated (la_step_rope with q == NULL rotates it alone).
+ *     The result has the bits of la_step_rope on q followed by la_step_attention.
+ *   rotate_keys != 0: step_k arrives unrotated as well and is not modified; every workgroup
+ *     turns the step keys it has staged before it multiplies with them.  The result has the
+ *     bits of la_step_rope on q and step_k followed by la_step_attention, with no pass over
+ *     the step's tensors at all.  Append the accepted rows with la_kv_commit_rope then, which
+ *     turns the few key rows it copies.
  *
  *   cos, sin     fp32 [max_pos][head_dim/2] on the device, 16-byte aligned
  *   max_pos      positions the tables hold; the step reaches P + max(W + N - 2, N - 1)
@@ -143,12 +148,12 @@ la_status la_step_attention_fp8kv(const void* q, const void* k_cache, const void
  * Everything else as la_step_attention.  Limit: the table rows of the step's positions are
  * staged beside the key/value ring; with head_dim 128 there is room for 32 positions
  * (W + N - 2 <= 31) in the common decomposition.  A step that needs more is refused with
- * LA_EUNSUPPORTED: rotate q with la_step_rope then.
+ * LA_EUNSUPPORTED: rotate with la_step_rope then.
  */
 la_status la_step_attention_rope(const void* q, const void* k_cache, const void* v_cache, const void* step_k,
                                  const void* step_v, const float* cos, const float* sin, int max_pos, int interleaved,
-                                 int P, int W, int N, int G, int heads, int kv_heads, int head_dim, void* out,
-                                 void* stream);
+                                 int rotate_keys, int P, int W, int N, int G, int heads, int kv_heads, int head_dim,
+                                 void* out, void* stream);
 
 /*
  * The same step over a cache allocated for more keys than it holds, as a decoding loop keeps
@@ -183,6 +188,22 @@ la_status la_step_attention_cap(const void* q, const void* k_cache, const void* 
 la_status la_kv_commit(void* k_cache, void* v_cache, long long capacity, const void* step_k,
                        const void* step_v, int P, int W, int N, int G, int kv_heads, int head_dim,
                        const int* best, const int* n_out, void* stream);
+
+/*
+ * la_kv_commit for a step whose keys were left unrotated in memory (la_step_attention_rope
+ * with rotate_keys != 0): the key row appended as cache row P + i is turned by position P + i,
+ * the position its step evaluated it at (Sec. 3.3; Fig. 2(b): the current token at P, token
+ * i - 1 of a candidate at P + i), with the arithmetic of la_step_rope, so the cache holds the
+ * bits that la_step_rope followed by la_kv_commit would have left.  Values are copied.
+ *
+ *   cos, sin, max_pos, interleaved  as la_step_rope; the append reaches position P + N - 1
+ *   head_dim: a multiple of 16 up to 1024.  Contiguous bf16 caches only.
+ * Everything else as la_kv_commit.
+ */
+la_status la_kv_commit_rope(void* k_cache, void* v_cache, long long capacity, const void* step_k,
+                            const void* step_v, const float* cos, const float* sin, int max_pos, int interleaved,
+                            int P, int W, int N, int G, int kv_heads, int head_dim, const int* best,
+                            const int* n_out, void* stream);
 
 /*
  * The same step and the same append over a PAGED cache, as a serving system keeps it:

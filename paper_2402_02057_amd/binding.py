@@ -72,13 +72,15 @@ def load():
     lib.la_step_attention_noalloc.restype = i
     lib.la_step_attention_fp8kv.argtypes = [p, p, p, p, p, p, p, i, i, i, i, i, i, i, p, p]
     lib.la_step_attention_fp8kv.restype = i
-    lib.la_step_attention_rope.argtypes = [p, p, p, p, p, p, p, i, i, i, i, i, i, i, i, i, p, p]
+    lib.la_step_attention_rope.argtypes = [p, p, p, p, p, p, p, i, i, i, i, i, i, i, i, i, i, p, p]
     lib.la_step_attention_rope.restype = i
     ll = ctypes.c_longlong
     lib.la_step_attention_cap.argtypes = [p, p, p, ll, p, p, i, i, i, i, i, i, i, p, p]
     lib.la_step_attention_cap.restype = i
     lib.la_kv_commit.argtypes = [p, p, ll, p, p, i, i, i, i, i, i, p, p, p]
     lib.la_kv_commit.restype = i
+    lib.la_kv_commit_rope.argtypes = [p, p, ll, p, p, p, p, i, i, i, i, i, i, i, i, p, p, p]
+    lib.la_kv_commit_rope.restype = i
     lib.la_verify_sample_batch.argtypes = [p, i, i, i, i, p]
     lib.la_verify_sample_batch.restype = i
     lib.la_step_rope.argtypes = [p, p, p, p, i, i, i, i, i, i, i, i, i, p]
@@ -123,7 +125,7 @@ def load():
     return lib
 
 
-EXPORTS = ("la_step_rope", "la_step_attention", "la_step_attention_noalloc", "la_step_attention_fp8kv", "la_step_attention_rope", "la_step_attention_cap", "la_kv_commit", "la_step_attention_paged", "la_kv_commit_paged", "la_kv_commit_batch", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_step_batch", "la_verify_sample", "la_verify_sample_batch", "la_step_attention_workspace_bytes", "la_shutdown", "la_select_workspace", "la_debug_override", "la_probe_stream_read", "la_probe_mfma",
+EXPORTS = ("la_step_rope", "la_step_attention", "la_step_attention_noalloc", "la_step_attention_fp8kv", "la_step_attention_rope", "la_step_attention_cap", "la_kv_commit", "la_kv_commit_rope", "la_step_attention_paged", "la_kv_commit_paged", "la_kv_commit_batch", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_step_batch", "la_verify_sample", "la_verify_sample_batch", "la_step_attention_workspace_bytes", "la_shutdown", "la_select_workspace", "la_debug_override", "la_probe_stream_read", "la_probe_mfma",
            "la_last_error", "la_version")
 
 
@@ -247,9 +249,11 @@ def la_step_rope(q, step_k, cos, sin, P, W, N, G, heads, kv_heads, head_dim, int
 
 
 def la_step_attention_rope(q, k_cache, v_cache, step_k, step_v, cos, sin, P, W, N, G, heads, kv_heads, head_dim, out,
-                           interleaved=False, stream=None):
-    """la_step_attention with q rotated inside the kernel (q is left as it is; step_k must be rotated
-    already, e.g. by la_step_rope(None, step_k, ...)); asynchronous."""
+                           interleaved=False, stream=None, rotate_keys=False):
+    """la_step_attention with q rotated inside the kernel (q is left as it is).  rotate_keys False:
+    step_k must be rotated already, e.g. by la_step_rope(None, step_k, ...); True: step_k comes
+    unrotated too and the kernel turns the step keys it stages (append with la_kv_commit_rope then);
+    asynchronous."""
     T = 1 + (W + G) * (N - 1)
     bf = torch.bfloat16
     max_pos = int(cos.shape[0])
@@ -261,7 +265,7 @@ def la_step_attention_rope(q, k_cache, v_cache, step_k, step_v, cos, sin, P, W, 
         _ptr(step_v, bf, (T, kv_heads, head_dim), "step_v"),
         _ptr(cos, torch.float32, (max_pos, head_dim // 2), "cos"),
         _ptr(sin, torch.float32, (max_pos, head_dim // 2), "sin"),
-        max_pos, 1 if interleaved else 0, P, W, N, G, heads, kv_heads, head_dim,
+        max_pos, 1 if interleaved else 0, 1 if rotate_keys else 0, P, W, N, G, heads, kv_heads, head_dim,
         _ptr(out, bf, (T, heads, head_dim), "out"), _stream(stream))
     _check(rc)
     return out
@@ -279,6 +283,26 @@ def la_kv_commit(k_cache, v_cache, step_k, step_v, P, W, N, G, kv_heads, head_di
         _ptr(step_k, bf, (T, kv_heads, head_dim), "step_k"),
         _ptr(step_v, bf, (T, kv_heads, head_dim), "step_v"),
         P, W, N, G, kv_heads, head_dim,
+        _ptr(best, torch.int32, (1,), "best"), _ptr(n_out, torch.int32, (1,), "n_out"), _stream(stream))
+    _check(rc)
+
+
+def la_kv_commit_rope(k_cache, v_cache, step_k, step_v, cos, sin, P, W, N, G, kv_heads, head_dim, best, n_out,
+                      interleaved=False, stream=None):
+    """la_kv_commit for unrotated step keys: the appended key rows are turned by their cache positions
+    (tables as for la_step_rope); asynchronous."""
+    T = 1 + (W + G) * (N - 1)
+    bf = torch.bfloat16
+    capacity = int(k_cache.shape[1])
+    max_pos = int(cos.shape[0])
+    rc = load().la_kv_commit_rope(
+        _ptr(k_cache, bf, (kv_heads, capacity, head_dim), "k_cache"),
+        _ptr(v_cache, bf, (kv_heads, capacity, head_dim), "v_cache"), capacity,
+        _ptr(step_k, bf, (T, kv_heads, head_dim), "step_k"),
+        _ptr(step_v, bf, (T, kv_heads, head_dim), "step_v"),
+        _ptr(cos, torch.float32, (max_pos, head_dim // 2), "cos"),
+        _ptr(sin, torch.float32, (max_pos, head_dim // 2), "sin"),
+        max_pos, 1 if interleaved else 0, P, W, N, G, kv_heads, head_dim,
         _ptr(best, torch.int32, (1,), "best"), _ptr(n_out, torch.int32, (1,), "n_out"), _stream(stream))
     _check(rc)
 

@@ -229,8 +229,8 @@ la_status la_step_attention_fp8kv(const void* q, const void* k_cache, const void
 
 la_status la_step_attention_rope(const void* q, const void* k_cache, const void* v_cache, const void* step_k,
                                  const void* step_v, const float* cos, const float* sin, int max_pos, int interleaved,
-                                 int P, int W, int N, int G, int heads, int kv_heads, int head_dim, void* out,
-                                 void* stream)
+                                 int rotate_keys, int P, int W, int N, int G, int heads, int kv_heads, int head_dim,
+                                 void* out, void* stream)
 {
     if (P < 0 || W < 0 || G < 0 || N < 2)
         return la::fail(LA_EINVAL, "la_step_attention_rope: need P,W,G >= 0, N >= 2 (got P=%d W=%d N=%d G=%d)", P, W, N, G);
@@ -240,7 +240,7 @@ la_status la_step_attention_rope(const void* q, const void* k_cache, const void*
     if (max_pos < 1 || furthest >= max_pos)
         return la::fail(LA_EINVAL, "la_step_attention_rope: the tables hold %d positions, the step reaches position %lld",
                         max_pos, furthest);
-    const la::RopeTables rope = {cos, sin, interleaved != 0};
+    const la::RopeTables rope = {cos, sin, interleaved != 0, rotate_keys != 0};
     return step_attention_checked("la_step_attention_rope", q, k_cache, v_cache, P, nullptr, 0, 0, step_k, step_v,
                                   P, W, N, G, heads, kv_heads, head_dim, out, stream, nullptr, 0, nullptr, nullptr,
                                   nullptr, &rope);
@@ -394,6 +394,37 @@ la_status la_kv_commit(void* k_cache, void* v_cache, long long capacity, const v
         return la::fail(LA_EINVAL, "la_kv_commit: best and n_out must be 4-byte aligned");
     return la::launch_kv_commit(k_cache, v_cache, capacity, nullptr, 0, 0, step_k, step_v, P, W, N, G, kv_heads,
                                 head_dim, best, n_out, (hipStream_t)stream);
+}
+
+la_status la_kv_commit_rope(void* k_cache, void* v_cache, long long capacity, const void* step_k,
+                            const void* step_v, const float* cos, const float* sin, int max_pos, int interleaved,
+                            int P, int W, int N, int G, int kv_heads, int head_dim, const int* best,
+                            const int* n_out, void* stream)
+{
+    if (P < 0 || W < 0 || G < 0 || N < 2 || kv_heads < 1)
+        return la::fail(LA_EINVAL, "la_kv_commit_rope: need P,W,G >= 0, N >= 2, kv_heads >= 1 "
+                                   "(got P=%d W=%d N=%d G=%d kv_heads=%d)", P, W, N, G, kv_heads);
+    if (head_dim < 16 || head_dim % 16 != 0 || head_dim > 1024)
+        return la::fail(LA_EUNSUPPORTED, "la_kv_commit_rope: head_dim %d is not a multiple of 16 in 16..1024", head_dim);
+    if (1 + (long long)(W + G) * (N - 1) > (1 << 20) || N > 65535)
+        return la::fail(LA_EINVAL, "la_kv_commit_rope: step too large");
+    if (capacity > (1ll << 40) || (long long)P + N > capacity)
+        return la::fail(LA_EINVAL, "la_kv_commit_rope: capacity %lld cannot take N = %d more rows after P = %d",
+                        capacity, N, P);
+    // row i of the append is turned by position P + i; a candidate's last token sits at P + N - 1
+    const long long furthest = (long long)P + (G > 0 ? N - 1 : 0);
+    if (max_pos < 1 || furthest >= max_pos)
+        return la::fail(LA_EINVAL, "la_kv_commit_rope: the tables hold %d positions, the append reaches position %lld",
+                        max_pos, furthest);
+    if (!k_cache || !v_cache || !step_k || !step_v || !cos || !sin || !best || !n_out)
+        return la::fail(LA_EINVAL, "la_kv_commit_rope: null pointer");
+    if (((uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)step_k | (uintptr_t)step_v | (uintptr_t)cos |
+         (uintptr_t)sin) & 15)
+        return la::fail(LA_EINVAL, "la_kv_commit_rope: caches, step tensors and tables must be 16-byte aligned");
+    if (((uintptr_t)best | (uintptr_t)n_out) & 3)
+        return la::fail(LA_EINVAL, "la_kv_commit_rope: best and n_out must be 4-byte aligned");
+    return la::launch_kv_commit_rope(k_cache, v_cache, capacity, step_k, step_v, cos, sin, interleaved != 0, P, W, N,
+                                     G, kv_heads, head_dim, best, n_out, (hipStream_t)stream);
 }
 
 la_status la_kv_commit_batch(const la_commit_desc* descs, int n_descs, int page_size, int n_pages, int W, int N,

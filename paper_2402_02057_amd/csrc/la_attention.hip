@@ -95,7 +95,8 @@ struct AttnParams {
     };
     int rope_rows;         // positions P .. P + rope_rows - 1 are staged in LDS
     int rope_block;        // LDS bytes reserved per table (rope_rows * head_dim * 2 rounded up to 1 KB)
-    int rope_interleaved;  // pairing of the rotation: 0 (x[i], x[i + d/2]), 1 (x[2i], x[2i + 1])
+    int rope_flags;  // bit 0: pairing of the rotation, 0 (x[i], x[i + d/2]), 1 (x[2i], x[2i + 1]);
+                     // bit 1: the step keys are rotated in the kernel as well
     void* partials;     // XS > 1: per workgroup and wave, fragment-layout bf16 slices and fp32 (m, l)
     unsigned* tickets;  // XS > 1: one counter (kTicketStride words apart) per (KV head, row block, wave), zero between calls
     int P, W, N, G, T;
@@ -578,6 +579,26 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
     issue_first(true);
     LA_STAMP(1);
 
+    // Eight pairs of one 16-bit row in LDS (pieces of 16 bytes, swizzled with `sw`), turned in place by
+    // the table rows of position digit `digit` staged behind the ring: unit c of D/16.
+    auto rotate_unit = [&](unsigned char* row, int sw, int c, int digit) {
+        constexpr int UPR = D / 16;  // units of eight pairs per row
+        const bool inter = (p.rope_flags & 1) != 0;
+        bf16x8* va = reinterpret_cast<bf16x8*>(row + (((inter ? 2 * c : c) ^ sw) << 4));
+        bf16x8* vb = reinterpret_cast<bf16x8*>(row + (((inter ? 2 * c + 1 : c + UPR) ^ sw) << 4));
+        const float* cs = reinterpret_cast<const float*>(lds + C::ROPE_OFFSET + digit * C::ROPE_POS_BYTES) + c * 8;
+        const float* sn = reinterpret_cast<const float*>(lds + C::ROPE_OFFSET + p.rope_block + digit * C::ROPE_POS_BYTES) + c * 8;
+        const f32x4 c0 = *reinterpret_cast<const f32x4*>(cs), c1 = *reinterpret_cast<const f32x4*>(cs + 4);
+        const f32x4 s0 = *reinterpret_cast<const f32x4*>(sn), s1 = *reinterpret_cast<const f32x4*>(sn + 4);
+        const float co[8] = {c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
+        const float si[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
+        const bf16x8 xa = *va, xb = *vb;
+        bf16x8 ya, yb;
+        rope_eight_pairs(xa, xb, co, si, inter, ya, yb);
+        *va = ya;
+        *vb = yb;
+    };
+
     if constexpr (ROPE) {
         // Q and the table rows are older than every chunk requested so far: wait for them alone,
         // then every thread turns eight pairs of the workgroup's query rows in place (the same
@@ -586,27 +607,11 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
         // (a ring requested in full: the first chunk is waited for as well; the counter has 6 bits)
         wait_young<C::LPW, NSTAGE - 1>(min(issued, NSTAGE - 1));
         __syncthreads();
-        constexpr int UPR = D / 16;  // units of eight pairs per row
-        const bool inter = p.rope_interleaved != 0;
-        for (int u = tid; u < C::ROWS * UPR; u += C::NT) {
-            const int r = u / UPR, c = u - r * UPR;
+        for (int u = tid; u < C::ROWS * (D / 16); u += C::NT) {
+            const int r = u / (D / 16), c = u - r * (D / 16);
             const int rr = min(rb * C::ROWS + r, p.R - 1);
             const int digit = min(step_row_digit(div_small(rr, p.inv_group), p.W, p.N, p.inv_W, p.inv_n1), p.rope_rows - 1);
-            unsigned char* qrow = lds + C::Q_OFFSET + r * C::QRBYTES;
-            const int sw = swizzle<D>(r);
-            bf16x8* va = reinterpret_cast<bf16x8*>(qrow + (((inter ? 2 * c : c) ^ sw) << 4));
-            bf16x8* vb = reinterpret_cast<bf16x8*>(qrow + (((inter ? 2 * c + 1 : c + UPR) ^ sw) << 4));
-            const float* cs = reinterpret_cast<const float*>(lds + C::ROPE_OFFSET + digit * C::ROPE_POS_BYTES) + c * 8;
-            const float* sn = reinterpret_cast<const float*>(lds + C::ROPE_OFFSET + p.rope_block + digit * C::ROPE_POS_BYTES) + c * 8;
-            const f32x4 c0 = *reinterpret_cast<const f32x4*>(cs), c1 = *reinterpret_cast<const f32x4*>(cs + 4);
-            const f32x4 s0 = *reinterpret_cast<const f32x4*>(sn), s1 = *reinterpret_cast<const f32x4*>(sn + 4);
-            const float co[8] = {c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
-            const float si[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
-            const bf16x8 xa = *va, xb = *vb;
-            bf16x8 ya, yb;
-            rope_eight_pairs(xa, xb, co, si, inter, ya, yb);
-            *va = ya;
-            *vb = yb;
+            rotate_unit(lds + C::Q_OFFSET + r * C::QRBYTES, swizzle<D>(r), c, digit);
         }
     }
 
@@ -700,6 +705,30 @@ __device__ __forceinline__ void step_attention_body(const AttnParams& p, const i
             wait_young<C::LPW, NSTAGE - C::CPI>(issued - min(n_my, done + C::CPI));
             __syncthreads();  // these chunks are complete in LDS; everyone is done with the last ones
             if (it < 4) LA_STAMP(8 + 2 * it);
+            if constexpr (ROPE) {
+                // Step keys that come as the projection left them: the chunks of this iteration that
+                // hold step rows are turned in place by all threads, once per workgroup, before anyone
+                // multiplies with them (row r of step chunk c is step row c*KC + r; rows past the end
+                // repeat the last row's position and are masked out anyway).
+                if (p.rope_flags & 2) {
+                    bool any = false;
+#pragma unroll
+                    for (int j = 0; j < C::CPI; ++j) {
+                        const int c_abs = c_begin + done + j;
+                        if (done + j < n_my && c_abs >= n_prefix_chunks) {  // (uniform over the workgroup)
+                            any = true;
+                            unsigned char* stage = lds + ((done + j) % NSTAGE) * C::STAGE_BYTES;
+                            const int t0 = (c_abs - n_prefix_chunks) * KC;
+                            for (int u = tid; u < KC * (D / 16); u += C::NT) {
+                                const int r = u / (D / 16), c = u - r * (D / 16);
+                                const int digit = min(step_row_digit(min(t0 + r, n_T - 1), p.W, p.N, p.inv_W, p.inv_n1), p.rope_rows - 1);
+                                rotate_unit(stage + r * C::RBYTES, swizzle<D>(r), c, digit);
+                            }
+                        }
+                    }
+                    if (any) __syncthreads();
+                }
+            }
             if (it == 0 && pass == 0) {
                 // Q has landed with the first chunks: move this wave's rows to registers
                 const int qrow = rt * 32 + l32;
@@ -1306,7 +1335,7 @@ la_status build_params(AttnParams& prm, const Overrides& ov, const Plan& pl, con
     prm.step_k = (const __bf16*)step_k;
     prm.step_v = (const __bf16*)step_v;
     prm.out = (__bf16*)out;
-    prm.rope_rows = prm.rope_block = prm.rope_interleaved = 0;
+    prm.rope_rows = prm.rope_block = prm.rope_flags = 0;
     prm.partials = nullptr;
     prm.tickets = nullptr;
     prm.P = P; prm.W = W; prm.N = N; prm.G = G; prm.T = T;
@@ -1445,7 +1474,7 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
         const int far = W > 0 ? (W + N - 2 > N - 1 ? W + N - 2 : N - 1) : (G > 0 ? N - 1 : 0);
         prm.rope_rows = far + 1;
         prm.rope_block = (prm.rope_rows * head_dim * 2 + 1023) / 1024 * 1024;
-        prm.rope_interleaved = rope->interleaved ? 1 : 0;
+        prm.rope_flags = (rope->interleaved ? 1 : 0) | (rope->rotate_keys ? 2 : 0);
         const bool compiled = pl.KC == 64 && pl.NS == 4 &&
                               (head_dim == 128 ? ((pl.RT == 2 && pl.KS == 4) || (pl.RT == 1 && pl.KS == 2) ||
                                                   (pl.RT == 2 && pl.KS == 2))

@@ -5,6 +5,7 @@
 // A copy of at most N rows per KV head, driven by the device-side result of la_verify_step:
 // one workgroup per appended row, 16 bytes per thread and trip.
 #include "la_internal.h"
+#include "la_rope_common.h"
 
 namespace la {
 namespace {
@@ -56,6 +57,54 @@ __device__ __forceinline__ void commit_row(const CommitParams& p, int i)
 }
 
 __global__ __launch_bounds__(256) void kv_commit_kernel(CommitParams p) { commit_row(p, blockIdx.x); }
+
+// The same append for a step whose keys were left unrotated in memory (the attention kernel turned
+// them on the way in): the key rows are turned here, by the position they take in the cache, P + i,
+// which is the position the step evaluated them at (current token: P; token i - 1 of a candidate:
+// P + i).  A work item is eight pairs of one KV head's key row, with the arithmetic of the pass of
+// its own, and the same two 16-byte pieces of the value row, copied as they are.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+struct CommitRope {
+    const float* cos;
+    const float* sin;
+    int interleaved;
+};
+
+__global__ __launch_bounds__(256) void kv_commit_rope_kernel(CommitParams p, CommitRope rp)
+{
+    const int i = blockIdx.x;
+    int n = *p.n_out;
+    n = n < 1 ? 1 : (n > p.N ? p.N : n);
+    if (i >= n) return;
+    int src = 0;
+    if (i > 0) {
+        int g = *p.best;
+        g = g < 0 ? 0 : (g >= p.G ? p.G - 1 : g);
+        if (p.G == 0) return;
+        src = 1 + p.W * (p.N - 1) + g * (p.N - 1) + (i - 1);
+    }
+    const int units = p.row_bytes / 32;     // units of eight pairs per head row
+    const float* cs = rp.cos + (size_t)(p.P + i) * (p.row_bytes / 4);
+    const float* sn = rp.sin + (size_t)(p.P + i) * (p.row_bytes / 4);
+    for (int x = threadIdx.x; x < p.kv_heads * units; x += blockDim.x) {
+        const int h = x / units, c = x - h * units;
+        const int pa = rp.interleaved ? 2 * c : c, pb = rp.interleaved ? 2 * c + 1 : c + units;
+        const size_t from = ((size_t)src * p.kv_heads + h) * p.row_bytes;
+        const size_t to = ((size_t)h * (size_t)p.capacity + (size_t)(p.P + i)) * p.row_bytes;
+        const bf16x8 xa = *reinterpret_cast<const bf16x8*>(p.step_k + from + pa * 16);
+        const bf16x8 xb = *reinterpret_cast<const bf16x8*>(p.step_k + from + pb * 16);
+        const float4 c0 = *reinterpret_cast<const float4*>(cs + c * 8), c1 = *reinterpret_cast<const float4*>(cs + c * 8 + 4);
+        const float4 s0 = *reinterpret_cast<const float4*>(sn + c * 8), s1 = *reinterpret_cast<const float4*>(sn + c * 8 + 4);
+        const float co[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+        const float si[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+        bf16x8 ya, yb;
+        rope_eight_pairs(xa, xb, co, si, rp.interleaved != 0, ya, yb);
+        *reinterpret_cast<bf16x8*>(p.k_cache + to + pa * 16) = ya;
+        *reinterpret_cast<bf16x8*>(p.k_cache + to + pb * 16) = yb;
+        *reinterpret_cast<uint4*>(p.v_cache + to + pa * 16) = *reinterpret_cast<const uint4*>(p.step_v + from + pa * 16);
+        *reinterpret_cast<uint4*>(p.v_cache + to + pb * 16) = *reinterpret_cast<const uint4*>(p.step_v + from + pb * 16);
+    }
+}
 
 // Several appends in one launch (the layers of a model after a step, or several sequences):
 // blockIdx.y names the append, blockIdx.x its row.  What differs between appends travels as a
@@ -119,6 +168,34 @@ la_status launch_kv_commit(void* k_cache, void* v_cache, long long capacity, con
     hipLaunchKernelGGL(kv_commit_kernel, dim3((unsigned)N), dim3(256), 0, stream, p);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(LA_EHIP, "la_kv_commit launch: %s", hipGetErrorString(e));
+    return LA_OK;
+}
+
+la_status launch_kv_commit_rope(void* k_cache, void* v_cache, long long capacity, const void* step_k,
+                                const void* step_v, const float* cos, const float* sin, int interleaved, int P,
+                                int W, int N, int G, int kv_heads, int head_dim, const int* best, const int* n_out,
+                                hipStream_t stream)
+{
+    CommitParams p;
+    p.k_cache = (unsigned char*)k_cache;
+    p.v_cache = (unsigned char*)v_cache;
+    p.step_k = (const unsigned char*)step_k;
+    p.step_v = (const unsigned char*)step_v;
+    p.best = best;
+    p.n_out = n_out;
+    p.capacity = capacity;
+    p.block_table = nullptr;
+    p.page_size = 0;
+    p.n_pages = 0;
+    p.P = P; p.W = W; p.N = N; p.G = G; p.kv_heads = kv_heads;
+    p.row_bytes = head_dim * 2;
+    CommitRope rp;
+    rp.cos = cos;
+    rp.sin = sin;
+    rp.interleaved = interleaved;
+    hipLaunchKernelGGL(kv_commit_rope_kernel, dim3((unsigned)N), dim3(256), 0, stream, p, rp);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(LA_EHIP, "la_kv_commit_rope launch: %s", hipGetErrorString(e));
     return LA_OK;
 }
 

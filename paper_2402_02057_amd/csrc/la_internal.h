@@ -63,6 +63,7 @@ struct RopeTables {
     const float* cos;
     const float* sin;
     bool interleaved;
+    bool rotate_keys;  // the step keys come unrotated too: the kernel turns them as their chunks land
 };
 // The library's own fixed block on the current device (a file-scope device array; no allocation).
 la_status fixed_workspace(FixedWorkspace* ws);
@@ -96,6 +97,11 @@ la_status launch_kv_commit(void* k_cache, void* v_cache, long long capacity, con
                            int page_size, int n_pages, const void* step_k, const void* step_v, int P, int W,
                            int N, int G, int kv_heads, int head_dim, const int* best, const int* n_out,
                            hipStream_t stream);
+// The append with the key rows turned by their cache positions (contiguous caches only).
+la_status launch_kv_commit_rope(void* k_cache, void* v_cache, long long capacity, const void* step_k,
+                                const void* step_v, const float* cos, const float* sin, int interleaved, int P,
+                                int W, int N, int G, int kv_heads, int head_dim, const int* best, const int* n_out,
+                                hipStream_t stream);
 // One sequence of a batched la_verify_sample (pointers as for launch_verify_sample).
 struct SampleSeq {
     const float* logits_cur;

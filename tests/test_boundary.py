@@ -94,17 +94,27 @@ def test_quantised_and_rotating_forms_report_argument_errors_without_a_gpu(lib):
     rc = lib.la_step_attention_fp8kv(A, A, A, A, A, A, A, 10, 1, 3, 1, 4, 4, 96, A, None)
     assert rc == -2 and b"head_dim" in lib.la_last_error()
     # rotation inside the kernel: tables present, aligned, and long enough for the step's furthest position
-    args = (10, 3, 4, 2, 4, 4, 128, A, None)            # P, W, N, G, heads, kv_heads, head_dim, out, stream
+    args = (1, 10, 3, 4, 2, 4, 4, 128, A, None)   # rotate_keys, P, W, N, G, heads, kv_heads, head_dim, out, stream
     rc = lib.la_step_attention_rope(A, A, A, A, A, None, A, 64, 0, *args)
     assert rc == -1 and b"cos" in lib.la_last_error()
     rc = lib.la_step_attention_rope(A, A, A, A, A, A + 4, A, 64, 0, *args)
     assert rc == -1 and b"aligned" in lib.la_last_error()
     rc = lib.la_step_attention_rope(A, A, A, A, A, A, A, 15, 0, *args)       # reaches 10 + 3 + 4 - 2 = 15
     assert rc == -1 and b"positions" in lib.la_last_error()
-    rc = lib.la_step_attention_rope(A, A, A, A, A, A, A, 16, 0, 10, 3, 1, 2, 4, 4, 128, A, None)
+    rc = lib.la_step_attention_rope(A, A, A, A, A, A, A, 16, 0, 0, 10, 3, 1, 2, 4, 4, 128, A, None)
     assert rc == -1 and b"N >= 2" in lib.la_last_error()
     rc = lib.la_step_attention_rope(A, A, A, None, A, A, A, 16, 0, *args)
     assert rc == -1 and b"null" in lib.la_last_error()
+    # the rotating append: room for N rows, tables up to position P + N - 1, whole units of eight pairs
+    c = (10, 3, 4, 2, 4, 128, A, A, None)                # P, W, N, G, kv_heads, head_dim, best, n_out, stream
+    rc = lib.la_kv_commit_rope(A, A, 13, A, A, A, A, 64, 0, *c)
+    assert rc == -1 and b"capacity" in lib.la_last_error()
+    rc = lib.la_kv_commit_rope(A, A, 64, A, A, A, A, 13, 0, *c)              # reaches 10 + 4 - 1 = 13
+    assert rc == -1 and b"positions" in lib.la_last_error()
+    assert lib.la_kv_commit_rope(A, A, 64, A, A, A, A, 14, 0, 10, 3, 4, 2, 4, 128, None, A, None) == -1  # null best
+    assert lib.la_kv_commit_rope(A, A, 64, A, A, A + 8, A, 14, 0, *c) == -1  # misaligned table
+    rc = lib.la_kv_commit_rope(A, A, 64, A, A, A, A, 14, 0, 10, 3, 4, 2, 4, 24, A, A, None)
+    assert rc == -2 and b"multiple of 16" in lib.la_last_error()
     # the rope pass takes a null q (keys alone) but not null keys or tables
     rc = lib.la_step_rope(None, None, A, A, 64, 10, 3, 4, 2, 4, 4, 128, 0, None)
     assert rc == -1 and b"null" in lib.la_last_error()

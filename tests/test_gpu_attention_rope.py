@@ -1,5 +1,5 @@
-"""GPU parity of la_step_attention_rope (query rows rotated inside the attention kernel) and of the
-keys-only mode of la_step_rope.
+"""GPU parity of la_step_attention_rope (query rows, and on request the step's keys, rotated inside
+the attention kernel), of the keys-only mode of la_step_rope and of la_kv_commit_rope.
 
 Two bars: against the oracle (step_rope in fp64, rounded to bf16 as the tensors in memory are, then
 step_attention) within 2e-2; and against the library's own two-pass path (la_step_rope on q and
@@ -50,6 +50,16 @@ def run_case(seed, P, W, N, G, H, KV, d, interleaved, oracle=True):
     assert torch.equal(k1.view(torch.int16), k2.view(torch.int16)), "keys-only rotation differs from the full pass"
     assert torch.equal(dev["q"].view(torch.int16), q_before.view(torch.int16)), "q was modified"
     assert torch.equal(one.view(torch.int16), two.view(torch.int16)), "fused and two-pass outputs differ"
+
+    # nothing rotated in memory: q and the step keys are turned inside the attention kernel
+    k_before = dev["step_k"].clone()
+    none = torch.full((T, H, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    binding.la_step_attention_rope(dev["q"], dev["k_cache"], dev["v_cache"], dev["step_k"], dev["step_v"], dcos, dsin,
+                                   P, W, N, G, H, KV, d, none, interleaved, rotate_keys=True)
+    torch.cuda.synchronize()
+    assert torch.equal(dev["step_k"].view(torch.int16), k_before.view(torch.int16)), "step_k was modified"
+    assert torch.equal(dev["q"].view(torch.int16), q_before.view(torch.int16)), "q was modified"
+    assert torch.equal(none.view(torch.int16), two.view(torch.int16)), "keys rotated in the kernel: output differs"
 
     if oracle:
         rq, rk = orc.step_rope(orc.bf16_to_f64(x["q"]), orc.bf16_to_f64(x["step_k"]), cos, sin, P, W, N, G, interleaved)
@@ -127,3 +137,73 @@ def test_limits_and_argument_errors():
     with pytest.raises(binding.LaError, match="positions"):
         binding.la_step_attention_rope(dev["q"], dev["k_cache"], dev["v_cache"], dev["step_k"], dev["step_v"],
                                        dcos[:P + 10].contiguous(), dsin[:P + 10].contiguous(), P, W, N, G, H, KV, d, out)
+
+
+@pytest.mark.parametrize("interleaved", [False, True])
+@pytest.mark.parametrize("P,W,N,G,KV,d,best,n_out", [
+    (64, 4, 3, 2, 4, 64, 1, 3),        # a full match of the second candidate
+    (0, 5, 4, 2, 1, 64, 0, 2),         # empty prefix, one candidate token accepted
+    (333, 15, 5, 15, 4, 128, 7, 5),    # the 7B step, full match
+    (333, 15, 5, 15, 4, 128, -1, 1),   # nothing accepted: the current token alone
+    (17, 4, 2, 0, 1, 128, -1, 1),      # no candidates at all
+    (100, 3, 7, 3, 2, 256, 2, 4),      # head_dim 256
+])
+def test_commit_rope_leaves_the_bits_of_rotate_then_commit(P, W, N, G, KV, d, best, n_out, interleaved):
+    """The appended key rows, turned by their cache positions, against la_step_rope on the whole step
+    followed by la_kv_commit; values and everything outside the appended rows untouched.  The oracle's
+    rotation and append decide the values (keys within one bf16 rounding of the fp64 rotation)."""
+    print("case", dict(P=P, W=W, N=N, G=G, KV=KV, d=d, best=best, n_out=n_out, interleaved=interleaved), flush=True)
+    rng = np.random.default_rng(P + W + d + n_out)
+    T = 1 + (W + G) * (N - 1)
+    cap = P + N + 3
+    bf = lambda shape: wl.f32_to_bf16_bits(rng.standard_normal(size=shape, dtype=np.float32))
+    kc, vc, sk, sv = bf((KV, cap, d)), bf((KV, cap, d)), bf((T, KV, d)), bf((T, KV, d))
+    cos, sin = wl.rope_tables(P + W + N + 5, d)
+    dcos, dsin = torch.from_numpy(cos).cuda(), torch.from_numpy(sin).cuda()
+    dbest = torch.tensor([best], dtype=torch.int32, device="cuda")
+    dn = torch.tensor([n_out], dtype=torch.int32, device="cuda")
+
+    k_a, v_a = binding.bf16_tensor(kc), binding.bf16_tensor(vc)
+    sk_rot = binding.bf16_tensor(sk)
+    binding.la_step_rope(None, sk_rot, dcos, dsin, P, W, N, G, 1, KV, d, interleaved)
+    binding.la_kv_commit(k_a, v_a, sk_rot, binding.bf16_tensor(sv), P, W, N, G, KV, d, dbest, dn)
+
+    k_b, v_b = binding.bf16_tensor(kc), binding.bf16_tensor(vc)
+    dsk = binding.bf16_tensor(sk)
+    binding.la_kv_commit_rope(k_b, v_b, dsk, binding.bf16_tensor(sv), dcos, dsin, P, W, N, G, KV, d, dbest, dn,
+                              interleaved)
+    torch.cuda.synchronize()
+    assert torch.equal(dsk.view(torch.int16).cpu(), torch.from_numpy(sk.view(np.int16))), "step_k was modified"
+    assert torch.equal(k_a.view(torch.int16), k_b.view(torch.int16))
+    assert torch.equal(v_a.view(torch.int16), v_b.view(torch.int16))
+
+    # the oracle: rotate the step's keys in fp64, append the rows the result names
+    _, rk = orc.step_rope(np.zeros((T, 1, d)), orc.bf16_to_f64(sk), cos, sin, P, W, N, G, interleaved)
+    want_k, want_v = orc.bf16_to_f64(kc), orc.bf16_to_f64(vc)
+    assert orc.kv_commit(want_k, want_v, rk, orc.bf16_to_f64(sv), P, W, N, G, best, n_out) == P + n_out
+    got_k = k_b.float().cpu().numpy().astype(np.float64)
+    got_v = v_b.float().cpu().numpy().astype(np.float64)
+    np.testing.assert_array_equal(got_v, want_v)
+    np.testing.assert_array_equal(got_k[:, :P], want_k[:, :P])
+    np.testing.assert_array_equal(got_k[:, P + n_out:], want_k[:, P + n_out:])
+    new = slice(P, P + n_out)
+    assert np.abs(got_k[:, new] - want_k[:, new]).max() <= 2.0 ** -8 * max(1.0, np.abs(want_k[:, new]).max()) + 1e-6
+
+
+def test_commit_rope_argument_errors():
+    P, W, N, G, KV, d = 10, 2, 3, 2, 2, 64
+    T = 1 + (W + G) * (N - 1)
+    z = lambda *shape: torch.zeros(shape, dtype=torch.bfloat16, device="cuda")
+    cos, sin = wl.rope_tables(P + N + 4, d)
+    dcos, dsin = torch.from_numpy(cos).cuda(), torch.from_numpy(sin).cuda()
+    one = torch.ones(1, dtype=torch.int32, device="cuda")
+    with pytest.raises(binding.LaError, match="capacity"):
+        binding.la_kv_commit_rope(z(KV, P + 1, d), z(KV, P + 1, d), z(T, KV, d), z(T, KV, d), dcos, dsin, P, W, N, G,
+                                  KV, d, one, one)
+    with pytest.raises(binding.LaError, match="positions"):
+        binding.la_kv_commit_rope(z(KV, P + N, d), z(KV, P + N, d), z(T, KV, d), z(T, KV, d), dcos[:P + 1].contiguous(),
+                                  dsin[:P + 1].contiguous(), P, W, N, G, KV, d, one, one)
+    with pytest.raises(binding.LaError, match="multiple of 16"):
+        t24 = torch.zeros((P + N + 4, 12), dtype=torch.float32, device="cuda")
+        binding.la_kv_commit_rope(z(KV, P + N, 24), z(KV, P + N, 24), z(T, KV, 24), z(T, KV, 24), t24, t24, P, W, N, G,
+                                  KV, 24, one, one)
