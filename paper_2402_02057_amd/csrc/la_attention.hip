@@ -45,7 +45,8 @@
 //
 // Variants of the same kernel (template parameters): a paged cache (block table), a subset of
 // the step's rows, keys and values as 8-bit floats with a scale per KV head (converted exactly
-// to bf16 in front of the MFMA), and query rows rotated on the way in (rotary embedding).
+// to bf16 in front of the MFMA), and query rows (optionally the step keys too) rotated on the
+// way in (rotary embedding).
 #include <stdlib.h>
 
 #include <mutex>

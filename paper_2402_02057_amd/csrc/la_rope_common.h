@@ -1,6 +1,7 @@
-// Rotary position embedding, the arithmetic shared by the pass of its own (la_step_rope) and by the
-// attention kernel that rotates its query rows on the way in: written out operation by
-// operation, so that both give the same bits.
+// Rotary position embedding, the arithmetic shared by the pass of its own (la_step_rope), by the
+// attention kernel that rotates its query rows (and, on request, the step keys) on the way in and
+// by the append that rotates the key rows it copies: written out operation by operation, so that
+// all of them give the same bits.
 #pragma once
 #include <hip/hip_runtime.h>
 
