@@ -12,7 +12,8 @@ measured time against the MI355X peak that bounds the shape (HBM 8 TB/s or bf16 
 and against what this machine reaches at best in the same run (`achievable`: a streaming read, a
 register-resident MFMA loop), plus the HBM traffic recorded in profiles/.  `cpu_baseline`: the CPU
 oracle timed on the host cores (all of them, and one).  The other objects time the remaining entry
-points on their own.  --workload: llama2-7b (default), llama2-13b, llama2-70b-gqa, tiny, ragged.
+points on their own.  --workload: llama2-7b (default), llama2-13b, llama2-70b-gqa, tiny, ragged,
+llama2-7b-p256 (the 7B step on a 256-token prefix: the shape of the short-prefix kernel).
 """
 import argparse
 import json
@@ -27,7 +28,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
-LAYERS = {"tiny": 8, "llama2-7b": 32, "llama2-13b": 40, "llama2-70b-gqa": 80}
+LAYERS = {"tiny": 8, "llama2-7b": 32, "llama2-13b": 40, "llama2-70b-gqa": 80, "llama2-7b-p256": 32}
 RAGGED_W = (5, 10, 15, 20, 30)
 
 
@@ -563,7 +564,9 @@ def main():
     abytes = algorithmic_bytes(s)
     aflops = algorithmic_flops(s)
     traffic, traffic_source = profile_traffic(args.workload)
-    roof, t_roof = roofline_object(abytes, aflops, attn_us, peaks, "step_attention_kernel", traffic, traffic_source)
+    kernel_name = "step_attention_rowtile_kernel" if binding.la_step_attention_kernel(P, s.W, s.N, s.G, H, KV, d) == 1 \
+        else "step_attention_kernel"
+    roof, t_roof = roofline_object(abytes, aflops, attn_us, peaks, kernel_name, traffic, traffic_source)
     t_hbm, t_mfma = abytes / (HBM_PEAK_GBS * 1e9), aflops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
 
     # the same launch L times on ONE layer's buffers: the caches then come from the Infinity Cache

@@ -459,6 +459,9 @@ la_status la_step_attention_noalloc(const void* q, const void* k_cache, const vo
  *   "attn_plan"        (LA_ATTN_PLAN)        "RT,KS,XS,NS,KC[,PRE]": the decomposition of the one-step
  *                                            entry points forced by hand (ignored where no such
  *                                            kernel is compiled); NULL or "" = the library's choice
+ *                                            (a forced decomposition is one of the staged kernel)
+ *   "attn_rowtile"     (no variable)         "1" / "0": the row-tile kernel forced on (where it
+ *                                            applies) / off; NULL = the library's choice
  *   "batch_plan"       (LA_BATCH_PLAN)       "2" or "4": 32-row tiles per workgroup of a batched launch
  *   "force_recompute"  (LA_FORCE_RECOMPUTE)  "1": treat every split group as spread over several
  *                                            XCDs, so that the recompute path runs
@@ -481,9 +484,22 @@ la_status la_debug_override(const char* key, const char* value);
 la_status la_probe_stream_read(const void* src, long long bytes, void* sink, void* stream);
 long long la_probe_mfma(int iters, void* sink, void* stream);
 
-/* Bytes of device workspace la_step_attention needs for this shape (0 if none). */
+/*
+ * Bytes of device workspace la_step_attention may need for this shape (0 if none; an upper
+ * bound: a shape that takes the row-tile kernel, see la_step_attention_kernel, needs none).
+ */
 long long la_step_attention_workspace_bytes(int P, int W, int N, int G, int heads, int kv_heads,
                                             int head_dim);
+
+/*
+ * Which kernel la_step_attention, la_step_attention_cap and la_step_attention_noalloc take for
+ * this shape: 0 the staged kernel (workgroups split the keys of a row block and combine partial
+ * results; every shape), 1 the row-tile kernel (a workgroup walks all keys for 32 rows and half
+ * of the value columns and writes `out` directly; head_dim 128, picked for short prefixes,
+ * where it measures 10 to 28 % faster).  Both compute the step of Sec. 3.3 to the same bar; the
+ * output bits may differ between them.  -1 for arguments la_step_attention would refuse.
+ */
+int la_step_attention_kernel(int P, int W, int N, int G, int heads, int kv_heads, int head_dim);
 
 /* Free the per-device workspaces.  No call may be in flight.  Optional at exit. */
 void la_shutdown(void);

@@ -107,6 +107,8 @@ def load():
     lib.la_verify_sample.restype = i
     lib.la_step_attention_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
     lib.la_step_attention_workspace_bytes.restype = ctypes.c_longlong
+    lib.la_step_attention_kernel.argtypes = [i, i, i, i, i, i, i]
+    lib.la_step_attention_kernel.restype = i
     lib.la_shutdown.argtypes = []
     lib.la_shutdown.restype = None
     lib.la_last_error.argtypes = []
@@ -125,7 +127,7 @@ def load():
     return lib
 
 
-EXPORTS = ("la_step_rope", "la_step_attention", "la_step_attention_noalloc", "la_step_attention_fp8kv", "la_step_attention_rope", "la_step_attention_cap", "la_kv_commit", "la_kv_commit_rope", "la_step_attention_paged", "la_kv_commit_paged", "la_kv_commit_batch", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_step_batch", "la_verify_sample", "la_verify_sample_batch", "la_step_attention_workspace_bytes", "la_shutdown", "la_select_workspace", "la_debug_override", "la_probe_stream_read", "la_probe_mfma",
+EXPORTS = ("la_step_rope", "la_step_attention", "la_step_attention_noalloc", "la_step_attention_fp8kv", "la_step_attention_rope", "la_step_attention_cap", "la_kv_commit", "la_kv_commit_rope", "la_step_attention_paged", "la_kv_commit_paged", "la_kv_commit_batch", "la_step_attention_rows", "la_step_attention_batch", "la_step_attention_batch_paged", "la_verify", "la_verify_step", "la_verify_step_batch", "la_verify_sample", "la_verify_sample_batch", "la_step_attention_workspace_bytes", "la_step_attention_kernel", "la_shutdown", "la_select_workspace", "la_debug_override", "la_probe_stream_read", "la_probe_mfma",
            "la_last_error", "la_version")
 
 
@@ -523,6 +525,11 @@ def la_verify_sample_batch(seqs, N, G, V, stream=None):
         d.n_out = _ptr(x["n_out"], i32, (1,), "n_out")
         d.temperature, d.reserved = float(x["temperature"]), 0
     _check(load().la_verify_sample_batch(ctypes.cast(descs, ctypes.c_void_p), len(seqs), N, G, V, _stream(stream)))
+
+
+def la_step_attention_kernel(P, W, N, G, heads, kv_heads, head_dim):
+    """0: the staged kernel, 1: the row-tile kernel (what la_step_attention takes for this shape)."""
+    return int(load().la_step_attention_kernel(P, W, N, G, heads, kv_heads, head_dim))
 
 
 def la_step_attention_workspace_bytes(P, W, N, G, heads, kv_heads, head_dim):

@@ -601,6 +601,14 @@ long long la_step_attention_workspace_bytes(int P, int W, int N, int G, int head
     return (long long)la::step_attention_workspace_bytes(P, W, N, G, heads, kv_heads, head_dim);
 }
 
+int la_step_attention_kernel(int P, int W, int N, int G, int heads, int kv_heads, int head_dim)
+{
+    if (P < 0 || W < 0 || G < 0 || N < 2 || heads < 1 || kv_heads < 1 || heads % kv_heads != 0 ||
+        (head_dim != 64 && head_dim != 128))
+        return -1;
+    return la::step_attention_kernel_choice(P, W, N, G, heads, kv_heads, head_dim);
+}
+
 la_status la_probe_stream_read(const void* src, long long bytes, void* sink, void* stream)
 {
     if (!src || !sink || bytes < 16 || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)sink & 3))

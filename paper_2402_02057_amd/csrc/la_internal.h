@@ -91,6 +91,14 @@ struct BatchSeq {
     void* out;
     int P;
 };
+// The decomposition without partial results between workgroups (la_attention_rowtile.hip): packed or
+// in-place bf16 caches, whole steps, head_dim 128.
+bool rowtile_supported(int head_dim, int group, int T);
+// 1: la_step_attention / _cap / _noalloc take the row-tile kernel for this shape; 0: the staged one.
+int step_attention_kernel_choice(int P, int W, int N, int G, int heads, int kv_heads, int head_dim);
+la_status launch_step_attention_rowtile(const void* q, const void* k_cache, const void* v_cache, long long capacity,
+                                        const void* step_k, const void* step_v, int P, int W, int N, int G, int heads,
+                                        int kv_heads, void* out, hipStream_t stream);
 la_status launch_step_attention_batch(const BatchSeq* seqs, int n_seqs, int page_size, int n_pages, int W, int N,
                                       int G, int heads, int kv_heads, int head_dim, hipStream_t stream);
 la_status launch_kv_commit(void* k_cache, void* v_cache, long long capacity, const int* block_table,

@@ -41,7 +41,10 @@ TINY = StepShape("tiny", 0, 4, 4, 64, 64, 4, 3, 2, 512, False)
 LLAMA2_7B = StepShape("llama2-7b", 1, 32, 32, 128, 1024, 15, 5, 15, 32000, True)
 LLAMA2_13B = StepShape("llama2-13b", 2, 40, 40, 128, 2048, 10, 5, 10, 32000, True)
 LLAMA2_70B = StepShape("llama2-70b-gqa", 3, 64, 8, 128, 4096, 7, 5, 7, 32000, True)
-SHAPES = {s.name: s for s in (TINY, LLAMA2_7B, LLAMA2_13B, LLAMA2_70B)}
+# the 7B step early in a sequence: the prefix of a short prompt (not one of the benchmark's configs;
+# the shape the short-prefix kernel is measured and profiled on)
+LLAMA2_7B_P256 = StepShape("llama2-7b-p256", 9, 32, 32, 128, 256, 15, 5, 15, 32000, True)
+SHAPES = {s.name: s for s in (TINY, LLAMA2_7B, LLAMA2_13B, LLAMA2_70B, LLAMA2_7B_P256)}
 
 RAGGED_W = (5, 10, 15, 20, 30)
 RAGGED_SEQS = 8

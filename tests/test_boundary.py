@@ -267,3 +267,30 @@ def test_binding_rejects_host_tensors():
     z = torch.zeros((1, 1, 64), dtype=torch.bfloat16)
     with pytest.raises(ValueError):
         binding.la_step_attention(z, None, None, z, z, 0, 0, 2, 0, 1, 1, 64, z)
+
+
+def test_kernel_choice_is_a_host_side_query(lib):
+    """Which kernel a plain step takes, without a GPU: the benchmark's shapes keep the staged kernel,
+    the 7B step on a short prefix takes the row-tile one; the hooks force either."""
+    k = lib.la_step_attention_kernel
+    assert k(1024, 15, 5, 15, 32, 32, 128) == 0        # the 7B configuration
+    assert k(2048, 10, 5, 10, 40, 40, 128) == 0
+    assert k(4096, 7, 5, 7, 64, 8, 128) == 0
+    assert k(256, 15, 5, 15, 32, 32, 128) == 1         # 6 chunks, 256 workgroups
+    assert k(640, 15, 5, 15, 32, 32, 128) == 1         # 12 chunks: the last one it takes
+    assert k(704, 15, 5, 15, 32, 32, 128) == 0
+    assert k(256, 30, 5, 30, 32, 32, 128) == 0         # 512 workgroups: more than one round
+    assert k(64, 4, 3, 2, 4, 4, 64) == 0               # head_dim 64: the staged kernel only
+    assert k(64, 4, 1, 2, 4, 4, 128) == -1 and k(64, 4, 3, 2, 4, 3, 128) == -1
+    try:
+        assert lib.la_debug_override(b"attn_rowtile", b"1") == 0
+        assert k(1024, 15, 5, 15, 32, 32, 128) == 1 and k(64, 4, 3, 2, 4, 4, 64) == 0
+        assert lib.la_debug_override(b"attn_plan", b"2,4,0,4,64") == 0
+        assert k(256, 15, 5, 15, 32, 32, 128) == 0     # a forced decomposition is the staged kernel
+        assert lib.la_debug_override(b"attn_plan", None) == 0
+        assert lib.la_debug_override(b"attn_rowtile", b"0") == 0
+        assert k(256, 15, 5, 15, 32, 32, 128) == 0
+    finally:
+        lib.la_debug_override(b"attn_plan", None)
+        lib.la_debug_override(b"attn_rowtile", None)
+    assert k(256, 15, 5, 15, 32, 32, 128) == 1

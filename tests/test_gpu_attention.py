@@ -15,6 +15,17 @@ pytestmark = pytest.mark.gpu
 TOL = 2e-2
 
 
+@pytest.fixture(autouse=True, params=["auto", "staged", "rowtile"])
+def kernel_choice(request, override):
+    """Every test of this file runs three times: with the library's own choice between its two kernels
+    (the staged one with partial results, and the row-tile one that walks all keys per workgroup and is
+    picked for short prefixes), and with each of them forced (a forced row-tile kernel still gives way
+    where it does not apply: head_dim 64, forced decompositions)."""
+    if request.param != "auto":
+        override("attn_rowtile", "1" if request.param == "rowtile" else "0")
+    return request.param
+
+
 def run_hip(x, P, W, N, G, H, KV, d, poison=True):
     T = 1 + (W + G) * (N - 1)
     dev = {k: binding.bf16_tensor(v) for k, v in x.items()}
@@ -167,9 +178,11 @@ def test_ragged_long_context(seq, W):
           s.name)
 
 
-def test_recompute_path_for_groups_not_on_one_xcd(override):
+def test_recompute_path_for_groups_not_on_one_xcd(override, kernel_choice):
     """Force the path the last workgroup takes when its split group is spread over several
     XCDs (it recomputes from the inputs instead of reading the other workgroups' partials)."""
+    if kernel_choice == "rowtile":
+        pytest.skip("the row-tile kernel has no split groups")
     override("force_recompute", "1")
     for s in (wl.LLAMA2_7B, wl.LLAMA2_70B, wl.TINY):
         check(wl.attention_inputs(s), s.P, s.W, s.N, s.G, s.heads, s.kv_heads, s.head_dim,
@@ -189,8 +202,10 @@ PLANS_D64 = ["1,2,3,2,64", "1,2,1,4,64", "2,2,4,4,64", "2,2,1,2,64", "4,1,2,4,64
 
 
 @pytest.mark.parametrize("plan", PLANS_D128)
-def test_every_kernel_variant(override, plan):
+def test_every_kernel_variant(override, plan, kernel_choice):
     """Each compiled decomposition (row tiles, key-split waves, splits, stages, up-front depth)."""
+    if kernel_choice != "auto":
+        pytest.skip("a forced decomposition is the staged kernel whatever the choice")
     override("attn_plan", plan)
     x = rand_inputs(123, 777, 9, 5, 9, 8, 2, 128)      # R = 292 rows per KV head
     check(x, 777, 9, 5, 9, 8, 2, 128, "plan " + plan)
@@ -199,7 +214,9 @@ def test_every_kernel_variant(override, plan):
 
 
 @pytest.mark.parametrize("plan", PLANS_D64)
-def test_every_kernel_variant_head_dim_64(override, plan):
+def test_every_kernel_variant_head_dim_64(override, plan, kernel_choice):
+    if kernel_choice != "auto":
+        pytest.skip("a forced decomposition is the staged kernel whatever the choice")
     override("attn_plan", plan)
     x = rand_inputs(125, 700, 7, 5, 7, 6, 2, 64)       # R = 171 rows per KV head
     check(x, 700, 7, 5, 7, 6, 2, 64, "plan " + plan)
@@ -207,7 +224,9 @@ def test_every_kernel_variant_head_dim_64(override, plan):
     check(x, 65, 2, 3, 1, 2, 2, 64, "plan " + plan)
 
 
-def test_errors_surface_as_exceptions():
+def test_errors_surface_as_exceptions(kernel_choice):
+    if kernel_choice != "auto":
+        pytest.skip("argument checks come before the choice of a kernel")
     z = torch.zeros((1, 4, 96), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(binding.LaError) as e:
         binding.la_step_attention(z, None, None, z, z, 0, 0, 2, 0, 4, 4, 96, z)

@@ -28,6 +28,16 @@ def make(seed, P, W, N, G, H, KV, d):
 
 def run_case(seed, P, W, N, G, H, KV, d, interleaved, oracle=True):
     print("case", dict(P=P, W=W, N=N, G=G, H=H, KV=KV, d=d, interleaved=interleaved), flush=True)
+    # the rotating entry point is a variant of the staged kernel: the plain step it is compared with
+    # bit by bit must take that kernel too (short prefixes would otherwise go to the row-tile kernel)
+    binding.la_debug_override("attn_rowtile", "0")
+    try:
+        _run_case(seed, P, W, N, G, H, KV, d, interleaved, oracle)
+    finally:
+        binding.la_debug_override("attn_rowtile", None)
+
+
+def _run_case(seed, P, W, N, G, H, KV, d, interleaved, oracle):
     x, cos, sin = make(seed, P, W, N, G, H, KV, d)
     T = 1 + (W + G) * (N - 1)
     dev = {k: binding.bf16_tensor(v) for k, v in x.items()}
