@@ -1379,6 +1379,11 @@ la_status build_params(AttnParams& prm, const Overrides& ov, const Plan& pl, con
     // and a full ring keeps three chunks in flight instead of two (measured 6-8 % at 50 chunks
     // per workgroup, a loss at 8).
     if (pl.PRE == 0 && cpi == 1 && prm.chunks_lo >= 16) prm.pre = pl.NS;
+    // Short walks with two chunks per iteration (the 7B configuration: 4 or 5 chunks per workgroup):
+    // only the first iteration's chunks up front.  Every request that stands in front of them
+    // delays the first MFMA of every workgroup on the chip, and with so few iterations nothing
+    // amortises that (11.8 against 12.1 us in alternating runs; no difference from 11 chunks on).
+    if (pl.PRE == 0 && cpi == 2 && prm.chunks_lo <= 6) prm.pre = cpi;
     // testing hook: exercise the path taken when a split group is not on one XCD
     prm.force_recompute = ov.force_recompute ? 1 : 0;
     return LA_OK;
