@@ -1,6 +1,7 @@
 // Device-side helpers shared by the lookahead-step attention kernels (la_attention.hip: the
-// staged kernel with shared key blocks; la_attention_pk.hip: the kernel whose waves own their
-// key blocks).  Nothing here is part of the C ABI.
+// staged kernel, whose workgroups split the keys of a row block and combine partial results;
+// la_attention_rowtile.hip: the kernel whose workgroups walk all keys for one row tile).  Nothing
+// here is part of the C ABI.
 #pragma once
 #include <hip/hip_runtime.h>
 

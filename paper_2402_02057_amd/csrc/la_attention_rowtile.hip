@@ -20,7 +20,7 @@
 // exponentials, both measured slower) and 1.5 us to merge and write, against 8 us and more of
 // fixed cost for the staged kernel with its split groups: ahead up to a dozen chunks (prefix
 // + step <= 768 keys) if its workgroups, 2 per row tile and KV head, fit one round of the compute
-// units, behind beyond that (7B shape at 1024 keys: 12.7 against 11.6 us).
+// units, behind beyond that (the 7B configuration, 1145 keys: 12.7 against 11.3 us).
 //
 // Same arithmetic per block as the staged kernel (la_attention.hip): S^T = K Q^T and
 // O^T += V^T P^T with v_mfma_f32_32x32x16_bf16, softmax weights in bf16 with the row sum over the
@@ -85,7 +85,9 @@ static_assert(NWC * MERGE_WAVE_BYTES <= NSTAGE * STAGE_BYTES, "the merge reuses 
 // other pair of rows has the halves of its pieces exchanged.
 __device__ __forceinline__ int vh_swizzle(int row) { return (row & 2) << 1; }
 
-__global__ __launch_bounds__((NWC + NWP) * 64) __attribute__((amdgpu_waves_per_eu((NWC + NWP + 3) / 4, (NWC + NWP + 3) / 4))) void step_attention_rowtile_kernel(const RowTileParams)
+// (two waves per SIMD are all there will be: the compiler need not save registers for more)
+__global__ __launch_bounds__((NWC + NWP) * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void step_attention_rowtile_kernel(const RowTileParams)
 {
     const RowTileParams& p = warmed_arguments<RowTileParams>();
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
