@@ -145,10 +145,11 @@ la_status la_step_attention_fp8kv(const void* q, const void* k_cache, const void
  *   cos, sin     fp32 [max_pos][head_dim/2] on the device, 16-byte aligned
  *   max_pos      positions the tables hold; the step reaches P + max(W + N - 2, N - 1)
  *   interleaved  0: pair i is (x[i], x[i + head_dim/2]);  nonzero: (x[2i], x[2i + 1])
- * Everything else as la_step_attention.  Limit: the table rows of the step's positions are
- * staged beside the key/value ring; with head_dim 128 there is room for 32 positions
- * (W + N - 2 <= 31) in the common decomposition.  A step that needs more is refused with
- * LA_EUNSUPPORTED: rotate with la_step_rope then.
+ * Everything else as la_step_attention (the choice between the two kernels included, see
+ * la_step_attention_kernel).  Limit: the table rows of the step's positions are staged beside
+ * the key/value ring; with head_dim 128 there is room for 32 positions (W + N - 2 <= 31) in the
+ * staged kernel's common decomposition and for 64 in the row-tile kernel.  A step that needs
+ * more is refused with LA_EUNSUPPORTED: rotate with la_step_rope then.
  */
 la_status la_step_attention_rope(const void* q, const void* k_cache, const void* v_cache, const void* step_k,
                                  const void* step_v, const float* cos, const float* sin, int max_pos, int interleaved,

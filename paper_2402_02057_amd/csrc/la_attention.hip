@@ -1426,9 +1426,14 @@ la_status launch_step_attention(const void* q, const void* k_cache, const void* 
         (long long)kv_heads * head_dim * 2 >= (1 << 24))
         return fail(LA_EUNSUPPORTED, "la_step_attention: step too large (T=%d, heads=%d)", T, heads);
     const Overrides ov = current_overrides();
-    if (!block_table && !row_ids && !k_scale && !rope && picks_rowtile(ov, P, T, group, kv_heads, head_dim))
-        return launch_step_attention_rowtile(q, k_cache, v_cache, capacity, step_k, step_v, P, W, N, G, heads, kv_heads,
-                                             out, stream);
+    if (!block_table && !row_ids && !k_scale && picks_rowtile(ov, P, T, group, kv_heads, head_dim)) {
+        // (the rotating form of the row-tile kernel stages fewer positions than the staged kernel's:
+        // a wider step stays with the staged kernel)
+        const int far = W > 0 ? (W + N - 2 > N - 1 ? W + N - 2 : N - 1) : (G > 0 ? N - 1 : 0);
+        if (!rope || far + 1 <= rowtile_rope_positions())
+            return launch_step_attention_rowtile(q, k_cache, v_cache, capacity, step_k, step_v, P, W, N, G, heads,
+                                                 kv_heads, out, stream, rope);
+    }
     const Plan pl = make_plan(ov, P, T, group, kv_heads, head_dim, block_table != nullptr, row_ids != nullptr,
                               rope != nullptr);
     AttnParams prm;

@@ -26,12 +26,18 @@
 // O^T += V^T P^T with v_mfma_f32_32x32x16_bf16, softmax weights in bf16 with the row sum over the
 // rounded values, lazy moves of the running reference, mask words from indices.  The four waves'
 // states are merged through LDS in fp32, in key order.
+//
+// Rotating form (ROPE): the query rows, and on request the step keys, arrive as the projection
+// left them and are turned in LDS at the positions of Fig. 2(b), with the arithmetic of
+// la_step_rope; the table rows of those positions are staged behind Q, in the room of the ring's
+// sixth stage.
 #include <math.h>
 
 #include <mutex>
 
 #include "la_internal.h"
 #include "la_attention_common.h"
+#include "la_rope_common.h"
 
 #ifdef LA_DEV_HOOKS_ROWTILE
 #include LA_DEV_HOOKS_ROWTILE  // developer builds only: timing stamps, never part of the product build
@@ -57,28 +63,42 @@ struct RowTileParams {
     int n_prefix_chunks, n_chunks;
     int total_wg, wg_per_xcd;
     float scale_log2, inv_group, inv_W, inv_n1, inv_tiles;
+    // rotating variant: the rows of the model's tables from the prefix length on ([rope_rows][D/2]
+    // fp32 each), staged in LDS; bit 0 of the flags: pairing (x[2i], x[2i+1]); bit 1: the step keys
+    // arrive unrotated as well
+    const float* rope_cos;
+    const float* rope_sin;
+    int rope_rows, rope_block, rope_flags;
 };
 
 constexpr int D = 128;
 constexpr int KC = 64;                    // keys per chunk
-constexpr int NSTAGE = 6;
 constexpr int NWC = 4, NWP = 4;           // computing and requesting waves
 constexpr int CPI = NWC / 2;              // chunks per iteration: a 32-key block per computing wave
 constexpr int K_BYTES = KC * D * 2;       // 16 KB
 constexpr int VH_BYTES = KC * D;          // half of the value columns: 8 KB
 constexpr int STAGE_BYTES = K_BYTES + VH_BYTES;
-constexpr int Q_OFFSET = NSTAGE * STAGE_BYTES;
 constexpr int Q_BYTES = 32 * D * 2;
-constexpr int LDS_BYTES = Q_OFFSET + Q_BYTES;
+// The ring: six chunks, or five in the rotating variant, which needs the room for the table rows of
+// the step's positions (up to 64 positions of 256 + 256 bytes behind Q).
+template <bool ROPE>
+struct Ring {
+    static constexpr int NSTAGE = ROPE ? 5 : 6;
+    static constexpr int Q_OFFSET = NSTAGE * STAGE_BYTES;
+    static constexpr int ROPE_OFFSET = Q_OFFSET + Q_BYTES;
+    static constexpr int ROPE_MAX_BYTES = ROPE ? 160 * 1024 - ROPE_OFFSET : 0;  // both tables
+    static constexpr int LDS_BYTES = ROPE_OFFSET + ROPE_MAX_BYTES;
+};
+constexpr int ROPE_POS_BYTES = D * 2;     // one position of one table (D/2 fp32)
 constexpr int K_LOADS = K_BYTES / 1024 / NWP;   // per requesting wave and chunk: 4
 constexpr int V_LOADS = VH_BYTES / 1024 / NWP;  // 2
 constexpr int LPW = K_LOADS + V_LOADS;
 // merge of the four waves' states: per wave two 32 x 32 slices in fp32 and (m, l) per lane
 constexpr int MERGE_WAVE_BYTES = 2 * 16 * 64 * 4 + 64 * 8;
-static_assert(LDS_BYTES <= 160 * 1024, "LDS of a compute unit");
-static_assert(NSTAGE >= 2 * CPI, "an iteration's chunks are requested while the last iteration's are read");
-static_assert(LPW * (NSTAGE - CPI) < 64, "vmcnt is a 6-bit counter");
-static_assert(NWC * MERGE_WAVE_BYTES <= NSTAGE * STAGE_BYTES, "the merge reuses the ring");
+static_assert(Ring<false>::LDS_BYTES <= 160 * 1024 && Ring<true>::LDS_BYTES <= 160 * 1024, "LDS of a compute unit");
+static_assert(Ring<true>::NSTAGE >= 2 * CPI, "an iteration's chunks are requested while the last iteration's are read");
+static_assert(LPW * (Ring<false>::NSTAGE - CPI) < 64, "vmcnt is a 6-bit counter");
+static_assert(NWC * MERGE_WAVE_BYTES <= Ring<true>::NSTAGE * STAGE_BYTES, "the merge reuses the ring");
 
 // Rows of the value half are 128 bytes, two to a sweep of the banks: the transposing read takes 64
 // bytes of each of rows r .. r+3 per half-wave; rows two apart start at the same bank, so every
@@ -86,9 +106,11 @@ static_assert(NWC * MERGE_WAVE_BYTES <= NSTAGE * STAGE_BYTES, "the merge reuses 
 __device__ __forceinline__ int vh_swizzle(int row) { return (row & 2) << 1; }
 
 // (two waves per SIMD are all there will be: the compiler need not save registers for more)
+template <bool ROPE>
 __global__ __launch_bounds__((NWC + NWP) * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void step_attention_rowtile_kernel(const RowTileParams)
 {
+    constexpr int NSTAGE = Ring<ROPE>::NSTAGE, Q_OFFSET = Ring<ROPE>::Q_OFFSET, ROPE_OFFSET = Ring<ROPE>::ROPE_OFFSET;
     const RowTileParams& p = warmed_arguments<RowTileParams>();
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     LA_STAMP(0);
@@ -110,6 +132,60 @@ void step_attention_rowtile_kernel(const RowTileParams)
     f32x16 o[2];
     float m_run = kNegInf, l_run = 0.0f;
     const float sl2 = p.scale_log2;
+
+    // ---- rotating variant: what every thread of the workgroup does behind an iteration's barrier.
+    //      Eight pairs of one 16-bit row in LDS (16-byte pieces swizzled with `sw`) are turned in place
+    //      by the staged table rows of position digit `digit`, with the arithmetic of la_step_rope.
+    auto rotate_unit = [&](unsigned char* row, int sw, int c, int digit) {
+        constexpr int UPR = D / 16;  // units of eight pairs per row
+        const bool inter = (p.rope_flags & 1) != 0;
+        bf16x8* va = reinterpret_cast<bf16x8*>(row + (((inter ? 2 * c : c) ^ sw) << 4));
+        bf16x8* vb = reinterpret_cast<bf16x8*>(row + (((inter ? 2 * c + 1 : c + UPR) ^ sw) << 4));
+        const float* cs = reinterpret_cast<const float*>(lds + ROPE_OFFSET + digit * ROPE_POS_BYTES) + c * 8;
+        const float* sn = reinterpret_cast<const float*>(lds + ROPE_OFFSET + p.rope_block + digit * ROPE_POS_BYTES) + c * 8;
+        const f32x4 c0 = *reinterpret_cast<const f32x4*>(cs), c1 = *reinterpret_cast<const f32x4*>(cs + 4);
+        const f32x4 s0 = *reinterpret_cast<const f32x4*>(sn), s1 = *reinterpret_cast<const f32x4*>(sn + 4);
+        const float co[8] = {c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
+        const float si[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
+        const bf16x8 xa = *va, xb = *vb;
+        bf16x8 ya, yb;
+        rope_eight_pairs(xa, xb, co, si, inter, ya, yb);
+        *va = ya;
+        *vb = yb;
+    };
+    // Behind the barrier of iteration `it`: in the first one the tile's query rows, and in any one
+    // the K rows of those of its chunks that hold step keys (if the keys arrive unrotated), followed
+    // by one more barrier.  Whether there is anything to do is the same for every wave.
+    auto rotate_after_barrier = [&](int it) {
+        if constexpr (ROPE) {
+            const int first = it * CPI;
+            const bool keys = (p.rope_flags & 2) != 0 && min(first + CPI, n_chunks) > n_prefix_chunks;
+            if (it != 0 && !keys) return;
+            if (it == 0) {
+                for (int u = tid; u < 32 * (D / 16); u += (NWC + NWP) * 64) {
+                    const int r = u / (D / 16), c = u - r * (D / 16);
+                    const int rr = min(tile * 32 + r, p.R - 1);
+                    const int digit = min(step_row_digit(div_small(rr, p.inv_group), p.W, p.N, p.inv_W, p.inv_n1), p.rope_rows - 1);
+                    rotate_unit(lds + Q_OFFSET + r * (D * 2), swizzle<D>(r), c, digit);
+                }
+            }
+            if (keys) {
+                for (int j = 0; j < CPI; ++j) {
+                    const int c_abs = first + j;
+                    if (c_abs < n_chunks && c_abs >= n_prefix_chunks) {
+                        unsigned char* stage = lds + (c_abs % NSTAGE) * STAGE_BYTES;
+                        const int t0 = (c_abs - n_prefix_chunks) * KC;
+                        for (int u = tid; u < KC * (D / 16); u += (NWC + NWP) * 64) {
+                            const int r = u / (D / 16), c = u - r * (D / 16);
+                            const int digit = min(step_row_digit(min(t0 + r, p.T - 1), p.W, p.N, p.inv_W, p.inv_n1), p.rope_rows - 1);
+                            rotate_unit(stage + r * (D * 2), swizzle<D>(r), c, digit);
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    };
 
     if (wave >= NWC) {
         // ---------------- requesting waves
@@ -161,6 +237,18 @@ void step_attention_rowtile_kernel(const RowTileParams)
                 dma16_base(p.q, off, lds_base + Q_OFFSET + wl * 1024);
             }
         };
+        if constexpr (ROPE) {
+            // the table rows of the step's positions first (they are needed with Q): two linear blocks,
+            // 1 KB per wave-load, lanes past the end repeat the last 16 bytes
+            const int per_table = p.rope_block >> 10;
+            const unsigned last = (unsigned)(p.rope_rows * ROPE_POS_BYTES - 16);
+            for (int i = lw; i < 2 * per_table; i += NWP) {
+                const bool is_sin = i >= per_table;
+                const int j = is_sin ? i - per_table : i;
+                dma16_base(is_sin ? p.rope_sin : p.rope_cos, min((unsigned)(j * 1024 + lane * 16), last),
+                           lds_base + ROPE_OFFSET + (is_sin ? p.rope_block : 0) + j * 1024);
+            }
+        }
         int issued = 0;
         const int upfront = min(n_chunks, NSTAGE);
 #pragma unroll
@@ -177,6 +265,7 @@ void step_attention_rowtile_kernel(const RowTileParams)
             // the stages read in the last iteration are free: the ring has room up to chunk done + NSTAGE - 1
             const int room = min(n_chunks, done + NSTAGE);
             while (issued < room) issue_chunk(issued++);
+            rotate_after_barrier(it);
         }
         wait_vmcnt<0>();
         __syncthreads();  // (the computing waves are through with the ring)
@@ -224,6 +313,7 @@ void step_attention_rowtile_kernel(const RowTileParams)
     for (int it = 0, done = 0; it < n_iter; ++it, done += CPI) {
         __syncthreads();  // this iteration's chunks have landed; everyone is done with the last ones
         if (it < 4) LA_STAMP(8 + 2 * it);
+        rotate_after_barrier(it);
         if (it == 0) {
             const unsigned char* qr = lds + Q_OFFSET + l32 * (D * 2);
             const int qsw = swizzle<D>(l32);
@@ -401,9 +491,42 @@ bool rowtile_supported(int head_dim, int group, int T)
     return head_dim == D && (long long)T * group < (1 << 21);
 }
 
+// Positions whose table rows fit behind the rotating variant's ring.
+int rowtile_rope_positions() { return Ring<true>::ROPE_MAX_BYTES / (2 * ROPE_POS_BYTES); }
+
+namespace {
+
+template <bool ROPE>
+la_status launch_rowtile(const RowTileParams& p, hipStream_t stream)
+{
+    constexpr int kLds = Ring<ROPE>::LDS_BYTES;
+    auto kern = step_attention_rowtile_kernel<ROPE>;
+    static bool attr_set[16] = {false};
+    static std::mutex mutex;
+    {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return fail(LA_EHIP, "hipGetDevice failed");
+        std::lock_guard<std::mutex> lock(mutex);
+        if (!attr_set[dev]) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+            if (e != hipSuccess) return fail(LA_EHIP, "hipFuncSetAttribute(%d bytes LDS): %s", kLds, hipGetErrorString(e));
+            attr_set[dev] = true;
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)p.wg_per_xcd * 8u), dim3((NWC + NWP) * 64), kLds, stream, p);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(LA_EHIP, "la_step_attention launch: %s", hipGetErrorString(e));
+    return LA_OK;
+}
+
+}  // namespace
+
+// `rope` != nullptr: q (and with rope->rotate_keys the step keys) arrive unrotated; the caller has
+// checked that the tables cover the step's positions and that those fit (rowtile_rope_positions).
 la_status launch_step_attention_rowtile(const void* q, const void* k_cache, const void* v_cache, long long capacity,
                                         const void* step_k, const void* step_v, int P, int W, int N, int G, int heads,
-                                        int kv_heads, void* out, hipStream_t stream)
+                                        int kv_heads, void* out, hipStream_t stream, const RopeTables* rope)
 {
     RowTileParams p;
     p.q = (const __bf16*)q;
@@ -427,24 +550,19 @@ la_status launch_step_attention_rowtile(const void* q, const void* k_cache, cons
     p.inv_W = W > 0 ? 1.0f / (float)W : 1.0f;
     p.inv_n1 = 1.0f / (float)(N - 1);
     p.inv_tiles = 1.0f / (float)p.n_tiles;
-    static bool attr_set[16] = {false};
-    static std::mutex mutex;
-    {
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return fail(LA_EHIP, "hipGetDevice failed");
-        std::lock_guard<std::mutex> lock(mutex);
-        if (!attr_set[dev]) {
-            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(step_attention_rowtile_kernel),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-            if (e != hipSuccess) return fail(LA_EHIP, "hipFuncSetAttribute(%d bytes LDS): %s", LDS_BYTES, hipGetErrorString(e));
-            attr_set[dev] = true;
-        }
-    }
-    hipLaunchKernelGGL(step_attention_rowtile_kernel, dim3((unsigned)p.wg_per_xcd * 8u), dim3((NWC + NWP) * 64), LDS_BYTES,
-                       stream, p);
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return fail(LA_EHIP, "la_step_attention launch: %s", hipGetErrorString(e));
-    return LA_OK;
+    p.rope_cos = p.rope_sin = nullptr;
+    p.rope_rows = p.rope_block = p.rope_flags = 0;
+    if (!rope) return launch_rowtile<false>(p, stream);
+    // the furthest position of the step: the newest window level's last column, or a candidate's last token
+    const int far = W > 0 ? (W + N - 2 > N - 1 ? W + N - 2 : N - 1) : (G > 0 ? N - 1 : 0);
+    p.rope_rows = far + 1;
+    p.rope_block = (p.rope_rows * ROPE_POS_BYTES + 1023) / 1024 * 1024;
+    if (2 * p.rope_block > Ring<true>::ROPE_MAX_BYTES)
+        return fail(LA_EUNSUPPORTED, "la_step_attention_rope: %d positions do not fit beside the ring", p.rope_rows);
+    p.rope_flags = (rope->interleaved ? 1 : 0) | (rope->rotate_keys ? 2 : 0);
+    p.rope_cos = rope->cos + (size_t)P * (D / 2);
+    p.rope_sin = rope->sin + (size_t)P * (D / 2);
+    return launch_rowtile<true>(p, stream);
 }
 
 }  // namespace la

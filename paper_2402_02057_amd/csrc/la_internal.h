@@ -96,9 +96,10 @@ struct BatchSeq {
 bool rowtile_supported(int head_dim, int group, int T);
 // 1: la_step_attention / _cap / _noalloc take the row-tile kernel for this shape; 0: the staged one.
 int step_attention_kernel_choice(int P, int W, int N, int G, int heads, int kv_heads, int head_dim);
+int rowtile_rope_positions();
 la_status launch_step_attention_rowtile(const void* q, const void* k_cache, const void* v_cache, long long capacity,
                                         const void* step_k, const void* step_v, int P, int W, int N, int G, int heads,
-                                        int kv_heads, void* out, hipStream_t stream);
+                                        int kv_heads, void* out, hipStream_t stream, const RopeTables* rope = nullptr);
 la_status launch_step_attention_batch(const BatchSeq* seqs, int n_seqs, int page_size, int n_pages, int W, int N,
                                       int G, int heads, int kv_heads, int head_dim, hipStream_t stream);
 la_status launch_kv_commit(void* k_cache, void* v_cache, long long capacity, const int* block_table,

@@ -26,18 +26,18 @@ def make(seed, P, W, N, G, H, KV, d):
     return x, cos, sin
 
 
+@pytest.fixture(autouse=True, params=["auto", "staged", "rowtile"])
+def kernel_choice(request, override):
+    """Both attention kernels have a rotating form, picked by the same rule as the plain step's kernel:
+    every test runs with the library's choice and with each kernel forced, so that the rotating entry
+    point and the plain step it is compared with bit by bit always take the same kernel."""
+    if request.param != "auto":
+        override("attn_rowtile", "1" if request.param == "rowtile" else "0")
+    return request.param
+
+
 def run_case(seed, P, W, N, G, H, KV, d, interleaved, oracle=True):
     print("case", dict(P=P, W=W, N=N, G=G, H=H, KV=KV, d=d, interleaved=interleaved), flush=True)
-    # the rotating entry point is a variant of the staged kernel: the plain step it is compared with
-    # bit by bit must take that kernel too (short prefixes would otherwise go to the row-tile kernel)
-    binding.la_debug_override("attn_rowtile", "0")
-    try:
-        _run_case(seed, P, W, N, G, H, KV, d, interleaved, oracle)
-    finally:
-        binding.la_debug_override("attn_rowtile", None)
-
-
-def _run_case(seed, P, W, N, G, H, KV, d, interleaved, oracle):
     x, cos, sin = make(seed, P, W, N, G, H, KV, d)
     T = 1 + (W + G) * (N - 1)
     dev = {k: binding.bf16_tensor(v) for k, v in x.items()}
@@ -133,8 +133,12 @@ def test_recompute_path(override):
     run_case(32, 900, 15, 5, 15, 8, 8, 128, False)
 
 
-def test_limits_and_argument_errors():
-    # 34 positions (W = 30, N = 5) do not fit beside the ring at head_dim 128
+def test_limits_and_argument_errors(kernel_choice, override):
+    if kernel_choice != "auto":
+        pytest.skip("sets the kernel itself")
+    # 34 positions (W = 30, N = 5) do not fit beside the staged kernel's ring at head_dim 128 (the
+    # row-tile kernel, which this short prefix would take, has room for 64: see the next test)
+    override("attn_rowtile", "0")
     P, W, N, G, H, KV, d = 300, 30, 5, 30, 8, 2, 128
     x, cos, sin = make(1, P, W, N, G, H, KV, d)
     dev = {k: binding.bf16_tensor(v) for k, v in x.items()}
@@ -217,3 +221,23 @@ def test_commit_rope_argument_errors():
         t24 = torch.zeros((P + N + 4, 12), dtype=torch.float32, device="cuda")
         binding.la_kv_commit_rope(z(KV, P + N, 24), z(KV, P + N, 24), z(T, KV, 24), z(T, KV, 24), t24, t24, P, W, N, G,
                                   KV, 24, one, one)
+
+
+def test_wide_window_on_a_short_prefix_takes_the_row_tile_kernel(kernel_choice):
+    """34 positions: more than the staged kernel stages, fewer than the row-tile kernel's 64."""
+    if kernel_choice == "staged":
+        pytest.skip("the staged kernel refuses this step (test_limits_and_argument_errors)")
+    P, W, N, G, H, KV, d = 300, 30, 5, 30, 8, 2, 128
+    assert binding.la_step_attention_kernel(P, W, N, G, H, KV, d) == 1
+    run_case(41, P, W, N, G, H, KV, d, False)
+
+
+def test_recompute_and_forced_decompositions_stay_with_the_staged_kernel(kernel_choice):
+    """(run_case compares bits: with a forced decomposition both sides are the staged kernel)"""
+    if kernel_choice != "rowtile":
+        pytest.skip("covered by test_other_decompositions")
+    binding.la_debug_override("attn_plan", "2,4,2,4,64")
+    try:
+        run_case(31, 200, 10, 5, 10, 8, 4, 128, False)
+    finally:
+        binding.la_debug_override("attn_plan", None)
