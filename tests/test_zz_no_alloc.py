@@ -58,7 +58,9 @@ def both(shape, seed):
 def test_two_calls_second_smaller():
     torch.cuda.set_device(0)
     big = (1024, 15, 5, 15, 32, 32, 128)     # the 7B shape: 256 workgroups, four-way key split
-    small = (333, 4, 3, 2, 8, 4, 128)        # fewer split groups, shorter partials
+    small = (900, 4, 3, 2, 8, 4, 128)        # fewer split groups, shorter partials (15 chunks: still the
+                                             # staged kernel, the one that uses the scratch block)
+    assert binding.la_step_attention_kernel(*small) == 0 and binding.la_step_attention_workspace_bytes(*small) > 0
     _, (fixed, pooled) = both(big, 11)
     assert np.array_equal(fixed, pooled), "7B shape: noalloc differs from la_step_attention"
     x, (fixed, pooled) = both(small, 12)
@@ -70,6 +72,11 @@ def test_two_calls_second_smaller():
     assert np.abs(got - want).max() <= TOL
     # and once more at the large shape: the block keeps the small call's contents
     _, (fixed, pooled) = both(big, 13)
+    assert np.array_equal(fixed, pooled)
+    # a step short enough for the kernel that needs no scratch memory at all goes through as well
+    tiny = (333, 4, 3, 2, 8, 4, 128)
+    assert binding.la_step_attention_kernel(*tiny) == 1
+    _, (fixed, pooled) = both(tiny, 14)
     assert np.array_equal(fixed, pooled)
 
 
