@@ -194,3 +194,39 @@ def test_a_capture_that_would_have_to_grow_the_workspace_is_refused():
     graph2.replay()
     torch.cuda.synchronize()
     assert torch.equal(out, eager)
+
+
+def test_the_row_tile_kernel_in_a_graph_with_an_empty_workspace():
+    """A short-prefix step takes the kernel that needs no workspace: it can be recorded with nothing
+    allocated, and every replay (with eager work of the same library between the replays) gives the
+    eager result, rotating form included."""
+    torch.cuda.synchronize()
+    binding.la_shutdown()
+    s = wl.LLAMA2_7B_P256
+    W, N, G, H, KV, d, P, T = s.W, s.N, s.G, s.heads, s.kv_heads, s.head_dim, s.P, s.T
+    assert binding.la_step_attention_kernel(P, W, N, G, H, KV, d) == 1
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(17)
+
+    def rb(*shape):
+        return torch.randn(shape, device="cuda", generator=gen).bfloat16()
+    q, kc, vc, sk, sv = rb(T, H, d), rb(KV, P, d), rb(KV, P, d), rb(T, KV, d), rb(T, KV, d)
+    cos, sin = [torch.from_numpy(t).cuda() for t in wl.rope_tables(P + W + N, d)]
+    out, out_r = [torch.zeros((T, H, d), dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        binding.la_step_attention(q, kc, vc, sk, sv, P, W, N, G, H, KV, d, out)
+        binding.la_step_attention_rope(q, kc, vc, sk, sv, cos, sin, P, W, N, G, H, KV, d, out_r, rotate_keys=True)
+    eager, eager_r = torch.empty_like(out), torch.empty_like(out)
+    binding.la_step_attention(q, kc, vc, sk, sv, P, W, N, G, H, KV, d, eager)
+    binding.la_step_attention_rope(q, kc, vc, sk, sv, cos, sin, P, W, N, G, H, KV, d, eager_r, rotate_keys=True)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        out.zero_()
+        out_r.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager) and torch.equal(out_r, eager_r), "replay %d" % rep
+        binding.la_step_attention(q, kc, vc, sk, sv, P, W, N, G, H, KV, d, torch.empty_like(out))  # eager work between
+        torch.cuda.synchronize()
+    assert not torch.equal(eager, eager_r)
