@@ -92,7 +92,30 @@ def test_small_shapes(P, W, N, G, H, KV, d):
     check(x, P, W, N, G, H, KV, d)
 
 
-@pytest.mark.parametrize("shape", [wl.LLAMA2_7B, wl.LLAMA2_13B, wl.LLAMA2_70B], ids=lambda s: s.name)
+def _random_shapes(n, seed):
+    """Seeded draws over the ranges a decoding run visits: prefixes on both sides of the chunk size and
+    of the point where the library changes kernels, windows and candidate counts down to none, every
+    n-gram size of Table 4, one to eight heads per KV head."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        P = int(rng.choice([0, 1, 63, 64, 65, 127, 128, 129, int(rng.integers(0, 400)), int(rng.integers(400, 1100))]))
+        W, G, N = int(rng.integers(0, 13)), int(rng.integers(0, 13)), int(rng.integers(2, 8))
+        KV = int(rng.choice([1, 2, 3, 4]))
+        H = KV * int(rng.choice([1, 2, 4, 8]))
+        d = int(rng.choice([64, 128, 128, 128]))
+        if (1 + (W + G) * (N - 1)) * H * d <= 200000:      # keeps the oracle to a fraction of a second per case
+            out.append((P, W, N, G, H, KV, d))
+    return out
+
+
+@pytest.mark.parametrize("P,W,N,G,H,KV,d", _random_shapes(24, 20240205))
+def test_random_shapes(P, W, N, G, H, KV, d):
+    x = rand_inputs(P * 13 + W * 5 + G * 3 + H + d, P, W, N, G, H, KV, d)
+    check(x, P, W, N, G, H, KV, d, "random")
+
+
+@pytest.mark.parametrize("shape", [wl.LLAMA2_7B, wl.LLAMA2_13B, wl.LLAMA2_70B, wl.LLAMA2_7B_P256], ids=lambda s: s.name)
 def test_paper_configs_full_size(shape):
     s = shape
     check(wl.attention_inputs(s), s.P, s.W, s.N, s.G, s.heads, s.kv_heads, s.head_dim, s.name)
