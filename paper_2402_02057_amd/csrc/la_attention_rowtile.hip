@@ -14,13 +14,13 @@
 // memory pipeline is full; on a wave of its own that stall costs nothing.  The ring holds six
 // chunks of 64 keys (K 16 KB + half of V 8 KB each): two being read, four in flight.
 //
-// Where it is used: the launch costs about 3 us until the first chunks have landed, 0.95 us per
+// Where it is used: the launch costs about 2.5 us until the first chunks have landed, 0.95 us per
 // 128 keys (a lone wave per SIMD issues its block's ~300 instructions in order; six computing
 // waves with three chunks in flight, and a loop that overlaps the next block's MFMAs with the
 // exponentials, both measured slower) and 1.5 us to merge and write, against 8 us and more of
 // fixed cost for the staged kernel with its split groups: ahead up to a dozen chunks (prefix
 // + step <= 768 keys) if its workgroups, 2 per row tile and KV head, fit one round of the compute
-// units, behind beyond that (the 7B configuration, 1145 keys: 12.7 against 11.3 us).
+// units, behind beyond that (the 7B configuration, 1145 keys: 12.1 against 11.3 us).
 //
 // Same arithmetic per block as the staged kernel (la_attention.hip): S^T = K Q^T and
 // O^T += V^T P^T with v_mfma_f32_32x32x16_bf16, softmax weights in bf16 with the row sum over the
