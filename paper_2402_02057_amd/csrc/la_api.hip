@@ -633,6 +633,6 @@ la_status la_debug_override(const char* key, const char* value) { return la::set
 
 const char* la_last_error(void) { return la::g_error; }
 
-int la_version(void) { return 1012; }
+int la_version(void) { return 1013; }
 
 }  // extern "C"
