@@ -14,10 +14,13 @@
 // memory pipeline is full; on a wave of its own that stall costs nothing.  The ring holds six
 // chunks of 64 keys (K 16 KB + half of V 8 KB each): two being read, four in flight.
 //
-// Where it is used: the launch costs about 2.5 us until the first chunks have landed, 0.95 us per
-// 128 keys (a lone wave per SIMD issues its block's ~300 instructions in order; six computing
-// waves with three chunks in flight, and a loop that overlaps the next block's MFMAs with the
-// exponentials, both measured slower) and 1.5 us to merge and write, against 8 us and more of
+// Where it is used: the launch costs about 2.5 us until the first chunks have landed, 0.75 us per
+// 128 keys with up to 128 workgroups (the compute unit's intake plus a part of the block) and
+// 0.95 us with 256 (what the L2s deliver to all compute units at once, every workgroup of a head
+// pulling all of K; the arithmetic is hidden then), and 1.5 us to merge and write.  Measured and
+// dropped: six computing waves with three chunks in flight, a loop that overlaps the next
+// block's MFMAs with the exponentials, 16-row waves, two waves per SIMD half an iteration apart,
+// two tiles per workgroup.  That compares with 8 us and more of
 // fixed cost for the staged kernel with its split groups: ahead up to a dozen chunks (prefix
 // + step <= 768 keys) if its workgroups, 2 per row tile and KV head, fit one round of the compute
 // units, behind beyond that (the 7B configuration, 1145 keys: 12.1 against 11.3 us).
